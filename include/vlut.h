@@ -1,0 +1,176 @@
+/*
+ * vlut.h -- C ABI of the vector-LUT ternary x INT8 mixed-precision GEMM for
+ * AMD Instinct MI355X (gfx950).
+ *
+ * The library computes O = W x A (Vec-LUT paper, Table 2) for ternary weights
+ * W in {-1,0,+1}^(M x K) and INT8 activations A in Z^(K x N), N parallel tokens,
+ * with the paper's vector-table method (Sec. 3.2, Alg. 1): every g = 4
+ * consecutive weights of a row are one base-3 byte, every group of 4 activation
+ * rows yields one sub-table of 3^4 = 81 signed partial sums across the N tokens,
+ * and each packed byte performs one 1 -> N lookup-accumulate.
+ *
+ * Conventions for every entry point
+ *   - Pointers marked "dev" are device (HBM) pointers of the current HIP device;
+ *     pointers marked "host" are ordinary host pointers.  Nothing is copied
+ *     between host and device by the library.
+ *   - The caller owns every buffer.  The library allocates no device memory and
+ *     keeps no state between calls, except the optional per-thread tuning
+ *     override of vlut_set_plan.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Runtime entry points only enqueue work on `stream`; they never
+ *     synchronise.  vlut_pack_weights is an offline step and may synchronise.
+ *   - Return value: VLUT_OK (0) or a negative VLUT_ERR_* code.  Argument checks
+ *     (null pointers, shapes, buffer sizes) happen before the first HIP call,
+ *     so they behave the same on a machine without a GPU.  No exception crosses
+ *     this boundary.
+ *   - Shapes: M >= 1, N >= 1, K >= 4 and K % 4 == 0 (the paper's g | K condition,
+ *     Sec. 3.3 "Flexible sub-2-bit weight packing"); M, N need not be multiples
+ *     of any tile.  Each of M, K, N must be below 2^24.
+ */
+#ifndef VLUT_H
+#define VLUT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VLUT_OK 0
+#define VLUT_ERR_NULL (-1)         /* a required pointer is NULL                      */
+#define VLUT_ERR_SHAPE (-2)        /* M, K, N, ldx or ldy outside the supported range */
+#define VLUT_ERR_SMALL_BUFFER (-3) /* a byte count passed in is below the required one */
+#define VLUT_ERR_VALUE (-4)        /* a weight outside {-1,0,+1}                      */
+#define VLUT_ERR_DEVICE (-5)       /* a HIP call or kernel launch failed              */
+#define VLUT_ERR_UNSUPPORTED (-6)  /* valid request this build cannot serve           */
+
+#define VLUT_GROUP 4     /* g: weights per packed byte (2.00 bits per weight, the paper's I2) */
+#define VLUT_ROWS 81     /* 3^g rows per sub-table                                            */
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* vlut_status_string(int status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int vlut_version(void);
+
+/*
+ * Bytes of the packed weight blob for an M x K matrix (0 if the shape is
+ * invalid).  The blob holds one byte per group of 4 weights (Sec. 3.3
+ * "Tile-contiguous packed weight layout"), in tiles of 4 rows x 16 groups;
+ * rows are padded to a multiple of 4 and groups to a multiple of 16 with the
+ * byte 40 (the all-zero pattern), so the size is
+ * ceil(M/4) * ceil(K/64) * 64.  The blob is position independent: it can be
+ * saved and reloaded byte for byte.
+ */
+size_t vlut_packed_weight_bytes(int64_t M, int64_t K);
+
+/*
+ * Byte offset, inside the packed blob, of the index of row m and group kg
+ * (weights W[m][4kg .. 4kg+3]).  Host-only helper that documents the tile
+ * layout; returns (size_t)-1 for an out-of-range argument.
+ */
+size_t vlut_packed_offset(int64_t M, int64_t K, int64_t m, int64_t kg);
+
+/* Bytes of the full vector table T for K x N activations: (K/4) * 81 * N * 2
+ * (Sec. 1 quotes 285.5 MiB for K = 14436, N = 512).  0 if the shape is invalid. */
+size_t vlut_lut_bytes(int64_t K, int64_t N);
+
+/* Bytes of scratch vlut_mpgemm needs for this shape (split-K partial sums); may be 0. */
+size_t vlut_workspace_bytes(int64_t M, int64_t K, int64_t N);
+
+/*
+ * Offline weight transformation (Sec. 3.1 stage i, Sec. 3.3): ternary weights
+ * to base-3 bytes, idx = sum_j (W[m][4kg+j] + 1) * 3^(3-j), so that the byte's
+ * decimal value is the table row (Fig. 5 caption; the digit order follows the
+ * worked example of Sec. 3.2: 23 <-> (-1,+1,0,+1)), stored in the tile layout
+ * described at vlut_packed_weight_bytes.
+ *   w_ternary    dev, int8 [M][K] row-major, every value in {-1,0,+1}
+ *   packed       dev, packed_bytes >= vlut_packed_weight_bytes(M, K); fully overwritten
+ * Synchronises `stream` to report VLUT_ERR_VALUE when a weight is not ternary
+ * (the blob content is then unspecified).
+ */
+int vlut_pack_weights(const int8_t* w_ternary, int64_t M, int64_t K, uint8_t* packed,
+                      size_t packed_bytes, void* stream);
+
+/*
+ * Per-token symmetric INT8 quantisation fused with the transposition to the
+ * token-contiguous layout (Sec. 3.4 first paragraph; Sec. 3.3 "Fused activation
+ * and output transformation").  For every token n, in fp32:
+ *   amax = max_k |x[n][k]|;  a_scale[n] = amax / 127;
+ *   inv = 127 / amax (0 when amax == 0);
+ *   a_q[k][n] = clamp(round_half_even(x[n][k] * inv), -127, 127).
+ * -128 is never produced (the INT16 block bound of Sec. 3.4 relies on |q| <= 127).
+ *   x        dev, fp32 [N][ldx], feature-contiguous, ldx >= K; finite values
+ *   a_q      dev, int8 [K][N], token-contiguous
+ *   a_scale  dev, fp32 [N]
+ */
+int vlut_quantize_act(const float* x, int64_t N, int64_t K, int64_t ldx, int8_t* a_q,
+                      float* a_scale, void* stream);
+
+/*
+ * Materialises the whole vector table in device memory (Alg. 1 function
+ * Precompute, Eq. 1, built with the topological order of Sec. 4):
+ *   lut[kg][i][n] = sum_{j<4} (digit_j(i) - 1) * a_q[4kg+j][n],
+ * digit_0 the most significant base-3 digit of i; int16, layout [K/4][81][N]
+ * with N contiguous (Sec. 3.3 "Token-contiguous LUT layout").
+ *   lut_bytes >= vlut_lut_bytes(K, N)
+ * The hot path does not need this call (it builds table tiles in LDS on the
+ * fly, Sec. 3.4 "Streamed precomputing-lookup execution"); it exists for
+ * inspection and for the un-streamed variant of vlut_mpgemm.
+ */
+int vlut_build_lut(const int8_t* a_q, int64_t K, int64_t N, int16_t* lut, size_t lut_bytes,
+                   void* stream);
+
+/*
+ * The mpGeMM itself (Alg. 1 main loop, Eq. 2; Sec. 3.4): for every packed byte
+ * one lookup of an 81-row sub-table row and a vector add over the tokens,
+ * INT16 inside blocks of at most 64 lookups, INT32 across blocks, then the
+ * scale step y[n][m] = (float)acc[m][n] * (w_scale * a_scale[n]).
+ *   packed        dev, blob written by vlut_pack_weights for the same M, K
+ *   w_scale       per-tensor weight scale
+ *   a_q, a_scale  dev, as written by vlut_quantize_act for the same K, N
+ *   lut_or_null   dev or NULL.  NULL: sub-tables are built in LDS tile by tile
+ *                 (streamed, the default).  Non-NULL: a table written by
+ *                 vlut_build_lut for (a_q, K, N) is read instead (un-streamed
+ *                 variant kept for the ablation of Sec. 5.6).
+ *   y             dev, fp32 [N][ldy], feature-contiguous, ldy >= M; may be NULL
+ *                 when acc_or_null is given
+ *   acc_or_null   dev or NULL, int32 [M][N] raw accumulators (token-contiguous)
+ *   workspace     dev, workspace_bytes >= vlut_workspace_bytes(M, K, N); may be
+ *                 NULL when that size is 0
+ */
+int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale,
+                const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y, int64_t ldy,
+                int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Same contract and same results as vlut_mpgemm (lut_or_null must be NULL), but
+ * computed the multiply-add way the paper contrasts with (Sec. 2.2.1): packed
+ * bytes are unpacked to INT8 and multiplied on the INT8 matrix cores.  In-run
+ * comparison only.
+ */
+int vlut_mpgemm_mfma(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale,
+                     const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y,
+                     int64_t ldy, int32_t* acc_or_null, void* workspace, size_t workspace_bytes,
+                     void* stream);
+
+/*
+ * Tuning hook: forces the launch plan of vlut_mpgemm for subsequent calls from
+ * this thread (interleave factor J in {1,2,4,8,16} = sub-tables per 256-byte
+ * table row, row groups per wave R, waves per workgroup, split-K factor).
+ * Any argument 0 = choose automatically.  Returns VLUT_ERR_UNSUPPORTED for a
+ * combination the kernels are not built for.  Results never depend on the plan.
+ */
+int vlut_set_plan(int J, int R, int waves, int split_k);
+
+/*
+ * Reports the launch plan vlut_mpgemm would use for this shape (after any vlut_set_plan override of the
+ * calling thread): out4 (host, 4 ints) = { J, R, split_k, number of workgroup tiles }.
+ */
+int vlut_query_plan(int64_t M, int64_t K, int64_t N, int* out4);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VLUT_H */

@@ -1,0 +1,158 @@
+"""Thin Python binding of the C ABI in include/vlut.h (argument marshalling only).
+
+Device buffers are torch tensors on a ROCm device; this module passes their raw
+pointers and the current HIP stream to libvlut.so.  Every step of the path runs
+inside the library's kernels; there is no fallback: if the library is missing or
+a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvlut.so")
+
+VLUT_OK = 0
+VLUT_ERR_NULL, VLUT_ERR_SHAPE, VLUT_ERR_SMALL_BUFFER = -1, -2, -3
+VLUT_ERR_VALUE, VLUT_ERR_DEVICE, VLUT_ERR_UNSUPPORTED = -4, -5, -6
+
+EXPORTS = [
+    "vlut_status_string", "vlut_version", "vlut_packed_weight_bytes", "vlut_packed_offset", "vlut_lut_bytes",
+    "vlut_workspace_bytes", "vlut_pack_weights", "vlut_quantize_act", "vlut_build_lut", "vlut_mpgemm",
+    "vlut_mpgemm_mfma", "vlut_set_plan", "vlut_query_plan",
+]
+
+_lib = None
+
+
+class VlutError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libvlut.so; building it is the job of __graft_entry__.build() / paper_2512_06443_amd.build."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2512_06443_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        i64, sz, p, ci, cf = ctypes.c_int64, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+        L.vlut_status_string.argtypes, L.vlut_status_string.restype = [ci], ctypes.c_char_p
+        L.vlut_version.argtypes, L.vlut_version.restype = [], ci
+        L.vlut_packed_weight_bytes.argtypes, L.vlut_packed_weight_bytes.restype = [i64, i64], sz
+        L.vlut_packed_offset.argtypes, L.vlut_packed_offset.restype = [i64, i64, i64, i64], sz
+        L.vlut_lut_bytes.argtypes, L.vlut_lut_bytes.restype = [i64, i64], sz
+        L.vlut_workspace_bytes.argtypes, L.vlut_workspace_bytes.restype = [i64, i64, i64], sz
+        L.vlut_pack_weights.argtypes, L.vlut_pack_weights.restype = [p, i64, i64, p, sz, p], ci
+        L.vlut_quantize_act.argtypes, L.vlut_quantize_act.restype = [p, i64, i64, i64, p, p, p], ci
+        L.vlut_build_lut.argtypes, L.vlut_build_lut.restype = [p, i64, i64, p, sz, p], ci
+        gemm_args = [p, cf, p, p, p, i64, i64, i64, p, i64, p, p, sz, p]
+        L.vlut_mpgemm.argtypes, L.vlut_mpgemm.restype = gemm_args, ci
+        L.vlut_mpgemm_mfma.argtypes, L.vlut_mpgemm_mfma.restype = gemm_args, ci
+        L.vlut_set_plan.argtypes, L.vlut_set_plan.restype = [ci, ci, ci, ci], ci
+        L.vlut_query_plan.argtypes, L.vlut_query_plan.restype = [i64, i64, i64, ctypes.POINTER(ci)], ci
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().vlut_status_string(status).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != VLUT_OK:
+        raise VlutError(status, where)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def packed_weight_bytes(M: int, K: int) -> int:
+    return lib().vlut_packed_weight_bytes(M, K)
+
+
+def packed_offset(M: int, K: int, m: int, kg: int) -> int:
+    return lib().vlut_packed_offset(M, K, m, kg)
+
+
+def lut_bytes(K: int, N: int) -> int:
+    return lib().vlut_lut_bytes(K, N)
+
+
+def workspace_bytes(M: int, K: int, N: int) -> int:
+    return lib().vlut_workspace_bytes(M, K, N)
+
+
+def set_plan(J: int = 0, R: int = 0, waves: int = 0, split_k: int = 0) -> None:
+    _check(lib().vlut_set_plan(J, R, waves, split_k), "vlut_set_plan")
+
+
+def query_plan(M: int, K: int, N: int) -> Tuple[int, int, int, int]:
+    out = (ctypes.c_int * 4)()
+    _check(lib().vlut_query_plan(M, K, N, out), "vlut_query_plan")
+    return out[0], out[1], out[2], out[3]
+
+
+def pack_weights(w_ternary: torch.Tensor) -> torch.Tensor:
+    """int8 [M][K] on the GPU -> packed uint8 blob (opaque tile layout) on the GPU."""
+    assert w_ternary.is_cuda and w_ternary.dtype == torch.int8 and w_ternary.is_contiguous()
+    M, K = w_ternary.shape
+    nbytes = packed_weight_bytes(M, K)
+    if nbytes == 0:
+        raise VlutError(VLUT_ERR_SHAPE, "vlut_packed_weight_bytes")
+    packed = torch.empty(nbytes, dtype=torch.uint8, device=w_ternary.device)
+    _check(lib().vlut_pack_weights(_ptr(w_ternary), M, K, _ptr(packed), nbytes, _stream()), "vlut_pack_weights")
+    return packed
+
+
+def quantize_act(x: torch.Tensor, a_q: Optional[torch.Tensor] = None, a_scale: Optional[torch.Tensor] = None):
+    """fp32 [N][K] (row stride >= K) -> (int8 [K][N], fp32 [N])."""
+    assert x.is_cuda and x.dtype == torch.float32 and x.dim() == 2 and x.stride(1) == 1
+    N, K = x.shape
+    if a_q is None:
+        a_q = torch.empty((K, N), dtype=torch.int8, device=x.device)
+    if a_scale is None:
+        a_scale = torch.empty(N, dtype=torch.float32, device=x.device)
+    _check(lib().vlut_quantize_act(_ptr(x), N, K, x.stride(0), _ptr(a_q), _ptr(a_scale), _stream()), "vlut_quantize_act")
+    return a_q, a_scale
+
+
+def build_lut(a_q: torch.Tensor, lut: Optional[torch.Tensor] = None) -> torch.Tensor:
+    assert a_q.is_cuda and a_q.dtype == torch.int8 and a_q.is_contiguous()
+    K, N = a_q.shape
+    if lut is None:
+        lut = torch.empty((K // 4, 81, N), dtype=torch.int16, device=a_q.device)
+    _check(lib().vlut_build_lut(_ptr(a_q), K, N, _ptr(lut), lut.numel() * 2, _stream()), "vlut_build_lut")
+    return lut
+
+
+def mpgemm(packed: torch.Tensor, w_scale: float, a_q: torch.Tensor, a_scale: torch.Tensor, M: int,
+           y: Optional[torch.Tensor] = None, acc: Optional[torch.Tensor] = None, lut: Optional[torch.Tensor] = None,
+           workspace: Optional[torch.Tensor] = None, want_acc: bool = False, mfma: bool = False):
+    """Runs vlut_mpgemm (or the MFMA comparison path).  Returns (y fp32 [N][M], acc int32 [M][N] or None)."""
+    K, N = a_q.shape
+    dev = a_q.device
+    if y is None:
+        y = torch.empty((N, M), dtype=torch.float32, device=dev)
+    if acc is None and want_acc:
+        acc = torch.empty((M, N), dtype=torch.int32, device=dev)
+    ws_bytes = workspace_bytes(M, K, N)
+    if workspace is None and ws_bytes:
+        workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    fn = lib().vlut_mpgemm_mfma if mfma else lib().vlut_mpgemm
+    rc = fn(_ptr(packed), float(w_scale), _ptr(a_q), _ptr(a_scale), _ptr(lut), M, K, N, _ptr(y), y.stride(0),
+            _ptr(acc), _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+            _stream())
+    _check(rc, "vlut_mpgemm_mfma" if mfma else "vlut_mpgemm")
+    return y, acc

@@ -1,0 +1,787 @@
+// Vector-LUT ternary x INT8 mpGeMM for MI355X (gfx950): kernels and C ABI.
+//
+// Data layout in LDS (one "slot" = one 81-row table whose rows are 256 bytes):
+//   a 256-byte row is 16 slices of 16 bytes; slice l belongs to LDS banks 4l..4l+3,
+//   so 16 lanes that each read "their" slice of 16 different rows never conflict.
+//   A slice holds 8 INT16 table entries (8 tokens) of ONE sub-table.  With
+//   J = 1,2,4,8,16 sub-tables interleaved per row, a slot serves J sub-tables x
+//   (128/J) tokens: slice l = j * (16/J) + t  (j = sub-table selector, t = 8-token chunk).
+//   Lane (grp = lane/16, l = lane%16) of a wave looks up row idx of slice l for
+//   output row 4*rowgroup + grp, so one ds_read_b128 serves 4 output rows x 128
+//   (sub-table, token) pairs; the J partial sums of a token are added across lanes
+//   once, after the K loop.
+//
+// Paper references: Alg. 1 (lookup/accumulate and Precompute), Eq. 1-2, Sec. 3.3
+// (token-contiguous tables, tile-contiguous packed weights), Sec. 3.4 (tiling,
+// streamed precompute-lookup, INT16->INT32 hierarchy, block size 64), Sec. 4
+// (topological precompute).
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstring>
+#include <mutex>
+
+#include "vlut.h"
+
+namespace {
+
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) i32x4 lds_i32x4;
+typedef __attribute__((address_space(3))) int lds_i32;
+
+constexpr int kRows = 81;                    // 3^4 rows per sub-table
+constexpr int kRowBytes = 256;               // LDS bytes per table row (16 slices x 16 B)
+constexpr int kSlotBytes = kRows * kRowBytes;  // 20736
+constexpr int kStageSlots = 4;               // slots resident per stage (one weight dword = 4 lookups)
+constexpr int kLdsBytes = kStageSlots * kSlotBytes;  // 82944
+constexpr int kWaves = 16;                   // waves per workgroup
+constexpr int kThreads = kWaves * 64;
+constexpr int kBuilders = kStageSlots * 9 * 16;  // 576 build tasks per stage
+constexpr unsigned kZeroIdx4 = 0x28282828u;  // four copies of index 40 (the all-zero pattern)
+constexpr int kMaxDim = 1 << 24;
+constexpr int kBlockLookups = 64;            // INT16 block size B for g = 4 (Sec. 3.4)
+
+struct LookupParams {
+    const uint8_t* packed;
+    const int8_t* a_q;
+    const float* a_scale;
+    const int16_t* lut;
+    float* y;
+    int32_t* acc;
+    int32_t* ws;
+    float w_scale;
+    int M, K, N, G, KCn, RGtotal, ldy;
+    int Jlog, S, tiles_m, tiles_n, RGW, stages_total, stages_per_split, total_tiles, per_xcd;
+    int aligned8;
+};
+
+__device__ __forceinline__ unsigned lds_base_of(void* p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (unsigned)(__attribute__((address_space(3))) char*)p;
+#else
+    (void)p;
+    return 0u;   // host pass of the single-source compile; never executed
+#endif
+}
+
+// addr is a byte address inside LDS; OFF16 is a compile-time offset in units of 16 bytes, kept apart so that it
+// lands in the instruction's immediate offset field instead of costing a VALU add.
+template <int OFF16>
+__device__ __forceinline__ i32x4 lds_read128(unsigned addr) {
+    return ((const lds_i32x4*)addr)[OFF16];
+}
+template <int OFF16>
+__device__ __forceinline__ void lds_write128(unsigned addr, i32x4 v) {
+    ((lds_i32x4*)addr)[OFF16] = v;
+}
+
+__device__ __forceinline__ s16x2 as_s16x2(int v) { return __builtin_bit_cast(s16x2, v); }
+__device__ __forceinline__ int as_int(s16x2 v) { return __builtin_bit_cast(int, v); }
+
+// Two INT8 values (bytes 2h and 2h+1 of x) -> sign-extended packed INT16 pair.
+__device__ __forceinline__ s16x2 unpack_pair(unsigned x, int h) {
+    unsigned sel = h ? 0x070c060cu : 0x050c040cu;   // {0, byte, 0, byte}: value in the high byte of each half
+    s16x2 v = as_s16x2((int)__builtin_amdgcn_perm(x, 0u, sel));
+    return v >> (short)8;                            // arithmetic shift per half
+}
+
+// ---------------------------------------------------------------------------------------------
+// Offline packing (Sec. 3.3): one thread per packed byte, including the padding bytes.
+// ---------------------------------------------------------------------------------------------
+__device__ int g_pack_error;
+
+__global__ void pack_kernel(const int8_t* __restrict__ w, int M, int K, int G, int KCn, int RGtotal,
+                            uint8_t* __restrict__ packed) {
+    size_t total = (size_t)RGtotal * KCn * 64;
+    size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    int b = (int)(i & 15);
+    int r = (int)((i >> 4) & 3);
+    size_t tile = i >> 6;
+    int kc = (int)(tile % KCn);
+    int rg = (int)(tile / KCn);
+    int m = rg * 4 + r;
+    int kg = kc * 16 + b;
+    unsigned v = 40;
+    if (m < M && kg < G) {
+        const int8_t* p = w + (size_t)m * K + (size_t)kg * 4;
+        int w0 = p[0], w1 = p[1], w2 = p[2], w3 = p[3];
+        bool ok = (w0 >= -1 && w0 <= 1) && (w1 >= -1 && w1 <= 1) && (w2 >= -1 && w2 <= 1) && (w3 >= -1 && w3 <= 1);
+        if (!ok) atomicOr(&g_pack_error, 1);
+        v = (unsigned)((w0 + 1) * 27 + (w1 + 1) * 9 + (w2 + 1) * 3 + (w3 + 1));
+    }
+    packed[i] = (uint8_t)v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Activation quantisation + transposition (Sec. 3.4 first paragraph, Sec. 3.3).
+// One workgroup handles TOK consecutive tokens over all K.
+// ---------------------------------------------------------------------------------------------
+template <int TOK>
+__global__ void __launch_bounds__(256) quantize_kernel(const float* __restrict__ x, int N, int K, int64_t ldx,
+                                                       int8_t* __restrict__ a_q, float* __restrict__ a_scale) {
+    __shared__ float red[4][TOK];
+    __shared__ float s_inv[TOK];
+    const int n0 = blockIdx.x * TOK;
+    const int tid = threadIdx.x;
+    float amax[TOK];
+#pragma unroll
+    for (int t = 0; t < TOK; ++t) amax[t] = 0.0f;
+    for (int k = tid; k < K; k += 256) {
+#pragma unroll
+        for (int t = 0; t < TOK; ++t) {
+            int n = n0 + t;
+            if (n < N) amax[t] = fmaxf(amax[t], fabsf(x[(size_t)n * ldx + k]));
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < TOK; ++t) {
+        float v = amax[t];
+        for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+        if ((tid & 63) == 0) red[tid >> 6][t] = v;
+    }
+    __syncthreads();
+    if (tid < TOK) {
+        float v = fmaxf(fmaxf(red[0][tid], red[1][tid]), fmaxf(red[2][tid], red[3][tid]));
+        int n = n0 + tid;
+        // IEEE-correct fp32 divisions (the default for HIP); no reciprocal approximation.
+        float inv = (v > 0.0f) ? 127.0f / v : 0.0f;
+        s_inv[tid] = inv;
+        if (n < N) a_scale[n] = v / 127.0f;
+    }
+    __syncthreads();
+    for (int k = tid; k < K; k += 256) {
+#pragma unroll
+        for (int t = 0; t < TOK; ++t) {
+            int n = n0 + t;
+            if (n < N) {
+                float p = x[(size_t)n * ldx + k] * s_inv[t];   // one rounded multiply
+                float r = rintf(p);                              // ties to even
+                r = fminf(fmaxf(r, -127.0f), 127.0f);
+                a_q[(size_t)k * N + n] = (int8_t)(int)r;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Whole table in global memory (Alg. 1 Precompute / Eq. 1), topological order of Sec. 4:
+// every row is one add/sub away from an earlier one.  One thread per (group, token).
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) build_lut_kernel(const int8_t* __restrict__ a_q, int G, int N,
+                                                        int16_t* __restrict__ lut) {
+    size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+    if (i >= (size_t)G * N) return;
+    int n = (int)(i % N);
+    int kg = (int)(i / N);
+    int a0 = a_q[(size_t)(4 * kg + 0) * N + n];
+    int a1 = a_q[(size_t)(4 * kg + 1) * N + n];
+    int a2 = a_q[(size_t)(4 * kg + 2) * N + n];
+    int a3 = a_q[(size_t)(4 * kg + 3) * N + n];
+    int16_t* t = lut + ((size_t)kg * kRows) * N + n;
+    int v0 = -a0 - a1 - a2 - a3;                       // row 0, then walk the digits
+    for (int d0 = 0; d0 < 3; ++d0) {
+        int v1 = v0;
+        for (int d1 = 0; d1 < 3; ++d1) {
+            int v2 = v1;
+            for (int d2 = 0; d2 < 3; ++d2) {
+                int v3 = v2;
+                for (int d3 = 0; d3 < 3; ++d3) {
+                    t[(size_t)(27 * d0 + 9 * d1 + 3 * d2 + d3) * N] = (int16_t)v3;
+                    v3 += a3;
+                }
+                v2 += a2;
+            }
+            v1 += a1;
+        }
+        v0 += a0;
+    }
+}
+
+// One lookup-accumulate (Alg. 1 lines 3-6): byte B of the weight dword is the row of slot B; the lane reads its
+// 16-byte slice of that row (8 INT16 entries) and adds it into 4 packed INT16 accumulators.
+template <int B>
+__device__ __forceinline__ void lookup_add(unsigned w, unsigned lanebase, s16x2 (&acc)[4]) {
+    const unsigned sel = 0x0c0c0000u | ((4u + (unsigned)B) << 8);
+    const unsigned addr = __builtin_amdgcn_perm(w, lanebase, sel);   // idx*256 + slice*16
+    const i32x4 v = lds_read128<B * (kSlotBytes / 16)>(addr);
+    acc[0] += as_s16x2(v.x);
+    acc[1] += as_s16x2(v.y);
+    acc[2] += as_s16x2(v.z);
+    acc[3] += as_s16x2(v.w);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The lookup kernel.
+//   R            row groups (of 4 output rows) per wave; workgroup tile = up to 64*R rows
+//   NEED32       more than 64 lookups per lane: widen INT16 block sums into INT32 every 16 stages
+//   FROM_GLOBAL  fill the LDS slots from a materialised table instead of building them
+// ---------------------------------------------------------------------------------------------
+template <int R, bool NEED32, bool FROM_GLOBAL>
+__global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    // The kernel has no static LDS, so the dynamic segment starts at LDS address 0; table addresses are formed
+    // as idx*256 + slice*16 by a byte permute and rely on that.
+    if (lds_base_of(smem) != 0u) return;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction
+
+    // ---- which tile (XCD-aware: the 8 XCDs take contiguous ranges of the tile list, so the
+    //      workgroups that share a weight tile also share an L2)
+    int L = (int)(blockIdx.x & 7) * p.per_xcd + (int)(blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= p.per_xcd || L >= p.total_tiles) return;
+    const int ks = L % p.S;
+    L /= p.S;
+    const int nt = L % p.tiles_n;
+    const int mt = L / p.tiles_n;
+
+    const int Jlog = p.Jlog;
+    const int J = 1 << Jlog;
+    const int TClog = 4 - Jlog;          // log2(token chunks per sub-table)
+    const int n_tile = 128 >> Jlog;
+    const int n0 = nt * n_tile;
+    const int rgw0 = mt * p.RGW;          // first row group of this workgroup
+
+    // ---- lookup role of this lane
+    const int l = lane & 15;
+    const int grp = lane >> 4;
+    const int j = l >> TClog;
+    const int t = l & ((1 << TClog) - 1);
+    const unsigned lanebase = (unsigned)l * 16u;
+
+    const int st_begin = ks * p.stages_per_split;
+    const int st_end = min(p.stages_total, st_begin + p.stages_per_split);
+
+    // Row group r of this wave: its packed tiles start at a wave-uniform address (scalar registers); the lane
+    // adds its row (grp) and, per stage, the tile and dword it needs.
+    const unsigned char* wbase[R];
+    bool wvalid[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int rgl = r * kWaves + wave;     // r-major: round r of the epilogue covers 64 consecutive rows
+        int rg = rgw0 + rgl;
+        wvalid[r] = (rgl < p.RGW) && (rg < p.RGtotal);
+        wbase[r] = p.packed + ((size_t)(wvalid[r] ? rg : 0) * p.KCn) * 64;
+    }
+
+    // ---- build role (threads 0..575): slot bb, slice lb, digit pair hh = 3*d0 + d1
+    const bool builder = tid < kBuilders;
+    const int lb = tid & 15;
+    const int bq = tid >> 4;
+    const int bb = bq / 9;
+    const int hh = bq - bb * 9;
+    const int jb = lb >> TClog;
+    const int tb = lb & ((1 << TClog) - 1);
+    const int nb = n0 + 8 * tb;          // first token of the builder's slice
+    unsigned act[4][2];
+
+    auto prefetch_act = [&](int st) {
+        int kg = st * 4 * J + 4 * jb + bb;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
+        if (kg < p.G && nb < p.N) {
+            const int8_t* src = p.a_q + (size_t)(4 * kg) * p.N + nb;
+            if (p.aligned8 && nb + 8 <= p.N) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    i32x2 v = *(const i32x2*)(src + (size_t)c * p.N);
+                    act[c][0] = (unsigned)v.x;
+                    act[c][1] = (unsigned)v.y;
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        unsigned byte = (nb + e < p.N) ? (unsigned)(uint8_t)src[(size_t)c * p.N + e] : 0u;
+                        act[c][e >> 2] |= byte << (8 * (e & 3));
+                    }
+                }
+            }
+        }
+    };
+
+    s16x2 acc16[R][4];
+    int acc32[NEED32 ? R : 1][8];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc16[r][q] = s16x2{0, 0};
+    if (NEED32) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc32[r][e] = 0;
+    }
+
+    if (builder && !FROM_GLOBAL && st_begin < st_end) prefetch_act(st_begin);
+
+    for (int st = st_begin; st < st_end; ++st) {
+        // weight dwords of this stage: dword q = st*J + j of each row (4 lookups)
+        unsigned w[R];
+        {
+            const int q = st * J + j;
+            const int kc = q >> 2;
+            const bool kvalid = kc < p.KCn;
+            const unsigned voff = (unsigned)(kc * 64 + grp * 16 + (q & 3) * 4);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                w[r] = (kvalid && wvalid[r]) ? *(const unsigned*)(wbase[r] + voff) : kZeroIdx4;
+        }
+
+        // ---- fill the 4 slots of this stage
+        if (builder) {
+            const unsigned dst = (unsigned)bb * kSlotBytes + (unsigned)(9 * hh) * kRowBytes + (unsigned)lb * 16u;
+            if (FROM_GLOBAL) {
+                const int kg = st * 4 * J + 4 * jb + bb;
+#pragma unroll
+                for (int i = 0; i < 9; ++i) {
+                    i32x4 v = {0, 0, 0, 0};
+                    if (kg < p.G && nb < p.N) {
+                        const int16_t* src = p.lut + ((size_t)kg * kRows + 9 * hh + i) * p.N + nb;
+                        if (p.aligned8 && nb + 8 <= p.N) {
+                            v = *(const i32x4*)src;
+                        } else {
+                            int tmp[4] = {0, 0, 0, 0};
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                unsigned hw = (nb + e < p.N) ? (unsigned)(uint16_t)src[e] : 0u;
+                                tmp[e >> 1] |= (int)(hw << (16 * (e & 1)));
+                            }
+                            v = i32x4{tmp[0], tmp[1], tmp[2], tmp[3]};
+                        }
+                    }
+                    lds_write128<0>(dst + (unsigned)i * kRowBytes, v);
+                }
+            } else {
+                // rows 9*hh .. 9*hh+8 of the sub-table: digits (d0,d1) fixed by hh, (d2,d3) enumerated.
+                const short s0 = (short)(hh / 3 - 1), s1 = (short)(hh % 3 - 1);
+                const s16x2 m0 = {s0, s0}, m1 = {s1, s1};
+                s16x2 a2[4], a3[4], base[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    s16x2 a0 = unpack_pair(act[0][q >> 1], q & 1);
+                    s16x2 a1 = unpack_pair(act[1][q >> 1], q & 1);
+                    a2[q] = unpack_pair(act[2][q >> 1], q & 1);
+                    a3[q] = unpack_pair(act[3][q >> 1], q & 1);
+                    base[q] = a0 * m0 + a1 * m1;
+                }
+#pragma unroll
+                for (int d2 = 0; d2 < 3; ++d2) {
+                    s16x2 u[4], lo[4], hi[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        u[q] = (d2 == 0) ? base[q] - a2[q] : (d2 == 1) ? base[q] : base[q] + a2[q];
+                        lo[q] = u[q] - a3[q];
+                        hi[q] = u[q] + a3[q];
+                    }
+                    if (d2 == 0) {
+                        lds_write128<0 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
+                        lds_write128<1 * 16>(dst, i32x4{as_int(u[0]), as_int(u[1]), as_int(u[2]), as_int(u[3])});
+                        lds_write128<2 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
+                    } else if (d2 == 1) {
+                        lds_write128<3 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
+                        lds_write128<4 * 16>(dst, i32x4{as_int(u[0]), as_int(u[1]), as_int(u[2]), as_int(u[3])});
+                        lds_write128<5 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
+                    } else {
+                        lds_write128<6 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
+                        lds_write128<7 * 16>(dst, i32x4{as_int(u[0]), as_int(u[1]), as_int(u[2]), as_int(u[3])});
+                        lds_write128<8 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (builder && !FROM_GLOBAL && st + 1 < st_end) prefetch_act(st + 1);
+
+        // ---- 4 lookups per row group: byte b of the weight dword selects the row of slot b
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            lookup_add<0>(w[r], lanebase, acc16[r]);
+            lookup_add<1>(w[r], lanebase, acc16[r]);
+            lookup_add<2>(w[r], lanebase, acc16[r]);
+            lookup_add<3>(w[r], lanebase, acc16[r]);
+        }
+        __syncthreads();
+
+        if (NEED32 && (((st - st_begin) & 15) == 15)) {   // 16 stages x 4 lookups = block of 64
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    acc32[r][2 * q] += (int)acc16[r][q].x;
+                    acc32[r][2 * q + 1] += (int)acc16[r][q].y;
+                    acc16[r][q] = s16x2{0, 0};
+                }
+        }
+    }
+
+    // ---- epilogue, one round per row group index r: every lane parks its partial sums in LDS
+    // ([64 rows][16 slices], row stride padded by 16 B), then the workgroup adds the J partial sums of
+    // each (row, token), applies the scales and writes 64 consecutive output rows per token.
+    constexpr int kEntry = NEED32 ? 4 : 2;                  // bytes per parked value
+    constexpr unsigned kStride = 128u * kEntry + 16u;       // bytes per parked row
+    const int m0 = rgw0 * 4;
+    const int rows_wg = min(p.RGW * 4, p.M - m0);
+    const int TC = 1 << TClog;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const unsigned prow = (unsigned)(wave * 4 + grp) * kStride + (unsigned)l * (8u * kEntry);
+        if (NEED32) {
+            int v[8];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                v[2 * q] = acc32[r][2 * q] + (int)acc16[r][q].x;
+                v[2 * q + 1] = acc32[r][2 * q + 1] + (int)acc16[r][q].y;
+            }
+            lds_write128<0>(prow, i32x4{v[0], v[1], v[2], v[3]});
+            lds_write128<1>(prow, i32x4{v[4], v[5], v[6], v[7]});
+        } else {
+            lds_write128<0>(prow, i32x4{as_int(acc16[r][0]), as_int(acc16[r][1]), as_int(acc16[r][2]), as_int(acc16[r][3])});
+        }
+        __syncthreads();
+        for (int i = tid; i < 64 * n_tile; i += kThreads) {
+            const int ml = i & 63;
+            const int nl = i >> 6;
+            const int mrow = r * 64 + ml;                  // row inside the workgroup tile
+            const int n = n0 + nl;
+            if (mrow < rows_wg && n < p.N) {
+                const unsigned src = (unsigned)ml * kStride + (unsigned)((nl >> 3) * 8 * kEntry + (nl & 7) * kEntry);
+                int val = 0;
+                for (int jj = 0; jj < J; ++jj) {
+                    const unsigned a = src + (unsigned)(jj * TC) * (8u * kEntry);
+                    if (NEED32) val += *(const lds_i32*)a;
+                    else val += (int)*(const __attribute__((address_space(3))) short*)a;
+                }
+                const int m = m0 + mrow;
+                if (p.S == 1) {
+                    if (p.y) p.y[(size_t)n * p.ldy + m] = (float)val * (p.w_scale * p.a_scale[n]);
+                    if (p.acc) p.acc[(size_t)m * p.N + n] = val;
+                } else {
+                    p.ws[((size_t)ks * p.N + n) * p.M + m] = val;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// Sum of the split-K partials (any order is exact: integers) + scale step.
+__global__ void __launch_bounds__(256) splitk_reduce_kernel(const int32_t* __restrict__ ws, int S, int M, int N,
+                                                            float w_scale, const float* __restrict__ a_scale,
+                                                            float* __restrict__ y, int64_t ldy,
+                                                            int32_t* __restrict__ acc) {
+    size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+    if (i >= (size_t)M * N) return;
+    int m = (int)(i % M);
+    int n = (int)(i / M);
+    int v = 0;
+    for (int s = 0; s < S; ++s) v += ws[((size_t)s * N + n) * M + m];
+    if (y) y[(size_t)n * ldy + m] = (float)v * (w_scale * a_scale[n]);
+    if (acc) acc[(size_t)m * N + n] = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------------------------
+struct Plan {
+    int Jlog, R, S;
+};
+
+thread_local Plan t_forced = {-1, 0, 0};
+
+const int kSupportedR[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12};
+
+bool r_supported(int R) {
+    for (int v : kSupportedR)
+        if (v == R) return true;
+    return false;
+}
+
+bool shape_ok(int64_t M, int64_t K, int64_t N) {
+    return M >= 1 && N >= 1 && K >= 4 && (K % 4) == 0 && M < kMaxDim && K < kMaxDim && N < kMaxDim;
+}
+
+struct Derived {
+    int G, KCn, RGtotal, n_tile, tiles_n, tiles_m, RGW, stages_total, stages_per_split, total, per_xcd;
+    bool need32;
+};
+
+Derived derive(const Plan& pl, int64_t M, int64_t K, int64_t N) {
+    Derived d;
+    d.G = (int)(K / 4);
+    d.KCn = (d.G + 15) / 16;
+    d.RGtotal = (int)((M + 3) / 4);
+    int J = 1 << pl.Jlog;
+    d.n_tile = 128 >> pl.Jlog;
+    d.tiles_n = (int)((N + d.n_tile - 1) / d.n_tile);
+    int cap = 16 * pl.R;                              // row groups a workgroup can hold
+    d.tiles_m = (d.RGtotal + cap - 1) / cap;
+    d.RGW = (d.RGtotal + d.tiles_m - 1) / d.tiles_m;  // balanced rows per workgroup
+    d.stages_total = (d.G + 4 * J - 1) / (4 * J);
+    d.stages_per_split = (d.stages_total + pl.S - 1) / pl.S;
+    d.total = d.tiles_m * d.tiles_n * pl.S;
+    d.per_xcd = (d.total + 7) / 8;
+    d.need32 = d.stages_per_split * 4 > kBlockLookups;
+    return d;
+}
+
+// Cost model in CU clocks, fitted to microbenchmarks of this chip: building one 81-row slot is bound by
+// LDS writes (~75 B/clk/CU -> ~280 clk per slot), one looked-up row of 128 (sub-table, token) pairs costs
+// ~1.3 clk (5 VALU issues per 4 rows per wave), and each stage pays two barriers.
+double plan_cost(const Plan& pl, int64_t M, int64_t K, int64_t N) {
+    Derived d = derive(pl, M, K, N);
+    double rows = 4.0 * d.RGW;
+    double rows_wave_max = 4.0 * ((d.RGW + kWaves - 1) / kWaves) * kWaves;   // slowest wave decides
+    (void)rows;
+    double stage = 4 * 280.0 + 4 * rows_wave_max * 1.3 + 150.0;
+    double wg = d.stages_per_split * stage + 2000.0 + (d.need32 ? 0.05 * d.stages_per_split * stage : 0.0);
+    double rounds = (double)((d.total + 255) / 256);
+    double t = rounds * wg;
+    if (pl.S > 1) t += 3000.0 + (double)pl.S * (double)M * (double)N * 8.0 / (256.0 * 16.0);
+    // weight bytes pulled from L2 by all token tiles (256 CUs x ~24 B/clk)
+    double traffic = (double)d.tiles_n * (double)d.RGtotal * d.KCn * 64.0 / (256.0 * 24.0);
+    return t > traffic ? t : traffic;
+}
+
+bool plan_valid(const Plan& pl, int64_t M, int64_t K, int64_t N) {
+    if (pl.Jlog < 0 || pl.Jlog > 4 || !r_supported(pl.R) || pl.S < 1 || pl.S > 16) return false;
+    Derived d = derive(pl, M, K, N);
+    if (d.need32 && pl.R > 6) return false;      // register budget of the INT32 variant
+    if (pl.S > d.stages_total) return false;
+    return true;
+}
+
+Plan choose_plan(int64_t M, int64_t K, int64_t N) {
+    Plan best = {0, 4, 1};
+    double best_cost = 1e300;
+    const int Ss[] = {1, 2, 3, 4, 6, 8};
+    for (int Jlog = 0; Jlog <= 4; ++Jlog)
+        for (int R : kSupportedR)
+            for (int S : Ss) {
+                Plan pl = {t_forced.Jlog >= 0 ? t_forced.Jlog : Jlog, t_forced.R > 0 ? t_forced.R : R,
+                           t_forced.S > 0 ? t_forced.S : S};
+                if (!plan_valid(pl, M, K, N)) continue;
+                double c = plan_cost(pl, M, K, N);
+                if (c < best_cost) { best_cost = c; best = pl; }
+            }
+    return best;
+}
+
+template <int R, bool NEED32, bool FROM_GLOBAL>
+int launch_lookup_t(const LookupParams& p, int grid, hipStream_t stream) {
+    auto kfn = lookup_kernel<R, NEED32, FROM_GLOBAL>;
+    static bool attr_done = false;   // benign race: the call is idempotent
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
+            return VLUT_ERR_DEVICE;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), kLdsBytes, stream, p);
+    return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
+}
+
+template <bool NEED32, bool FROM_GLOBAL>
+int launch_lookup_r(int R, const LookupParams& p, int grid, hipStream_t stream) {
+    switch (R) {
+    case 1: return launch_lookup_t<1, NEED32, FROM_GLOBAL>(p, grid, stream);
+    case 2: return launch_lookup_t<2, NEED32, FROM_GLOBAL>(p, grid, stream);
+    case 3: return launch_lookup_t<3, NEED32, FROM_GLOBAL>(p, grid, stream);
+    case 4: return launch_lookup_t<4, NEED32, FROM_GLOBAL>(p, grid, stream);
+    case 5: return launch_lookup_t<5, NEED32, FROM_GLOBAL>(p, grid, stream);
+    case 6: return launch_lookup_t<6, NEED32, FROM_GLOBAL>(p, grid, stream);
+    default: break;
+    }
+    if (NEED32) return VLUT_ERR_UNSUPPORTED;
+    if constexpr (!NEED32) {
+        switch (R) {
+        case 7: return launch_lookup_t<7, false, FROM_GLOBAL>(p, grid, stream);
+        case 8: return launch_lookup_t<8, false, FROM_GLOBAL>(p, grid, stream);
+        case 10: return launch_lookup_t<10, false, FROM_GLOBAL>(p, grid, stream);
+        case 12: return launch_lookup_t<12, false, FROM_GLOBAL>(p, grid, stream);
+        default: break;
+        }
+    }
+    return VLUT_ERR_UNSUPPORTED;
+}
+
+int check_mpgemm_args(const uint8_t* packed, const int8_t* a_q, const float* a_scale, int64_t M, int64_t K,
+                      int64_t N, float* y, int64_t ldy, int32_t* acc) {
+    if (!shape_ok(M, K, N)) return VLUT_ERR_SHAPE;
+    if (!packed || !a_q || !a_scale) return VLUT_ERR_NULL;
+    if (!y && !acc) return VLUT_ERR_NULL;
+    if (y && (ldy < M || ldy > INT32_MAX)) return VLUT_ERR_SHAPE;
+    return VLUT_OK;
+}
+
+std::mutex g_pack_mutex;
+
+}  // namespace
+
+extern "C" {
+
+const char* vlut_status_string(int status) {
+    switch (status) {
+    case VLUT_OK: return "VLUT_OK";
+    case VLUT_ERR_NULL: return "VLUT_ERR_NULL: a required pointer is NULL";
+    case VLUT_ERR_SHAPE: return "VLUT_ERR_SHAPE: shape or leading dimension out of range";
+    case VLUT_ERR_SMALL_BUFFER: return "VLUT_ERR_SMALL_BUFFER: buffer smaller than required";
+    case VLUT_ERR_VALUE: return "VLUT_ERR_VALUE: weight outside {-1,0,+1}";
+    case VLUT_ERR_DEVICE: return "VLUT_ERR_DEVICE: HIP call or kernel launch failed";
+    case VLUT_ERR_UNSUPPORTED: return "VLUT_ERR_UNSUPPORTED: request not supported by this build";
+    default: return "VLUT_ERR_UNKNOWN";
+    }
+}
+
+int vlut_version(void) { return 100; }
+
+size_t vlut_packed_weight_bytes(int64_t M, int64_t K) {
+    if (!shape_ok(M, K, 1)) return 0;
+    return (size_t)((M + 3) / 4) * (size_t)((K / 4 + 15) / 16) * 64;
+}
+
+size_t vlut_packed_offset(int64_t M, int64_t K, int64_t m, int64_t kg) {
+    if (!shape_ok(M, K, 1) || m < 0 || m >= M || kg < 0 || kg >= K / 4) return (size_t)-1;
+    size_t KCn = (size_t)((K / 4 + 15) / 16);
+    return (((size_t)(m / 4) * KCn + (size_t)(kg / 16)) * 64) + (size_t)(m % 4) * 16 + (size_t)(kg % 16);
+}
+
+size_t vlut_lut_bytes(int64_t K, int64_t N) {
+    if (!shape_ok(1, K, N)) return 0;
+    return (size_t)(K / 4) * kRows * (size_t)N * sizeof(int16_t);
+}
+
+size_t vlut_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+    if (!shape_ok(M, K, N)) return 0;
+    Plan pl = choose_plan(M, K, N);
+    return pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
+}
+
+int vlut_set_plan(int J, int R, int waves, int split_k) {
+    int Jlog = -1;
+    if (J != 0) {
+        for (int e = 0; e <= 4; ++e)
+            if ((1 << e) == J) Jlog = e;
+        if (Jlog < 0) return VLUT_ERR_UNSUPPORTED;
+    }
+    if (R != 0 && !r_supported(R)) return VLUT_ERR_UNSUPPORTED;
+    if (waves != 0 && waves != kWaves) return VLUT_ERR_UNSUPPORTED;
+    if (split_k < 0 || split_k > 16) return VLUT_ERR_UNSUPPORTED;
+    t_forced = {Jlog, R, split_k};
+    return VLUT_OK;
+}
+
+int vlut_query_plan(int64_t M, int64_t K, int64_t N, int* out4) {
+    if (!out4) return VLUT_ERR_NULL;
+    if (!shape_ok(M, K, N)) return VLUT_ERR_SHAPE;
+    Plan pl = choose_plan(M, K, N);
+    Derived d = derive(pl, M, K, N);
+    out4[0] = 1 << pl.Jlog;
+    out4[1] = pl.R;
+    out4[2] = pl.S;
+    out4[3] = d.total;
+    return VLUT_OK;
+}
+
+int vlut_pack_weights(const int8_t* w_ternary, int64_t M, int64_t K, uint8_t* packed, size_t packed_bytes,
+                      void* stream) {
+    if (!shape_ok(M, K, 1)) return VLUT_ERR_SHAPE;
+    if (!w_ternary || !packed) return VLUT_ERR_NULL;
+    size_t need = vlut_packed_weight_bytes(M, K);
+    if (packed_bytes < need) return VLUT_ERR_SMALL_BUFFER;
+    hipStream_t s = (hipStream_t)stream;
+    std::lock_guard<std::mutex> lock(g_pack_mutex);
+    int zero = 0;
+    if (hipMemcpyToSymbolAsync(HIP_SYMBOL(g_pack_error), &zero, sizeof(int), 0, hipMemcpyHostToDevice, s) != hipSuccess)
+        return VLUT_ERR_DEVICE;
+    int G = (int)(K / 4), KCn = (G + 15) / 16, RGtotal = (int)((M + 3) / 4);
+    size_t blocks = (need + 255) / 256;
+    hipLaunchKernelGGL(pack_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w_ternary, (int)M, (int)K, G, KCn, RGtotal,
+                       packed);
+    if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
+    int err = 0;
+    if (hipMemcpyFromSymbolAsync(&err, HIP_SYMBOL(g_pack_error), sizeof(int), 0, hipMemcpyDeviceToHost, s) != hipSuccess)
+        return VLUT_ERR_DEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess) return VLUT_ERR_DEVICE;
+    return err ? VLUT_ERR_VALUE : VLUT_OK;
+}
+
+int vlut_quantize_act(const float* x, int64_t N, int64_t K, int64_t ldx, int8_t* a_q, float* a_scale,
+                      void* stream) {
+    if (!shape_ok(1, K, N)) return VLUT_ERR_SHAPE;
+    if (ldx < K) return VLUT_ERR_SHAPE;
+    if (!x || !a_q || !a_scale) return VLUT_ERR_NULL;
+    hipStream_t s = (hipStream_t)stream;
+    if (N >= 1024) {
+        hipLaunchKernelGGL(quantize_kernel<4>, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, s, x, (int)N, (int)K, ldx, a_q, a_scale);
+    } else if (N >= 256) {
+        hipLaunchKernelGGL(quantize_kernel<2>, dim3((unsigned)((N + 1) / 2)), dim3(256), 0, s, x, (int)N, (int)K, ldx, a_q, a_scale);
+    } else {
+        hipLaunchKernelGGL(quantize_kernel<1>, dim3((unsigned)N), dim3(256), 0, s, x, (int)N, (int)K, ldx, a_q, a_scale);
+    }
+    return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
+}
+
+int vlut_build_lut(const int8_t* a_q, int64_t K, int64_t N, int16_t* lut, size_t lut_bytes, void* stream) {
+    if (!shape_ok(1, K, N)) return VLUT_ERR_SHAPE;
+    if (!a_q || !lut) return VLUT_ERR_NULL;
+    if (lut_bytes < vlut_lut_bytes(K, N)) return VLUT_ERR_SMALL_BUFFER;
+    size_t total = (size_t)(K / 4) * (size_t)N;
+    hipLaunchKernelGGL(build_lut_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream, a_q,
+                       (int)(K / 4), (int)N, lut);
+    return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
+}
+
+int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale,
+                const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y, int64_t ldy,
+                int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_mpgemm_args(packed, a_q, a_scale, M, K, N, y, ldy, acc_or_null);
+    if (rc != VLUT_OK) return rc;
+    Plan pl = choose_plan(M, K, N);
+    Derived d = derive(pl, M, K, N);
+    size_t ws_need = pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
+    if (ws_need > 0) {
+        if (!workspace) return VLUT_ERR_NULL;
+        if (workspace_bytes < ws_need) return VLUT_ERR_SMALL_BUFFER;
+    }
+    LookupParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.packed = packed; p.a_q = a_q; p.a_scale = a_scale; p.lut = lut_or_null;
+    p.y = y; p.acc = acc_or_null; p.ws = (int32_t*)workspace; p.w_scale = w_scale;
+    p.M = (int)M; p.K = (int)K; p.N = (int)N; p.G = d.G; p.KCn = d.KCn; p.RGtotal = d.RGtotal; p.ldy = (int)ldy;
+    p.Jlog = pl.Jlog; p.S = pl.S; p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.RGW = d.RGW;
+    p.stages_total = d.stages_total; p.stages_per_split = d.stages_per_split;
+    p.total_tiles = d.total; p.per_xcd = d.per_xcd;
+    bool al = (N % 8 == 0) && (((uintptr_t)a_q) % 8 == 0);
+    if (lut_or_null) al = al && (((uintptr_t)lut_or_null) % 16 == 0);
+    p.aligned8 = al ? 1 : 0;
+    hipStream_t s = (hipStream_t)stream;
+    int grid = d.per_xcd * 8;
+    if (lut_or_null)
+        rc = d.need32 ? launch_lookup_r<true, true>(pl.R, p, grid, s) : launch_lookup_r<false, true>(pl.R, p, grid, s);
+    else
+        rc = d.need32 ? launch_lookup_r<true, false>(pl.R, p, grid, s) : launch_lookup_r<false, false>(pl.R, p, grid, s);
+    if (rc != VLUT_OK) return rc;
+    if (pl.S > 1) {
+        size_t total = (size_t)M * (size_t)N;
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           (const int32_t*)workspace, pl.S, (int)M, (int)N, w_scale, a_scale, y, ldy, acc_or_null);
+        if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
+    }
+    return VLUT_OK;
+}
+
+int vlut_mpgemm_mfma(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale,
+                     const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y, int64_t ldy,
+                     int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes; (void)stream; (void)w_scale;
+    int rc = check_mpgemm_args(packed, a_q, a_scale, M, K, N, y, ldy, acc_or_null);
+    if (rc != VLUT_OK) return rc;
+    if (lut_or_null) return VLUT_ERR_UNSUPPORTED;
+    return VLUT_ERR_UNSUPPORTED;
+}
+
+}  // extern "C"

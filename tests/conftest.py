@@ -28,3 +28,12 @@ def read_golden(name="paper_values.txt"):
 @pytest.fixture(scope="session")
 def golden():
     return read_golden()
+
+
+@pytest.fixture(scope="session")
+def vlut_lib_path():
+    """Path of the built C-ABI library; builds it (hipcc cross-compiles without a GPU) only if nothing is built."""
+    from paper_2512_06443_amd import build as b
+    if not os.path.exists(b.LIB):
+        b.build()
+    return b.LIB

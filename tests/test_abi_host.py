@@ -1,0 +1,142 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every symbol that
+include/vlut.h declares, its size helpers match the closed forms the paper gives, and every
+argument error is reported before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from tests.conftest import ROOT
+
+i64, sz, vp, ci, cf = ctypes.c_int64, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+
+
+@pytest.fixture(scope="module")
+def L(vlut_lib_path):
+    lib = ctypes.CDLL(vlut_lib_path)
+    lib.vlut_status_string.argtypes, lib.vlut_status_string.restype = [ci], ctypes.c_char_p
+    lib.vlut_packed_weight_bytes.argtypes, lib.vlut_packed_weight_bytes.restype = [i64, i64], sz
+    lib.vlut_packed_offset.argtypes, lib.vlut_packed_offset.restype = [i64, i64, i64, i64], sz
+    lib.vlut_lut_bytes.argtypes, lib.vlut_lut_bytes.restype = [i64, i64], sz
+    lib.vlut_workspace_bytes.argtypes, lib.vlut_workspace_bytes.restype = [i64, i64, i64], sz
+    lib.vlut_pack_weights.argtypes = [vp, i64, i64, vp, sz, vp]
+    lib.vlut_quantize_act.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+    lib.vlut_build_lut.argtypes = [vp, i64, i64, vp, sz, vp]
+    g = [vp, cf, vp, vp, vp, i64, i64, i64, vp, i64, vp, vp, sz, vp]
+    lib.vlut_mpgemm.argtypes = g
+    lib.vlut_mpgemm_mfma.argtypes = g
+    lib.vlut_set_plan.argtypes = [ci, ci, ci, ci]
+    lib.vlut_query_plan.argtypes = [i64, i64, i64, ctypes.POINTER(ci)]
+    return lib
+
+
+def test_every_declared_symbol_is_exported(L):
+    header = open(os.path.join(ROOT, "include", "vlut.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = sorted(set(re.findall(r"\b(vlut_[a-z0-9_]+)\s*\(", header)))
+    assert {"vlut_pack_weights", "vlut_quantize_act", "vlut_build_lut", "vlut_mpgemm"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in vlut.h but not exported"
+    from paper_2512_06443_amd import binding
+    assert set(binding.EXPORTS) == set(names)
+
+
+def test_status_strings(L):
+    assert L.vlut_status_string(0) == b"VLUT_OK"
+    seen = {L.vlut_status_string(c) for c in range(-6, 1)}
+    assert len(seen) == 7 and all(s for s in seen)
+    assert L.vlut_status_string(-99).startswith(b"VLUT_ERR")
+
+
+def test_size_helpers(L, golden):
+    # 2.00 bits per weight when the shape needs no padding (Sec. 4: I2 = b2.00)
+    assert L.vlut_packed_weight_bytes(6912, 2560) == 6912 * 2560 // 4
+    assert L.vlut_packed_weight_bytes(256, 256) == 16384
+    # padding to 4 rows x 16 groups
+    assert L.vlut_packed_weight_bytes(257, 260) == 65 * 5 * 64
+    assert L.vlut_packed_weight_bytes(1, 4) == 64
+    for bad in [(0, 4), (4, 0), (4, 6), (-1, 8), (1 << 24, 4)]:
+        assert L.vlut_packed_weight_bytes(*bad) == 0
+    # the paper's full-table example (Sec. 1): 4096 x 14436 x 512 -> 285.5 MiB
+    K, N = int(golden["full_lut_K"][0]), int(golden["full_lut_N"][0])
+    assert round(L.vlut_lut_bytes(K, N) / 2 ** 20, 1) == float(golden["full_lut_mib"][0])
+    assert L.vlut_lut_bytes(256, 8) == 64 * 81 * 8 * 2
+    assert L.vlut_lut_bytes(6, 8) == 0 and L.vlut_lut_bytes(8, 0) == 0
+    assert L.vlut_workspace_bytes(0, 8, 8) == 0
+
+
+def test_packed_offset_is_a_bijection(L):
+    M, K = 10, 136            # 3 row tiles (padded), 34 groups -> 3 k-tiles (padded)
+    total = L.vlut_packed_weight_bytes(M, K)
+    assert total == 3 * 3 * 64
+    offs = {L.vlut_packed_offset(M, K, m, kg) for m in range(M) for kg in range(K // 4)}
+    assert len(offs) == M * (K // 4) and max(offs) < total
+    # tile structure: 4 rows x 16 groups contiguous, a row's 16 groups are 16 consecutive bytes
+    assert L.vlut_packed_offset(M, K, 0, 1) - L.vlut_packed_offset(M, K, 0, 0) == 1
+    assert L.vlut_packed_offset(M, K, 1, 0) - L.vlut_packed_offset(M, K, 0, 0) == 16
+    assert L.vlut_packed_offset(M, K, 0, 16) - L.vlut_packed_offset(M, K, 0, 0) == 64
+    assert L.vlut_packed_offset(M, K, 4, 0) - L.vlut_packed_offset(M, K, 0, 0) == 3 * 64
+    for bad in [(M, 0), (-1, 0), (0, 34), (0, -1)]:
+        assert L.vlut_packed_offset(M, K, *bad) == ctypes.c_size_t(-1).value
+
+
+def test_argument_errors_come_before_any_device_call(L):
+    d = 0x1000  # a fake non-null "device pointer": never dereferenced on these paths
+    assert L.vlut_pack_weights(None, 8, 8, d, 64, None) == -1
+    assert L.vlut_pack_weights(d, 8, 8, None, 64, None) == -1
+    assert L.vlut_pack_weights(d, 8, 6, d, 64, None) == -2
+    assert L.vlut_pack_weights(d, 0, 8, d, 64, None) == -2
+    assert L.vlut_pack_weights(d, 8, 8, d, 63, None) == -3
+    assert L.vlut_quantize_act(None, 4, 8, 8, d, d, None) == -1
+    assert L.vlut_quantize_act(d, 4, 8, 8, None, d, None) == -1
+    assert L.vlut_quantize_act(d, 4, 8, 8, d, None, None) == -1
+    assert L.vlut_quantize_act(d, 4, 8, 7, d, d, None) == -2      # ldx < K
+    assert L.vlut_quantize_act(d, 0, 8, 8, d, d, None) == -2
+    assert L.vlut_quantize_act(d, 4, 10, 10, d, d, None) == -2    # K % 4 != 0
+    assert L.vlut_build_lut(None, 8, 4, d, 1 << 20, None) == -1
+    assert L.vlut_build_lut(d, 8, 4, None, 1 << 20, None) == -1
+    assert L.vlut_build_lut(d, 8, 4, d, 2 * 81 * 4 * 2 - 1, None) == -3
+    assert L.vlut_build_lut(d, 9, 4, d, 1 << 20, None) == -2
+    for fn in (L.vlut_mpgemm, L.vlut_mpgemm_mfma):
+        assert fn(None, 1.0, d, d, None, 8, 8, 4, d, 8, None, None, 0, None) == -1
+        assert fn(d, 1.0, None, d, None, 8, 8, 4, d, 8, None, None, 0, None) == -1
+        assert fn(d, 1.0, d, None, None, 8, 8, 4, d, 8, None, None, 0, None) == -1
+        assert fn(d, 1.0, d, d, None, 8, 8, 4, None, 8, None, None, 0, None) == -1   # neither y nor acc
+        assert fn(d, 1.0, d, d, None, 8, 8, 4, d, 7, None, None, 0, None) == -2      # ldy < M
+        assert fn(d, 1.0, d, d, None, 8, 7, 4, d, 8, None, None, 0, None) == -2
+        assert fn(d, 1.0, d, d, None, 8, 8, 0, d, 8, None, None, 0, None) == -2
+    assert L.vlut_set_plan(3, 0, 0, 0) == -6 and L.vlut_set_plan(0, 9, 0, 0) == -6
+    assert L.vlut_set_plan(0, 0, 7, 0) == -6 and L.vlut_set_plan(0, 0, 0, 99) == -6
+    assert L.vlut_set_plan(0, 0, 0, 0) == 0
+    assert L.vlut_query_plan(8, 8, 8, None) == -1
+
+
+def test_split_k_needs_a_workspace(L):
+    d = 0x1000
+    assert L.vlut_set_plan(16, 1, 0, 2) == 0
+    try:
+        M, K, N = 8, 512, 8
+        need = L.vlut_workspace_bytes(M, K, N)
+        assert need == 2 * M * N * 4
+        assert L.vlut_mpgemm(d, 1.0, d, d, None, M, K, N, d, M, None, None, 0, None) == -1
+        assert L.vlut_mpgemm(d, 1.0, d, d, None, M, K, N, d, M, None, d, need - 1, None) == -3
+    finally:
+        assert L.vlut_set_plan(0, 0, 0, 0) == 0
+
+
+def test_plans_cover_all_benchmark_shapes(L):
+    out = (ci * 4)()
+    shapes = [(256, 256, 8), (6912, 2560, 128), (8640, 3200, 256), (3200, 8640, 256), (4096, 4096, 512),
+              (14336, 4096, 512), (4096, 14336, 512)]
+    shapes += [(m, k, n) for (m, k) in [(2560, 2560), (640, 2560), (6912, 2560), (2560, 6912)]
+               for n in (1, 16, 64, 256, 1024)]
+    for (M, K, N) in shapes:
+        assert L.vlut_query_plan(M, K, N, out) == 0
+        J, R, S, tiles = list(out)
+        assert J in (1, 2, 4, 8, 16) and 1 <= R <= 16 and 1 <= S <= 16 and tiles >= 1
+        n_tile = 128 // J
+        tiles_n = -(-N // n_tile)
+        assert tiles % (tiles_n * S) == 0
+        tiles_m = tiles // (tiles_n * S)
+        assert tiles_m * 64 * R >= M                                   # every row is covered

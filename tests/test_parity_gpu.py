@@ -1,0 +1,242 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI (via the thin binding).
+
+Bar: bit-exact for the packed bytes, the INT8 codes, the fp32 activation scales, the INT16 table and
+the INT32 accumulators; |y_gpu - y_ref| <= 1e-5 * |y_ref| elementwise for the fp32 output (y_ref is the
+oracle's fp64 value; exact zeros must be exact).
+"""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import oracle as O
+from paper_2512_06443_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def B(vlut_lib_path):
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2512_06443_amd import binding
+    binding.lib()
+    yield binding
+    binding.set_plan(0, 0, 0, 0)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def check_y(y_gpu, y_ref):
+    y_gpu = y_gpu.astype(np.float64)
+    err = np.abs(y_gpu - y_ref)
+    assert np.all(err <= RTOL * np.abs(y_ref)), f"max rel err {np.max(err / np.maximum(np.abs(y_ref), 1e-300))}"
+    assert np.all(y_gpu[y_ref == 0.0] == 0.0)
+
+
+def run_case(B, W, w_scale, x, plan=None, use_lut=False, tag=""):
+    print(f"case {tag} M={W.shape[0]} K={W.shape[1]} N={x.shape[0]} plan={plan} lut={use_lut}", flush=True)
+    M, K = W.shape
+    q_ref, s_ref, acc_ref, y_ref = O.mpgemm(W, w_scale, x)
+    B.set_plan(*(plan or (0, 0, 0, 0)))
+    try:
+        packed = B.pack_weights(dev(W))
+        a_q, a_s = B.quantize_act(dev(x))
+        assert np.array_equal(a_q.cpu().numpy(), q_ref)
+        assert np.array_equal(a_s.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
+        lut = B.build_lut(a_q) if use_lut else None
+        y, acc = B.mpgemm(packed, float(w_scale), a_q, a_s, M, lut=lut, want_acc=True)
+        torch.cuda.synchronize()
+    finally:
+        B.set_plan(0, 0, 0, 0)
+    assert np.array_equal(acc.cpu().numpy(), acc_ref), "int32 accumulators differ"
+    check_y(y.cpu().numpy(), y_ref)
+
+
+# ------------------------------------------------------------------ single steps
+def test_pack_bytes_match_oracle_and_padding(B):
+    for (M, K) in [(256, 256), (10, 136), (257, 260), (4, 64)]:
+        W = wl.ternary(M + K, M, K, 0.4)
+        packed = B.pack_weights(dev(W)).cpu().numpy()
+        idx = O.pack_indices(W)
+        assert packed.size == B.packed_weight_bytes(M, K) and packed.max() < 81
+        offs = np.array([[B.packed_offset(M, K, m, kg) for kg in range(K // 4)] for m in range(M)])
+        assert np.array_equal(packed[offs], idx)
+        pad = np.ones(packed.size, bool)
+        pad[offs.ravel()] = False
+        assert np.all(packed[pad] == 40)                    # padding is the all-zero pattern
+    with pytest.raises(B.VlutError) as e:
+        bad = wl.ternary(1, 8, 64, 0.4)
+        bad[3, 17] = 2
+        B.pack_weights(dev(bad))
+    assert e.value.status == B.VLUT_ERR_VALUE
+    B.pack_weights(dev(wl.ternary(1, 8, 64, 0.4)))          # the error flag does not stick
+
+
+def test_quantize_bit_exact(B):
+    cases = [wl.activations(0, 8, 256), wl.activations(1, 37, 100, 0.05), wl.activations(2, 130, 2560),
+             wl.activations(3, 1, 64), wl.activations(4, 300, 512, 0.01), wl.activations(5, 1030, 128)]
+    z = wl.activations(6, 5, 64)
+    z[2] = 0.0                                              # a zero token
+    z[3, :] = 3.25                                          # all-equal token
+    z[4, 0], z[4, 1], z[4, 2], z[4, 3] = 127.0, 0.5, 1.5, 2.5   # ties at inv == 1
+    cases.append(z)
+    for x in cases:
+        q_ref, s_ref = O.quantize(x)
+        a_q, a_s = B.quantize_act(dev(x))
+        assert np.array_equal(a_q.cpu().numpy(), q_ref)
+        assert np.array_equal(a_s.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
+    # row stride larger than K
+    big = np.full((37, 128), 1e9, np.float32)
+    big[:, :100] = cases[1]
+    xb = dev(big)[:, :100]
+    a_q, a_s = B.quantize_act(xb)
+    q_ref, s_ref = O.quantize(cases[1])
+    assert np.array_equal(a_q.cpu().numpy(), q_ref) and np.array_equal(a_s.cpu().numpy(), s_ref)
+
+
+def test_build_lut_matches_alg1(B, golden):
+    for (K, N) in [(256, 8), (64, 33), (132, 130)]:
+        q, _ = O.quantize(wl.activations(K + N, N, K))
+        T = B.build_lut(dev(q)).cpu().numpy()
+        assert np.array_equal(T, O.build_lut(q))
+        i = int(golden["example_index"][0])                 # the paper's worked example row
+        a = q[:4].astype(np.int64)
+        assert np.array_equal(T[0, i].astype(np.int64), -a[0] + a[1] + a[3])
+
+
+# ------------------------------------------------------------------ whole path
+def test_config_tiny(B):
+    w = wl.WORKLOADS["tiny"]
+    W, s, x = wl.make_case(w, w.linears[0], 8, 0)
+    run_case(B, W, s, x, tag="tiny")
+
+
+@pytest.mark.parametrize("J", [1, 2, 4, 8, 16])
+def test_every_interleave_factor(B, J):
+    W, s, x = wl.small_case(11, 257, 260, 130)              # ragged in M, K (not a multiple of 64) and N
+    run_case(B, W, s, x, plan=(J, 2, 0, 1), tag=f"J{J}")
+    W, s, x = wl.small_case(12, 70, 1024, 7)
+    run_case(B, W, s, x, plan=(J, 1, 0, 1), tag=f"J{J}-n7")
+
+
+@pytest.mark.parametrize("R", [1, 2, 3, 4, 5, 6, 7, 8, 10, 12])
+def test_every_rows_per_wave(B, R):
+    M = 64 * R * 2 - 37                                     # two row tiles, the second one ragged
+    W, s, x = wl.small_case(20 + R, M, 512, 33)
+    run_case(B, W, s, x, plan=(8, R, 0, 1), tag=f"R{R}")
+
+
+@pytest.mark.parametrize("J,R,S", [(1, 2, 1), (1, 6, 1), (2, 3, 1), (4, 5, 2), (16, 4, 3), (8, 2, 6)])
+def test_int32_widening_and_split_k(B, J, R, S):
+    # K = 4352 -> 1088 groups: more than 64 lookups per lane for small J, so the INT16 blocks get widened
+    W, s, x = wl.small_case(30 + J + S, 300, 4352, 40)
+    run_case(B, W, s, x, plan=(J, R, 0, S), tag=f"widen J{J} R{R} S{S}")
+
+
+def test_int16_block_is_overflow_free_at_the_extremes(B):
+    # all |q| = 127 and all weights equal: every 64-lookup block reaches +-32512 (Sec. 3.4 bound B = 64)
+    M, K, N = 64, 2048, 16
+    x = np.full((N, K), 5.0, np.float32)
+    x[1::2] = -5.0
+    for sign in (1, -1):
+        W = np.full((M, K), sign, np.int8)
+        for plan in [(1, 1, 0, 1), (16, 1, 0, 1), (4, 2, 0, 2)]:
+            run_case(B, W, np.float32(0.5), x, plan=plan, tag=f"extreme {sign}")
+    q, _ = O.quantize(x)
+    assert np.all(np.abs(q) == 127)
+
+
+def test_special_weights(B):
+    K, N = 256, 24
+    x = wl.activations(40, N, K)
+    run_case(B, np.zeros((33, K), np.int8), np.float32(1.0), x, tag="zero W")
+    run_case(B, np.eye(K, dtype=np.int8), np.float32(1.0), x, tag="identity")
+    run_case(B, -np.eye(K, dtype=np.int8), np.float32(2.0), x, tag="-identity")
+    xz = x.copy()
+    xz[5] = 0.0
+    W, s, _ = wl.small_case(41, 100, K, N)
+    run_case(B, W, s, xz, tag="zero token")
+
+
+def test_gemv_and_other_n(B):
+    for N in (1, 2, 15, 16, 17, 64):
+        W, s, x = wl.small_case(50 + N, 640, 2560, N)
+        run_case(B, W, s, x, tag=f"N{N}")
+
+
+def test_unstreamed_table_variant(B):
+    for (M, K, N, plan) in [(257, 260, 130, (2, 2, 0, 1)), (128, 512, 64, (0, 0, 0, 0)), (70, 4352, 9, (1, 1, 0, 1))]:
+        W, s, x = wl.small_case(60 + N, M, K, N)
+        run_case(B, W, s, x, plan=plan, use_lut=True, tag="unstreamed")
+
+
+def test_outlier_channels(B):
+    W = wl.ternary(70, 512, 1024, 0.35)
+    x = wl.activations(70, 48, 1024, outlier_frac=0.01)
+    run_case(B, W, wl.latent_weight_scale(70, 512, 1024), x, tag="outliers")
+
+
+def test_acc_only_and_ldy(B):
+    W, s, x = wl.small_case(80, 100, 256, 12)
+    q_ref, s_ref, acc_ref, y_ref = O.mpgemm(W, s, x)
+    packed = B.pack_weights(dev(W))
+    a_q, a_s = B.quantize_act(dev(x))
+    ybig = torch.full((12, 128), -7.0, device="cuda")
+    B.mpgemm(packed, float(s), a_q, a_s, 100, y=ybig[:, :100])
+    yb = ybig.cpu().numpy()
+    check_y(yb[:, :100], y_ref)
+    assert np.all(yb[:, 100:] == -7.0)                      # nothing written past M
+
+
+def test_run_to_run_determinism(B):
+    w = wl.WORKLOADS["bitnet2b_ffn_up"]
+    W, s, x = wl.small_case(90, 1000, 2560, 128)
+    packed = B.pack_weights(dev(W))
+    a_q, a_s = B.quantize_act(dev(x))
+    y1, acc1 = B.mpgemm(packed, float(s), a_q, a_s, 1000, want_acc=True)
+    y2, acc2 = B.mpgemm(packed, float(s), a_q, a_s, 1000, want_acc=True)
+    assert torch.equal(acc1, acc2) and torch.equal(y1.view(torch.int32), y2.view(torch.int32))
+
+
+# ------------------------------------------------------------------ full sizes, in the bench's launch configuration
+def _full_size(B, M, K, N, p_zero, outlier, seed, n_rows=96):
+    print(f"full size M={M} K={K} N={N}", flush=True)
+    W = wl.ternary(seed, M, K, p_zero)
+    w_scale = wl.latent_weight_scale(seed, M, K)
+    x = wl.activations(seed, N, K, outlier)
+    packed = B.pack_weights(dev(W))
+    a_q, a_s = B.quantize_act(dev(x))
+    q_ref, s_ref = O.quantize(x)
+    assert np.array_equal(a_q.cpu().numpy(), q_ref)
+    assert np.array_equal(a_s.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
+    y, acc = B.mpgemm(packed, float(w_scale), a_q, a_s, M, want_acc=True)   # automatic plan = the bench's plan
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([rng.integers(0, M, n_rows), [0, 1, 2, 3, M - 1, M - 2, M // 2]]))
+    acc_ref = O.gemm_acc(W[rows], q_ref)                    # the oracle, row by row, on sampled rows
+    assert np.array_equal(acc.cpu().numpy()[rows], acc_ref)
+    check_y(y.cpu().numpy()[:, rows], O.epilogue(acc_ref, w_scale, s_ref))
+    # property that holds at any size: column sums of acc equal (sum of W rows) . q
+    colsum = W.astype(np.int64).sum(0) @ q_ref.astype(np.int64)
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64).sum(0), colsum)
+
+
+def test_full_size_bitnet2b_ffn_up(B):
+    _full_size(B, 6912, 2560, 128, 0.4, 0.0, 0)
+
+
+def test_full_size_3b_and_8b_shapes(B):
+    _full_size(B, 8640, 3200, 256, 0.4, 0.0, 0)
+    _full_size(B, 3200, 8640, 256, 0.4, 0.0, 0)
+    _full_size(B, 4096, 14336, 512, 0.35, 0.01, 0, n_rows=48)
+
+
+def test_layer_n_sweep(B):
+    for seed, N in zip(range(5), (1, 16, 64, 256, 1024)):
+        for (M, K) in [(640, 2560), (2560, 6912)]:
+            _full_size(B, M, K, N, 0.4, 0.0, seed, n_rows=32)
