@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the vector-LUT ternary x INT8 mpGeMM hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input that is already
+resident in HBM: vlut_quantize_act (fp32 [N][K] -> INT8 [K][N] + scales) followed by vlut_mpgemm
+(streamed LDS table build + lookup-accumulate + scale epilogue).  Weight packing is the paper's
+offline stage and is not timed.  The packed weights rotate through a pool larger than the last-level
+cache, so every step streams its weights from HBM.
+
+Prints ONE JSON line on stdout.  `python bench.py --all` additionally writes a per-shape table for
+every benchmark shape to stderr (tuning aid; not part of the contract).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X published peaks used for the roofline fractions
+HBM_PEAK_GBS = 8000.0
+CUS, CLOCK_GHZ = 256, 2.4
+# packed INT16 adds: 64 lanes x 2 per CU per clock; table reads: 256 B per CU per clock (2 B per add)
+ALU_PEAK_TADDS = CUS * 64 * 2 * CLOCK_GHZ / 1e3          # 78.64 T INT16 adds/s
+LDS_PEAK_GBS = CUS * 256 * CLOCK_GHZ                      # 157286 GB/s
+
+# HBM bytes per launch of the lookup kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), see profiles/
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="bitnet2b_ffn_up")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-rotate", action="store_true", help="keep one weight buffer (cache-warm weights)")
+    ap.add_argument("--all", action="store_true", help="also time every benchmark shape (table on stderr)")
+    ap.add_argument("--plan", default="", help="force J,R,S for the lookup kernel (tuning)")
+    return ap.parse_args()
+
+
+class Case:
+    """Device-resident tensors of one linear layer at one N, with the C-ABI calls pre-marshalled."""
+
+    def __init__(self, B, torch, wl, W, w_scale, x, rotate_bytes):
+        self.M, self.K = W.shape
+        self.N = x.shape[0]
+        self.w_scale = float(w_scale)
+        packed = B.pack_weights(torch.from_numpy(W).cuda())
+        n_pool = 1 if rotate_bytes <= 0 else max(1, min(256, -(-rotate_bytes // packed.numel())))
+        self.pool = [packed] + [packed.clone() for _ in range(n_pool - 1)]
+        self.x = torch.from_numpy(x).cuda()
+        self.a_q = torch.empty((self.K, self.N), dtype=torch.int8, device="cuda")
+        self.a_s = torch.empty(self.N, dtype=torch.float32, device="cuda")
+        self.y = torch.empty((self.N, self.M), dtype=torch.float32, device="cuda")
+        ws = B.workspace_bytes(self.M, self.K, self.N)
+        self.ws = torch.empty(max(ws, 16), dtype=torch.uint8, device="cuda")
+        self.plan = B.query_plan(self.M, self.K, self.N)
+        L = B.lib()
+        self._check = B._check
+        self._quant = L.vlut_quantize_act
+        self._gemm = L.vlut_mpgemm
+        self._qargs = (self.x.data_ptr(), self.N, self.K, self.x.stride(0), self.a_q.data_ptr(), self.a_s.data_ptr())
+        self._gargs = [(pk.data_ptr(), self.w_scale, self.a_q.data_ptr(), self.a_s.data_ptr(), None, self.M, self.K,
+                        self.N, self.y.data_ptr(), self.y.stride(0), None, self.ws.data_ptr(), self.ws.numel())
+                       for pk in self.pool]
+
+    def quantize(self, stream):
+        self._check(self._quant(*self._qargs, stream), "vlut_quantize_act")
+
+    def gemm(self, i, stream):
+        self._check(self._gemm(*self._gargs[i % len(self._gargs)], stream), "vlut_mpgemm")
+
+    def step(self, i, stream):
+        self.quantize(stream)
+        self.gemm(i, stream)
+
+
+def run_timed(torch, fn, count, warmup):
+    """Times `count` calls of fn(i, stream) that are enqueued back to back.
+
+    The calls are captured once into a HIP graph (so the host's launch cost is not part of the GPU timeline) and the
+    graph is replayed inside the timed region; if capture is not possible the calls are enqueued directly.
+    Returns (wall ms per call with a device synchronize on both sides, GPU ms per call from HIP events on the
+    launch stream, launch mode)."""
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        for i in range(warmup):
+            fn(i, side.cuda_stream)
+    side.synchronize()
+    graph = None
+    try:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for i in range(count):
+                fn(i, torch.cuda.current_stream().cuda_stream)
+        graph = g
+    except Exception as e:  # noqa: BLE001 - fall back to plain stream launches
+        print(f"bench.py: graph capture unavailable ({type(e).__name__}: {e}); timing stream launches", file=sys.stderr)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(side):
+        if graph is not None:
+            graph.replay()          # untimed replay: first-use costs of the graph itself
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record(side)
+        if graph is not None:
+            graph.replay()
+        else:
+            for i in range(count):
+                fn(i, side.cuda_stream)
+        e1.record(side)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / count, e0.elapsed_time(e1) / count, ("hipGraph" if graph is not None else "stream")
+
+
+def time_case(B, torch, case, steps, warmup):
+    """(wall ms per whole step, GPU ms per mpgemm launch, launch mode).  The second figure comes from a timed region
+    that holds only the vlut_mpgemm launches (HIP events on their stream), after quantising once."""
+    ms_step, _, mode = run_timed(torch, case.step, steps, warmup)
+    _, ms_gemm, _ = run_timed(torch, case.gemm, steps, warmup)
+    return ms_step, ms_gemm, mode
+
+
+def cpu_baseline(wl, W, w_scale, x):
+    """The oracle as it stands on the host cores, on the same workload (one full pass, repeated to ~10 s)."""
+    from oracle import oracle as O
+    O.mpgemm(W[:64], w_scale, x)  # build + page in
+    M, K = W.shape
+    N = x.shape[0]
+    t_total, reps = 0.0, 0
+    while t_total < 10.0 and reps < 20:
+        t0 = time.perf_counter()
+        O.mpgemm(W, w_scale, x)
+        t_total += time.perf_counter() - t0
+        reps += 1
+    sec = t_total / reps
+    return {"value": 2.0 * M * K * N / sec / 1e9, "unit": "GOPS", "cores": O.num_threads(), "kind": "oracle",
+            "sample": f"whole workload (quantise + triple-loop GEMM + scale), {reps} passes, {sec * 1e3:.0f} ms each"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (the path shards over tokens with no exchange; "
+              "see DESIGN.md). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2512_06443_amd import binding as B
+    from paper_2512_06443_amd import workloads as wl
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    B.lib()  # fails loudly if libvlut.so is missing
+    if args.plan:
+        j, r, s = (int(v) for v in args.plan.split(","))
+        B.set_plan(j, r, 0, s)
+
+    w = wl.WORKLOADS[args.workload]
+    lin, N, seed = w.linears[0], w.N[0], w.seeds[0]
+    W, w_scale, x = wl.make_case(w, lin, N, seed)
+    M, K = W.shape
+    rotate = 0 if args.no_rotate else 600 << 20
+    case = Case(B, torch, wl, W, w_scale, x, rotate)
+    y_ref = torch.empty_like(case.y)
+    case.step(0, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    y_ref.copy_(case.y)
+    ms_step, ms_kernel, mode = time_case(B, torch, case, args.steps, args.warmup)
+    if not torch.equal(y_ref, case.y):   # every pool buffer holds the same weights, so every step writes the same y
+        print("bench.py: output of the timed region differs from the reference launch", file=sys.stderr)
+        sys.exit(4)
+
+    ops = 2.0 * M * K * N
+    adds = M * (K // 4) * N                      # one INT16 add (= 2 table bytes) per (row, group, token)
+    gops = ops / (ms_step * 1e-3) / 1e9
+    achieved_tadds = adds / (ms_kernel * 1e-3) / 1e12
+    out = {
+        "metric": "ternary mpGeMM GOPS (2*M*K*N) + weight-stream GB/s",
+        "value": gops, "unit": "GOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int16/int32 (INT8 activations, ternary weights)", "data": "synthetic",
+        "config": {"workload": f"{w.name}: M={M} K={K} N={N}, ternary P(0)={w.p_zero}, INT8 per-token absmax "
+                               f"activations from N(0,1); step = quantize_act + mpgemm",
+                   "plan": {"J": case.plan[0], "R": case.plan[1], "split_k": case.plan[2], "workgroups": case.plan[3]},
+                   "weight_pool_buffers": len(case.pool), "launch": mode},
+        "weight_stream_GBs": (M * K / 4) / (ms_step * 1e-3) / 1e9,
+        "algorithmic_GBs": wl.algorithmic_bytes(M, K, N) / (ms_step * 1e-3) / 1e9,
+        "roofline": {
+            "kernel": "lookup_kernel (fused LDS table build + lookup-accumulate + epilogue)",
+            "bound": "alu", "achieved": achieved_tadds, "peak": ALU_PEAK_TADDS, "unit": "TOP/s",
+            "frac": achieved_tadds / ALU_PEAK_TADDS,
+            "kernel_ms": ms_kernel,
+            "lds_lookup_GBs": 2.0 * adds / (ms_kernel * 1e-3) / 1e9, "lds_peak_GBs": LDS_PEAK_GBS,
+            "lds_frac": 2.0 * adds / (ms_kernel * 1e-3) / 1e9 / LDS_PEAK_GBS,
+            "hbm_frac": wl.algorithmic_bytes(M, K, N) / (ms_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, W, w_scale, x)
+
+    if args.all:
+        rows = []
+        for name, wk in wl.WORKLOADS.items():
+            for linr in wk.linears:
+                for n in wk.N:
+                    Wm, ws_, xm = wl.make_case(wk, linr, n, wk.seeds[0])
+                    c = Case(B, torch, wl, Wm, ws_, xm, rotate)
+                    st, km, _ = time_case(B, torch, c, max(20, args.steps // 4), 5)
+                    mm, kk = Wm.shape
+                    a = mm * (kk // 4) * n
+                    rows.append((name, linr.name, mm, kk, n, c.plan, st * 1e3, km * 1e3,
+                                 2.0 * mm * kk * n / (st * 1e-3) / 1e12, a / (km * 1e-3) / 1e12 / ALU_PEAK_TADDS,
+                                 wl.algorithmic_bytes(mm, kk, n) / (km * 1e-3) / 1e9 / HBM_PEAK_GBS))
+                    del c
+                    torch.cuda.empty_cache()
+        print(f"{'workload':18s} {'lin':7s} {'M':>6s} {'K':>6s} {'N':>5s} {'plan(J,R,S,WG)':>18s} {'step us':>9s} "
+              f"{'mpgemm us':>9s} {'TOPS':>7s} {'alu/lds frac':>12s} {'hbm frac':>8s}", file=sys.stderr)
+        for r in rows:
+            print(f"{r[0]:18s} {r[1]:7s} {r[2]:6d} {r[3]:6d} {r[4]:5d} {str(r[5]):>18s} {r[6]:9.1f} {r[7]:9.1f} "
+                  f"{r[8]:7.1f} {r[9]:12.3f} {r[10]:8.3f}", file=sys.stderr)
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

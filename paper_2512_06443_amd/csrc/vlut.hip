@@ -35,7 +35,8 @@ constexpr int kRows = 81;                    // 3^4 rows per sub-table
 constexpr int kRowBytes = 256;               // LDS bytes per table row (16 slices x 16 B)
 constexpr int kSlotBytes = kRows * kRowBytes;  // 20736
 constexpr int kStageSlots = 4;               // slots resident per stage (one weight dword = 4 lookups)
-constexpr int kLdsBytes = kStageSlots * kSlotBytes;  // 82944
+constexpr int kTableBytes = kStageSlots * kSlotBytes;  // 82944
+constexpr int kLdsBytes = kTableBytes + 128 * 4;    // + the output scales of the tile's tokens
 constexpr int kWaves = 16;                   // waves per workgroup
 constexpr int kThreads = kWaves * 64;
 constexpr int kBuilders = kStageSlots * 9 * 16;  // 576 build tasks per stage
@@ -75,6 +76,13 @@ __device__ __forceinline__ i32x4 lds_read128(unsigned addr) {
 template <int OFF16>
 __device__ __forceinline__ void lds_write128(unsigned addr, i32x4 v) {
     ((lds_i32x4*)addr)[OFF16] = v;
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global load
+// and store of the wave (vmcnt(0)), which would expose the latency of the weight and activation prefetches at
+// every stage; here a wave only has to finish its own LDS reads/writes before it signals the barrier.
+__device__ __forceinline__ void wg_barrier_lds() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 __device__ __forceinline__ s16x2 as_s16x2(int v) { return __builtin_bit_cast(s16x2, v); }
@@ -258,13 +266,12 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     // Row group r of this wave: its packed tiles start at a wave-uniform address (scalar registers); the lane
     // adds its row (grp) and, per stage, the tile and dword it needs.
     const unsigned char* wbase[R];
-    bool wvalid[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        int rgl = r * kWaves + wave;     // r-major: round r of the epilogue covers 64 consecutive rows
-        int rg = rgw0 + rgl;
-        wvalid[r] = (rgl < p.RGW) && (rg < p.RGtotal);
-        wbase[r] = p.packed + ((size_t)(wvalid[r] ? rg : 0) * p.KCn) * 64;
+        const int rgl = r * kWaves + wave;     // r-major: round r of the epilogue covers 64 consecutive rows
+        const int rg = rgw0 + rgl;
+        const bool valid = (rgl < p.RGW) && (rg < p.RGtotal);
+        wbase[r] = p.packed + ((size_t)(valid ? rg : 0) * p.KCn) * 64;
     }
 
     // ---- build role (threads 0..575): slot bb, slice lb, digit pair hh = 3*d0 + d1
@@ -277,21 +284,28 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     const int tb = lb & ((1 << TClog) - 1);
     const int nb = n0 + 8 * tb;          // first token of the builder's slice
     unsigned act[4][2];
+    bool act_valid = false;
 
+    // Loads for the NEXT stage's tables.  The fast path is branch-free (addresses clamped into the tensor, validity
+    // applied when the values are used) so that nothing has to wait for the data before the next build phase.
     auto prefetch_act = [&](int st) {
-        int kg = st * 4 * J + 4 * jb + bb;
+        const int kg = st * 4 * J + 4 * jb + bb;
+        act_valid = (kg < p.G) && (nb < p.N);
+        if (p.aligned8) {
+            const int kgc = min(kg, p.G - 1);
+            const int nbc = (nb < p.N) ? nb : 0;
+            const int8_t* src = p.a_q + (size_t)(4 * kgc) * p.N + nbc;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
-        if (kg < p.G && nb < p.N) {
-            const int8_t* src = p.a_q + (size_t)(4 * kg) * p.N + nb;
-            if (p.aligned8 && nb + 8 <= p.N) {
+            for (int c = 0; c < 4; ++c) {
+                const i32x2 v = *(const i32x2*)(src + (size_t)c * p.N);
+                act[c][0] = (unsigned)v.x;
+                act[c][1] = (unsigned)v.y;
+            }
+        } else {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    i32x2 v = *(const i32x2*)(src + (size_t)c * p.N);
-                    act[c][0] = (unsigned)v.x;
-                    act[c][1] = (unsigned)v.y;
-                }
-            } else {
+            for (int c = 0; c < 4; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
+            if (act_valid) {
+                const int8_t* src = p.a_q + (size_t)(4 * kg) * p.N + nb;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
 #pragma unroll
@@ -317,20 +331,27 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
             for (int e = 0; e < 8; ++e) acc32[r][e] = 0;
     }
 
+    // Output scale of every token of the tile, parked behind the tables (read in the epilogue).
+    typedef __attribute__((address_space(3))) float lds_f32;
+    lds_f32* scale_lds = (lds_f32*)(unsigned)kTableBytes;
+    if (tid < n_tile) scale_lds[tid] = (n0 + tid < p.N) ? p.w_scale * p.a_scale[n0 + tid] : 0.0f;
+
     if (builder && !FROM_GLOBAL && st_begin < st_end) prefetch_act(st_begin);
 
-    for (int st = st_begin; st < st_end; ++st) {
-        // weight dwords of this stage: dword q = st*J + j of each row (4 lookups)
-        unsigned w[R];
-        {
-            const int q = st * J + j;
-            const int kc = q >> 2;
-            const bool kvalid = kc < p.KCn;
-            const unsigned voff = (unsigned)(kc * 64 + grp * 16 + (q & 3) * 4);
+    // Weight dwords (4 lookups each) are fetched one whole stage ahead into the buffer the next stage reads, so
+    // their HBM latency hides behind a full build + lookup phase.  Dword q = st*J + j of each row.
+    // Out-of-range cases need no masking: a tile index past the end of K is clamped to the last tile and meets
+    // tables built from zero activations, and rows past M are clamped to row group 0 and never stored.
+    auto load_weights = [&](int st, unsigned (&wdst)[R]) {
+        const int q = st * J + j;
+        const int kc = min(q >> 2, p.KCn - 1);
+        const unsigned voff = (unsigned)(kc * 64 + grp * 16 + (q & 3) * 4);
 #pragma unroll
-            for (int r = 0; r < R; ++r)
-                w[r] = (kvalid && wvalid[r]) ? *(const unsigned*)(wbase[r] + voff) : kZeroIdx4;
-        }
+        for (int r = 0; r < R; ++r) wdst[r] = *(const unsigned*)(wbase[r] + voff);
+    };
+
+    auto stage = [&](int st, unsigned (&w)[R], unsigned (&wnext)[R]) {
+        load_weights(st + 1, wnext);
 
         // ---- fill the 4 slots of this stage
         if (builder) {
@@ -358,6 +379,10 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                 }
             } else {
                 // rows 9*hh .. 9*hh+8 of the sub-table: digits (d0,d1) fixed by hh, (d2,d3) enumerated.
+                if (!act_valid) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
+                }
                 const short s0 = (short)(hh / 3 - 1), s1 = (short)(hh % 3 - 1);
                 const s16x2 m0 = {s0, s0}, m1 = {s1, s1};
                 s16x2 a2[4], a3[4], base[4];
@@ -394,7 +419,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                 }
             }
         }
-        __syncthreads();
+        wg_barrier_lds();
         if (builder && !FROM_GLOBAL && st + 1 < st_end) prefetch_act(st + 1);
 
         // ---- 4 lookups per row group: byte b of the weight dword selects the row of slot b
@@ -405,7 +430,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
             lookup_add<2>(w[r], lanebase, acc16[r]);
             lookup_add<3>(w[r], lanebase, acc16[r]);
         }
-        __syncthreads();
+        wg_barrier_lds();
 
         if (NEED32 && (((st - st_begin) & 15) == 15)) {   // 16 stages x 4 lookups = block of 64
 #pragma unroll
@@ -417,55 +442,96 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                     acc16[r][q] = s16x2{0, 0};
                 }
         }
+    };
+
+    unsigned wa[R], wb[R];
+    load_weights(st_begin, wa);
+    for (int st = st_begin; st < st_end; st += 2) {
+        stage(st, wa, wb);
+        if (st + 1 < st_end) stage(st + 1, wb, wa);
     }
 
-    // ---- epilogue, one round per row group index r: every lane parks its partial sums in LDS
-    // ([64 rows][16 slices], row stride padded by 16 B), then the workgroup adds the J partial sums of
-    // each (row, token), applies the scales and writes 64 consecutive output rows per token.
-    constexpr int kEntry = NEED32 ? 4 : 2;                  // bytes per parked value
-    constexpr unsigned kStride = 128u * kEntry + 16u;       // bytes per parked row
+    // ---- epilogue.  Per row group: widen to INT32, add the J partial sums of each token across the 16 lanes of
+    // the group with a reduce-scatter (each step halves the tokens a lane keeps), park the sums in LDS as
+    // [token][row] and let the whole workgroup write 128 consecutive output rows per token.
+    constexpr int RC = R > 1 ? 2 : 1;                       // row-group rounds parked per chunk
+    constexpr int kParkStride = RC * 64 + 4;                // ints per parked token; +4 keeps the writes conflict-free
+    lds_i32* park = (lds_i32*)0u;
     const int m0 = rgw0 * 4;
     const int rows_wg = min(p.RGW * 4, p.M - m0);
     const int TC = 1 << TClog;
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const unsigned prow = (unsigned)(wave * 4 + grp) * kStride + (unsigned)l * (8u * kEntry);
-        if (NEED32) {
-            int v[8];
+    for (int c0 = 0; c0 < R; c0 += RC) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                v[2 * q] = acc32[r][2 * q] + (int)acc16[r][q].x;
-                v[2 * q + 1] = acc32[r][2 * q + 1] + (int)acc16[r][q].y;
-            }
-            lds_write128<0>(prow, i32x4{v[0], v[1], v[2], v[3]});
-            lds_write128<1>(prow, i32x4{v[4], v[5], v[6], v[7]});
-        } else {
-            lds_write128<0>(prow, i32x4{as_int(acc16[r][0]), as_int(acc16[r][1]), as_int(acc16[r][2]), as_int(acc16[r][3])});
-        }
-        __syncthreads();
-        for (int i = tid; i < 64 * n_tile; i += kThreads) {
-            const int ml = i & 63;
-            const int nl = i >> 6;
-            const int mrow = r * 64 + ml;                  // row inside the workgroup tile
-            const int n = n0 + nl;
-            if (mrow < rows_wg && n < p.N) {
-                const unsigned src = (unsigned)ml * kStride + (unsigned)((nl >> 3) * 8 * kEntry + (nl & 7) * kEntry);
-                int val = 0;
-                for (int jj = 0; jj < J; ++jj) {
-                    const unsigned a = src + (unsigned)(jj * TC) * (8u * kEntry);
-                    if (NEED32) val += *(const lds_i32*)a;
-                    else val += (int)*(const __attribute__((address_space(3))) short*)a;
+        for (int rr = 0; rr < RC; ++rr) {
+            const int r = c0 + rr;
+            if (r < R) {
+                int v[8];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    v[2 * q] = (int)acc16[r][q].x + (NEED32 ? acc32[r][2 * q] : 0);
+                    v[2 * q + 1] = (int)acc16[r][q].y + (NEED32 ? acc32[r][2 * q + 1] : 0);
                 }
+                int tokoff = 0;
+                bool owner = true;
+                if (Jlog > 0) {
+                    const int bit = j & 1;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int send = bit ? v[e] : v[e + 4];
+                        const int keep = bit ? v[e + 4] : v[e];
+                        v[e] = keep + __shfl_xor(send, TC);
+                    }
+                    tokoff += bit * 4;
+                }
+                if (Jlog > 1) {
+                    const int bit = (j >> 1) & 1;
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const int send = bit ? v[e] : v[e + 2];
+                        const int keep = bit ? v[e + 2] : v[e];
+                        v[e] = keep + __shfl_xor(send, TC << 1);
+                    }
+                    tokoff += bit * 2;
+                }
+                if (Jlog > 2) {
+                    const int bit = (j >> 2) & 1;
+                    const int send = bit ? v[0] : v[1];
+                    const int keep = bit ? v[1] : v[0];
+                    v[0] = keep + __shfl_xor(send, TC << 2);
+                    tokoff += bit;
+                }
+                if (Jlog > 3) {
+                    v[0] += __shfl_xor(v[0], 8);
+                    owner = ((j >> 3) & 1) == 0;
+                }
+                const int cnt = 8 >> min(Jlog, 3);
+                if (owner) {
+                    const int col = rr * 64 + wave * 4 + grp;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (e < cnt) park[(8 * t + tokoff + e) * kParkStride + col] = v[e];
+                }
+            }
+        }
+        wg_barrier_lds();
+        for (int i = tid; i < RC * 64 * n_tile; i += kThreads) {
+            const int col = i % (RC * 64);
+            const int nl = i / (RC * 64);
+            const int mrow = c0 * 64 + col;                 // row inside the workgroup tile
+            const int n = n0 + nl;
+            if (mrow < rows_wg && mrow < R * 64 && n < p.N) {
+                const int val = park[nl * kParkStride + col];
                 const int m = m0 + mrow;
                 if (p.S == 1) {
-                    if (p.y) p.y[(size_t)n * p.ldy + m] = (float)val * (p.w_scale * p.a_scale[n]);
+                    if (p.y) p.y[(size_t)n * p.ldy + m] = (float)val * scale_lds[nl];
                     if (p.acc) p.acc[(size_t)m * p.N + n] = val;
                 } else {
                     p.ws[((size_t)ks * p.N + n) * p.M + m] = val;
                 }
             }
         }
-        __syncthreads();
+        wg_barrier_lds();
     }
 }
 
@@ -550,12 +616,12 @@ double plan_cost(const Plan& pl, int64_t M, int64_t K, int64_t N) {
 bool plan_valid(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     if (pl.Jlog < 0 || pl.Jlog > 4 || !r_supported(pl.R) || pl.S < 1 || pl.S > 16) return false;
     Derived d = derive(pl, M, K, N);
-    if (d.need32 && pl.R > 6) return false;      // register budget of the INT32 variant
+    if (d.need32 && pl.R > 5) return false;      // register budget of the INT32 variant
     if (pl.S > d.stages_total) return false;
     return true;
 }
 
-Plan choose_plan(int64_t M, int64_t K, int64_t N) {
+Plan search_plan(int64_t M, int64_t K, int64_t N) {
     Plan best = {0, 4, 1};
     double best_cost = 1e300;
     const int Ss[] = {1, 2, 3, 4, 6, 8};
@@ -569,6 +635,25 @@ Plan choose_plan(int64_t M, int64_t K, int64_t N) {
                 if (c < best_cost) { best_cost = c; best = pl; }
             }
     return best;
+}
+
+// The search above costs microseconds of host time; a launch-bound caller repeats a handful of shapes, so the
+// last few answers are kept per thread (invalidated by vlut_set_plan).
+struct PlanCacheEntry {
+    int64_t M, K, N;
+    Plan plan;
+};
+thread_local PlanCacheEntry t_cache[8];
+thread_local int t_cache_used = 0, t_cache_next = 0;
+
+Plan choose_plan(int64_t M, int64_t K, int64_t N) {
+    for (int i = 0; i < t_cache_used; ++i)
+        if (t_cache[i].M == M && t_cache[i].K == K && t_cache[i].N == N) return t_cache[i].plan;
+    Plan pl = search_plan(M, K, N);
+    t_cache[t_cache_next] = {M, K, N, pl};
+    t_cache_next = (t_cache_next + 1) % 8;
+    if (t_cache_used < 8) ++t_cache_used;
+    return pl;
 }
 
 template <int R, bool NEED32, bool FROM_GLOBAL>
@@ -592,12 +677,12 @@ int launch_lookup_r(int R, const LookupParams& p, int grid, hipStream_t stream) 
     case 3: return launch_lookup_t<3, NEED32, FROM_GLOBAL>(p, grid, stream);
     case 4: return launch_lookup_t<4, NEED32, FROM_GLOBAL>(p, grid, stream);
     case 5: return launch_lookup_t<5, NEED32, FROM_GLOBAL>(p, grid, stream);
-    case 6: return launch_lookup_t<6, NEED32, FROM_GLOBAL>(p, grid, stream);
     default: break;
     }
     if (NEED32) return VLUT_ERR_UNSUPPORTED;
     if constexpr (!NEED32) {
         switch (R) {
+        case 6: return launch_lookup_t<6, false, FROM_GLOBAL>(p, grid, stream);
         case 7: return launch_lookup_t<7, false, FROM_GLOBAL>(p, grid, stream);
         case 8: return launch_lookup_t<8, false, FROM_GLOBAL>(p, grid, stream);
         case 10: return launch_lookup_t<10, false, FROM_GLOBAL>(p, grid, stream);
@@ -671,6 +756,8 @@ int vlut_set_plan(int J, int R, int waves, int split_k) {
     if (waves != 0 && waves != kWaves) return VLUT_ERR_UNSUPPORTED;
     if (split_k < 0 || split_k > 16) return VLUT_ERR_UNSUPPORTED;
     t_forced = {Jlog, R, split_k};
+    t_cache_used = 0;
+    t_cache_next = 0;
     return VLUT_OK;
 }
 

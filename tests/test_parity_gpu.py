@@ -131,7 +131,7 @@ def test_every_rows_per_wave(B, R):
     run_case(B, W, s, x, plan=(8, R, 0, 1), tag=f"R{R}")
 
 
-@pytest.mark.parametrize("J,R,S", [(1, 2, 1), (1, 6, 1), (2, 3, 1), (4, 5, 2), (16, 4, 3), (8, 2, 6)])
+@pytest.mark.parametrize("J,R,S", [(1, 2, 1), (1, 5, 1), (2, 3, 1), (4, 5, 2), (16, 4, 3), (8, 2, 6)])
 def test_int32_widening_and_split_k(B, J, R, S):
     # K = 4352 -> 1088 groups: more than 64 lookups per lane for small J, so the INT16 blocks get widened
     W, s, x = wl.small_case(30 + J + S, 300, 4352, 40)
