@@ -72,6 +72,14 @@ size_t vlut_packed_weight_bytes(int64_t M, int64_t K);
  */
 size_t vlut_packed_offset(int64_t M, int64_t K, int64_t m, int64_t kg);
 
+/*
+ * Bytes of the quantised activation buffer a_q for K x N activations: ceil(N/8) * K * 8.
+ * Layout (token-chunked, the GPU form of Sec. 3.3's token-contiguous activations): tokens are grouped in
+ * chunks of 8; a_q[(n/8)][k][n%8], i.e. for every k the 8 tokens of a chunk are 8 consecutive bytes and
+ * a chunk's [K][8] block is contiguous.  Tokens past N in the last chunk hold 0.  0 if the shape is invalid.
+ */
+size_t vlut_act_bytes(int64_t K, int64_t N);
+
 /* Bytes of the full vector table T for K x N activations: (K/4) * 81 * N * 2
  * (Sec. 1 quotes 285.5 MiB for K = 14436, N = 512).  0 if the shape is invalid. */
 size_t vlut_lut_bytes(int64_t K, int64_t N);
@@ -102,7 +110,8 @@ int vlut_pack_weights(const int8_t* w_ternary, int64_t M, int64_t K, uint8_t* pa
  *   a_q[k][n] = clamp(round_half_even(x[n][k] * inv), -127, 127).
  * -128 is never produced (the INT16 block bound of Sec. 3.4 relies on |q| <= 127).
  *   x        dev, fp32 [N][ldx], feature-contiguous, ldx >= K; finite values
- *   a_q      dev, int8 [K][N], token-contiguous
+ *   a_q      dev, int8, token-chunked [ceil(N/8)][K][8] (see vlut_act_bytes), 16-byte aligned; the
+ *            caller provides vlut_act_bytes(K, N) bytes; fully overwritten, padding tokens included
  *   a_scale  dev, fp32 [N]
  */
 int vlut_quantize_act(const float* x, int64_t N, int64_t K, int64_t ldx, int8_t* a_q,
@@ -111,7 +120,7 @@ int vlut_quantize_act(const float* x, int64_t N, int64_t K, int64_t ldx, int8_t*
 /*
  * Materialises the whole vector table in device memory (Alg. 1 function
  * Precompute, Eq. 1, built with the topological order of Sec. 4):
- *   lut[kg][i][n] = sum_{j<4} (digit_j(i) - 1) * a_q[4kg+j][n],
+ *   lut[kg][i][n] = sum_{j<4} (digit_j(i) - 1) * A[4kg+j][n],   A[k][n] = a_q[n/8][k][n%8],
  * digit_0 the most significant base-3 digit of i; int16, layout [K/4][81][N]
  * with N contiguous (Sec. 3.3 "Token-contiguous LUT layout").
  *   lut_bytes >= vlut_lut_bytes(K, N)

@@ -21,7 +21,8 @@ VLUT_ERR_NULL, VLUT_ERR_SHAPE, VLUT_ERR_SMALL_BUFFER = -1, -2, -3
 VLUT_ERR_VALUE, VLUT_ERR_DEVICE, VLUT_ERR_UNSUPPORTED = -4, -5, -6
 
 EXPORTS = [
-    "vlut_status_string", "vlut_version", "vlut_packed_weight_bytes", "vlut_packed_offset", "vlut_lut_bytes",
+    "vlut_status_string", "vlut_version", "vlut_packed_weight_bytes", "vlut_packed_offset", "vlut_act_bytes",
+    "vlut_lut_bytes",
     "vlut_workspace_bytes", "vlut_pack_weights", "vlut_quantize_act", "vlut_build_lut", "vlut_mpgemm",
     "vlut_mpgemm_mfma", "vlut_set_plan", "vlut_query_plan",
 ]
@@ -47,6 +48,7 @@ def lib() -> ctypes.CDLL:
         L.vlut_version.argtypes, L.vlut_version.restype = [], ci
         L.vlut_packed_weight_bytes.argtypes, L.vlut_packed_weight_bytes.restype = [i64, i64], sz
         L.vlut_packed_offset.argtypes, L.vlut_packed_offset.restype = [i64, i64, i64, i64], sz
+        L.vlut_act_bytes.argtypes, L.vlut_act_bytes.restype = [i64, i64], sz
         L.vlut_lut_bytes.argtypes, L.vlut_lut_bytes.restype = [i64, i64], sz
         L.vlut_workspace_bytes.argtypes, L.vlut_workspace_bytes.restype = [i64, i64, i64], sz
         L.vlut_pack_weights.argtypes, L.vlut_pack_weights.restype = [p, i64, i64, p, sz, p], ci
@@ -86,6 +88,16 @@ def packed_offset(M: int, K: int, m: int, kg: int) -> int:
     return lib().vlut_packed_offset(M, K, m, kg)
 
 
+def act_bytes(K: int, N: int) -> int:
+    return lib().vlut_act_bytes(K, N)
+
+
+def act_chunked_to_kn(a_q: torch.Tensor, N: int) -> torch.Tensor:
+    """View helper for checks: token-chunked int8 [ceil(N/8)][K][8] -> plain [K][N] (a copy)."""
+    C, K, _ = a_q.shape
+    return a_q.permute(1, 0, 2).reshape(K, C * 8)[:, :N].contiguous()
+
+
 def lut_bytes(K: int, N: int) -> int:
     return lib().vlut_lut_bytes(K, N)
 
@@ -117,20 +129,21 @@ def pack_weights(w_ternary: torch.Tensor) -> torch.Tensor:
 
 
 def quantize_act(x: torch.Tensor, a_q: Optional[torch.Tensor] = None, a_scale: Optional[torch.Tensor] = None):
-    """fp32 [N][K] (row stride >= K) -> (int8 [K][N], fp32 [N])."""
+    """fp32 [N][K] (row stride >= K) -> (int8 token-chunked [ceil(N/8)][K][8], fp32 [N])."""
     assert x.is_cuda and x.dtype == torch.float32 and x.dim() == 2 and x.stride(1) == 1
     N, K = x.shape
     if a_q is None:
-        a_q = torch.empty((K, N), dtype=torch.int8, device=x.device)
+        a_q = torch.empty(((N + 7) // 8, K, 8), dtype=torch.int8, device=x.device)
     if a_scale is None:
         a_scale = torch.empty(N, dtype=torch.float32, device=x.device)
     _check(lib().vlut_quantize_act(_ptr(x), N, K, x.stride(0), _ptr(a_q), _ptr(a_scale), _stream()), "vlut_quantize_act")
     return a_q, a_scale
 
 
-def build_lut(a_q: torch.Tensor, lut: Optional[torch.Tensor] = None) -> torch.Tensor:
-    assert a_q.is_cuda and a_q.dtype == torch.int8 and a_q.is_contiguous()
-    K, N = a_q.shape
+def build_lut(a_q: torch.Tensor, N: int, lut: Optional[torch.Tensor] = None) -> torch.Tensor:
+    assert a_q.is_cuda and a_q.dtype == torch.int8 and a_q.is_contiguous() and a_q.dim() == 3
+    K = a_q.shape[1]
+    assert a_q.shape[0] == (N + 7) // 8
     if lut is None:
         lut = torch.empty((K // 4, 81, N), dtype=torch.int16, device=a_q.device)
     _check(lib().vlut_build_lut(_ptr(a_q), K, N, _ptr(lut), lut.numel() * 2, _stream()), "vlut_build_lut")
@@ -141,7 +154,7 @@ def mpgemm(packed: torch.Tensor, w_scale: float, a_q: torch.Tensor, a_scale: tor
            y: Optional[torch.Tensor] = None, acc: Optional[torch.Tensor] = None, lut: Optional[torch.Tensor] = None,
            workspace: Optional[torch.Tensor] = None, want_acc: bool = False, mfma: bool = False):
     """Runs vlut_mpgemm (or the MFMA comparison path).  Returns (y fp32 [N][M], acc int32 [M][N] or None)."""
-    K, N = a_q.shape
+    K, N = a_q.shape[1], a_scale.shape[0]
     dev = a_q.device
     if y is None:
         y = torch.empty((N, M), dtype=torch.float32, device=dev)

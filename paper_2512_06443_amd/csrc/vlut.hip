@@ -20,6 +20,7 @@
 #include <cstdint>
 #include <cstring>
 #include <mutex>
+#include <type_traits>
 
 #include "vlut.h"
 
@@ -39,7 +40,7 @@ constexpr int kTableBytes = kStageSlots * kSlotBytes;  // 82944
 constexpr int kLdsBytes = kTableBytes + 128 * 4;    // + the output scales of the tile's tokens
 constexpr int kWaves = 16;                   // waves per workgroup
 constexpr int kThreads = kWaves * 64;
-constexpr int kBuilders = kStageSlots * 9 * 16;  // 576 build tasks per stage
+constexpr int kBuilders = kStageSlots * 9 * 16;  // 576 build tasks per stage: (slot, slice, two leading digits)
 constexpr unsigned kZeroIdx4 = 0x28282828u;  // four copies of index 40 (the all-zero pattern)
 constexpr int kMaxDim = 1 << 24;
 constexpr int kBlockLookups = 64;            // INT16 block size B for g = 4 (Sec. 3.4)
@@ -125,51 +126,80 @@ __global__ void pack_kernel(const int8_t* __restrict__ w, int M, int K, int G, i
 
 // ---------------------------------------------------------------------------------------------
 // Activation quantisation + transposition (Sec. 3.4 first paragraph, Sec. 3.3).
-// One workgroup handles TOK consecutive tokens over all K.
+// One workgroup handles one chunk of 8 consecutive tokens over all K and writes the chunk's
+// [K][8] block, which is contiguous in the token-chunked layout.  KPT = k values per thread kept
+// in registers between the absmax pass and the rounding pass (0: re-read x, for large K).
 // ---------------------------------------------------------------------------------------------
-template <int TOK>
-__global__ void __launch_bounds__(256) quantize_kernel(const float* __restrict__ x, int N, int K, int64_t ldx,
-                                                       int8_t* __restrict__ a_q, float* __restrict__ a_scale) {
-    __shared__ float red[4][TOK];
-    __shared__ float s_inv[TOK];
-    const int n0 = blockIdx.x * TOK;
+constexpr int kQuantThreads = 1024;
+
+template <int KPT>
+__global__ void __launch_bounds__(kQuantThreads) quantize_kernel(const float* __restrict__ x, int N, int K, int64_t ldx,
+                                                                 int8_t* __restrict__ a_q, float* __restrict__ a_scale) {
+    __shared__ float red[kQuantThreads / 64][8];
+    __shared__ float s_inv[8];
+    const int chunk = blockIdx.x;
+    const int n0 = chunk * 8;
     const int tid = threadIdx.x;
-    float amax[TOK];
+    const int ntok = min(8, N - n0);
+    float amax[8];
+    float xv[KPT > 0 ? KPT : 1][8];
 #pragma unroll
-    for (int t = 0; t < TOK; ++t) amax[t] = 0.0f;
-    for (int k = tid; k < K; k += 256) {
+    for (int t = 0; t < 8; ++t) amax[t] = 0.0f;
+    if (KPT > 0) {
 #pragma unroll
-        for (int t = 0; t < TOK; ++t) {
-            int n = n0 + t;
-            if (n < N) amax[t] = fmaxf(amax[t], fabsf(x[(size_t)n * ldx + k]));
+        for (int i = 0; i < KPT; ++i) {
+            const int k = tid + i * kQuantThreads;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                xv[i][t] = (k < K && t < ntok) ? x[(size_t)(n0 + t) * ldx + k] : 0.0f;
+                amax[t] = fmaxf(amax[t], fabsf(xv[i][t]));
+            }
         }
+    } else {
+        for (int k = tid; k < K; k += kQuantThreads)
+#pragma unroll
+            for (int t = 0; t < 8; ++t)
+                if (t < ntok) amax[t] = fmaxf(amax[t], fabsf(x[(size_t)(n0 + t) * ldx + k]));
     }
 #pragma unroll
-    for (int t = 0; t < TOK; ++t) {
+    for (int t = 0; t < 8; ++t) {
         float v = amax[t];
         for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
         if ((tid & 63) == 0) red[tid >> 6][t] = v;
     }
     __syncthreads();
-    if (tid < TOK) {
-        float v = fmaxf(fmaxf(red[0][tid], red[1][tid]), fmaxf(red[2][tid], red[3][tid]));
-        int n = n0 + tid;
+    if (tid < 8) {
+        float v = 0.0f;
+        for (int w = 0; w < kQuantThreads / 64; ++w) v = fmaxf(v, red[w][tid]);
         // IEEE-correct fp32 divisions (the default for HIP); no reciprocal approximation.
-        float inv = (v > 0.0f) ? 127.0f / v : 0.0f;
-        s_inv[tid] = inv;
-        if (n < N) a_scale[n] = v / 127.0f;
+        s_inv[tid] = (v > 0.0f) ? 127.0f / v : 0.0f;
+        if (tid < ntok) a_scale[n0 + tid] = v / 127.0f;
     }
     __syncthreads();
-    for (int k = tid; k < K; k += 256) {
+    int8_t* dst = a_q + (size_t)chunk * K * 8;
+    auto emit = [&](int k, const float (&vals)[8]) {
+        unsigned lo = 0, hi = 0;
 #pragma unroll
-        for (int t = 0; t < TOK; ++t) {
-            int n = n0 + t;
-            if (n < N) {
-                float p = x[(size_t)n * ldx + k] * s_inv[t];   // one rounded multiply
-                float r = rintf(p);                              // ties to even
-                r = fminf(fmaxf(r, -127.0f), 127.0f);
-                a_q[(size_t)k * N + n] = (int8_t)(int)r;
-            }
+        for (int t = 0; t < 8; ++t) {
+            float r = rintf(vals[t] * s_inv[t]);             // one rounded multiply, ties to even
+            r = fminf(fmaxf(r, -127.0f), 127.0f);
+            const unsigned byte = (unsigned)(int)r & 0xffu;  // padded tokens of the last chunk: x = 0 -> code 0
+            if (t < 4) lo |= byte << (8 * t); else hi |= byte << (8 * (t - 4));
+        }
+        *(i32x2*)(dst + (size_t)k * 8) = i32x2{(int)lo, (int)hi};
+    };
+    if (KPT > 0) {
+#pragma unroll
+        for (int i = 0; i < KPT; ++i) {
+            const int k = tid + i * kQuantThreads;
+            if (k < K) emit(k, xv[i]);
+        }
+    } else {
+        for (int k = tid; k < K; k += kQuantThreads) {
+            float vals[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) vals[t] = (t < ntok) ? x[(size_t)(n0 + t) * ldx + k] : 0.0f;
+            emit(k, vals);
         }
     }
 }
@@ -184,10 +214,8 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const int8_t* __restrict
     if (i >= (size_t)G * N) return;
     int n = (int)(i % N);
     int kg = (int)(i / N);
-    int a0 = a_q[(size_t)(4 * kg + 0) * N + n];
-    int a1 = a_q[(size_t)(4 * kg + 1) * N + n];
-    int a2 = a_q[(size_t)(4 * kg + 2) * N + n];
-    int a3 = a_q[(size_t)(4 * kg + 3) * N + n];
+    const int8_t* a = a_q + ((size_t)(n >> 3) * (4 * G) + 4 * kg) * 8 + (n & 7);   // [N/8][K][8]
+    int a0 = a[0], a1 = a[8], a2 = a[16], a3 = a[24];
     int16_t* t = lut + ((size_t)kg * kRows) * N + n;
     int v0 = -a0 - a1 - a2 - a3;                       // row 0, then walk the digits
     for (int d0 = 0; d0 < 3; ++d0) {
@@ -208,26 +236,95 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const int8_t* __restrict
     }
 }
 
-// One lookup-accumulate (Alg. 1 lines 3-6): byte B of the weight dword is the row of slot B; the lane reads its
-// 16-byte slice of that row (8 INT16 entries) and adds it into 4 packed INT16 accumulators.
-template <int B>
-__device__ __forceinline__ void lookup_add(unsigned w, unsigned lanebase, s16x2 (&acc)[4]) {
-    const unsigned sel = 0x0c0c0000u | ((4u + (unsigned)B) << 8);
-    const unsigned addr = __builtin_amdgcn_perm(w, lanebase, sel);   // idx*256 + slice*16
-    const i32x4 v = lds_read128<B * (kSlotBytes / 16)>(addr);
-    acc[0] += as_s16x2(v.x);
-    acc[1] += as_s16x2(v.y);
-    acc[2] += as_s16x2(v.z);
-    acc[3] += as_s16x2(v.w);
+// ---------------------------------------------------------------------------------------------
+// The lookup kernel (Alg. 1 main loop + streamed Precompute, Sec. 3.4).
+//   R       row groups (of 4 output rows) per wave; workgroup tile = up to 64*R rows
+//   NEED32  more than 64 lookups per lane: widen INT16 block sums into INT32 every 16 stages
+//   MODE    kFast: tables built in LDS from the token-chunked INT8 activations (streamed, the hot path)
+//           kFromGlobal: LDS slots are filled from a table materialised by vlut_build_lut
+// ---------------------------------------------------------------------------------------------
+enum { kFast = 0, kFromGlobal = 2 };
+
+// Issues the table read of lookup number I of a stage (b-major: I = b*R + r).  Byte b of the row group's weight
+// dword is the row of slot b; the lane reads its 16-byte slice of that row (8 INT16 entries).
+template <int R, int I>
+__device__ __forceinline__ i32x4 lookup_read(const unsigned (&w)[R], unsigned lanebase) {
+    constexpr int b = I / R, r = I % R;
+    constexpr unsigned sel = 0x0c0c0000u | ((4u + (unsigned)b) << 8);
+    const unsigned addr = __builtin_amdgcn_perm(w[r], lanebase, sel);   // idx*256 + slice*16
+    return lds_read128<b * (kSlotBytes / 16)>(addr);
 }
 
-// ---------------------------------------------------------------------------------------------
-// The lookup kernel.
-//   R            row groups (of 4 output rows) per wave; workgroup tile = up to 64*R rows
-//   NEED32       more than 64 lookups per lane: widen INT16 block sums into INT32 every 16 stages
-//   FROM_GLOBAL  fill the LDS slots from a materialised table instead of building them
-// ---------------------------------------------------------------------------------------------
-template <int R, bool NEED32, bool FROM_GLOBAL>
+template <int R, int I>
+__device__ __forceinline__ void lookup_accumulate(s16x2 (&acc16)[R][4], const i32x4 v) {
+    constexpr int r = I % R;
+    acc16[r][0] += as_s16x2(v.x);
+    acc16[r][1] += as_s16x2(v.y);
+    acc16[r][2] += as_s16x2(v.z);
+    acc16[r][3] += as_s16x2(v.w);
+}
+
+// The 4*R lookups of a stage, software pipelined in batches of NB: the reads of batch k+1 are in flight while the
+// packed INT16 adds of batch k issue (Alg. 1 lines 3-6: one shared index, one vector add over the tokens).
+template <int R, int NB, int K0>
+__device__ __forceinline__ void lookup_batches(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4],
+                                               i32x4 (&cur)[NB]) {
+    constexpr int total = 4 * R;
+    if constexpr (K0 < total) {
+        i32x4 nxt[NB];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) nxt[i] = i32x4{0, 0, 0, 0};
+        // reads of the next batch
+        if constexpr (K0 + NB + 0 < total && NB > 0) nxt[0] = lookup_read<R, (K0 + NB + 0 < total ? K0 + NB + 0 : 0)>(w, lanebase);
+        if constexpr (K0 + NB + 1 < total && NB > 1) nxt[1] = lookup_read<R, (K0 + NB + 1 < total ? K0 + NB + 1 : 0)>(w, lanebase);
+        if constexpr (K0 + NB + 2 < total && NB > 2) nxt[2] = lookup_read<R, (K0 + NB + 2 < total ? K0 + NB + 2 : 0)>(w, lanebase);
+        if constexpr (K0 + NB + 3 < total && NB > 3) nxt[3] = lookup_read<R, (K0 + NB + 3 < total ? K0 + NB + 3 : 0)>(w, lanebase);
+        __builtin_amdgcn_sched_barrier(0);
+        // adds of the current batch
+        if constexpr (K0 + 0 < total && NB > 0) lookup_accumulate<R, (K0 + 0 < total ? K0 + 0 : 0)>(acc16, cur[0]);
+        if constexpr (K0 + 1 < total && NB > 1) lookup_accumulate<R, (K0 + 1 < total ? K0 + 1 : 0)>(acc16, cur[1]);
+        if constexpr (K0 + 2 < total && NB > 2) lookup_accumulate<R, (K0 + 2 < total ? K0 + 2 : 0)>(acc16, cur[2]);
+        if constexpr (K0 + 3 < total && NB > 3) lookup_accumulate<R, (K0 + 3 < total ? K0 + 3 : 0)>(acc16, cur[3]);
+        __builtin_amdgcn_sched_barrier(0);
+        lookup_batches<R, NB, K0 + NB>(w, lanebase, acc16, nxt);
+    }
+}
+
+template <int R>
+__device__ __forceinline__ void lookup_stage(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4]) {
+    constexpr int NB = 4;
+    i32x4 first[NB];
+    first[0] = lookup_read<R, 0>(w, lanebase);
+    first[1] = lookup_read<R, 1>(w, lanebase);
+    first[2] = lookup_read<R, 2>(w, lanebase);
+    first[3] = lookup_read<R, 3>(w, lanebase);
+    __builtin_amdgcn_sched_barrier(0);
+    lookup_batches<R, NB, 0>(w, lanebase, acc16, first);
+}
+
+// Nine table rows that share their two leading digits (b1 = their common part): the third and fourth digits add or
+// subtract a2 and a3.  Row offsets 0..8 from dst.
+__device__ __forceinline__ void build_rows9(unsigned dst, const s16x2 (&b1)[4], const s16x2 (&a2)[4],
+                                            const s16x2 (&a3)[4]) {
+    s16x2 u[4], lo[4], hi[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { u[q] = b1[q] - a2[q]; lo[q] = u[q] - a3[q]; hi[q] = u[q] + a3[q]; }
+    lds_write128<0 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
+    lds_write128<1 * 16>(dst, i32x4{as_int(u[0]), as_int(u[1]), as_int(u[2]), as_int(u[3])});
+    lds_write128<2 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { lo[q] = b1[q] - a3[q]; hi[q] = b1[q] + a3[q]; }
+    lds_write128<3 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
+    lds_write128<4 * 16>(dst, i32x4{as_int(b1[0]), as_int(b1[1]), as_int(b1[2]), as_int(b1[3])});
+    lds_write128<5 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { u[q] = b1[q] + a2[q]; lo[q] = u[q] - a3[q]; hi[q] = u[q] + a3[q]; }
+    lds_write128<6 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
+    lds_write128<7 * 16>(dst, i32x4{as_int(u[0]), as_int(u[1]), as_int(u[2]), as_int(u[3])});
+    lds_write128<8 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
+}
+
+template <int R, bool NEED32, int MODE>
 __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // The kernel has no static LDS, so the dynamic segment starts at LDS address 0; table addresses are formed
@@ -274,7 +371,9 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         wbase[r] = p.packed + ((size_t)(valid ? rg : 0) * p.KCn) * 64;
     }
 
-    // ---- build role (threads 0..575): slot bb, slice lb, digit pair hh = 3*d0 + d1
+    // ---- build role (waves 0..8): slot bb, slice lb, leading digits hh = 3*d0 + d1 (9 table rows per task).
+    // Filling the slots is bound by LDS write bandwidth (~75 B/clk/CU); one wave can only issue a 1 KB write every
+    // ~60 clocks, so the work is spread over nine waves with nine writes each.
     const bool builder = tid < kBuilders;
     const int lb = tid & 15;
     const int bq = tid >> 4;
@@ -283,38 +382,25 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     const int jb = lb >> TClog;
     const int tb = lb & ((1 << TClog) - 1);
     const int nb = n0 + 8 * tb;          // first token of the builder's slice
-    unsigned act[4][2];
-    bool act_valid = false;
+    unsigned actA[4][2], actB[4][2];
+    bool validA = false, validB = false;
 
-    // Loads for the NEXT stage's tables.  The fast path is branch-free (addresses clamped into the tensor, validity
-    // applied when the values are used) so that nothing has to wait for the data before the next build phase.
-    auto prefetch_act = [&](int st) {
+    // Loads for the NEXT stage's tables: the 4 activation rows of the task's sub-table for its 8 tokens are 32
+    // contiguous bytes of the token-chunked layout.  Branch-free (address clamped into the tensor, validity applied
+    // when the values are used) so that nothing has to wait for the data before the next build phase.
+    const int chunk_b = nb >> 3;
+    auto prefetch_act = [&](int st, unsigned (&act)[4][2], bool& act_valid) {
         const int kg = st * 4 * J + 4 * jb + bb;
         act_valid = (kg < p.G) && (nb < p.N);
-        if (p.aligned8) {
+        if (MODE == kFast) {
             const int kgc = min(kg, p.G - 1);
-            const int nbc = (nb < p.N) ? nb : 0;
-            const int8_t* src = p.a_q + (size_t)(4 * kgc) * p.N + nbc;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const i32x2 v = *(const i32x2*)(src + (size_t)c * p.N);
-                act[c][0] = (unsigned)v.x;
-                act[c][1] = (unsigned)v.y;
-            }
-        } else {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
-            if (act_valid) {
-                const int8_t* src = p.a_q + (size_t)(4 * kg) * p.N + nb;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        unsigned byte = (nb + e < p.N) ? (unsigned)(uint8_t)src[(size_t)c * p.N + e] : 0u;
-                        act[c][e >> 2] |= byte << (8 * (e & 3));
-                    }
-                }
-            }
+            const int cc = (nb < p.N) ? chunk_b : 0;
+            const i32x4* src = (const i32x4*)(p.a_q + ((size_t)cc * p.K + 4 * kgc) * 8);
+            const i32x4 v0 = src[0], v1 = src[1];
+            act[0][0] = (unsigned)v0.x; act[0][1] = (unsigned)v0.y;
+            act[1][0] = (unsigned)v0.z; act[1][1] = (unsigned)v0.w;
+            act[2][0] = (unsigned)v1.x; act[2][1] = (unsigned)v1.y;
+            act[3][0] = (unsigned)v1.z; act[3][1] = (unsigned)v1.w;
         }
     };
 
@@ -336,7 +422,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     lds_f32* scale_lds = (lds_f32*)(unsigned)kTableBytes;
     if (tid < n_tile) scale_lds[tid] = (n0 + tid < p.N) ? p.w_scale * p.a_scale[n0 + tid] : 0.0f;
 
-    if (builder && !FROM_GLOBAL && st_begin < st_end) prefetch_act(st_begin);
+    if (builder && st_begin < st_end) prefetch_act(st_begin, actA, validA);
 
     // Weight dwords (4 lookups each) are fetched one whole stage ahead into the buffer the next stage reads, so
     // their HBM latency hides behind a full build + lookup phase.  Dword q = st*J + j of each row.
@@ -350,13 +436,16 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         for (int r = 0; r < R; ++r) wdst[r] = *(const unsigned*)(wbase[r] + voff);
     };
 
-    auto stage = [&](int st, unsigned (&w)[R], unsigned (&wnext)[R]) {
+    auto stage = [&](int st, unsigned (&w)[R], unsigned (&wnext)[R], unsigned (&act)[4][2], bool& act_valid,
+                     unsigned (&act_next)[4][2], bool& valid_next) {
+        // prefetches for the next stage first: they have this whole stage to arrive
+        if (builder && st + 1 < st_end) prefetch_act(st + 1, act_next, valid_next);
         load_weights(st + 1, wnext);
 
         // ---- fill the 4 slots of this stage
         if (builder) {
             const unsigned dst = (unsigned)bb * kSlotBytes + (unsigned)(9 * hh) * kRowBytes + (unsigned)lb * 16u;
-            if (FROM_GLOBAL) {
+            if (MODE == kFromGlobal) {
                 const int kg = st * 4 * J + 4 * jb + bb;
 #pragma unroll
                 for (int i = 0; i < 9; ++i) {
@@ -378,58 +467,28 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                     lds_write128<0>(dst + (unsigned)i * kRowBytes, v);
                 }
             } else {
-                // rows 9*hh .. 9*hh+8 of the sub-table: digits (d0,d1) fixed by hh, (d2,d3) enumerated.
+                // rows 9*hh .. 9*hh+8 of the sub-table: two leading digits fixed per task, the other two enumerated;
+                // every row is one packed add/sub away from an earlier one (topological order, Sec. 4).
                 if (!act_valid) {
 #pragma unroll
                     for (int c = 0; c < 4; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
                 }
                 const short s0 = (short)(hh / 3 - 1), s1 = (short)(hh % 3 - 1);
                 const s16x2 m0 = {s0, s0}, m1 = {s1, s1};
-                s16x2 a2[4], a3[4], base[4];
+                s16x2 a2[4], a3[4], b1[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    s16x2 a0 = unpack_pair(act[0][q >> 1], q & 1);
-                    s16x2 a1 = unpack_pair(act[1][q >> 1], q & 1);
+                    b1[q] = unpack_pair(act[0][q >> 1], q & 1) * m0 + unpack_pair(act[1][q >> 1], q & 1) * m1;
                     a2[q] = unpack_pair(act[2][q >> 1], q & 1);
                     a3[q] = unpack_pair(act[3][q >> 1], q & 1);
-                    base[q] = a0 * m0 + a1 * m1;
                 }
-#pragma unroll
-                for (int d2 = 0; d2 < 3; ++d2) {
-                    s16x2 u[4], lo[4], hi[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        u[q] = (d2 == 0) ? base[q] - a2[q] : (d2 == 1) ? base[q] : base[q] + a2[q];
-                        lo[q] = u[q] - a3[q];
-                        hi[q] = u[q] + a3[q];
-                    }
-                    if (d2 == 0) {
-                        lds_write128<0 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
-                        lds_write128<1 * 16>(dst, i32x4{as_int(u[0]), as_int(u[1]), as_int(u[2]), as_int(u[3])});
-                        lds_write128<2 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
-                    } else if (d2 == 1) {
-                        lds_write128<3 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
-                        lds_write128<4 * 16>(dst, i32x4{as_int(u[0]), as_int(u[1]), as_int(u[2]), as_int(u[3])});
-                        lds_write128<5 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
-                    } else {
-                        lds_write128<6 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
-                        lds_write128<7 * 16>(dst, i32x4{as_int(u[0]), as_int(u[1]), as_int(u[2]), as_int(u[3])});
-                        lds_write128<8 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
-                    }
-                }
+                build_rows9(dst, b1, a2, a3);
             }
         }
         wg_barrier_lds();
-        if (builder && !FROM_GLOBAL && st + 1 < st_end) prefetch_act(st + 1);
 
         // ---- 4 lookups per row group: byte b of the weight dword selects the row of slot b
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            lookup_add<0>(w[r], lanebase, acc16[r]);
-            lookup_add<1>(w[r], lanebase, acc16[r]);
-            lookup_add<2>(w[r], lanebase, acc16[r]);
-            lookup_add<3>(w[r], lanebase, acc16[r]);
-        }
+        lookup_stage<R>(w, lanebase, acc16);
         wg_barrier_lds();
 
         if (NEED32 && (((st - st_begin) & 15) == 15)) {   // 16 stages x 4 lookups = block of 64
@@ -447,19 +506,22 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     unsigned wa[R], wb[R];
     load_weights(st_begin, wa);
     for (int st = st_begin; st < st_end; st += 2) {
-        stage(st, wa, wb);
-        if (st + 1 < st_end) stage(st + 1, wb, wa);
+        stage(st, wa, wb, actA, validA, actB, validB);
+        if (st + 1 < st_end) stage(st + 1, wb, wa, actB, validB, actA, validA);
     }
 
     // ---- epilogue.  Per row group: widen to INT32, add the J partial sums of each token across the 16 lanes of
     // the group with a reduce-scatter (each step halves the tokens a lane keeps), park the sums in LDS as
     // [token][row] and let the whole workgroup write 128 consecutive output rows per token.
-    constexpr int RC = R > 1 ? 2 : 1;                       // row-group rounds parked per chunk
-    constexpr int kParkStride = RC * 64 + 4;                // ints per parked token; +4 keeps the writes conflict-free
     lds_i32* park = (lds_i32*)0u;
     const int m0 = rgw0 * 4;
     const int rows_wg = min(p.RGW * 4, p.M - m0);
     const int TC = 1 << TClog;
+    // RC = row-group rounds parked per pass.  All R at once when the tile has few tokens (the R independent
+    // shuffle chains then overlap); two at a time when [tokens][rows] would not fit in LDS.
+    auto epilogue = [&](auto rc_tag) {
+    constexpr int RC = decltype(rc_tag)::value;
+    constexpr int kParkStride = RC * 64 + 4;                // ints per parked token; +4 keeps the writes conflict-free
 #pragma unroll
     for (int c0 = 0; c0 < R; c0 += RC) {
 #pragma unroll
@@ -533,6 +595,9 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         }
         wg_barrier_lds();
     }
+    };
+    if (n_tile * (R * 64 + 4) * 4 <= kTableBytes) epilogue(std::integral_constant<int, R>{});
+    else epilogue(std::integral_constant<int, (R > 1 ? 2 : 1)>{});
 }
 
 // Sum of the split-K partials (any order is exact: integers) + scale step.
@@ -616,7 +681,7 @@ double plan_cost(const Plan& pl, int64_t M, int64_t K, int64_t N) {
 bool plan_valid(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     if (pl.Jlog < 0 || pl.Jlog > 4 || !r_supported(pl.R) || pl.S < 1 || pl.S > 16) return false;
     Derived d = derive(pl, M, K, N);
-    if (d.need32 && pl.R > 5) return false;      // register budget of the INT32 variant
+    if (d.need32 && pl.R > 4) return false;      // register budget of the INT32 variant
     if (pl.S > d.stages_total) return false;
     return true;
 }
@@ -656,9 +721,9 @@ Plan choose_plan(int64_t M, int64_t K, int64_t N) {
     return pl;
 }
 
-template <int R, bool NEED32, bool FROM_GLOBAL>
+template <int R, bool NEED32, int MODE>
 int launch_lookup_t(const LookupParams& p, int grid, hipStream_t stream) {
-    auto kfn = lookup_kernel<R, NEED32, FROM_GLOBAL>;
+    auto kfn = lookup_kernel<R, NEED32, MODE>;
     static bool attr_done = false;   // benign race: the call is idempotent
     if (!attr_done) {
         if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
@@ -669,28 +734,37 @@ int launch_lookup_t(const LookupParams& p, int grid, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
 
-template <bool NEED32, bool FROM_GLOBAL>
-int launch_lookup_r(int R, const LookupParams& p, int grid, hipStream_t stream) {
-    switch (R) {
-    case 1: return launch_lookup_t<1, NEED32, FROM_GLOBAL>(p, grid, stream);
-    case 2: return launch_lookup_t<2, NEED32, FROM_GLOBAL>(p, grid, stream);
-    case 3: return launch_lookup_t<3, NEED32, FROM_GLOBAL>(p, grid, stream);
-    case 4: return launch_lookup_t<4, NEED32, FROM_GLOBAL>(p, grid, stream);
-    case 5: return launch_lookup_t<5, NEED32, FROM_GLOBAL>(p, grid, stream);
-    default: break;
-    }
-    if (NEED32) return VLUT_ERR_UNSUPPORTED;
-    if constexpr (!NEED32) {
+// The streamed kernels exist for every supported R; the variant that reads a materialised table only for a few
+// small R (the launcher maps R down).
+template <bool NEED32>
+int launch_lookup_r(int R, int mode, const LookupParams& p, int grid, hipStream_t stream) {
+    if (mode == kFast) {
         switch (R) {
-        case 6: return launch_lookup_t<6, false, FROM_GLOBAL>(p, grid, stream);
-        case 7: return launch_lookup_t<7, false, FROM_GLOBAL>(p, grid, stream);
-        case 8: return launch_lookup_t<8, false, FROM_GLOBAL>(p, grid, stream);
-        case 10: return launch_lookup_t<10, false, FROM_GLOBAL>(p, grid, stream);
-        case 12: return launch_lookup_t<12, false, FROM_GLOBAL>(p, grid, stream);
+        case 1: return launch_lookup_t<1, NEED32, kFast>(p, grid, stream);
+        case 2: return launch_lookup_t<2, NEED32, kFast>(p, grid, stream);
+        case 3: return launch_lookup_t<3, NEED32, kFast>(p, grid, stream);
+        case 4: return launch_lookup_t<4, NEED32, kFast>(p, grid, stream);
         default: break;
         }
+        if constexpr (!NEED32) {
+            switch (R) {
+            case 5: return launch_lookup_t<5, false, kFast>(p, grid, stream);
+            case 6: return launch_lookup_t<6, false, kFast>(p, grid, stream);
+            case 7: return launch_lookup_t<7, false, kFast>(p, grid, stream);
+            case 8: return launch_lookup_t<8, false, kFast>(p, grid, stream);
+            case 10: return launch_lookup_t<10, false, kFast>(p, grid, stream);
+            case 12: return launch_lookup_t<12, false, kFast>(p, grid, stream);
+            default: break;
+            }
+        }
+        return VLUT_ERR_UNSUPPORTED;
     }
-    return VLUT_ERR_UNSUPPORTED;
+    switch (R) {
+    case 1: return launch_lookup_t<1, NEED32, kFromGlobal>(p, grid, stream);
+    case 2: return launch_lookup_t<2, NEED32, kFromGlobal>(p, grid, stream);
+    case 4: return launch_lookup_t<4, NEED32, kFromGlobal>(p, grid, stream);
+    default: return VLUT_ERR_UNSUPPORTED;
+    }
 }
 
 int check_mpgemm_args(const uint8_t* packed, const int8_t* a_q, const float* a_scale, int64_t M, int64_t K,
@@ -732,6 +806,11 @@ size_t vlut_packed_offset(int64_t M, int64_t K, int64_t m, int64_t kg) {
     if (!shape_ok(M, K, 1) || m < 0 || m >= M || kg < 0 || kg >= K / 4) return (size_t)-1;
     size_t KCn = (size_t)((K / 4 + 15) / 16);
     return (((size_t)(m / 4) * KCn + (size_t)(kg / 16)) * 64) + (size_t)(m % 4) * 16 + (size_t)(kg % 16);
+}
+
+size_t vlut_act_bytes(int64_t K, int64_t N) {
+    if (!shape_ok(1, K, N)) return 0;
+    return (size_t)((N + 7) / 8) * (size_t)K * 8;
 }
 
 size_t vlut_lut_bytes(int64_t K, int64_t N) {
@@ -801,14 +880,15 @@ int vlut_quantize_act(const float* x, int64_t N, int64_t K, int64_t ldx, int8_t*
     if (!shape_ok(1, K, N)) return VLUT_ERR_SHAPE;
     if (ldx < K) return VLUT_ERR_SHAPE;
     if (!x || !a_q || !a_scale) return VLUT_ERR_NULL;
+    if (((uintptr_t)a_q) % 8 != 0) return VLUT_ERR_UNSUPPORTED;
     hipStream_t s = (hipStream_t)stream;
-    if (N >= 1024) {
-        hipLaunchKernelGGL(quantize_kernel<4>, dim3((unsigned)((N + 3) / 4)), dim3(256), 0, s, x, (int)N, (int)K, ldx, a_q, a_scale);
-    } else if (N >= 256) {
-        hipLaunchKernelGGL(quantize_kernel<2>, dim3((unsigned)((N + 1) / 2)), dim3(256), 0, s, x, (int)N, (int)K, ldx, a_q, a_scale);
-    } else {
-        hipLaunchKernelGGL(quantize_kernel<1>, dim3((unsigned)N), dim3(256), 0, s, x, (int)N, (int)K, ldx, a_q, a_scale);
-    }
+    const unsigned chunks = (unsigned)((N + 7) / 8);
+    if (K <= 2 * kQuantThreads)
+        hipLaunchKernelGGL(quantize_kernel<2>, dim3(chunks), dim3(kQuantThreads), 0, s, x, (int)N, (int)K, ldx, a_q, a_scale);
+    else if (K <= 4 * kQuantThreads)
+        hipLaunchKernelGGL(quantize_kernel<4>, dim3(chunks), dim3(kQuantThreads), 0, s, x, (int)N, (int)K, ldx, a_q, a_scale);
+    else
+        hipLaunchKernelGGL(quantize_kernel<0>, dim3(chunks), dim3(kQuantThreads), 0, s, x, (int)N, (int)K, ldx, a_q, a_scale);
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
 
@@ -828,6 +908,10 @@ int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const f
     int rc = check_mpgemm_args(packed, a_q, a_scale, M, K, N, y, ldy, acc_or_null);
     if (rc != VLUT_OK) return rc;
     Plan pl = choose_plan(M, K, N);
+    if (((uintptr_t)a_q) % 16 != 0) return VLUT_ERR_UNSUPPORTED;      // the [N/8][K][8] blocks are read 16 bytes at a time
+    const bool al = lut_or_null && (N % 8 == 0) && (((uintptr_t)lut_or_null) % 16 == 0);
+    const int mode = lut_or_null ? kFromGlobal : kFast;
+    if (mode != kFast) pl.R = pl.R >= 4 ? 4 : (pl.R >= 2 ? 2 : 1);   // the general-purpose kernels are built for these R only
     Derived d = derive(pl, M, K, N);
     size_t ws_need = pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
     if (ws_need > 0) {
@@ -842,15 +926,10 @@ int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const f
     p.Jlog = pl.Jlog; p.S = pl.S; p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.RGW = d.RGW;
     p.stages_total = d.stages_total; p.stages_per_split = d.stages_per_split;
     p.total_tiles = d.total; p.per_xcd = d.per_xcd;
-    bool al = (N % 8 == 0) && (((uintptr_t)a_q) % 8 == 0);
-    if (lut_or_null) al = al && (((uintptr_t)lut_or_null) % 16 == 0);
     p.aligned8 = al ? 1 : 0;
     hipStream_t s = (hipStream_t)stream;
     int grid = d.per_xcd * 8;
-    if (lut_or_null)
-        rc = d.need32 ? launch_lookup_r<true, true>(pl.R, p, grid, s) : launch_lookup_r<false, true>(pl.R, p, grid, s);
-    else
-        rc = d.need32 ? launch_lookup_r<true, false>(pl.R, p, grid, s) : launch_lookup_r<false, false>(pl.R, p, grid, s);
+    rc = d.need32 ? launch_lookup_r<true>(pl.R, mode, p, grid, s) : launch_lookup_r<false>(pl.R, mode, p, grid, s);
     if (rc != VLUT_OK) return rc;
     if (pl.S > 1) {
         size_t total = (size_t)M * (size_t)N;

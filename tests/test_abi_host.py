@@ -19,6 +19,7 @@ def L(vlut_lib_path):
     lib.vlut_packed_weight_bytes.argtypes, lib.vlut_packed_weight_bytes.restype = [i64, i64], sz
     lib.vlut_packed_offset.argtypes, lib.vlut_packed_offset.restype = [i64, i64, i64, i64], sz
     lib.vlut_lut_bytes.argtypes, lib.vlut_lut_bytes.restype = [i64, i64], sz
+    lib.vlut_act_bytes.argtypes, lib.vlut_act_bytes.restype = [i64, i64], sz
     lib.vlut_workspace_bytes.argtypes, lib.vlut_workspace_bytes.restype = [i64, i64, i64], sz
     lib.vlut_pack_weights.argtypes = [vp, i64, i64, vp, sz, vp]
     lib.vlut_quantize_act.argtypes = [vp, i64, i64, i64, vp, vp, vp]
@@ -62,6 +63,8 @@ def test_size_helpers(L, golden):
     K, N = int(golden["full_lut_K"][0]), int(golden["full_lut_N"][0])
     assert round(L.vlut_lut_bytes(K, N) / 2 ** 20, 1) == float(golden["full_lut_mib"][0])
     assert L.vlut_lut_bytes(256, 8) == 64 * 81 * 8 * 2
+    assert L.vlut_act_bytes(2560, 128) == 2560 * 128 and L.vlut_act_bytes(64, 9) == 2 * 64 * 8
+    assert L.vlut_act_bytes(6, 8) == 0
     assert L.vlut_lut_bytes(6, 8) == 0 and L.vlut_lut_bytes(8, 0) == 0
     assert L.vlut_workspace_bytes(0, 8, 8) == 0
 
@@ -82,7 +85,7 @@ def test_packed_offset_is_a_bijection(L):
 
 
 def test_argument_errors_come_before_any_device_call(L):
-    d = 0x1000  # a fake non-null "device pointer": never dereferenced on these paths
+    d = 0x1000  # a fake non-null, 16-byte aligned "device pointer": never dereferenced on these paths
     assert L.vlut_pack_weights(None, 8, 8, d, 64, None) == -1
     assert L.vlut_pack_weights(d, 8, 8, None, 64, None) == -1
     assert L.vlut_pack_weights(d, 8, 6, d, 64, None) == -2

@@ -31,6 +31,15 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
+def codes_kn(B, a_q, N):
+    """GPU activation codes (token-chunked) as a plain [K][N] numpy array; also checks the padding tokens are 0."""
+    full = a_q.cpu().numpy()                                 # [ceil(N/8)][K][8]
+    C, K, _ = full.shape
+    kn = full.transpose(1, 0, 2).reshape(K, C * 8)
+    assert not kn[:, N:].any()
+    return np.ascontiguousarray(kn[:, :N])
+
+
 def check_y(y_gpu, y_ref):
     y_gpu = y_gpu.astype(np.float64)
     err = np.abs(y_gpu - y_ref)
@@ -46,9 +55,9 @@ def run_case(B, W, w_scale, x, plan=None, use_lut=False, tag=""):
     try:
         packed = B.pack_weights(dev(W))
         a_q, a_s = B.quantize_act(dev(x))
-        assert np.array_equal(a_q.cpu().numpy(), q_ref)
+        assert np.array_equal(codes_kn(B, a_q, x.shape[0]), q_ref)
         assert np.array_equal(a_s.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
-        lut = B.build_lut(a_q) if use_lut else None
+        lut = B.build_lut(a_q, x.shape[0]) if use_lut else None
         y, acc = B.mpgemm(packed, float(w_scale), a_q, a_s, M, lut=lut, want_acc=True)
         torch.cuda.synchronize()
     finally:
@@ -79,7 +88,8 @@ def test_pack_bytes_match_oracle_and_padding(B):
 
 def test_quantize_bit_exact(B):
     cases = [wl.activations(0, 8, 256), wl.activations(1, 37, 100, 0.05), wl.activations(2, 130, 2560),
-             wl.activations(3, 1, 64), wl.activations(4, 300, 512, 0.01), wl.activations(5, 1030, 128)]
+             wl.activations(3, 1, 64), wl.activations(4, 300, 512, 0.01), wl.activations(5, 1030, 128),
+             wl.activations(7, 9, 6912), wl.activations(8, 5, 14336, 0.01)]
     z = wl.activations(6, 5, 64)
     z[2] = 0.0                                              # a zero token
     z[3, :] = 3.25                                          # all-equal token
@@ -88,7 +98,8 @@ def test_quantize_bit_exact(B):
     for x in cases:
         q_ref, s_ref = O.quantize(x)
         a_q, a_s = B.quantize_act(dev(x))
-        assert np.array_equal(a_q.cpu().numpy(), q_ref)
+        assert a_q.numel() == B.act_bytes(x.shape[1], x.shape[0])
+        assert np.array_equal(codes_kn(B, a_q, x.shape[0]), q_ref)
         assert np.array_equal(a_s.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
     # row stride larger than K
     big = np.full((37, 128), 1e9, np.float32)
@@ -96,13 +107,15 @@ def test_quantize_bit_exact(B):
     xb = dev(big)[:, :100]
     a_q, a_s = B.quantize_act(xb)
     q_ref, s_ref = O.quantize(cases[1])
-    assert np.array_equal(a_q.cpu().numpy(), q_ref) and np.array_equal(a_s.cpu().numpy(), s_ref)
+    assert np.array_equal(codes_kn(B, a_q, 37), q_ref) and np.array_equal(a_s.cpu().numpy(), s_ref)
 
 
 def test_build_lut_matches_alg1(B, golden):
     for (K, N) in [(256, 8), (64, 33), (132, 130)]:
-        q, _ = O.quantize(wl.activations(K + N, N, K))
-        T = B.build_lut(dev(q)).cpu().numpy()
+        xx = wl.activations(K + N, N, K)
+        q, _ = O.quantize(xx)
+        a_q, _ = B.quantize_act(dev(xx))
+        T = B.build_lut(a_q, N).cpu().numpy()
         assert np.array_equal(T, O.build_lut(q))
         i = int(golden["example_index"][0])                 # the paper's worked example row
         a = q[:4].astype(np.int64)
@@ -131,7 +144,7 @@ def test_every_rows_per_wave(B, R):
     run_case(B, W, s, x, plan=(8, R, 0, 1), tag=f"R{R}")
 
 
-@pytest.mark.parametrize("J,R,S", [(1, 2, 1), (1, 5, 1), (2, 3, 1), (4, 5, 2), (16, 4, 3), (8, 2, 6)])
+@pytest.mark.parametrize("J,R,S", [(1, 2, 1), (1, 4, 1), (2, 3, 1), (4, 4, 2), (16, 4, 3), (8, 2, 6)])
 def test_int32_widening_and_split_k(B, J, R, S):
     # K = 4352 -> 1088 groups: more than 64 lookups per lane for small J, so the INT16 blocks get widened
     W, s, x = wl.small_case(30 + J + S, 300, 4352, 40)
@@ -212,7 +225,7 @@ def _full_size(B, M, K, N, p_zero, outlier, seed, n_rows=96):
     packed = B.pack_weights(dev(W))
     a_q, a_s = B.quantize_act(dev(x))
     q_ref, s_ref = O.quantize(x)
-    assert np.array_equal(a_q.cpu().numpy(), q_ref)
+    assert np.array_equal(codes_kn(B, a_q, N), q_ref)
     assert np.array_equal(a_s.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
     y, acc = B.mpgemm(packed, float(w_scale), a_q, a_s, M, want_acc=True)   # automatic plan = the bench's plan
     torch.cuda.synchronize()
