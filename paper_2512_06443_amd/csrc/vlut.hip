@@ -79,6 +79,20 @@ __device__ __forceinline__ void lds_write128(unsigned addr, i32x4 v) {
     ((lds_i32x4*)addr)[OFF16] = v;
 }
 
+// Value of x held by the lane whose index differs in bit MASK (1, 2, 4 or 8), inside each row of 16 lanes: data
+// parallel primitives (no LDS traffic).  row_ror:8 swaps the halves of a row; for 4 the two directions are written
+// under complementary bank masks; 2 and 1 are quad permutes.
+template <int MASK>
+__device__ __forceinline__ int lane_xor16(int x) {
+    if (MASK == 8) return __builtin_amdgcn_update_dpp(0, x, 0x128, 0xF, 0xF, false);
+    if (MASK == 4) {
+        int t = __builtin_amdgcn_update_dpp(0, x, 0x104, 0xF, 0x5, false);   // lanes 0-3, 8-11 <- lane + 4
+        return __builtin_amdgcn_update_dpp(t, x, 0x114, 0xF, 0xA, false);     // lanes 4-7, 12-15 <- lane - 4
+    }
+    if (MASK == 2) return __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false);
+    return __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false);
+}
+
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global load
 // and store of the wave (vmcnt(0)), which would expose the latency of the weight and activation prefetches at
 // every stage; here a wave only has to finish its own LDS reads/writes before it signals the barrier.
@@ -534,38 +548,40 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                     v[2 * q] = (int)acc16[r][q].x + (NEED32 ? acc32[r][2 * q] : 0);
                     v[2 * q + 1] = (int)acc16[r][q].y + (NEED32 ? acc32[r][2 * q + 1] : 0);
                 }
+                // Reduce-scatter over the sub-table selector j (the top Jlog bits of the lane's slice index): each
+                // step exchanges half of the remaining tokens with the lane whose index differs in one bit.
                 int tokoff = 0;
                 bool owner = true;
                 if (Jlog > 0) {
-                    const int bit = j & 1;
+                    const bool hi = (l & 8) != 0;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const int send = bit ? v[e] : v[e + 4];
-                        const int keep = bit ? v[e + 4] : v[e];
-                        v[e] = keep + __shfl_xor(send, TC);
+                        const int send = hi ? v[e] : v[e + 4];
+                        const int keep = hi ? v[e + 4] : v[e];
+                        v[e] = keep + lane_xor16<8>(send);
                     }
-                    tokoff += bit * 4;
+                    tokoff += hi ? 4 : 0;
                 }
                 if (Jlog > 1) {
-                    const int bit = (j >> 1) & 1;
+                    const bool hi = (l & 4) != 0;
 #pragma unroll
                     for (int e = 0; e < 2; ++e) {
-                        const int send = bit ? v[e] : v[e + 2];
-                        const int keep = bit ? v[e + 2] : v[e];
-                        v[e] = keep + __shfl_xor(send, TC << 1);
+                        const int send = hi ? v[e] : v[e + 2];
+                        const int keep = hi ? v[e + 2] : v[e];
+                        v[e] = keep + lane_xor16<4>(send);
                     }
-                    tokoff += bit * 2;
+                    tokoff += hi ? 2 : 0;
                 }
                 if (Jlog > 2) {
-                    const int bit = (j >> 2) & 1;
-                    const int send = bit ? v[0] : v[1];
-                    const int keep = bit ? v[1] : v[0];
-                    v[0] = keep + __shfl_xor(send, TC << 2);
-                    tokoff += bit;
+                    const bool hi = (l & 2) != 0;
+                    const int send = hi ? v[0] : v[1];
+                    const int keep = hi ? v[1] : v[0];
+                    v[0] = keep + lane_xor16<2>(send);
+                    tokoff += hi ? 1 : 0;
                 }
                 if (Jlog > 3) {
-                    v[0] += __shfl_xor(v[0], 8);
-                    owner = ((j >> 3) & 1) == 0;
+                    v[0] += lane_xor16<1>(v[0]);
+                    owner = (l & 1) == 0;
                 }
                 const int cnt = 8 >> min(Jlog, 3);
                 if (owner) {
