@@ -140,82 +140,87 @@ __global__ void pack_kernel(const int8_t* __restrict__ w, int M, int K, int G, i
 
 // ---------------------------------------------------------------------------------------------
 // Activation quantisation + transposition (Sec. 3.4 first paragraph, Sec. 3.3).
-// One workgroup handles one chunk of 8 consecutive tokens over all K and writes the chunk's
-// [K][8] block, which is contiguous in the token-chunked layout.  KPT = k values per thread kept
-// in registers between the absmax pass and the rounding pass (0: re-read x, for large K).
+// One workgroup handles one chunk of 8 consecutive tokens over all K: 128 threads per token read the
+// token's row with 16-byte loads, the 8 codes of every k are gathered in LDS as the chunk's [K][8]
+// block, which is contiguous in the token-chunked layout and leaves with 16-byte stores.
+//   NV  float4 values per thread kept in registers between the absmax pass and the rounding pass
+//       (0: x is read twice, for large K)
+//   VEC true when rows can be read as float4 (x and ldx 16-byte aligned)
 // ---------------------------------------------------------------------------------------------
 constexpr int kQuantThreads = 1024;
 
-template <int KPT>
+template <int NV, bool VEC>
 __global__ void __launch_bounds__(kQuantThreads) quantize_kernel(const float* __restrict__ x, int N, int K, int64_t ldx,
                                                                  int8_t* __restrict__ a_q, float* __restrict__ a_scale) {
-    __shared__ float red[kQuantThreads / 64][8];
+    extern __shared__ __attribute__((aligned(16))) unsigned char q_lds[];   // [K][8] codes
+    __shared__ float red[kQuantThreads / 64];
     __shared__ float s_inv[8];
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
     const int chunk = blockIdx.x;
-    const int n0 = chunk * 8;
     const int tid = threadIdx.x;
-    const int ntok = min(8, N - n0);
-    float amax[8];
-    float xv[KPT > 0 ? KPT : 1][8];
+    const int t = tid >> 7;                    // token of the chunk
+    const int kq = tid & 127;                  // this thread handles k = 4*(kq + 128*i) .. +3
+    const int n = chunk * 8 + t;
+    const bool live = n < N;
+    const float* row = x + (size_t)(live ? n : 0) * ldx;
+    const int nquad = K >> 2;                  // K % 4 == 0
+
+    auto load4 = [&](int qi) -> f32x4 {
+        if (VEC) return *(const f32x4*)(row + 4 * (size_t)qi);
+        return f32x4{row[4 * (size_t)qi], row[4 * (size_t)qi + 1], row[4 * (size_t)qi + 2], row[4 * (size_t)qi + 3]};
+    };
+
+    f32x4 xv[NV > 0 ? NV : 1];
+    float amax = 0.0f;
+    if (NV > 0) {
 #pragma unroll
-    for (int t = 0; t < 8; ++t) amax[t] = 0.0f;
-    if (KPT > 0) {
-#pragma unroll
-        for (int i = 0; i < KPT; ++i) {
-            const int k = tid + i * kQuantThreads;
-#pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                xv[i][t] = (k < K && t < ntok) ? x[(size_t)(n0 + t) * ldx + k] : 0.0f;
-                amax[t] = fmaxf(amax[t], fabsf(xv[i][t]));
-            }
+        for (int i = 0; i < NV; ++i) {
+            const int qi = kq + 128 * i;
+            xv[i] = (live && qi < nquad) ? load4(qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+            amax = fmaxf(fmaxf(amax, fmaxf(fabsf(xv[i].x), fabsf(xv[i].y))), fmaxf(fabsf(xv[i].z), fabsf(xv[i].w)));
         }
-    } else {
-        for (int k = tid; k < K; k += kQuantThreads)
-#pragma unroll
-            for (int t = 0; t < 8; ++t)
-                if (t < ntok) amax[t] = fmaxf(amax[t], fabsf(x[(size_t)(n0 + t) * ldx + k]));
+    } else if (live) {
+        for (int qi = kq; qi < nquad; qi += 128) {
+            const f32x4 v = load4(qi);
+            amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+        }
     }
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        float v = amax[t];
-        for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
-        if ((tid & 63) == 0) red[tid >> 6][t] = v;
-    }
+    for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+    if ((tid & 63) == 0) red[tid >> 6] = amax;
     __syncthreads();
     if (tid < 8) {
-        float v = 0.0f;
-        for (int w = 0; w < kQuantThreads / 64; ++w) v = fmaxf(v, red[w][tid]);
+        const float v = fmaxf(red[2 * tid], red[2 * tid + 1]);   // the two waves of token tid
         // IEEE-correct fp32 divisions (the default for HIP); no reciprocal approximation.
         s_inv[tid] = (v > 0.0f) ? 127.0f / v : 0.0f;
-        if (tid < ntok) a_scale[n0 + tid] = v / 127.0f;
+        if (chunk * 8 + tid < N) a_scale[chunk * 8 + tid] = v / 127.0f;
     }
     __syncthreads();
-    int8_t* dst = a_q + (size_t)chunk * K * 8;
-    auto emit = [&](int k, const float (&vals)[8]) {
-        unsigned lo = 0, hi = 0;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            float r = rintf(vals[t] * s_inv[t]);             // one rounded multiply, ties to even
-            r = fminf(fmaxf(r, -127.0f), 127.0f);
-            const unsigned byte = (unsigned)(int)r & 0xffu;  // padded tokens of the last chunk: x = 0 -> code 0
-            if (t < 4) lo |= byte << (8 * t); else hi |= byte << (8 * (t - 4));
-        }
-        *(i32x2*)(dst + (size_t)k * 8) = i32x2{(int)lo, (int)hi};
+    const float inv = s_inv[t];
+    auto code = [&](float v) -> unsigned char {
+        float r = rintf(v * inv);                 // one rounded multiply, ties to even
+        r = fminf(fmaxf(r, -127.0f), 127.0f);
+        return (unsigned char)(int)r;             // tokens past N: x = 0 -> code 0
     };
-    if (KPT > 0) {
+    auto emit = [&](int qi, const f32x4 v) {
+        unsigned char* d = q_lds + (size_t)qi * 32 + t;
+        d[0] = code(v.x);
+        d[8] = code(v.y);
+        d[16] = code(v.z);
+        d[24] = code(v.w);
+    };
+    if (NV > 0) {
 #pragma unroll
-        for (int i = 0; i < KPT; ++i) {
-            const int k = tid + i * kQuantThreads;
-            if (k < K) emit(k, xv[i]);
+        for (int i = 0; i < NV; ++i) {
+            const int qi = kq + 128 * i;
+            if (qi < nquad) emit(qi, xv[i]);
         }
     } else {
-        for (int k = tid; k < K; k += kQuantThreads) {
-            float vals[8];
-#pragma unroll
-            for (int t = 0; t < 8; ++t) vals[t] = (t < ntok) ? x[(size_t)(n0 + t) * ldx + k] : 0.0f;
-            emit(k, vals);
-        }
+        for (int qi = kq; qi < nquad; qi += 128) emit(qi, live ? load4(qi) : f32x4{0.f, 0.f, 0.f, 0.f});
     }
+    __syncthreads();
+    i32x4* dst = (i32x4*)(a_q + (size_t)chunk * K * 8);
+    const i32x4* src = (const i32x4*)q_lds;
+    for (int i = tid; i < K / 2; i += kQuantThreads) dst[i] = src[i];   // 16 bytes = 2 k-rows of 8 codes
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -896,16 +901,26 @@ int vlut_quantize_act(const float* x, int64_t N, int64_t K, int64_t ldx, int8_t*
     if (!shape_ok(1, K, N)) return VLUT_ERR_SHAPE;
     if (ldx < K) return VLUT_ERR_SHAPE;
     if (!x || !a_q || !a_scale) return VLUT_ERR_NULL;
-    if (((uintptr_t)a_q) % 8 != 0) return VLUT_ERR_UNSUPPORTED;
+    if (((uintptr_t)a_q) % 16 != 0) return VLUT_ERR_UNSUPPORTED;
+    if (K * 8 > 160 * 1024 - 1024) return VLUT_ERR_UNSUPPORTED;   // the chunk's [K][8] block is staged in LDS
     hipStream_t s = (hipStream_t)stream;
     const unsigned chunks = (unsigned)((N + 7) / 8);
-    if (K <= 2 * kQuantThreads)
-        hipLaunchKernelGGL(quantize_kernel<2>, dim3(chunks), dim3(kQuantThreads), 0, s, x, (int)N, (int)K, ldx, a_q, a_scale);
-    else if (K <= 4 * kQuantThreads)
-        hipLaunchKernelGGL(quantize_kernel<4>, dim3(chunks), dim3(kQuantThreads), 0, s, x, (int)N, (int)K, ldx, a_q, a_scale);
-    else
-        hipLaunchKernelGGL(quantize_kernel<0>, dim3(chunks), dim3(kQuantThreads), 0, s, x, (int)N, (int)K, ldx, a_q, a_scale);
-    return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
+    const bool vec = (((uintptr_t)x) % 16 == 0) && (ldx % 4 == 0);
+    const size_t lds = (size_t)K * 8;
+    const int nquad_per_thread = (int)((K / 4 + 127) / 128);
+    auto launch = [&](auto kfn) -> int {
+        if (lds > 48 * 1024 &&
+            hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return VLUT_ERR_DEVICE;
+        hipLaunchKernelGGL(kfn, dim3(chunks), dim3(kQuantThreads), lds, s, x, (int)N, (int)K, ldx, a_q, a_scale);
+        return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
+    };
+    if (vec) {
+        if (nquad_per_thread <= 5) return launch(quantize_kernel<5, true>);
+        if (nquad_per_thread <= 8) return launch(quantize_kernel<8, true>);
+        return launch(quantize_kernel<0, true>);
+    }
+    return launch(quantize_kernel<0, false>);
 }
 
 int vlut_build_lut(const int8_t* a_q, int64_t K, int64_t N, int16_t* lut, size_t lut_bytes, void* stream) {
