@@ -277,10 +277,13 @@ __device__ __forceinline__ i32x4 lookup_read(const unsigned (&w)[R], unsigned la
 template <int R, int I>
 __device__ __forceinline__ void lookup_accumulate(s16x2 (&acc16)[R][4], const i32x4 v) {
     constexpr int r = I % R;
-    acc16[r][0] += as_s16x2(v.x);
-    acc16[r][1] += as_s16x2(v.y);
-    acc16[r][2] += as_s16x2(v.z);
-    acc16[r][3] += as_s16x2(v.w);
+    // Written as instructions with the accumulator tied to one register ("+v"): left to the register allocator, the
+    // two unrolled copies of the stage keep the accumulators in two alternating register sets, which doubles their
+    // footprint and caps the row groups a wave can hold.
+    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][0]) : "v"(v.x));
+    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][1]) : "v"(v.y));
+    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][2]) : "v"(v.z));
+    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][3]) : "v"(v.w));
 }
 
 // The 4*R lookups of a stage, software pipelined in batches of NB: the reads of batch k+1 are in flight while the
@@ -393,7 +396,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     // ---- build role (waves 0..8): slot bb, slice lb, leading digits hh = 3*d0 + d1 (9 table rows per task).
     // Filling the slots is bound by LDS write bandwidth (~75 B/clk/CU); one wave can only issue a 1 KB write every
     // ~60 clocks, so the work is spread over nine waves with nine writes each.
-    const bool builder = tid < kBuilders;
+    const bool builder = wave < kBuilders / 64;   // wave-uniform (scalar) condition
     const int lb = tid & 15;
     const int bq = tid >> 4;
     const int bb = bq / 9;
@@ -401,8 +404,8 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     const int jb = lb >> TClog;
     const int tb = lb & ((1 << TClog) - 1);
     const int nb = n0 + 8 * tb;          // first token of the builder's slice
-    unsigned actA[4][2], actB[4][2];
-    bool validA = false, validB = false;
+    unsigned act[4][2];
+    bool act_valid = false;
 
     // Loads for the NEXT stage's tables: the 4 activation rows of the task's sub-table for its 8 tokens are 32
     // contiguous bytes of the token-chunked layout.  Branch-free (address clamped into the tensor, validity applied
@@ -441,7 +444,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     lds_f32* scale_lds = (lds_f32*)(unsigned)kTableBytes;
     if (tid < n_tile) scale_lds[tid] = (n0 + tid < p.N) ? p.w_scale * p.a_scale[n0 + tid] : 0.0f;
 
-    if (builder && st_begin < st_end) prefetch_act(st_begin, actA, validA);
+    if (builder && st_begin < st_end) prefetch_act(st_begin, act, act_valid);
 
     // Weight dwords (4 lookups each) are fetched one whole stage ahead into the buffer the next stage reads, so
     // their HBM latency hides behind a full build + lookup phase.  Dword q = st*J + j of each row.
@@ -455,11 +458,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         for (int r = 0; r < R; ++r) wdst[r] = *(const unsigned*)(wbase[r] + voff);
     };
 
-    auto stage = [&](int st, unsigned (&w)[R], unsigned (&wnext)[R], unsigned (&act)[4][2], bool& act_valid,
-                     unsigned (&act_next)[4][2], bool& valid_next) {
-        // prefetches for the next stage first: they have this whole stage to arrive
-        if (builder && st + 1 < st_end) prefetch_act(st + 1, act_next, valid_next);
-        load_weights(st + 1, wnext);
+    auto stage = [&](int st, unsigned (&w)[R], unsigned (&wnext)[R]) {
 
         // ---- fill the 4 slots of this stage
         if (builder) {
@@ -503,7 +502,12 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                 }
                 build_rows9(dst, b1, a2, a3);
             }
+            if (st + 1 < st_end) prefetch_act(st + 1, act, act_valid);   // lands during this stage's lookups
         }
+        // Prefetch of the next stage's weights, placed after the build: a wave issues in order and the CU's
+        // vector-memory queue is busy with everybody's loads here, so loads in front of the build would delay the
+        // phase every other wave is waiting for.  The other waves reach this point immediately.
+        load_weights(st + 1, wnext);
         wg_barrier_lds();
 
         // ---- 4 lookups per row group: byte b of the weight dword selects the row of slot b
@@ -525,8 +529,8 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     unsigned wa[R], wb[R];
     load_weights(st_begin, wa);
     for (int st = st_begin; st < st_end; st += 2) {
-        stage(st, wa, wb, actA, validA, actB, validB);
-        if (st + 1 < st_end) stage(st + 1, wb, wa, actB, validB, actA, validA);
+        stage(st, wa, wb);
+        if (st + 1 < st_end) stage(st + 1, wb, wa);
     }
 
     // ---- epilogue.  Per row group: widen to INT32, add the J partial sums of each token across the 16 lanes of
