@@ -40,7 +40,6 @@ constexpr int kTableBytes = kStageSlots * kSlotBytes;  // 82944
 constexpr int kLdsBytes = kTableBytes + 128 * 4;    // + the output scales of the tile's tokens
 constexpr int kWaves = 16;                   // waves per workgroup
 constexpr int kThreads = kWaves * 64;
-constexpr int kBuilders = kStageSlots * 9 * 16;  // 576 build tasks per stage: (slot, slice, two leading digits)
 constexpr unsigned kZeroIdx4 = 0x28282828u;  // four copies of index 40 (the all-zero pattern)
 constexpr int kMaxDim = 1 << 24;
 constexpr int kBlockLookups = 64;            // INT16 block size B for g = 4 (Sec. 3.4)
@@ -257,28 +256,37 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const int8_t* __restrict
 
 // ---------------------------------------------------------------------------------------------
 // The lookup kernel (Alg. 1 main loop + streamed Precompute, Sec. 3.4).
-//   R       row groups (of 4 output rows) per wave; workgroup tile = up to 64*R rows
+//
+// Roles inside the 16-wave workgroup: waves 0..3 (one per SIMD) only BUILD tables, waves 4..15 only LOOK UP.
+// The four LDS slots are used as two halves of two slots each: while the lookup waves read one half, the build
+// waves fill the other half with the next two sub-table sets, and one barrier per half-stage hands the halves over.
+// The lookups are bound by VALU issue (one address permute + four packed adds per 16-byte table read), the build
+// by LDS write bandwidth, so the two overlap well.
+//   R       row groups (of 4 output rows) per lookup wave; workgroup tile = up to 48*R rows
 //   NEED32  more than 64 lookups per lane: widen INT16 block sums into INT32 every 16 stages
 //   MODE    kFast: tables built in LDS from the token-chunked INT8 activations (streamed, the hot path)
 //           kFromGlobal: LDS slots are filled from a table materialised by vlut_build_lut
 // ---------------------------------------------------------------------------------------------
 enum { kFast = 0, kFromGlobal = 2 };
+constexpr int kBuildWaves = 4;
+constexpr int kLookupWaves = kWaves - kBuildWaves;     // 12
+constexpr int kRoundRows = kLookupWaves * 4;           // 48 output rows per row-group round of the workgroup
 
-// Issues the table read of lookup number I of a stage (b-major: I = b*R + r).  Byte b of the row group's weight
-// dword is the row of slot b; the lane reads its 16-byte slice of that row (8 INT16 entries).
-template <int R, int I>
+// Issues the table read of lookup number I of half-stage HALF (b-major: I = b*R + r, b = 0,1).  Byte 2*HALF + b of
+// the row group's weight dword is the row of slot 2*HALF + b; the lane reads its 16-byte slice (8 INT16 entries).
+template <int R, int HALF, int I>
 __device__ __forceinline__ i32x4 lookup_read(const unsigned (&w)[R], unsigned lanebase) {
-    constexpr int b = I / R, r = I % R;
-    constexpr unsigned sel = 0x0c0c0000u | ((4u + (unsigned)b) << 8);
+    constexpr int slot = 2 * HALF + I / R, r = I % R;
+    constexpr unsigned sel = 0x0c0c0000u | ((4u + (unsigned)slot) << 8);
     const unsigned addr = __builtin_amdgcn_perm(w[r], lanebase, sel);   // idx*256 + slice*16
-    return lds_read128<b * (kSlotBytes / 16)>(addr);
+    return lds_read128<slot * (kSlotBytes / 16)>(addr);
 }
 
 template <int R, int I>
 __device__ __forceinline__ void lookup_accumulate(s16x2 (&acc16)[R][4], const i32x4 v) {
     constexpr int r = I % R;
     // Written as instructions with the accumulator tied to one register ("+v"): left to the register allocator, the
-    // two unrolled copies of the stage keep the accumulators in two alternating register sets, which doubles their
+    // unrolled copies of the stage keep the accumulators in alternating register sets, which doubles their
     // footprint and caps the row groups a wave can hold.
     asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][0]) : "v"(v.x));
     asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][1]) : "v"(v.y));
@@ -286,42 +294,43 @@ __device__ __forceinline__ void lookup_accumulate(s16x2 (&acc16)[R][4], const i3
     asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][3]) : "v"(v.w));
 }
 
-// The 4*R lookups of a stage, software pipelined in batches of NB: the reads of batch k+1 are in flight while the
-// packed INT16 adds of batch k issue (Alg. 1 lines 3-6: one shared index, one vector add over the tokens).
-template <int R, int NB, int K0>
+// The 2*R lookups of a half-stage, software pipelined in batches of NB: the reads of batch k+1 are in flight while
+// the packed INT16 adds of batch k issue (Alg. 1 lines 3-6: one shared index, one vector add over the tokens).
+template <int R, int HALF, int NB, int K0>
 __device__ __forceinline__ void lookup_batches(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4],
                                                i32x4 (&cur)[NB]) {
-    constexpr int total = 4 * R;
+    constexpr int total = 2 * R;
     if constexpr (K0 < total) {
         i32x4 nxt[NB];
 #pragma unroll
         for (int i = 0; i < NB; ++i) nxt[i] = i32x4{0, 0, 0, 0};
-        // reads of the next batch
-        if constexpr (K0 + NB + 0 < total && NB > 0) nxt[0] = lookup_read<R, (K0 + NB + 0 < total ? K0 + NB + 0 : 0)>(w, lanebase);
-        if constexpr (K0 + NB + 1 < total && NB > 1) nxt[1] = lookup_read<R, (K0 + NB + 1 < total ? K0 + NB + 1 : 0)>(w, lanebase);
-        if constexpr (K0 + NB + 2 < total && NB > 2) nxt[2] = lookup_read<R, (K0 + NB + 2 < total ? K0 + NB + 2 : 0)>(w, lanebase);
-        if constexpr (K0 + NB + 3 < total && NB > 3) nxt[3] = lookup_read<R, (K0 + NB + 3 < total ? K0 + NB + 3 : 0)>(w, lanebase);
+        if constexpr (K0 + NB + 0 < total && NB > 0) nxt[0] = lookup_read<R, HALF, (K0 + NB + 0 < total ? K0 + NB + 0 : 0)>(w, lanebase);
+        if constexpr (K0 + NB + 1 < total && NB > 1) nxt[1] = lookup_read<R, HALF, (K0 + NB + 1 < total ? K0 + NB + 1 : 0)>(w, lanebase);
+        if constexpr (K0 + NB + 2 < total && NB > 2) nxt[2] = lookup_read<R, HALF, (K0 + NB + 2 < total ? K0 + NB + 2 : 0)>(w, lanebase);
+        if constexpr (K0 + NB + 3 < total && NB > 3) nxt[3] = lookup_read<R, HALF, (K0 + NB + 3 < total ? K0 + NB + 3 : 0)>(w, lanebase);
         __builtin_amdgcn_sched_barrier(0);
-        // adds of the current batch
         if constexpr (K0 + 0 < total && NB > 0) lookup_accumulate<R, (K0 + 0 < total ? K0 + 0 : 0)>(acc16, cur[0]);
         if constexpr (K0 + 1 < total && NB > 1) lookup_accumulate<R, (K0 + 1 < total ? K0 + 1 : 0)>(acc16, cur[1]);
         if constexpr (K0 + 2 < total && NB > 2) lookup_accumulate<R, (K0 + 2 < total ? K0 + 2 : 0)>(acc16, cur[2]);
         if constexpr (K0 + 3 < total && NB > 3) lookup_accumulate<R, (K0 + 3 < total ? K0 + 3 : 0)>(acc16, cur[3]);
         __builtin_amdgcn_sched_barrier(0);
-        lookup_batches<R, NB, K0 + NB>(w, lanebase, acc16, nxt);
+        lookup_batches<R, HALF, NB, K0 + NB>(w, lanebase, acc16, nxt);
     }
 }
 
-template <int R>
-__device__ __forceinline__ void lookup_stage(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4]) {
+template <int R, int HALF>
+__device__ __forceinline__ void lookup_half(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4]) {
     constexpr int NB = 4;
+    constexpr int total = 2 * R;
     i32x4 first[NB];
-    first[0] = lookup_read<R, 0>(w, lanebase);
-    first[1] = lookup_read<R, 1>(w, lanebase);
-    first[2] = lookup_read<R, 2>(w, lanebase);
-    first[3] = lookup_read<R, 3>(w, lanebase);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) first[i] = i32x4{0, 0, 0, 0};
+    first[0] = lookup_read<R, HALF, 0>(w, lanebase);
+    if constexpr (total > 1) first[1] = lookup_read<R, HALF, 1>(w, lanebase);
+    if constexpr (total > 2) first[2] = lookup_read<R, HALF, (total > 2 ? 2 : 0)>(w, lanebase);
+    if constexpr (total > 3) first[3] = lookup_read<R, HALF, (total > 3 ? 3 : 0)>(w, lanebase);
     __builtin_amdgcn_sched_barrier(0);
-    lookup_batches<R, NB, 0>(w, lanebase, acc16, first);
+    lookup_batches<R, HALF, NB, 0>(w, lanebase, acc16, first);
 }
 
 // Nine table rows that share their two leading digits (b1 = their common part): the third and fourth digits add or
@@ -372,59 +381,21 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     const int n0 = nt * n_tile;
     const int rgw0 = mt * p.RGW;          // first row group of this workgroup
 
-    // ---- lookup role of this lane
-    const int l = lane & 15;
+    const int l = lane & 15;             // 16-byte slice of the table rows this lane reads or writes
     const int grp = lane >> 4;
-    const int j = l >> TClog;
-    const int t = l & ((1 << TClog) - 1);
+    const int j = l >> TClog;            // sub-table selector of the slice
+    const int t = l & ((1 << TClog) - 1);   // 8-token chunk of the slice
     const unsigned lanebase = (unsigned)l * 16u;
 
     const int st_begin = ks * p.stages_per_split;
     const int st_end = min(p.stages_total, st_begin + p.stages_per_split);
+    const bool builder = wave < kBuildWaves;          // scalar condition
+    const int lw = wave - kBuildWaves;                // index among the lookup waves
 
-    // Row group r of this wave: its packed tiles start at a wave-uniform address (scalar registers); the lane
-    // adds its row (grp) and, per stage, the tile and dword it needs.
-    const unsigned char* wbase[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int rgl = r * kWaves + wave;     // r-major: round r of the epilogue covers 64 consecutive rows
-        const int rg = rgw0 + rgl;
-        const bool valid = (rgl < p.RGW) && (rg < p.RGtotal);
-        wbase[r] = p.packed + ((size_t)(valid ? rg : 0) * p.KCn) * 64;
-    }
-
-    // ---- build role (waves 0..8): slot bb, slice lb, leading digits hh = 3*d0 + d1 (9 table rows per task).
-    // Filling the slots is bound by LDS write bandwidth (~75 B/clk/CU); one wave can only issue a 1 KB write every
-    // ~60 clocks, so the work is spread over nine waves with nine writes each.
-    const bool builder = wave < kBuilders / 64;   // wave-uniform (scalar) condition
-    const int lb = tid & 15;
-    const int bq = tid >> 4;
-    const int bb = bq / 9;
-    const int hh = bq - bb * 9;
-    const int jb = lb >> TClog;
-    const int tb = lb & ((1 << TClog) - 1);
-    const int nb = n0 + 8 * tb;          // first token of the builder's slice
-    unsigned act[4][2];
-    bool act_valid = false;
-
-    // Loads for the NEXT stage's tables: the 4 activation rows of the task's sub-table for its 8 tokens are 32
-    // contiguous bytes of the token-chunked layout.  Branch-free (address clamped into the tensor, validity applied
-    // when the values are used) so that nothing has to wait for the data before the next build phase.
-    const int chunk_b = nb >> 3;
-    auto prefetch_act = [&](int st, unsigned (&act)[4][2], bool& act_valid) {
-        const int kg = st * 4 * J + 4 * jb + bb;
-        act_valid = (kg < p.G) && (nb < p.N);
-        if (MODE == kFast) {
-            const int kgc = min(kg, p.G - 1);
-            const int cc = (nb < p.N) ? chunk_b : 0;
-            const i32x4* src = (const i32x4*)(p.a_q + ((size_t)cc * p.K + 4 * kgc) * 8);
-            const i32x4 v0 = src[0], v1 = src[1];
-            act[0][0] = (unsigned)v0.x; act[0][1] = (unsigned)v0.y;
-            act[1][0] = (unsigned)v0.z; act[1][1] = (unsigned)v0.w;
-            act[2][0] = (unsigned)v1.x; act[2][1] = (unsigned)v1.y;
-            act[3][0] = (unsigned)v1.z; act[3][1] = (unsigned)v1.w;
-        }
-    };
+    // Output scale of every token of the tile, parked behind the tables (read in the epilogue).
+    typedef __attribute__((address_space(3))) float lds_f32;
+    lds_f32* scale_lds = (lds_f32*)(unsigned)kTableBytes;
+    if (tid < n_tile) scale_lds[tid] = (n0 + tid < p.N) ? p.w_scale * p.a_scale[n0 + tid] : 0.0f;
 
     s16x2 acc16[R][4];
     int acc32[NEED32 ? R : 1][8];
@@ -439,37 +410,44 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
             for (int e = 0; e < 8; ++e) acc32[r][e] = 0;
     }
 
-    // Output scale of every token of the tile, parked behind the tables (read in the epilogue).
-    typedef __attribute__((address_space(3))) float lds_f32;
-    lds_f32* scale_lds = (lds_f32*)(unsigned)kTableBytes;
-    if (tid < n_tile) scale_lds[tid] = (n0 + tid < p.N) ? p.w_scale * p.a_scale[n0 + tid] : 0.0f;
+    if (builder) {
+        // ================================ build role ================================
+        // Task of a lane for one half-stage: slot s2 of the half (0/1), slice l, leading digits hh = u (table rows
+        // 9u .. 9u+8); the ninth digit pair (rows 72..80) is shared out one row per lane, lane u = 0 takes two.
+        const int u = (wave * 4 + grp) & 7;
+        const int s2 = (wave * 4 + grp) >> 3;
+        const int nb = n0 + 8 * t;                   // first token of the slice
+        const int chunk_b = nb >> 3;
+        unsigned actA[4][2], actB[4][2];
+        bool validA = false, validB = false;
 
-    if (builder && st_begin < st_end) prefetch_act(st_begin, act, act_valid);
+        // Half-stage hs = 2*stage + half holds slots 2*half, 2*half+1 = sub-tables kg = stage*4J + 4j + slot.
+        auto fetch_act = [&](int hs, unsigned (&act)[4][2], bool& valid) {
+            const int kg = (hs >> 1) * 4 * J + 4 * j + 2 * (hs & 1) + s2;
+            valid = (hs < 2 * st_end) && (kg < p.G) && (nb < p.N);
+            if (MODE == kFast) {
+                // 4 activation rows x 8 tokens = 32 contiguous bytes of the token-chunked layout; branch-free
+                // (address clamped into the tensor, validity applied at use) so nothing waits on the data early.
+                const int kgc = min(kg, p.G - 1);
+                const int cc = (nb < p.N) ? chunk_b : 0;
+                const i32x4* src = (const i32x4*)(p.a_q + ((size_t)cc * p.K + 4 * kgc) * 8);
+                const i32x4 v0 = src[0], v1 = src[1];
+                act[0][0] = (unsigned)v0.x; act[0][1] = (unsigned)v0.y;
+                act[1][0] = (unsigned)v0.z; act[1][1] = (unsigned)v0.w;
+                act[2][0] = (unsigned)v1.x; act[2][1] = (unsigned)v1.y;
+                act[3][0] = (unsigned)v1.z; act[3][1] = (unsigned)v1.w;
+            }
+        };
 
-    // Weight dwords (4 lookups each) are fetched one whole stage ahead into the buffer the next stage reads, so
-    // their HBM latency hides behind a full build + lookup phase.  Dword q = st*J + j of each row.
-    // Out-of-range cases need no masking: a tile index past the end of K is clamped to the last tile and meets
-    // tables built from zero activations, and rows past M are clamped to row group 0 and never stored.
-    auto load_weights = [&](int st, unsigned (&wdst)[R]) {
-        const int q = st * J + j;
-        const int kc = min(q >> 2, p.KCn - 1);
-        const unsigned voff = (unsigned)(kc * 64 + grp * 16 + (q & 3) * 4);
-#pragma unroll
-        for (int r = 0; r < R; ++r) wdst[r] = *(const unsigned*)(wbase[r] + voff);
-    };
-
-    auto stage = [&](int st, unsigned (&w)[R], unsigned (&wnext)[R]) {
-
-        // ---- fill the 4 slots of this stage
-        if (builder) {
-            const unsigned dst = (unsigned)bb * kSlotBytes + (unsigned)(9 * hh) * kRowBytes + (unsigned)lb * 16u;
+        auto build_half = [&](int hs, unsigned (&act)[4][2], bool valid) {
+            const unsigned slot = (unsigned)(2 * (hs & 1) + s2);
+            const unsigned dst = slot * kSlotBytes + (unsigned)l * 16u;
             if (MODE == kFromGlobal) {
-                const int kg = st * 4 * J + 4 * jb + bb;
-#pragma unroll
-                for (int i = 0; i < 9; ++i) {
+                const int kg = (hs >> 1) * 4 * J + 4 * j + 2 * (hs & 1) + s2;
+                auto copy_row = [&](int row) {
                     i32x4 v = {0, 0, 0, 0};
                     if (kg < p.G && nb < p.N) {
-                        const int16_t* src = p.lut + ((size_t)kg * kRows + 9 * hh + i) * p.N + nb;
+                        const int16_t* src = p.lut + ((size_t)kg * kRows + row) * p.N + nb;
                         if (p.aligned8 && nb + 8 <= p.N) {
                             v = *(const i32x4*)src;
                         } else {
@@ -482,71 +460,125 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                             v = i32x4{tmp[0], tmp[1], tmp[2], tmp[3]};
                         }
                     }
-                    lds_write128<0>(dst + (unsigned)i * kRowBytes, v);
-                }
+                    lds_write128<0>(dst + (unsigned)row * kRowBytes, v);
+                };
+#pragma unroll
+                for (int i = 0; i < 9; ++i) copy_row(9 * u + i);
+                copy_row(72 + u);
+                if (u == 0) copy_row(80);
             } else {
-                // rows 9*hh .. 9*hh+8 of the sub-table: two leading digits fixed per task, the other two enumerated;
-                // every row is one packed add/sub away from an earlier one (topological order, Sec. 4).
-                if (!act_valid) {
+                // Every row is one packed add/sub away from an earlier one (topological order, Sec. 4).
+                if (!valid) {
 #pragma unroll
                     for (int c = 0; c < 4; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
                 }
-                const short s0 = (short)(hh / 3 - 1), s1 = (short)(hh % 3 - 1);
+                const short s0 = (short)(u / 3 - 1), s1 = (short)(u % 3 - 1);
                 const s16x2 m0 = {s0, s0}, m1 = {s1, s1};
-                s16x2 a2[4], a3[4], b1[4];
+                const short e2 = (short)(u / 3 - 1), e3 = (short)(u % 3 - 1);    // digits (d2,d3) of the extra row 72+u
+                const s16x2 x2 = {e2, e2}, x3 = {e3, e3};
+                s16x2 a2[4], a3[4], b1[4], ex[4], top[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    b1[q] = unpack_pair(act[0][q >> 1], q & 1) * m0 + unpack_pair(act[1][q >> 1], q & 1) * m1;
+                    const s16x2 a0 = unpack_pair(act[0][q >> 1], q & 1);
+                    const s16x2 a1 = unpack_pair(act[1][q >> 1], q & 1);
                     a2[q] = unpack_pair(act[2][q >> 1], q & 1);
                     a3[q] = unpack_pair(act[3][q >> 1], q & 1);
+                    b1[q] = a0 * m0 + a1 * m1;
+                    top[q] = a0 + a1;                               // leading digits (2,2)
+                    ex[q] = top[q] + a2[q] * x2 + a3[q] * x3;       // row 72 + 3*d2 + d3 with (d2,d3) = (u/3, u%3)
                 }
-                build_rows9(dst, b1, a2, a3);
+                build_rows9(dst + (unsigned)(9 * u) * kRowBytes, b1, a2, a3);
+                lds_write128<0>(dst + (unsigned)(72 + u) * kRowBytes,
+                                i32x4{as_int(ex[0]), as_int(ex[1]), as_int(ex[2]), as_int(ex[3])});
+                if (u == 0) {
+                    lds_write128<80 * 16>(dst, i32x4{as_int(top[0] + a2[0] + a3[0]), as_int(top[1] + a2[1] + a3[1]),
+                                                      as_int(top[2] + a2[2] + a3[2]), as_int(top[3] + a2[3] + a3[3])});
+                }
             }
-            if (st + 1 < st_end) prefetch_act(st + 1, act, act_valid);   // lands during this stage's lookups
+        };
+
+        const int hs0 = 2 * st_begin, hs1 = 2 * st_end;
+        if (hs0 < hs1) {
+            fetch_act(hs0, actA, validA);
+            fetch_act(hs0 + 1, actB, validB);
+            build_half(hs0, actA, validA);
+            fetch_act(hs0 + 2, actA, validA);
         }
-        // Prefetch of the next stage's weights, placed after the build: a wave issues in order and the CU's
-        // vector-memory queue is busy with everybody's loads here, so loads in front of the build would delay the
-        // phase every other wave is waiting for.  The other waves reach this point immediately.
-        load_weights(st + 1, wnext);
         wg_barrier_lds();
-
-        // ---- 4 lookups per row group: byte b of the weight dword selects the row of slot b
-        lookup_stage<R>(w, lanebase, acc16);
-        wg_barrier_lds();
-
-        if (NEED32 && (((st - st_begin) & 15) == 15)) {   // 16 stages x 4 lookups = block of 64
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    acc32[r][2 * q] += (int)acc16[r][q].x;
-                    acc32[r][2 * q + 1] += (int)acc16[r][q].y;
-                    acc16[r][q] = s16x2{0, 0};
-                }
+        for (int hs = hs0; hs < hs1; hs += 2) {
+            // lookups read half 0 now: fill half 1 (hs + 1), then fetch what half 1 will hold two steps later
+            build_half(hs + 1, actB, validB);
+            fetch_act(hs + 3, actB, validB);
+            wg_barrier_lds();
+            // lookups read half 1 now: fill half 0 with hs + 2
+            if (hs + 2 < hs1) {
+                build_half(hs + 2, actA, validA);
+                fetch_act(hs + 4, actA, validA);
+            }
+            wg_barrier_lds();
         }
-    };
-
-    unsigned wa[R], wb[R];
-    load_weights(st_begin, wa);
-    for (int st = st_begin; st < st_end; st += 2) {
-        stage(st, wa, wb);
-        if (st + 1 < st_end) stage(st + 1, wb, wa);
+    } else {
+        // ================================ lookup role ================================
+        // Row group r of this wave: its packed tiles start at a wave-uniform address (scalar registers); the lane
+        // adds its row (grp) and, per stage, the tile and dword it needs.
+        const unsigned char* wbase[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int rgl = r * kLookupWaves + lw;   // r-major: round r of the epilogue covers 48 consecutive rows
+            const int rg = rgw0 + rgl;
+            const bool valid = (rgl < p.RGW) && (rg < p.RGtotal);
+            wbase[r] = p.packed + ((size_t)(valid ? rg : 0) * p.KCn) * 64;
+        }
+        // Weight dwords (4 lookups each) are fetched one whole stage ahead.  Dword q = st*J + j of each row.
+        // Out-of-range cases need no masking: a tile index past the end of K is clamped to the last tile and meets
+        // tables built from zero activations, and rows past M are clamped to row group 0 and never stored.
+        auto load_weights = [&](int st, unsigned (&wdst)[R]) {
+            const int q = st * J + j;
+            const int kc = min(q >> 2, p.KCn - 1);
+            const unsigned voff = (unsigned)(kc * 64 + grp * 16 + (q & 3) * 4);
+#pragma unroll
+            for (int r = 0; r < R; ++r) wdst[r] = *(const unsigned*)(wbase[r] + voff);
+        };
+        auto stage = [&](int st, unsigned (&w)[R], unsigned (&wnext)[R]) {
+            load_weights(st + 1, wnext);
+            lookup_half<R, 0>(w, lanebase, acc16);
+            wg_barrier_lds();
+            lookup_half<R, 1>(w, lanebase, acc16);
+            wg_barrier_lds();
+            if (NEED32 && (((st - st_begin) & 15) == 15)) {   // 16 stages x 4 lookups = block of 64 (Sec. 3.4)
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        acc32[r][2 * q] += (int)acc16[r][q].x;
+                        acc32[r][2 * q + 1] += (int)acc16[r][q].y;
+                        acc16[r][q] = s16x2{0, 0};
+                    }
+            }
+        };
+        unsigned wa[R], wb[R];
+        load_weights(st_begin, wa);
+        wg_barrier_lds();                      // half-stage 0 of the first stage is built
+        for (int st = st_begin; st < st_end; st += 2) {
+            stage(st, wa, wb);
+            if (st + 1 < st_end) stage(st + 1, wb, wa);
+        }
     }
 
     // ---- epilogue.  Per row group: widen to INT32, add the J partial sums of each token across the 16 lanes of
     // the group with a reduce-scatter (each step halves the tokens a lane keeps), park the sums in LDS as
-    // [token][row] and let the whole workgroup write 128 consecutive output rows per token.
+    // [token][row] and let the whole workgroup write consecutive output rows per token.
     lds_i32* park = (lds_i32*)0u;
     const int m0 = rgw0 * 4;
     const int rows_wg = min(p.RGW * 4, p.M - m0);
-    const int TC = 1 << TClog;
     // RC = row-group rounds parked per pass.  All R at once when the tile has few tokens (the R independent
-    // shuffle chains then overlap); two at a time when [tokens][rows] would not fit in LDS.
+    // reduction chains then overlap); two at a time when [tokens][rows] would not fit in LDS.
     auto epilogue = [&](auto rc_tag) {
     constexpr int RC = decltype(rc_tag)::value;
-    constexpr int kParkStride = RC * 64 + 4;                // ints per parked token; +4 keeps the writes conflict-free
+    constexpr int kParkStride = RC * kRoundRows + 4;        // ints per parked token; +4 keeps the writes conflict-free
 #pragma unroll
     for (int c0 = 0; c0 < R; c0 += RC) {
+        if (!builder) {
 #pragma unroll
         for (int rr = 0; rr < RC; ++rr) {
             const int r = c0 + rr;
@@ -594,20 +626,21 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                 }
                 const int cnt = 8 >> min(Jlog, 3);
                 if (owner) {
-                    const int col = rr * 64 + wave * 4 + grp;
+                    const int col = rr * kRoundRows + lw * 4 + grp;
 #pragma unroll
                     for (int e = 0; e < 8; ++e)
                         if (e < cnt) park[(8 * t + tokoff + e) * kParkStride + col] = v[e];
                 }
             }
         }
+        }
         wg_barrier_lds();
-        for (int i = tid; i < RC * 64 * n_tile; i += kThreads) {
-            const int col = i % (RC * 64);
-            const int nl = i / (RC * 64);
-            const int mrow = c0 * 64 + col;                 // row inside the workgroup tile
+        for (int i = tid; i < RC * kRoundRows * n_tile; i += kThreads) {
+            const int col = i % (RC * kRoundRows);
+            const int nl = i / (RC * kRoundRows);
+            const int mrow = c0 * kRoundRows + col;         // row inside the workgroup tile
             const int n = n0 + nl;
-            if (mrow < rows_wg && mrow < R * 64 && n < p.N) {
+            if (mrow < rows_wg && mrow < R * kRoundRows && n < p.N) {
                 const int val = park[nl * kParkStride + col];
                 const int m = m0 + mrow;
                 if (p.S == 1) {
@@ -621,7 +654,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         wg_barrier_lds();
     }
     };
-    if (n_tile * (R * 64 + 4) * 4 <= kTableBytes) epilogue(std::integral_constant<int, R>{});
+    if (n_tile * (R * kRoundRows + 4) * 4 <= kTableBytes) epilogue(std::integral_constant<int, R>{});
     else epilogue(std::integral_constant<int, (R > 1 ? 2 : 1)>{});
 }
 
@@ -649,7 +682,7 @@ struct Plan {
 
 thread_local Plan t_forced = {-1, 0, 0};
 
-const int kSupportedR[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12};
+const int kSupportedR[] = {1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 14};
 
 bool r_supported(int R) {
     for (int v : kSupportedR)
@@ -674,7 +707,7 @@ Derived derive(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     int J = 1 << pl.Jlog;
     d.n_tile = 128 >> pl.Jlog;
     d.tiles_n = (int)((N + d.n_tile - 1) / d.n_tile);
-    int cap = 16 * pl.R;                              // row groups a workgroup can hold
+    int cap = kLookupWaves * pl.R;                    // row groups a workgroup can hold
     d.tiles_m = (d.RGtotal + cap - 1) / cap;
     d.RGW = (d.RGtotal + d.tiles_m - 1) / d.tiles_m;  // balanced rows per workgroup
     d.stages_total = (d.G + 4 * J - 1) / (4 * J);
@@ -685,16 +718,16 @@ Derived derive(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     return d;
 }
 
-// Cost model in CU clocks, fitted to microbenchmarks of this chip: building one 81-row slot is bound by
-// LDS writes (~75 B/clk/CU -> ~280 clk per slot), one looked-up row of 128 (sub-table, token) pairs costs
-// ~1.3 clk (5 VALU issues per 4 rows per wave), and each stage pays two barriers.
+// Cost model in CU clocks, fitted to microbenchmarks of this chip.  Per stage (4 slots) the lookup waves issue, per
+// SIMD, 3 waves x 4 lookups x 5 VALU instructions per row group, next to ~230 VALU instructions of the SIMD's build
+// wave; the LDS pipe serves the table reads (~4.3 clk per wave read) and ~83 KB of table writes (~1400 clk).
 double plan_cost(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     Derived d = derive(pl, M, K, N);
-    double rows = 4.0 * d.RGW;
-    double rows_wave_max = 4.0 * ((d.RGW + kWaves - 1) / kWaves) * kWaves;   // slowest wave decides
-    (void)rows;
-    double stage = 4 * 280.0 + 4 * rows_wave_max * 1.3 + 150.0;
-    double wg = d.stages_per_split * stage + 2000.0 + (d.need32 ? 0.05 * d.stages_per_split * stage : 0.0);
+    double rw = (double)((d.RGW + kLookupWaves - 1) / kLookupWaves);   // row groups of the slowest lookup wave
+    double valu = 240.0 * rw + 920.0;
+    double lds = 206.0 * rw + 1400.0;
+    double stage = (valu > lds ? valu : lds) + 200.0;
+    double wg = d.stages_per_split * stage + 5000.0 + 700.0 * rw + (d.need32 ? 0.05 * d.stages_per_split * stage : 0.0);
     double rounds = (double)((d.total + 255) / 256);
     double t = rounds * wg;
     if (pl.S > 1) t += 3000.0 + (double)pl.S * (double)M * (double)N * 8.0 / (256.0 * 16.0);
@@ -706,7 +739,7 @@ double plan_cost(const Plan& pl, int64_t M, int64_t K, int64_t N) {
 bool plan_valid(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     if (pl.Jlog < 0 || pl.Jlog > 4 || !r_supported(pl.R) || pl.S < 1 || pl.S > 16) return false;
     Derived d = derive(pl, M, K, N);
-    if (d.need32 && pl.R > 4) return false;      // register budget of the INT32 variant
+    if (d.need32 && pl.R > 6) return false;      // register budget of the INT32 variant
     if (pl.S > d.stages_total) return false;
     return true;
 }
@@ -769,16 +802,19 @@ int launch_lookup_r(int R, int mode, const LookupParams& p, int grid, hipStream_
         case 2: return launch_lookup_t<2, NEED32, kFast>(p, grid, stream);
         case 3: return launch_lookup_t<3, NEED32, kFast>(p, grid, stream);
         case 4: return launch_lookup_t<4, NEED32, kFast>(p, grid, stream);
+        case 5: return launch_lookup_t<5, NEED32, kFast>(p, grid, stream);
+        case 6: return launch_lookup_t<6, NEED32, kFast>(p, grid, stream);
         default: break;
         }
         if constexpr (!NEED32) {
             switch (R) {
-            case 5: return launch_lookup_t<5, false, kFast>(p, grid, stream);
-            case 6: return launch_lookup_t<6, false, kFast>(p, grid, stream);
             case 7: return launch_lookup_t<7, false, kFast>(p, grid, stream);
             case 8: return launch_lookup_t<8, false, kFast>(p, grid, stream);
+            case 9: return launch_lookup_t<9, false, kFast>(p, grid, stream);
             case 10: return launch_lookup_t<10, false, kFast>(p, grid, stream);
+            case 11: return launch_lookup_t<11, false, kFast>(p, grid, stream);
             case 12: return launch_lookup_t<12, false, kFast>(p, grid, stream);
+            case 14: return launch_lookup_t<14, false, kFast>(p, grid, stream);
             default: break;
             }
         }

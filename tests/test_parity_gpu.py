@@ -137,14 +137,14 @@ def test_every_interleave_factor(B, J):
     run_case(B, W, s, x, plan=(J, 1, 0, 1), tag=f"J{J}-n7")
 
 
-@pytest.mark.parametrize("R", [1, 2, 3, 4, 5, 6, 7, 8, 10, 12])
+@pytest.mark.parametrize("R", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 14])
 def test_every_rows_per_wave(B, R):
-    M = 64 * R * 2 - 37                                     # two row tiles, the second one ragged
+    M = 48 * R * 2 - 37                                     # two row tiles, the second one ragged
     W, s, x = wl.small_case(20 + R, M, 512, 33)
     run_case(B, W, s, x, plan=(8, R, 0, 1), tag=f"R{R}")
 
 
-@pytest.mark.parametrize("J,R,S", [(1, 2, 1), (1, 4, 1), (2, 3, 1), (4, 4, 2), (16, 4, 3), (8, 2, 6)])
+@pytest.mark.parametrize("J,R,S", [(1, 2, 1), (1, 6, 1), (2, 3, 1), (4, 5, 2), (16, 4, 3), (8, 2, 6)])
 def test_int32_widening_and_split_k(B, J, R, S):
     # K = 4352 -> 1088 groups: more than 64 lookups per lane for small J, so the INT16 blocks get widened
     W, s, x = wl.small_case(30 + J + S, 300, 4352, 40)
