@@ -31,7 +31,7 @@ ALU_PEAK_TADDS = CUS * 64 * 2 * CLOCK_GHZ / 1e3          # 78.64 T INT16 adds/s
 LDS_PEAK_GBS = CUS * 256 * CLOCK_GHZ                      # 157286 GB/s
 
 # HBM bytes per launch of the lookup kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), see profiles/
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"bitnet2b_ffn_up": 10.86e6}   # profiles/lookup_kernel_bitnet2b_ffn_up_hbm_traffic.md
 
 
 def parse_args():
@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--no-rotate", action="store_true", help="keep one weight buffer (cache-warm weights)")
     ap.add_argument("--all", action="store_true", help="also time every benchmark shape (table on stderr)")
     ap.add_argument("--plan", default="", help="force J,R,S for the lookup kernel (tuning)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one 64 MiB device-to-device copy (known size: the reference a rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE run of this command is scaled by)")
     return ap.parse_args()
 
 
@@ -213,6 +216,13 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, W, w_scale, x)
+
+    if args.copy_probe:
+        src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
 
     if args.all:
         rows = []
