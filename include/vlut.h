@@ -153,11 +153,15 @@ int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const f
                 const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y, int64_t ldy,
                 int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Bytes of scratch vlut_mpgemm_mfma needs: a [tokens padded to 16][K padded to 64] INT8 copy of the activations. */
+size_t vlut_mfma_workspace_bytes(int64_t M, int64_t K, int64_t N);
+
 /*
  * Same contract and same results as vlut_mpgemm (lut_or_null must be NULL), but
  * computed the multiply-add way the paper contrasts with (Sec. 2.2.1): packed
  * bytes are unpacked to INT8 and multiplied on the INT8 matrix cores.  In-run
- * comparison only.
+ * comparison only.  workspace is required: 16-byte aligned,
+ * workspace_bytes >= vlut_mfma_workspace_bytes(M, K, N).
  */
 int vlut_mpgemm_mfma(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale,
                      const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y,

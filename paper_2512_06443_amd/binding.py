@@ -24,7 +24,7 @@ EXPORTS = [
     "vlut_status_string", "vlut_version", "vlut_packed_weight_bytes", "vlut_packed_offset", "vlut_act_bytes",
     "vlut_lut_bytes",
     "vlut_workspace_bytes", "vlut_pack_weights", "vlut_quantize_act", "vlut_build_lut", "vlut_mpgemm",
-    "vlut_mpgemm_mfma", "vlut_set_plan", "vlut_query_plan",
+    "vlut_mpgemm_mfma", "vlut_mfma_workspace_bytes", "vlut_set_plan", "vlut_query_plan",
 ]
 
 _lib = None
@@ -51,6 +51,7 @@ def lib() -> ctypes.CDLL:
         L.vlut_act_bytes.argtypes, L.vlut_act_bytes.restype = [i64, i64], sz
         L.vlut_lut_bytes.argtypes, L.vlut_lut_bytes.restype = [i64, i64], sz
         L.vlut_workspace_bytes.argtypes, L.vlut_workspace_bytes.restype = [i64, i64, i64], sz
+        L.vlut_mfma_workspace_bytes.argtypes, L.vlut_mfma_workspace_bytes.restype = [i64, i64, i64], sz
         L.vlut_pack_weights.argtypes, L.vlut_pack_weights.restype = [p, i64, i64, p, sz, p], ci
         L.vlut_quantize_act.argtypes, L.vlut_quantize_act.restype = [p, i64, i64, i64, p, p, p], ci
         L.vlut_build_lut.argtypes, L.vlut_build_lut.restype = [p, i64, i64, p, sz, p], ci
@@ -160,7 +161,7 @@ def mpgemm(packed: torch.Tensor, w_scale: float, a_q: torch.Tensor, a_scale: tor
         y = torch.empty((N, M), dtype=torch.float32, device=dev)
     if acc is None and want_acc:
         acc = torch.empty((M, N), dtype=torch.int32, device=dev)
-    ws_bytes = workspace_bytes(M, K, N)
+    ws_bytes = lib().vlut_mfma_workspace_bytes(M, K, N) if mfma else workspace_bytes(M, K, N)
     if workspace is None and ws_bytes:
         workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     fn = lib().vlut_mpgemm_mfma if mfma else lib().vlut_mpgemm

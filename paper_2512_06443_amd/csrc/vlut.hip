@@ -658,6 +658,93 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     else epilogue(std::integral_constant<int, (R > 1 ? 2 : 1)>{});
 }
 
+// ---------------------------------------------------------------------------------------------
+// Comparison path (not the method): the multiply-add way of Sec. 2.2.1 on the INT8 matrix cores.
+// Packed bytes are unpacked to four INT8 weights through an 81-entry table in LDS and multiplied with
+// v_mfma_i32_16x16x64_i8.  Activations are first copied to a [tokens][K] layout (k contiguous) so that a
+// lane's 16 consecutive k of one token are one 16-byte load.
+// ---------------------------------------------------------------------------------------------
+// a_q token-chunked [N/8][K][8] -> aT [Npad][Kp], Npad = multiple of 16 >= N, Kp = multiple of 64 >= K, zero padded.
+__global__ void __launch_bounds__(256) act_transpose_kernel(const int8_t* __restrict__ a_q, int N, int K, int Npad, int Kp,
+                                                            int8_t* __restrict__ aT) {
+    const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;     // one dword (4 k) of aT per thread
+    const int kq = Kp / 4;
+    if (i >= (size_t)Npad * kq) return;
+    const int n = (int)(i / kq);
+    const int k = (int)(i % kq) * 4;
+    unsigned v = 0;
+    if (n < N) {
+        const int8_t* src = a_q + ((size_t)(n >> 3) * K) * 8 + (n & 7);
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (k + c < K) v |= (unsigned)(uint8_t)src[(size_t)(k + c) * 8] << (8 * c);
+    }
+    *(unsigned*)(aT + (size_t)n * Kp + k) = v;
+}
+
+struct MfmaParams {
+    const uint8_t* packed;
+    const int8_t* aT;
+    const float* a_scale;
+    float* y;
+    int32_t* acc;
+    float w_scale;
+    int M, N, Npad, Kp, KCn, RGtotal, ldy;
+};
+
+// One workgroup = 4 waves x 16 output rows; each wave multiplies its 16 x Kp weight strip with NT tiles of 16 tokens.
+template <int NT>
+__global__ void __launch_bounds__(256) mfma_kernel(const MfmaParams p) {
+    __shared__ unsigned dec[kRows];            // index -> four INT8 weights (first weight in the low byte)
+    const int tid = threadIdx.x;
+    if (tid < kRows) {
+        const int d0 = tid / 27, d1 = (tid / 9) % 3, d2 = (tid / 3) % 3, d3 = tid % 3;
+        dec[tid] = ((unsigned)(d0 - 1) & 0xffu) | (((unsigned)(d1 - 1) & 0xffu) << 8) | (((unsigned)(d2 - 1) & 0xffu) << 16) |
+                   (((unsigned)(d3 - 1) & 0xffu) << 24);
+    }
+    __syncthreads();
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int i = lane & 15;                   // row of the A tile / token of the B tile / column of the C tile
+    const int kblk = lane >> 4;                // which 16 of the 64 k of a step this lane holds (same for A and B)
+    const int m_row = blockIdx.x * 64 + wave * 16 + i;
+    const int n0 = blockIdx.y * 16 * NT;
+    const int mc = min(m_row, p.RGtotal * 4 - 1);          // rows past the padded matrix read row data that is discarded
+    const unsigned char* arow = p.packed + ((size_t)(mc >> 2) * p.KCn) * 64 + (mc & 3) * 16 + kblk * 4;
+    const int8_t* brow[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) brow[t] = p.aT + (size_t)min(n0 + 16 * t + i, p.Npad - 1) * p.Kp + kblk * 16;
+    i32x4 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = i32x4{0, 0, 0, 0};
+    for (int ks = 0; ks < p.KCn; ++ks) {
+        const unsigned w = *(const unsigned*)(arow + (size_t)ks * 64);
+        const i32x4 a = {(int)dec[w & 0xffu], (int)dec[(w >> 8) & 0xffu], (int)dec[(w >> 16) & 0xffu], (int)dec[w >> 24]};
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const i32x4 b = *(const i32x4*)(brow[t] + (size_t)ks * 64);
+            acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[t], 0, 0, 0);
+        }
+    }
+    // C tile: lane (column = token i, row block kblk) holds rows 4*kblk .. 4*kblk+3
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int n = n0 + 16 * t + i;
+        if (n < p.N) {
+            const float sc = p.w_scale * p.a_scale[n];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int m = blockIdx.x * 64 + wave * 16 + 4 * kblk + r;
+                if (m < p.M) {
+                    const int v = acc[t][r];
+                    if (p.y) p.y[(size_t)n * p.ldy + m] = (float)v * sc;
+                    if (p.acc) p.acc[(size_t)m * p.N + n] = v;
+                }
+            }
+        }
+    }
+}
+
 // Sum of the split-K partials (any order is exact: integers) + scale step.
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const int32_t* __restrict__ ws, int S, int M, int N,
                                                             float w_scale, const float* __restrict__ a_scale,
@@ -1011,14 +1098,35 @@ int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const f
     return VLUT_OK;
 }
 
+size_t vlut_mfma_workspace_bytes(int64_t M, int64_t K, int64_t N) {
+    if (!shape_ok(M, K, N)) return 0;
+    return (size_t)((N + 15) / 16 * 16) * (size_t)((K + 63) / 64 * 64);
+}
+
 int vlut_mpgemm_mfma(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale,
                      const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y, int64_t ldy,
                      int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream) {
-    (void)workspace; (void)workspace_bytes; (void)stream; (void)w_scale;
     int rc = check_mpgemm_args(packed, a_q, a_scale, M, K, N, y, ldy, acc_or_null);
     if (rc != VLUT_OK) return rc;
     if (lut_or_null) return VLUT_ERR_UNSUPPORTED;
-    return VLUT_ERR_UNSUPPORTED;
+    if (!workspace) return VLUT_ERR_NULL;
+    if (workspace_bytes < vlut_mfma_workspace_bytes(M, K, N)) return VLUT_ERR_SMALL_BUFFER;
+    if (((uintptr_t)workspace) % 16 != 0) return VLUT_ERR_UNSUPPORTED;
+    hipStream_t s = (hipStream_t)stream;
+    MfmaParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.packed = packed; p.aT = (const int8_t*)workspace; p.a_scale = a_scale; p.y = y; p.acc = acc_or_null;
+    p.w_scale = w_scale; p.M = (int)M; p.N = (int)N; p.Npad = (int)((N + 15) / 16 * 16); p.Kp = (int)((K + 63) / 64 * 64);
+    p.KCn = (int)((K / 4 + 15) / 16); p.RGtotal = (int)((M + 3) / 4); p.ldy = (int)ldy;
+    const size_t dwords = (size_t)p.Npad * (p.Kp / 4);
+    hipLaunchKernelGGL(act_transpose_kernel, dim3((unsigned)((dwords + 255) / 256)), dim3(256), 0, s, a_q, (int)N, (int)K, p.Npad,
+                       p.Kp, (int8_t*)workspace);
+    if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
+    const unsigned gx = (unsigned)((M + 63) / 64);
+    if (N <= 16) hipLaunchKernelGGL(mfma_kernel<1>, dim3(gx, (unsigned)(p.Npad / 16)), dim3(256), 0, s, p);
+    else if (N <= 32) hipLaunchKernelGGL(mfma_kernel<2>, dim3(gx, (unsigned)((p.Npad + 31) / 32)), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(mfma_kernel<4>, dim3(gx, (unsigned)((p.Npad + 63) / 64)), dim3(256), 0, s, p);
+    return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
 
 }  // extern "C"

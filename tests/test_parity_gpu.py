@@ -164,6 +164,20 @@ def test_int16_block_is_overflow_free_at_the_extremes(B):
     assert np.all(np.abs(q) == 127)
 
 
+@pytest.mark.parametrize("M,K,N", [(256, 256, 8), (257, 260, 130), (70, 1024, 7), (640, 2560, 1), (300, 4352, 40),
+                                    (1000, 2560, 128), (64, 64, 16), (129, 68, 33)])
+def test_mfma_comparison_path_is_exact_too(B, M, K, N):
+    print(f"mfma case M={M} K={K} N={N}", flush=True)
+    W, s, x = wl.small_case(100 + M + N, M, K, N)
+    q_ref, s_ref, acc_ref, y_ref = O.mpgemm(W, s, x)
+    packed = B.pack_weights(dev(W))
+    a_q, a_s = B.quantize_act(dev(x))
+    y, acc = B.mpgemm(packed, float(s), a_q, a_s, M, want_acc=True, mfma=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), acc_ref)
+    check_y(y.cpu().numpy(), y_ref)
+
+
 def test_special_weights(B):
     K, N = 256, 24
     x = wl.activations(40, N, K)
