@@ -75,12 +75,21 @@ class Case:
         self._gargs = [(pk.data_ptr(), self.w_scale, self.a_q.data_ptr(), self.a_s.data_ptr(), None, self.M, self.K,
                         self.N, self.y.data_ptr(), self.y.stride(0), None, self.ws.data_ptr(), self.ws.numel())
                        for pk in self.pool]
+        # the in-run comparison path (INT8 matrix cores) with its own scratch
+        self._mfma = L.vlut_mpgemm_mfma
+        self.mws = torch.empty(max(L.vlut_mfma_workspace_bytes(self.M, self.K, self.N), 16), dtype=torch.uint8, device="cuda")
+        self._margs = [(pk.data_ptr(), self.w_scale, self.a_q.data_ptr(), self.a_s.data_ptr(), None, self.M, self.K,
+                        self.N, self.y.data_ptr(), self.y.stride(0), None, self.mws.data_ptr(), self.mws.numel())
+                       for pk in self.pool]
 
     def quantize(self, stream):
         self._check(self._quant(*self._qargs, stream), "vlut_quantize_act")
 
     def gemm(self, i, stream):
         self._check(self._gemm(*self._gargs[i % len(self._gargs)], stream), "vlut_mpgemm")
+
+    def gemm_mfma(self, i, stream):
+        self._check(self._mfma(*self._margs[i % len(self._margs)], stream), "vlut_mpgemm_mfma")
 
     def step(self, i, stream):
         self.quantize(stream)
@@ -139,6 +148,12 @@ def time_case(B, torch, case, steps, warmup):
     return ms_step, ms_gemm, mode
 
 
+def time_mfma(torch, case, steps, warmup):
+    """GPU ms per vlut_mpgemm_mfma call (activation re-layout + INT8 matrix-core GEMM), same inputs."""
+    _, ms, _ = run_timed(torch, case.gemm_mfma, steps, warmup)
+    return ms
+
+
 def cpu_baseline(wl, W, w_scale, x):
     """The oracle as it stands on the host cores, on the same workload (one full pass, repeated to ~10 s)."""
     from oracle import oracle as O
@@ -188,6 +203,7 @@ def main():
         print("bench.py: output of the timed region differs from the reference launch", file=sys.stderr)
         sys.exit(4)
 
+    ms_mfma = time_mfma(torch, case, args.steps, args.warmup)
     ops = 2.0 * M * K * N
     adds = M * (K // 4) * N                      # one INT16 add (= 2 table bytes) per (row, group, token)
     gops = ops / (ms_step * 1e-3) / 1e9
@@ -203,6 +219,9 @@ def main():
                    "weight_pool_buffers": len(case.pool), "launch": mode},
         "weight_stream_GBs": (M * K / 4) / (ms_step * 1e-3) / 1e9,
         "algorithmic_GBs": wl.algorithmic_bytes(M, K, N) / (ms_step * 1e-3) / 1e9,
+        "mfma_comparison": {"what": "vlut_mpgemm_mfma on the same inputs (unpack to INT8 + v_mfma_i32_16x16x64_i8), "
+                                    "GPU ms per call incl. its activation re-layout kernel",
+                            "ms": ms_mfma, "lut_over_mfma_time": ms_kernel / ms_mfma},
         "roofline": {
             "kernel": "lookup_kernel (fused LDS table build + lookup-accumulate + epilogue)",
             "bound": "alu", "achieved": achieved_tadds, "peak": ALU_PEAK_TADDS, "unit": "TOP/s",
@@ -232,18 +251,19 @@ def main():
                     Wm, ws_, xm = wl.make_case(wk, linr, n, wk.seeds[0])
                     c = Case(B, torch, wl, Wm, ws_, xm, rotate)
                     st, km, _ = time_case(B, torch, c, max(20, args.steps // 4), 5)
+                    mf = time_mfma(torch, c, max(20, args.steps // 4), 5)
                     mm, kk = Wm.shape
                     a = mm * (kk // 4) * n
                     rows.append((name, linr.name, mm, kk, n, c.plan, st * 1e3, km * 1e3,
                                  2.0 * mm * kk * n / (st * 1e-3) / 1e12, a / (km * 1e-3) / 1e12 / ALU_PEAK_TADDS,
-                                 wl.algorithmic_bytes(mm, kk, n) / (km * 1e-3) / 1e9 / HBM_PEAK_GBS))
+                                 wl.algorithmic_bytes(mm, kk, n) / (km * 1e-3) / 1e9 / HBM_PEAK_GBS, mf * 1e3))
                     del c
                     torch.cuda.empty_cache()
         print(f"{'workload':18s} {'lin':7s} {'M':>6s} {'K':>6s} {'N':>5s} {'plan(J,R,S,WG)':>18s} {'step us':>9s} "
-              f"{'mpgemm us':>9s} {'TOPS':>7s} {'alu/lds frac':>12s} {'hbm frac':>8s}", file=sys.stderr)
+              f"{'mpgemm us':>9s} {'TOPS':>7s} {'alu/lds frac':>12s} {'hbm frac':>8s} {'mfma us':>8s}", file=sys.stderr)
         for r in rows:
             print(f"{r[0]:18s} {r[1]:7s} {r[2]:6d} {r[3]:6d} {r[4]:5d} {str(r[5]):>18s} {r[6]:9.1f} {r[7]:9.1f} "
-                  f"{r[8]:7.1f} {r[9]:12.3f} {r[10]:8.3f}", file=sys.stderr)
+                  f"{r[8]:7.1f} {r[9]:12.3f} {r[10]:8.3f} {r[11]:8.1f}", file=sys.stderr)
 
     print(json.dumps(out))
 
