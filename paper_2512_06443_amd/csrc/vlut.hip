@@ -37,9 +37,7 @@ constexpr int kRowBytes = 256;               // LDS bytes per table row (16 slic
 constexpr int kSlotBytes = kRows * kRowBytes;  // 20736
 constexpr int kStageSlots = 4;               // slots resident per stage (one weight dword = 4 lookups)
 constexpr int kTableBytes = kStageSlots * kSlotBytes;  // 82944
-constexpr int kFlagBase = kTableBytes + 128 * 4;    // hand-over counters of the two table halves (see lookup_kernel)
-constexpr int kLdsBytes = kFlagBase + 64;           // tables + the output scales of the tile's tokens + counters
-constexpr int kSpinLimit = 1 << 18;                 // bound of every wait loop: a wave always leaves it
+constexpr int kLdsBytes = kTableBytes + 128 * 4;    // + the output scales of the tile's tokens
 constexpr int kWaves = 16;                   // waves per workgroup
 constexpr int kThreads = kWaves * 64;
 constexpr unsigned kZeroIdx4 = 0x28282828u;  // four copies of index 40 (the all-zero pattern)
@@ -92,27 +90,6 @@ __device__ __forceinline__ int lane_xor16(int x) {
     }
     if (MASK == 2) return __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false);
     return __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false);
-}
-
-// Hand-over counters in LDS.  A wave finishes its own LDS traffic, then one lane adds 1; a waiting wave polls until
-// the counter reaches its target.  The poll loop is bounded, so every wave leaves it whatever happens.
-__device__ __forceinline__ void flag_signal(unsigned addr, int lane) {
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    if (lane == 0) __hip_atomic_fetch_add((lds_i32*)addr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-// For a wave that only read: its reads return in order, so once the data of the last one has been consumed nothing
-// of the half is outstanding and no wait is needed before the add.
-__device__ __forceinline__ void flag_signal_reader(unsigned addr, int lane) {
-    asm volatile("" ::: "memory");
-    if (lane == 0) __hip_atomic_fetch_add((lds_i32*)addr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-__device__ __forceinline__ void flag_wait(unsigned addr, int target) {
-    for (int spin = 0; spin < kSpinLimit; ++spin) {
-        const int v = __builtin_amdgcn_readfirstlane(*(volatile lds_i32*)addr);
-        if (v >= target) break;
-        __builtin_amdgcn_s_sleep(1);
-    }
-    asm volatile("" ::: "memory");
 }
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global load
@@ -282,8 +259,7 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const int8_t* __restrict
 //
 // Roles inside the 16-wave workgroup: waves 0..3 (one per SIMD) only BUILD tables, waves 4..15 only LOOK UP.
 // The four LDS slots are used as two halves of two slots each: while the lookup waves read one half, the build
-// waves fill the other half with the next two sub-table sets.  The halves are handed over with two pairs of LDS
-// counters (built / read-out), not with barriers, so no wave ever waits for the slowest one of the other role.
+// waves fill the other half with the next two sub-table sets, and one barrier per half-stage hands the halves over.
 // The lookups are bound by VALU issue (one address permute + four packed adds per 16-byte table read), the build
 // by LDS write bandwidth, so the two overlap well.
 //   R       row groups (of 4 output rows) per lookup wave; workgroup tile = up to 48*R rows
@@ -296,27 +272,16 @@ constexpr int kBuildWaves = 4;
 constexpr int kLookupWaves = kWaves - kBuildWaves;     // 12
 constexpr int kRoundRows = kLookupWaves * 4;           // 48 output rows per row-group round of the workgroup
 
-template <int V> using ic = std::integral_constant<int, V>;
-template <int I0, int I1, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-    if constexpr (I0 < I1) {
-        f(ic<I0>{});
-        static_for<I0 + 1, I1>(f);
-    }
-}
-
-// Issues the table read of lookup number I of a stage (slot-major: I = slot*R + r; slots 0,1 are the first half of
-// the LDS slots, 2,3 the second).  Byte `slot` of the row group's weight dword is the table row; the lane reads its
-// 16-byte slice (8 INT16 entries) of that row.
-template <int R, int I>
+// Issues the table read of lookup number I of half-stage HALF (b-major: I = b*R + r, b = 0,1).  Byte 2*HALF + b of
+// the row group's weight dword is the row of slot 2*HALF + b; the lane reads its 16-byte slice (8 INT16 entries).
+template <int R, int HALF, int I>
 __device__ __forceinline__ i32x4 lookup_read(const unsigned (&w)[R], unsigned lanebase) {
-    constexpr int slot = I / R, r = I % R;
+    constexpr int slot = 2 * HALF + I / R, r = I % R;
     constexpr unsigned sel = 0x0c0c0000u | ((4u + (unsigned)slot) << 8);
     const unsigned addr = __builtin_amdgcn_perm(w[r], lanebase, sel);   // idx*256 + slice*16
     return lds_read128<slot * (kSlotBytes / 16)>(addr);
 }
 
-// One lookup's vector add over the tokens (Alg. 1 lines 3-6), packed INT16.
 template <int R, int I>
 __device__ __forceinline__ void lookup_accumulate(s16x2 (&acc16)[R][4], const i32x4 v) {
     constexpr int r = I % R;
@@ -327,6 +292,67 @@ __device__ __forceinline__ void lookup_accumulate(s16x2 (&acc16)[R][4], const i3
     asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][1]) : "v"(v.y));
     asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][2]) : "v"(v.z));
     asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][3]) : "v"(v.w));
+}
+
+// The 2*R lookups of a half-stage, software pipelined in batches of NB: the reads of batch k+1 are in flight while
+// the packed INT16 adds of batch k issue (Alg. 1 lines 3-6: one shared index, one vector add over the tokens).
+template <int R, int HALF, int NB, int K0>
+__device__ __forceinline__ void lookup_batches(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4],
+                                               i32x4 (&cur)[NB]) {
+    constexpr int total = 2 * R;
+    if constexpr (K0 < total) {
+        i32x4 nxt[NB];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) nxt[i] = i32x4{0, 0, 0, 0};
+        if constexpr (K0 + NB + 0 < total && NB > 0) nxt[0] = lookup_read<R, HALF, (K0 + NB + 0 < total ? K0 + NB + 0 : 0)>(w, lanebase);
+        if constexpr (K0 + NB + 1 < total && NB > 1) nxt[1] = lookup_read<R, HALF, (K0 + NB + 1 < total ? K0 + NB + 1 : 0)>(w, lanebase);
+        if constexpr (K0 + NB + 2 < total && NB > 2) nxt[2] = lookup_read<R, HALF, (K0 + NB + 2 < total ? K0 + NB + 2 : 0)>(w, lanebase);
+        if constexpr (K0 + NB + 3 < total && NB > 3) nxt[3] = lookup_read<R, HALF, (K0 + NB + 3 < total ? K0 + NB + 3 : 0)>(w, lanebase);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (K0 + 0 < total && NB > 0) lookup_accumulate<R, (K0 + 0 < total ? K0 + 0 : 0)>(acc16, cur[0]);
+        if constexpr (K0 + 1 < total && NB > 1) lookup_accumulate<R, (K0 + 1 < total ? K0 + 1 : 0)>(acc16, cur[1]);
+        if constexpr (K0 + 2 < total && NB > 2) lookup_accumulate<R, (K0 + 2 < total ? K0 + 2 : 0)>(acc16, cur[2]);
+        if constexpr (K0 + 3 < total && NB > 3) lookup_accumulate<R, (K0 + 3 < total ? K0 + 3 : 0)>(acc16, cur[3]);
+        __builtin_amdgcn_sched_barrier(0);
+        lookup_batches<R, HALF, NB, K0 + NB>(w, lanebase, acc16, nxt);
+    }
+}
+
+template <int R, int HALF>
+__device__ __forceinline__ void lookup_half(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4]) {
+    constexpr int NB = 4;
+    constexpr int total = 2 * R;
+    i32x4 first[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) first[i] = i32x4{0, 0, 0, 0};
+    first[0] = lookup_read<R, HALF, 0>(w, lanebase);
+    if constexpr (total > 1) first[1] = lookup_read<R, HALF, 1>(w, lanebase);
+    if constexpr (total > 2) first[2] = lookup_read<R, HALF, (total > 2 ? 2 : 0)>(w, lanebase);
+    if constexpr (total > 3) first[3] = lookup_read<R, HALF, (total > 3 ? 3 : 0)>(w, lanebase);
+    __builtin_amdgcn_sched_barrier(0);
+    lookup_batches<R, HALF, NB, 0>(w, lanebase, acc16, first);
+}
+
+// Nine table rows that share their two leading digits (b1 = their common part): the third and fourth digits add or
+// subtract a2 and a3.  Row offsets 0..8 from dst.
+__device__ __forceinline__ void build_rows9(unsigned dst, const s16x2 (&b1)[4], const s16x2 (&a2)[4],
+                                            const s16x2 (&a3)[4]) {
+    s16x2 u[4], lo[4], hi[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { u[q] = b1[q] - a2[q]; lo[q] = u[q] - a3[q]; hi[q] = u[q] + a3[q]; }
+    lds_write128<0 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
+    lds_write128<1 * 16>(dst, i32x4{as_int(u[0]), as_int(u[1]), as_int(u[2]), as_int(u[3])});
+    lds_write128<2 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { lo[q] = b1[q] - a3[q]; hi[q] = b1[q] + a3[q]; }
+    lds_write128<3 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
+    lds_write128<4 * 16>(dst, i32x4{as_int(b1[0]), as_int(b1[1]), as_int(b1[2]), as_int(b1[3])});
+    lds_write128<5 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { u[q] = b1[q] + a2[q]; lo[q] = u[q] - a3[q]; hi[q] = u[q] + a3[q]; }
+    lds_write128<6 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
+    lds_write128<7 * 16>(dst, i32x4{as_int(u[0]), as_int(u[1]), as_int(u[2]), as_int(u[3])});
+    lds_write128<8 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
 }
 
 template <int R, bool NEED32, int MODE>
@@ -370,10 +396,6 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     typedef __attribute__((address_space(3))) float lds_f32;
     lds_f32* scale_lds = (lds_f32*)(unsigned)kTableBytes;
     if (tid < n_tile) scale_lds[tid] = (n0 + tid < p.N) ? p.w_scale * p.a_scale[n0 + tid] : 0.0f;
-    // counters: built[h] counts build waves that finished filling half h, readout[h] lookup waves that finished reading it
-    const unsigned built0 = kFlagBase, built1 = kFlagBase + 4, readout0 = kFlagBase + 8, readout1 = kFlagBase + 12;
-    if (tid < 4) ((lds_i32*)(unsigned)kFlagBase)[tid] = 0;
-    wg_barrier_lds();
 
     s16x2 acc16[R][4];
     int acc32[NEED32 ? R : 1][8];
@@ -390,24 +412,38 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
 
     if (builder) {
         // ================================ build role ================================
-        // The build waves are few and on the critical path of every hand-over: let them issue first.
-        __builtin_amdgcn_s_setprio(3);
         // Task of a lane for one half-stage: slot s2 of the half (0/1), slice l, leading digits hh = u (table rows
         // 9u .. 9u+8); the ninth digit pair (rows 72..80) is shared out one row per lane, lane u = 0 takes two.
         const int u = (wave * 4 + grp) & 7;
         const int s2 = (wave * 4 + grp) >> 3;
         const int nb = n0 + 8 * t;                   // first token of the slice
         const int chunk_b = nb >> 3;
-        const int hs0 = 2 * st_begin, hs1 = 2 * st_end;
-        // Half-stage hs = 2*stage + half holds slots 2*half, 2*half+1 = sub-tables kg = stage*4J + 4j + slot.
-        auto kg_of = [&](int hs) { return (hs >> 1) * 4 * J + 4 * j + 2 * (hs & 1) + s2; };
-        auto dst_of = [&](int hs) { return (unsigned)(2 * (hs & 1) + s2) * kSlotBytes + (unsigned)l * 16u; };
+        unsigned actA[4][2], actB[4][2];
+        bool validA = false, validB = false;
 
-        if constexpr (MODE == kFromGlobal) {
-            // Un-streamed variant: the rows come from the table in global memory.
-            auto copy_half = [&](int hs) {
-                const int kg = kg_of(hs);
-                const unsigned dst = dst_of(hs);
+        // Half-stage hs = 2*stage + half holds slots 2*half, 2*half+1 = sub-tables kg = stage*4J + 4j + slot.
+        auto fetch_act = [&](int hs, unsigned (&act)[4][2], bool& valid) {
+            const int kg = (hs >> 1) * 4 * J + 4 * j + 2 * (hs & 1) + s2;
+            valid = (hs < 2 * st_end) && (kg < p.G) && (nb < p.N);
+            if (MODE == kFast) {
+                // 4 activation rows x 8 tokens = 32 contiguous bytes of the token-chunked layout; branch-free
+                // (address clamped into the tensor, validity applied at use) so nothing waits on the data early.
+                const int kgc = min(kg, p.G - 1);
+                const int cc = (nb < p.N) ? chunk_b : 0;
+                const i32x4* src = (const i32x4*)(p.a_q + ((size_t)cc * p.K + 4 * kgc) * 8);
+                const i32x4 v0 = src[0], v1 = src[1];
+                act[0][0] = (unsigned)v0.x; act[0][1] = (unsigned)v0.y;
+                act[1][0] = (unsigned)v0.z; act[1][1] = (unsigned)v0.w;
+                act[2][0] = (unsigned)v1.x; act[2][1] = (unsigned)v1.y;
+                act[3][0] = (unsigned)v1.z; act[3][1] = (unsigned)v1.w;
+            }
+        };
+
+        auto build_half = [&](int hs, unsigned (&act)[4][2], bool valid) {
+            const unsigned slot = (unsigned)(2 * (hs & 1) + s2);
+            const unsigned dst = slot * kSlotBytes + (unsigned)l * 16u;
+            if (MODE == kFromGlobal) {
+                const int kg = (hs >> 1) * 4 * J + 4 * j + 2 * (hs & 1) + s2;
                 auto copy_row = [&](int row) {
                     i32x4 v = {0, 0, 0, 0};
                     if (kg < p.G && nb < p.N) {
@@ -430,113 +466,57 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                 for (int i = 0; i < 9; ++i) copy_row(9 * u + i);
                 copy_row(72 + u);
                 if (u == 0) copy_row(80);
-            };
-            for (int hs = hs0, rel = 0; hs < hs1; hs += 2, ++rel) {
-                flag_wait(readout0, kLookupWaves * rel);
-                copy_half(hs);
-                flag_signal(built0, lane);
-                flag_wait(readout1, kLookupWaves * rel);
-                copy_half(hs + 1);
-                flag_signal(built1, lane);
-            }
-        } else {
-            // Streamed: rows are computed from the token-chunked INT8 activations.  Activations are fetched four
-            // half-stages ahead (right after the quantiser they come from the memory-side cache), and the rows of
-            // half-stage h+1 are computed while the LDS writes of half-stage h drain.
-            struct Rows { s16x2 r[9][4], ex[4], last[4]; };
-            unsigned act0[4][2], act1[4][2], act2[4][2], act3[4][2];
-            bool valid0 = false, valid1 = false, valid2 = false, valid3 = false;
-
-            auto fetch_act = [&](int hs, unsigned (&act)[4][2], bool& valid) {
-                const int kg = kg_of(hs);
-                valid = (hs < hs1) && (kg < p.G) && (nb < p.N);
-                // 4 activation rows x 8 tokens = 32 contiguous bytes of the token-chunked layout; branch-free
-                // (address clamped into the tensor, validity applied at use) so nothing waits on the data early.
-                const int kgc = min(kg, p.G - 1);
-                const int cc = (nb < p.N) ? chunk_b : 0;
-                const i32x4* src = (const i32x4*)(p.a_q + ((size_t)cc * p.K + 4 * kgc) * 8);
-                const i32x4 v0 = src[0], v1 = src[1];
-                act[0][0] = (unsigned)v0.x; act[0][1] = (unsigned)v0.y;
-                act[1][0] = (unsigned)v0.z; act[1][1] = (unsigned)v0.w;
-                act[2][0] = (unsigned)v1.x; act[2][1] = (unsigned)v1.y;
-                act[3][0] = (unsigned)v1.z; act[3][1] = (unsigned)v1.w;
-            };
-            // Every row is one packed add/sub away from an earlier one (topological order, Sec. 4).
-            auto compute_rows = [&](unsigned (&act)[4][2], bool valid, Rows& rw) {
+            } else {
+                // Every row is one packed add/sub away from an earlier one (topological order, Sec. 4).
                 if (!valid) {
 #pragma unroll
                     for (int c = 0; c < 4; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
                 }
-                const short d0 = (short)(u / 3 - 1), d1 = (short)(u % 3 - 1);   // leading digits of rows 9u..9u+8,
-                const s16x2 m0 = {d0, d0}, m1 = {d1, d1};                         // and digits (d2,d3) of row 72+u
+                const short s0 = (short)(u / 3 - 1), s1 = (short)(u % 3 - 1);
+                const s16x2 m0 = {s0, s0}, m1 = {s1, s1};
+                const short e2 = (short)(u / 3 - 1), e3 = (short)(u % 3 - 1);    // digits (d2,d3) of the extra row 72+u
+                const s16x2 x2 = {e2, e2}, x3 = {e3, e3};
+                s16x2 a2[4], a3[4], b1[4], ex[4], top[4];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const s16x2 a0 = unpack_pair(act[0][q >> 1], q & 1);
                     const s16x2 a1 = unpack_pair(act[1][q >> 1], q & 1);
-                    const s16x2 a2 = unpack_pair(act[2][q >> 1], q & 1);
-                    const s16x2 a3 = unpack_pair(act[3][q >> 1], q & 1);
-                    const s16x2 b1 = a0 * m0 + a1 * m1;
-                    const s16x2 top = a0 + a1;                          // leading digits (2,2)
-                    const s16x2 lo = b1 - a2, hi = b1 + a2;
-                    rw.r[0][q] = lo - a3; rw.r[1][q] = lo; rw.r[2][q] = lo + a3;
-                    rw.r[3][q] = b1 - a3; rw.r[4][q] = b1; rw.r[5][q] = b1 + a3;
-                    rw.r[6][q] = hi - a3; rw.r[7][q] = hi; rw.r[8][q] = hi + a3;
-                    rw.ex[q] = top + a2 * m0 + a3 * m1;                 // row 72 + 3*d2 + d3 with (d2,d3) = (u/3, u%3)
-                    rw.last[q] = top + a2 + a3;                         // row 80
+                    a2[q] = unpack_pair(act[2][q >> 1], q & 1);
+                    a3[q] = unpack_pair(act[3][q >> 1], q & 1);
+                    b1[q] = a0 * m0 + a1 * m1;
+                    top[q] = a0 + a1;                               // leading digits (2,2)
+                    ex[q] = top[q] + a2[q] * x2 + a3[q] * x3;       // row 72 + 3*d2 + d3 with (d2,d3) = (u/3, u%3)
                 }
-                // Pin the finished rows in registers here, so that the arithmetic stays where it is written:
-                // between the LDS writes of the previous half-stage and the wait for them.
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-#pragma unroll
-                    for (int i = 0; i < 9; ++i) asm volatile("" : "+v"(rw.r[i][q]));
-                    asm volatile("" : "+v"(rw.ex[q]));
-                    asm volatile("" : "+v"(rw.last[q]));
-                }
-            };
-            auto write_rows = [&](int hs, const Rows& rw) {
-                const unsigned dst = dst_of(hs);
-                const unsigned dst9 = dst + (unsigned)(9 * u) * kRowBytes;
-                static_for<0, 9>([&](auto ic_) {
-                    constexpr int i = decltype(ic_)::value;
-                    lds_write128<i * 16>(dst9, i32x4{as_int(rw.r[i][0]), as_int(rw.r[i][1]), as_int(rw.r[i][2]), as_int(rw.r[i][3])});
-                });
+                build_rows9(dst + (unsigned)(9 * u) * kRowBytes, b1, a2, a3);
                 lds_write128<0>(dst + (unsigned)(72 + u) * kRowBytes,
-                                i32x4{as_int(rw.ex[0]), as_int(rw.ex[1]), as_int(rw.ex[2]), as_int(rw.ex[3])});
+                                i32x4{as_int(ex[0]), as_int(ex[1]), as_int(ex[2]), as_int(ex[3])});
                 if (u == 0) {
-                    lds_write128<80 * 16>(dst, i32x4{as_int(rw.last[0]), as_int(rw.last[1]), as_int(rw.last[2]), as_int(rw.last[3])});
-                }
-            };
-            // One half-stage: wait until the lookup waves have released the half, write the rows computed earlier,
-            // compute the next half-stage's rows from `act_next` and refill that activation buffer, then publish.
-            Rows rows;
-            auto step = [&](int hs, unsigned freed, int freed_target, unsigned built, unsigned (&act_next)[4][2],
-                            bool& valid_next) {
-                flag_wait(freed, freed_target);
-                write_rows(hs, rows);
-                compute_rows(act_next, valid_next, rows);
-                fetch_act(hs + 5, act_next, valid_next);
-                flag_signal(built, lane);
-            };
-            if (hs0 < hs1) {
-                fetch_act(hs0, act0, valid0);
-                fetch_act(hs0 + 1, act1, valid1);
-                fetch_act(hs0 + 2, act2, valid2);
-                fetch_act(hs0 + 3, act3, valid3);
-                compute_rows(act0, valid0, rows);
-                fetch_act(hs0 + 4, act0, valid0);
-            }
-            // Half h may be refilled for stage rel once all 12 lookup waves have read it for stage rel-1.
-            for (int hs = hs0, rel = 0; hs < hs1; hs += 4, rel += 2) {
-                step(hs, readout0, kLookupWaves * rel, built0, act1, valid1);
-                step(hs + 1, readout1, kLookupWaves * rel, built1, act2, valid2);
-                if (hs + 2 < hs1) {
-                    step(hs + 2, readout0, kLookupWaves * (rel + 1), built0, act3, valid3);
-                    step(hs + 3, readout1, kLookupWaves * (rel + 1), built1, act0, valid0);
+                    lds_write128<80 * 16>(dst, i32x4{as_int(top[0] + a2[0] + a3[0]), as_int(top[1] + a2[1] + a3[1]),
+                                                      as_int(top[2] + a2[2] + a3[2]), as_int(top[3] + a2[3] + a3[3])});
                 }
             }
+        };
+
+        const int hs0 = 2 * st_begin, hs1 = 2 * st_end;
+        if (hs0 < hs1) {
+            fetch_act(hs0, actA, validA);
+            fetch_act(hs0 + 1, actB, validB);
+            build_half(hs0, actA, validA);
+            fetch_act(hs0 + 2, actA, validA);
         }
-        __builtin_amdgcn_s_setprio(0);
+        wg_barrier_lds();
+        for (int hs = hs0; hs < hs1; hs += 2) {
+            // lookups read half 0 now: fill half 1 (hs + 1), then fetch what half 1 will hold two steps later
+            build_half(hs + 1, actB, validB);
+            fetch_act(hs + 3, actB, validB);
+            wg_barrier_lds();
+            // lookups read half 1 now: fill half 0 with hs + 2
+            if (hs + 2 < hs1) {
+                build_half(hs + 2, actA, validA);
+                fetch_act(hs + 4, actA, validA);
+            }
+            wg_barrier_lds();
+        }
     } else {
         // ================================ lookup role ================================
         // Row group r of this wave: its packed tiles start at a wave-uniform address (scalar registers); the lane
@@ -559,62 +539,13 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
 #pragma unroll
             for (int r = 0; r < R; ++r) wdst[r] = *(const unsigned*)(wbase[r] + voff);
         };
-        // The 4R lookups of a stage run as R batches of four table reads; D batches are in flight while the adds of
-        // an older batch issue, and the stream does not drain at half or stage boundaries: the last steps of a
-        // stage already issue the first batches of the next one.  A batch that first touches a half is preceded by
-        // a check of that half's built counter; the counter is probed one batch earlier so that the check normally
-        // finds its answer in a register.  Read-out counters are bumped right after the adds that consumed a
-        // half's last read.
-        constexpr int D = (R >= 2) ? 2 : 1;
-        constexpr int H1B = (2 * R) / 4;                  // first batch of a stage that reads the second half
-        i32x4 ring[D][4];
-        int seen0 = 0, seen1 = 0;                         // counter values seen by the probes
-        auto probe = [&](unsigned addr) -> int { return *(volatile lds_i32*)addr; };
-        auto ensure = [&](unsigned addr, int target, int seen) {
-            if (__builtin_amdgcn_readfirstlane(seen) < target) flag_wait(addr, target);
-        };
-        auto issue = [&](auto bc, auto sc, const unsigned (&wsrc)[R]) {
-            constexpr int B = decltype(bc)::value, S = decltype(sc)::value;
-            static_for<0, 4>([&](auto ec) {
-                constexpr int E = decltype(ec)::value;
-                ring[S][E] = lookup_read<R, 4 * B + E>(wsrc, lanebase);
-            });
-            __builtin_amdgcn_sched_barrier(0);
-        };
-        auto accumulate = [&](auto bc, auto sc) {
-            constexpr int B = decltype(bc)::value, S = decltype(sc)::value;
-            static_for<0, 4>([&](auto ec) {
-                constexpr int E = decltype(ec)::value;
-                lookup_accumulate<R, 4 * B + E>(acc16, ring[S][E]);
-            });
-            __builtin_amdgcn_sched_barrier(0);
-        };
-        auto stage = [&](auto pc, int st, unsigned (&w)[R], unsigned (&wnext)[R]) {
-            constexpr int P = decltype(pc)::value;        // batch b of this stage sits in ring[(b + P*R) % D]
-            const int rel = st - st_begin;
-            const bool has_next = st + 1 < st_end;
+        auto stage = [&](int st, unsigned (&w)[R], unsigned (&wnext)[R]) {
             load_weights(st + 1, wnext);
-            static_for<0, R>([&](auto bc) {
-                constexpr int b = decltype(bc)::value;
-                constexpr int S = (b + P * R) % D;
-                accumulate(bc, ic<S>{});
-                if constexpr (b == (2 * R - 1) / 4) flag_signal_reader(readout0, lane);
-                if constexpr (b == R - 1) flag_signal_reader(readout1, lane);
-                constexpr int nb = b + D;
-                if constexpr (nb < R) {
-                    if constexpr (nb == H1B) ensure(built1, kBuildWaves * (rel + 1), seen1);
-                    issue(ic<nb>{}, ic<S>{}, w);
-                    if constexpr (nb + 1 == H1B) seen1 = probe(built1);
-                    if constexpr (nb == R - 1) seen0 = probe(built0);
-                } else if (has_next) {
-                    constexpr int q = nb - R;             // batch q of the next stage
-                    if constexpr (q == 0) ensure(built0, kBuildWaves * (rel + 2), seen0);
-                    if constexpr (q == H1B) ensure(built1, kBuildWaves * (rel + 2), seen1);
-                    issue(ic<q>{}, ic<S>{}, wnext);
-                    if constexpr (q + 1 == H1B) seen1 = probe(built1);
-                }
-            });
-            if (NEED32 && ((rel & 15) == 15)) {           // 16 stages x 4 lookups = block of 64 (Sec. 3.4)
+            lookup_half<R, 0>(w, lanebase, acc16);
+            wg_barrier_lds();
+            lookup_half<R, 1>(w, lanebase, acc16);
+            wg_barrier_lds();
+            if (NEED32 && (((st - st_begin) & 15) == 15)) {   // 16 stages x 4 lookups = block of 64 (Sec. 3.4)
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -627,18 +558,12 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         };
         unsigned wa[R], wb[R];
         load_weights(st_begin, wa);
-        if (st_begin < st_end) {
-            flag_wait(built0, kBuildWaves);
-            if constexpr (H1B < D) flag_wait(built1, kBuildWaves);
-            static_for<0, D>([&](auto bc) { issue(bc, bc, wa); });
-        }
+        wg_barrier_lds();                      // half-stage 0 of the first stage is built
         for (int st = st_begin; st < st_end; st += 2) {
-            stage(ic<0>{}, st, wa, wb);
-            if (st + 1 < st_end) stage(ic<1>{}, st + 1, wb, wa);
+            stage(st, wa, wb);
+            if (st + 1 < st_end) stage(st + 1, wb, wa);
         }
     }
-
-    wg_barrier_lds();    // every lookup is done: the table space becomes the epilogue's parking space
 
     // ---- epilogue.  Per row group: widen to INT32, add the J partial sums of each token across the 16 lanes of
     // the group with a reduce-scatter (each step halves the tokens a lane keeps), park the sums in LDS as
