@@ -267,6 +267,15 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const int8_t* __restrict
 //   MODE    kFast: tables built in LDS from the token-chunked INT8 activations (streamed, the hot path)
 //           kFromGlobal: LDS slots are filled from a table materialised by vlut_build_lut
 // ---------------------------------------------------------------------------------------------
+template <int V> using ic = std::integral_constant<int, V>;
+template <int I0, int I1, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I0 < I1) {
+        f(ic<I0>{});
+        static_for<I0 + 1, I1>(f);
+    }
+}
+
 enum { kFast = 0, kFromGlobal = 2 };
 constexpr int kBuildWaves = 4;
 constexpr int kLookupWaves = kWaves - kBuildWaves;     // 12
@@ -498,24 +507,95 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         };
 
         const int hs0 = 2 * st_begin, hs1 = 2 * st_end;
-        if (hs0 < hs1) {
-            fetch_act(hs0, actA, validA);
-            fetch_act(hs0 + 1, actB, validB);
-            build_half(hs0, actA, validA);
-            fetch_act(hs0 + 2, actA, validA);
-        }
-        wg_barrier_lds();
-        for (int hs = hs0; hs < hs1; hs += 2) {
-            // lookups read half 0 now: fill half 1 (hs + 1), then fetch what half 1 will hold two steps later
-            build_half(hs + 1, actB, validB);
-            fetch_act(hs + 3, actB, validB);
+        if constexpr (MODE == kFromGlobal) {
+            if (hs0 < hs1) build_half(hs0, actA, validA);
             wg_barrier_lds();
-            // lookups read half 1 now: fill half 0 with hs + 2
-            if (hs + 2 < hs1) {
-                build_half(hs + 2, actA, validA);
-                fetch_act(hs + 4, actA, validA);
+            for (int hs = hs0; hs < hs1; hs += 2) {
+                build_half(hs + 1, actB, validB);     // lookups read half 0 now: fill half 1
+                wg_barrier_lds();
+                if (hs + 2 < hs1) build_half(hs + 2, actA, validA);   // lookups read half 1 now: fill half 0
+                wg_barrier_lds();
             }
-            wg_barrier_lds();
+        } else {
+            // The build waves are few and every barrier waits for them: let them issue first.
+            __builtin_amdgcn_s_setprio(3);
+            // Rows are computed one half-stage ahead: after a barrier a build wave only has to issue its eleven
+            // LDS writes, and it computes the next half-stage's rows while those writes drain.  Activations are
+            // fetched four half-stages ahead of their use.
+            struct Rows { s16x2 r[9][4], ex[4], last[4]; };
+            unsigned act2[4][2], act3[4][2];
+            bool valid2 = false, valid3 = false;
+            auto compute_rows = [&](unsigned (&act)[4][2], bool valid, Rows& rw) {
+                if (!valid) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
+                }
+                const short d0 = (short)(u / 3 - 1), d1 = (short)(u % 3 - 1);   // leading digits of rows 9u..9u+8,
+                const s16x2 m0 = {d0, d0}, m1 = {d1, d1};                         // and digits (d2,d3) of row 72+u
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const s16x2 a0 = unpack_pair(act[0][q >> 1], q & 1);
+                    const s16x2 a1 = unpack_pair(act[1][q >> 1], q & 1);
+                    const s16x2 a2 = unpack_pair(act[2][q >> 1], q & 1);
+                    const s16x2 a3 = unpack_pair(act[3][q >> 1], q & 1);
+                    const s16x2 b1 = a0 * m0 + a1 * m1;
+                    const s16x2 top = a0 + a1;                          // leading digits (2,2)
+                    const s16x2 lo = b1 - a2, hi = b1 + a2;
+                    rw.r[0][q] = lo - a3; rw.r[1][q] = lo; rw.r[2][q] = lo + a3;
+                    rw.r[3][q] = b1 - a3; rw.r[4][q] = b1; rw.r[5][q] = b1 + a3;
+                    rw.r[6][q] = hi - a3; rw.r[7][q] = hi; rw.r[8][q] = hi + a3;
+                    rw.ex[q] = top + a2 * m0 + a3 * m1;                 // row 72 + 3*d2 + d3 with (d2,d3) = (u/3, u%3)
+                    rw.last[q] = top + a2 + a3;                         // row 80
+                }
+                // Pin the finished rows in registers here, so that the arithmetic stays where it is written
+                // (between the LDS writes of one half-stage and the barrier) instead of sinking below the barrier.
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                    for (int i = 0; i < 9; ++i) asm volatile("" : "+v"(rw.r[i][q]));
+                    asm volatile("" : "+v"(rw.ex[q]));
+                    asm volatile("" : "+v"(rw.last[q]));
+                }
+            };
+            auto write_rows = [&](int hs, const Rows& rw) {
+                const unsigned dst = (unsigned)(2 * (hs & 1) + s2) * kSlotBytes + (unsigned)l * 16u;
+                const unsigned dst9 = dst + (unsigned)(9 * u) * kRowBytes;
+                static_for<0, 9>([&](auto ic_) {
+                    constexpr int i = decltype(ic_)::value;
+                    lds_write128<i * 16>(dst9, i32x4{as_int(rw.r[i][0]), as_int(rw.r[i][1]), as_int(rw.r[i][2]), as_int(rw.r[i][3])});
+                });
+                lds_write128<0>(dst + (unsigned)(72 + u) * kRowBytes,
+                                i32x4{as_int(rw.ex[0]), as_int(rw.ex[1]), as_int(rw.ex[2]), as_int(rw.ex[3])});
+                if (u == 0) {
+                    lds_write128<80 * 16>(dst, i32x4{as_int(rw.last[0]), as_int(rw.last[1]), as_int(rw.last[2]), as_int(rw.last[3])});
+                }
+            };
+            Rows rows;
+            // One half-stage: write the rows computed earlier (half-stage hs, if it exists), compute the rows of
+            // half-stage hs + 1 from `act_next`, refill that activation buffer, and meet the lookup waves.
+            auto step = [&](int hs, unsigned (&act_next)[4][2], bool& valid_next) {
+                if (hs < hs1) write_rows(hs, rows);
+                compute_rows(act_next, valid_next, rows);
+                fetch_act(hs + 5, act_next, valid_next);
+                wg_barrier_lds();
+            };
+            if (hs0 < hs1) {
+                fetch_act(hs0, actA, validA);
+                fetch_act(hs0 + 1, actB, validB);
+                fetch_act(hs0 + 2, act2, valid2);
+                fetch_act(hs0 + 3, act3, valid3);
+                compute_rows(actA, validA, rows);
+                fetch_act(hs0 + 4, actA, validA);
+            }
+            step(hs0, actB, validB);                  // half 0 of the first stage; the barrier hands it over
+            for (int hs = hs0; hs < hs1; hs += 4) {
+                step(hs + 1, act2, valid2);           // lookups read half 0 (hs): fill half 1
+                step(hs + 2, act3, valid3);           // lookups read half 1 (hs+1): fill half 0
+                step(hs + 3, actA, validA);           // (with an odd number of stages the last two steps only meet
+                                                      //  the lookup waves at their two matching barriers)
+                step(hs + 4, actB, validB);
+            }
+            __builtin_amdgcn_s_setprio(0);
         }
     } else {
         // ================================ lookup role ================================
@@ -561,7 +641,12 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         wg_barrier_lds();                      // half-stage 0 of the first stage is built
         for (int st = st_begin; st < st_end; st += 2) {
             stage(st, wa, wb);
-            if (st + 1 < st_end) stage(st + 1, wb, wa);
+            if (st + 1 < st_end) {
+                stage(st + 1, wb, wa);
+            } else if (MODE == kFast) {
+                wg_barrier_lds();              // the build waves run in units of two stages
+                wg_barrier_lds();
+            }
         }
     }
 
