@@ -91,6 +91,8 @@ __device__ __forceinline__ int lane_xor16(int x) {
     if (MASK == 2) return __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false);
     return __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false);
 }
+// Value of lane l ^ 7 (row_half_mirror reverses each group of 8 lanes): a one-instruction partner whose bit 2 differs.
+__device__ __forceinline__ int lane_xor7(int x) { return __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); }
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global load
 // and store of the wave (vmcnt(0)), which would expose the latency of the weight and activation prefetches at
@@ -404,7 +406,9 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     // Output scale of every token of the tile, parked behind the tables (read in the epilogue).
     typedef __attribute__((address_space(3))) float lds_f32;
     lds_f32* scale_lds = (lds_f32*)(unsigned)kTableBytes;
-    if (tid < n_tile) scale_lds[tid] = (n0 + tid < p.N) ? p.w_scale * p.a_scale[n0 + tid] : 0.0f;
+    // Loaded now, stored to LDS only when the K loop is over: nothing at the start of the kernel waits for it.
+    float my_scale = 0.0f;
+    if (tid < n_tile && n0 + tid < p.N) my_scale = p.w_scale * p.a_scale[n0 + tid];
 
     s16x2 acc16[R][4];
     int acc32[NEED32 ? R : 1][8];
@@ -654,6 +658,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     // the group with a reduce-scatter (each step halves the tokens a lane keeps), park the sums in LDS as
     // [token][row] and let the whole workgroup write consecutive output rows per token.
     lds_i32* park = (lds_i32*)0u;
+    if (tid < n_tile) scale_lds[tid] = my_scale;     // visible after the first barrier below
     const int m0 = rgw0 * 4;
     const int rows_wg = min(p.RGW * 4, p.M - m0);
     // RC = row-group rounds parked per pass.  All R at once when the tile has few tokens (the R independent
@@ -667,7 +672,38 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
 #pragma unroll
         for (int rr = 0; rr < RC; ++rr) {
             const int r = c0 + rr;
-            if (r < R) {
+            if (r < R && Jlog == 4) {
+                // 16 sub-tables per table row (the usual plan): the 16 lanes of a group hold 16 partial sums of the
+                // same 8 tokens.  Reduce-scatter with partners l^8, l^7, l^2, l^1 (each a single DPP operand): lane l
+                // ends with the total of token l >> 1.  The first exchange moves packed INT16 pairs and widens while
+                // adding.
+                const bool hi3 = (l & 8) != 0, hi2 = (l & 4) != 0, hi1 = (l & 2) != 0;
+                int w[4];
+                if constexpr (!NEED32) {
+                    const int a0 = as_int(acc16[r][0]), a1 = as_int(acc16[r][1]), a2 = as_int(acc16[r][2]), a3 = as_int(acc16[r][3]);
+                    const s16x2 kA = as_s16x2(hi3 ? a2 : a0), kB = as_s16x2(hi3 ? a3 : a1);
+                    const s16x2 rA = as_s16x2(lane_xor16<8>(hi3 ? a0 : a2)), rB = as_s16x2(lane_xor16<8>(hi3 ? a1 : a3));
+                    w[0] = (int)kA.x + (int)rA.x;
+                    w[1] = (int)kA.y + (int)rA.y;
+                    w[2] = (int)kB.x + (int)rB.x;
+                    w[3] = (int)kB.y + (int)rB.y;
+                } else {
+                    int v[8];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        v[2 * q] = (int)acc16[r][q].x + acc32[r][2 * q];
+                        v[2 * q + 1] = (int)acc16[r][q].y + acc32[r][2 * q + 1];
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = (hi3 ? v[e + 4] : v[e]) + lane_xor16<8>(hi3 ? v[e] : v[e + 4]);
+                }
+                const int x0 = (hi2 ? w[2] : w[0]) + lane_xor7(hi2 ? w[0] : w[2]);
+                const int x1 = (hi2 ? w[3] : w[1]) + lane_xor7(hi2 ? w[1] : w[3]);
+                const int y1 = (hi1 ? x1 : x0) + lane_xor16<2>(hi1 ? x0 : x1);
+                const int z = y1 + lane_xor16<1>(y1);
+                // both lanes of a pair hold the same total and store it to the same place
+                park[(l >> 1) * kParkStride + rr * kRoundRows + lw * 4 + grp] = z;
+            } else if (r < R) {
                 int v[8];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -896,13 +932,14 @@ Derived derive(const Plan& pl, int64_t M, int64_t K, int64_t N) {
 double plan_cost(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     Derived d = derive(pl, M, K, N);
     double rw = (double)((d.RGW + kLookupWaves - 1) / kLookupWaves);   // row groups of the slowest lookup wave
-    double valu = 240.0 * rw + 920.0;
-    double lds = 206.0 * rw + 1400.0;
-    double stage = (valu > lds ? valu : lds) + 200.0;
-    double wg = d.stages_per_split * stage + 5000.0 + 700.0 * rw + (d.need32 ? 0.05 * d.stages_per_split * stage : 0.0);
+    // Measured (K-scans at 256 workgroups, cycles of the shader clock): a stage of 64 k-groups costs about
+    // 2280 + 283 per row-group round: the table writes and the table reads share one LDS pipe and add up.
+    // Outside the K loop: first loads and first build, then the reduction and the stores of every round.
+    double stage = 2280.0 + 283.0 * rw;
+    double wg = d.stages_per_split * stage + 5900.0 + 840.0 * rw + (d.need32 ? 0.05 * d.stages_per_split * stage : 0.0);
     double rounds = (double)((d.total + 255) / 256);
     double t = rounds * wg;
-    if (pl.S > 1) t += 3000.0 + (double)pl.S * (double)M * (double)N * 8.0 / (256.0 * 16.0);
+    if (pl.S > 1) t += 5000.0 + (double)pl.S * (double)M * (double)N * 8.0 / (256.0 * 16.0);   // second kernel
     // weight bytes pulled from L2 by all token tiles (256 CUs x ~24 B/clk)
     double traffic = (double)d.tiles_n * (double)d.RGtotal * d.KCn * 64.0 / (256.0 * 24.0);
     return t > traffic ? t : traffic;
