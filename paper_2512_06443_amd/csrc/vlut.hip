@@ -939,7 +939,7 @@ double plan_cost(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     double wg = d.stages_per_split * stage + 5900.0 + 840.0 * rw + (d.need32 ? 0.05 * d.stages_per_split * stage : 0.0);
     double rounds = (double)((d.total + 255) / 256);
     double t = rounds * wg;
-    if (pl.S > 1) t += 5000.0 + (double)pl.S * (double)M * (double)N * 8.0 / (256.0 * 16.0);   // second kernel
+    if (pl.S > 1) t += 5000.0 + 600.0 * pl.S + (double)pl.S * (double)M * (double)N * 8.0 / (256.0 * 16.0);   // second kernel
     // weight bytes pulled from L2 by all token tiles (256 CUs x ~24 B/clk)
     double traffic = (double)d.tiles_n * (double)d.RGtotal * d.KCn * 64.0 / (256.0 * 24.0);
     return t > traffic ? t : traffic;
@@ -956,7 +956,7 @@ bool plan_valid(const Plan& pl, int64_t M, int64_t K, int64_t N) {
 Plan search_plan(int64_t M, int64_t K, int64_t N) {
     Plan best = {0, 4, 1};
     double best_cost = 1e300;
-    const int Ss[] = {1, 2, 3, 4, 6, 8};
+    const int Ss[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
     for (int Jlog = 0; Jlog <= 4; ++Jlog)
         for (int R : kSupportedR)
             for (int S : Ss) {
