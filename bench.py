@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--no-rotate", action="store_true", help="keep one weight buffer (cache-warm weights)")
     ap.add_argument("--all", action="store_true", help="also time every benchmark shape (table on stderr)")
     ap.add_argument("--plan", default="", help="force J,R,S for the lookup kernel (tuning)")
+    ap.add_argument("--ablation", action="store_true",
+                    help="also time the un-streamed variant (table materialised in HBM by vlut_build_lut, then read "
+                         "by vlut_mpgemm) against the streamed default, Sec. 5.6 of the paper (table on stderr)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one 64 MiB device-to-device copy (known size: the reference a rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE run of this command is scaled by)")
@@ -154,6 +157,37 @@ def time_mfma(torch, case, steps, warmup):
     return ms
 
 
+def time_ablation(B, torch, case, steps, warmup):
+    """Streamed (tables built in LDS on the fly) against materialised (whole table written to HBM, then read back
+    tile by tile), the ablation of Sec. 5.6.  Returns GPU ms per call: streamed mpgemm, build_lut + mpgemm(lut),
+    mpgemm(lut) alone."""
+    L = B.lib()
+    lut = torch.empty(L.vlut_lut_bytes(case.K, case.N) // 2, dtype=torch.int16, device="cuda")
+    bargs = (case.a_q.data_ptr(), case.K, case.N, lut.data_ptr(), lut.numel() * 2)
+    largs = [a[:4] + (lut.data_ptr(),) + a[5:] for a in case._gargs]
+
+    def build(i, stream):
+        case._check(L.vlut_build_lut(*bargs, stream), "vlut_build_lut")
+
+    def gemm_lut(i, stream):
+        case._check(case._gemm(*largs[i % len(largs)], stream), "vlut_mpgemm")
+
+    def both(i, stream):
+        build(i, stream)
+        gemm_lut(i, stream)
+
+    case.quantize(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    _, t_stream, _ = run_timed(torch, case.gemm, steps, warmup)
+    y_streamed = case.y.clone()
+    _, t_both, _ = run_timed(torch, both, steps, warmup)
+    if not torch.equal(y_streamed, case.y):
+        print("bench.py: the un-streamed variant disagrees with the streamed one", file=sys.stderr)
+        sys.exit(4)
+    _, t_lut, _ = run_timed(torch, gemm_lut, steps, warmup)
+    return t_stream, t_both, t_lut
+
+
 def cpu_baseline(wl, W, w_scale, x):
     """The oracle as it stands on the host cores, on the same workload (one full pass, repeated to ~10 s)."""
     from oracle import oracle as O
@@ -242,6 +276,29 @@ def main():
         torch.cuda.synchronize()
         dst.copy_(src)
         torch.cuda.synchronize()
+
+    if args.ablation:
+        abl = []
+        for wname, lname, n in (("bitnet2b_ffn_up", "up", 128), ("bitnet3b_prefill", "up", 256),
+                                ("layer2b4_nsweep", "gate", 16), ("layer2b4_nsweep", "gate", 1024)):
+            wk = wl.WORKLOADS[wname]
+            linr = [l_ for l_ in wk.linears if l_.name == lname][0]
+            Wm, ws_, xm = wl.make_case(wk, linr, n, wk.seeds[0])
+            c = Case(B, torch, wl, Wm, ws_, xm, rotate)
+            ts, tb, tl = time_ablation(B, torch, c, max(20, args.steps // 4), 5)
+            abl.append({"workload": wname, "linear": lname, "M": c.M, "K": c.K, "N": n,
+                        "lut_MB": B.lib().vlut_lut_bytes(c.K, n) / 1e6, "streamed_ms": ts,
+                        "build_lut_plus_mpgemm_ms": tb, "mpgemm_on_materialised_ms": tl,
+                        "streaming_gain": tb / ts})
+            del c
+            torch.cuda.empty_cache()
+        out["ablation_streamed_vs_materialised"] = abl
+        print(f"{'workload':18s} {'lin':5s} {'N':>5s} {'table MB':>9s} {'streamed us':>12s} {'build+gemm us':>14s} "
+              f"{'gemm(lut) us':>13s} {'gain':>6s}", file=sys.stderr)
+        for a in abl:
+            print(f"{a['workload']:18s} {a['linear']:5s} {a['N']:5d} {a['lut_MB']:9.1f} {a['streamed_ms'] * 1e3:12.1f} "
+                  f"{a['build_lut_plus_mpgemm_ms'] * 1e3:14.1f} {a['mpgemm_on_materialised_ms'] * 1e3:13.1f} "
+                  f"{a['streaming_gain']:6.2f}", file=sys.stderr)
 
     if args.all:
         rows = []
