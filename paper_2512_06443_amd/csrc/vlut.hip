@@ -376,6 +376,13 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction
 
+    // Fetch every launch parameter now, in one batch of scalar loads.  Left alone, the compiler loads only what the
+    // early exit below needs and the rest after it, so each workgroup would wait for the argument buffer twice.
+    asm volatile("" ::"s"(p.per_xcd), "s"(p.total_tiles), "s"(p.S), "s"(p.tiles_n), "s"(p.Jlog), "s"(p.RGW),
+                 "s"(p.stages_per_split), "s"(p.stages_total), "s"(p.K), "s"(p.N), "s"(p.G), "s"(p.KCn), "s"(p.RGtotal),
+                 "s"(p.M), "s"(p.ldy), "s"(p.w_scale), "s"(p.packed), "s"(p.a_q), "s"(p.a_scale), "s"(p.y), "s"(p.acc),
+                 "s"(p.ws), "s"(p.lut), "s"(p.aligned8));
+
     // ---- which tile (XCD-aware: the 8 XCDs take contiguous ranges of the tile list, so the
     //      workgroups that share a weight tile also share an L2)
     int L = (int)(blockIdx.x & 7) * p.per_xcd + (int)(blockIdx.x >> 3);
@@ -591,7 +598,11 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                 compute_rows(actA, validA, rows);
                 fetch_act(hs0 + 4, actA, validA);
             }
-            step(hs0, actB, validB);                  // half 0 of the first stage; the barrier hands it over
+            // half 0 of the first stage: hand it over as soon as it is written, compute the next rows afterwards
+            if (hs0 < hs1) write_rows(hs0, rows);
+            wg_barrier_lds();
+            compute_rows(actB, validB, rows);
+            fetch_act(hs0 + 5, actB, validB);
             for (int hs = hs0; hs < hs1; hs += 4) {
                 step(hs + 1, act2, valid2);           // lookups read half 0 (hs): fill half 1
                 step(hs + 2, act3, valid3);           // lookups read half 1 (hs+1): fill half 0
