@@ -31,7 +31,7 @@ ALU_PEAK_TADDS = CUS * 64 * 2 * CLOCK_GHZ / 1e3          # 78.64 T INT16 adds/s
 LDS_PEAK_GBS = CUS * 256 * CLOCK_GHZ                      # 157286 GB/s
 
 # HBM bytes per launch of the lookup kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), see profiles/
-MEASURED_TRAFFIC_BYTES = {"bitnet2b_ffn_up": 10.86e6}   # profiles/lookup_kernel_bitnet2b_ffn_up_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = {"bitnet2b_ffn_up": 10.95e6}   # profiles/lookup_kernel_bitnet2b_ffn_up_hbm_traffic.md
 
 
 def parse_args():
