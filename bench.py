@@ -44,6 +44,9 @@ def parse_args():
     ap.add_argument("--no-rotate", action="store_true", help="keep one weight buffer (cache-warm weights)")
     ap.add_argument("--all", action="store_true", help="also time every benchmark shape (table on stderr)")
     ap.add_argument("--plan", default="", help="force J,R,S for the lookup kernel (tuning)")
+    ap.add_argument("--layer", action="store_true",
+                    help="also time one decoder layer's seven linears at every N of the sweep: one launch per linear "
+                         "against stacked launches (q/k/v and gate/up share their input and their tables)")
     ap.add_argument("--ablation", action="store_true",
                     help="also time the un-streamed variant (table materialised in HBM by vlut_build_lut, then read "
                          "by vlut_mpgemm) against the streamed default, Sec. 5.6 of the paper (table on stderr)")
@@ -56,7 +59,7 @@ def parse_args():
 class Case:
     """Device-resident tensors of one linear layer at one N, with the C-ABI calls pre-marshalled."""
 
-    def __init__(self, B, torch, wl, W, w_scale, x, rotate_bytes):
+    def __init__(self, B, torch, wl, W, w_scale, x, rotate_bytes, w_rows=None):
         self.M, self.K = W.shape
         self.N = x.shape[0]
         self.w_scale = float(w_scale)
@@ -75,7 +78,12 @@ class Case:
         self._quant = L.vlut_quantize_act
         self._gemm = L.vlut_mpgemm
         self._qargs = (self.x.data_ptr(), self.N, self.K, self.x.stride(0), self.a_q.data_ptr(), self.a_s.data_ptr())
-        self._gargs = [(pk.data_ptr(), self.w_scale, self.a_q.data_ptr(), self.a_s.data_ptr(), None, self.M, self.K,
+        # stacked matrices (one launch for several projections of the same input): per-row weight scales
+        self.w_rows = None if w_rows is None else torch.from_numpy(w_rows).cuda()
+        if self.w_rows is not None:
+            self._gemm = L.vlut_mpgemm_rows
+        first = self.w_scale if self.w_rows is None else self.w_rows.data_ptr()
+        self._gargs = [(pk.data_ptr(), first, self.a_q.data_ptr(), self.a_s.data_ptr(), None, self.M, self.K,
                         self.N, self.y.data_ptr(), self.y.stride(0), None, self.ws.data_ptr(), self.ws.numel())
                        for pk in self.pool]
         # the in-run comparison path (INT8 matrix cores) with its own scratch
@@ -299,6 +307,48 @@ def main():
             print(f"{a['workload']:18s} {a['linear']:5s} {a['N']:5d} {a['lut_MB']:9.1f} {a['streamed_ms'] * 1e3:12.1f} "
                   f"{a['build_lut_plus_mpgemm_ms'] * 1e3:14.1f} {a['mpgemm_on_materialised_ms'] * 1e3:13.1f} "
                   f"{a['streaming_gain']:6.2f}", file=sys.stderr)
+
+    if args.layer:
+        import numpy as np
+        wk = wl.WORKLOADS["layer2b4_nsweep"]
+        lins = {l_.name: l_ for l_ in wk.linears}
+        layer_rows = []
+        for n in wk.N:
+            made = {name: wl.make_case(wk, lins[name], n, wk.seeds[0]) for name in lins}
+            single = [Case(B, torch, wl, *made[name], rotate // 4) for name in ("q", "k", "v", "o", "gate", "up", "down")]
+
+            def stacked(names):
+                Wm = np.concatenate([made[nm][0] for nm in names], axis=0)
+                wr = np.concatenate([np.full(made[nm][0].shape[0], made[nm][1], np.float32) for nm in names])
+                return Case(B, torch, wl, Wm, 1.0, made[names[0]][2], rotate // 4, w_rows=wr)
+
+            fused = [stacked(("q", "k", "v")), single[3], stacked(("gate", "up")), single[6]]
+            for c in single + fused:
+                c.quantize(torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+
+            def run_all(cases):
+                def fn(i, stream):
+                    for c in cases:
+                        c.gemm(i, stream)
+                return fn
+
+            cnt = max(10, args.steps // 8)
+            _, t_single, _ = run_timed(torch, run_all(single), cnt, 3)
+            _, t_fused, _ = run_timed(torch, run_all(fused), cnt, 3)
+            wbytes = sum(c.M * c.K // 4 for c in single)
+            layer_rows.append({"N": n, "launches_single": 7, "single_ms": t_single, "launches_stacked": 4,
+                               "stacked_ms": t_fused, "packed_weight_MB": wbytes / 1e6,
+                               "weight_stream_GBs_stacked": wbytes / (t_fused * 1e-3) / 1e9,
+                               "hbm_frac_stacked": wbytes / (t_fused * 1e-3) / 1e9 / HBM_PEAK_GBS})
+            del single, fused
+            torch.cuda.empty_cache()
+        out["layer_linears"] = layer_rows
+        print(f"{'N':>5s} {'7 launches us':>14s} {'4 stacked us':>13s} {'weights MB':>11s} {'GB/s stacked':>13s} {'hbm frac':>9s}",
+              file=sys.stderr)
+        for r in layer_rows:
+            print(f"{r['N']:5d} {r['single_ms'] * 1e3:14.1f} {r['stacked_ms'] * 1e3:13.1f} {r['packed_weight_MB']:11.2f} "
+                  f"{r['weight_stream_GBs_stacked']:13.1f} {r['hbm_frac_stacked']:9.3f}", file=sys.stderr)
 
     if args.all:
         rows = []

@@ -153,6 +153,19 @@ int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const f
                 const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y, int64_t ldy,
                 int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * vlut_mpgemm for several weight matrices that multiply the same activations in one launch (the q/k/v or the
+ * gate/up projections of a decoder layer).  The tables depend on the activations only (Eq. 1, Sec. 3.2), so the
+ * matrices are stacked along M before vlut_pack_weights and share every table a workgroup builds; each output
+ * row carries its own matrix' weight scale:
+ *   y[n][m] = (float)acc[m][n] * (w_scale_rows[m] * a_scale[n]).
+ *   w_scale_rows  dev, fp32 [M]: the weight scale of the matrix row m belongs to (required)
+ * Everything else as in vlut_mpgemm (same workspace size, same error codes).
+ */
+int vlut_mpgemm_rows(const uint8_t* packed, const float* w_scale_rows, const int8_t* a_q, const float* a_scale,
+                     const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y, int64_t ldy,
+                     int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Bytes of scratch vlut_mpgemm_mfma needs: a [tokens padded to 16][K padded to 64] INT8 copy of the activations. */
 size_t vlut_mfma_workspace_bytes(int64_t M, int64_t K, int64_t N);
 

@@ -24,7 +24,7 @@ EXPORTS = [
     "vlut_status_string", "vlut_version", "vlut_packed_weight_bytes", "vlut_packed_offset", "vlut_act_bytes",
     "vlut_lut_bytes",
     "vlut_workspace_bytes", "vlut_pack_weights", "vlut_quantize_act", "vlut_build_lut", "vlut_mpgemm",
-    "vlut_mpgemm_mfma", "vlut_mfma_workspace_bytes", "vlut_set_plan", "vlut_query_plan",
+    "vlut_mpgemm_rows", "vlut_mpgemm_mfma", "vlut_mfma_workspace_bytes", "vlut_set_plan", "vlut_query_plan",
 ]
 
 _lib = None
@@ -58,6 +58,7 @@ def lib() -> ctypes.CDLL:
         gemm_args = [p, cf, p, p, p, i64, i64, i64, p, i64, p, p, sz, p]
         L.vlut_mpgemm.argtypes, L.vlut_mpgemm.restype = gemm_args, ci
         L.vlut_mpgemm_mfma.argtypes, L.vlut_mpgemm_mfma.restype = gemm_args, ci
+        L.vlut_mpgemm_rows.argtypes, L.vlut_mpgemm_rows.restype = [p, p] + list(gemm_args[2:]), ci
         L.vlut_set_plan.argtypes, L.vlut_set_plan.restype = [ci, ci, ci, ci], ci
         L.vlut_query_plan.argtypes, L.vlut_query_plan.restype = [i64, i64, i64, ctypes.POINTER(ci)], ci
         _lib = L
@@ -169,4 +170,23 @@ def mpgemm(packed: torch.Tensor, w_scale: float, a_q: torch.Tensor, a_scale: tor
             _ptr(acc), _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
             _stream())
     _check(rc, "vlut_mpgemm_mfma" if mfma else "vlut_mpgemm")
+    return y, acc
+
+
+def mpgemm_rows(packed: torch.Tensor, w_scale_rows: torch.Tensor, a_q: torch.Tensor, a_scale: torch.Tensor, M: int,
+                y: Optional[torch.Tensor] = None, want_acc: bool = False, workspace: Optional[torch.Tensor] = None):
+    """Runs vlut_mpgemm_rows: stacked weight matrices, one weight scale per output row (fp32 [M] on the GPU)."""
+    assert w_scale_rows.is_cuda and w_scale_rows.dtype == torch.float32 and w_scale_rows.numel() == M
+    K, N = a_q.shape[1], a_scale.shape[0]
+    dev = a_q.device
+    if y is None:
+        y = torch.empty((N, M), dtype=torch.float32, device=dev)
+    acc = torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None
+    ws_bytes = workspace_bytes(M, K, N)
+    if workspace is None and ws_bytes:
+        workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    rc = lib().vlut_mpgemm_rows(_ptr(packed), _ptr(w_scale_rows), _ptr(a_q), _ptr(a_scale), None, M, K, N, _ptr(y),
+                                y.stride(0), _ptr(acc), _ptr(workspace),
+                                0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "vlut_mpgemm_rows")
     return y, acc

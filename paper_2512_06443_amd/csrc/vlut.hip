@@ -48,6 +48,7 @@ struct LookupParams {
     const uint8_t* packed;
     const int8_t* a_q;
     const float* a_scale;
+    const float* w_rows;      // per-output-row weight scales (stacked matrices) or null: w_scale for all rows
     const int16_t* lut;
     float* y;
     int32_t* acc;
@@ -381,7 +382,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     asm volatile("" ::"s"(p.per_xcd), "s"(p.total_tiles), "s"(p.S), "s"(p.tiles_n), "s"(p.Jlog), "s"(p.RGW),
                  "s"(p.stages_per_split), "s"(p.stages_total), "s"(p.K), "s"(p.N), "s"(p.G), "s"(p.KCn), "s"(p.RGtotal),
                  "s"(p.M), "s"(p.ldy), "s"(p.w_scale), "s"(p.packed), "s"(p.a_q), "s"(p.a_scale), "s"(p.y), "s"(p.acc),
-                 "s"(p.ws), "s"(p.lut), "s"(p.aligned8));
+                 "s"(p.ws), "s"(p.lut), "s"(p.aligned8), "s"(p.w_rows));
 
     // ---- which tile (XCD-aware: the 8 XCDs take contiguous ranges of the tile list, so the
     //      workgroups that share a weight tile also share an L2)
@@ -415,7 +416,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     lds_f32* scale_lds = (lds_f32*)(unsigned)kTableBytes;
     // Loaded now, stored to LDS only when the K loop is over: nothing at the start of the kernel waits for it.
     float my_scale = 0.0f;
-    if (tid < n_tile && n0 + tid < p.N) my_scale = p.w_scale * p.a_scale[n0 + tid];
+    if (tid < n_tile && n0 + tid < p.N) my_scale = p.w_rows ? p.a_scale[n0 + tid] : p.w_scale * p.a_scale[n0 + tid];
 
     s16x2 acc16[R][4];
     int acc32[NEED32 ? R : 1][8];
@@ -776,7 +777,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                 const int val = park[nl * kParkStride + col];
                 const int m = m0 + mrow;
                 if (p.S == 1) {
-                    if (p.y) p.y[(size_t)n * p.ldy + m] = (float)val * scale_lds[nl];
+                    if (p.y) p.y[(size_t)n * p.ldy + m] = (float)val * (p.w_rows ? p.w_rows[m] * scale_lds[nl] : scale_lds[nl]);
                     if (p.acc) p.acc[(size_t)m * p.N + n] = val;
                 } else {
                     p.ws[((size_t)ks * p.N + n) * p.M + m] = val;
@@ -879,7 +880,8 @@ __global__ void __launch_bounds__(256) mfma_kernel(const MfmaParams p) {
 
 // Sum of the split-K partials (any order is exact: integers) + scale step.
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const int32_t* __restrict__ ws, int S, int M, int N,
-                                                            float w_scale, const float* __restrict__ a_scale,
+                                                            float w_scale, const float* __restrict__ w_rows,
+                                                            const float* __restrict__ a_scale,
                                                             float* __restrict__ y, int64_t ldy,
                                                             int32_t* __restrict__ acc) {
     size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
@@ -888,7 +890,7 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const int32_t* __res
     int n = (int)(i / M);
     int v = 0;
     for (int s = 0; s < S; ++s) v += ws[((size_t)s * N + n) * M + m];
-    if (y) y[(size_t)n * ldy + m] = (float)v * (w_scale * a_scale[n]);
+    if (y) y[(size_t)n * ldy + m] = (float)v * ((w_rows ? w_rows[m] : w_scale) * a_scale[n]);
     if (acc) acc[(size_t)m * N + n] = v;
 }
 
@@ -1193,9 +1195,9 @@ int vlut_build_lut(const int8_t* a_q, int64_t K, int64_t N, int16_t* lut, size_t
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
 
-int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale,
-                const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y, int64_t ldy,
-                int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream) {
+static int mpgemm_impl(const uint8_t* packed, float w_scale, const float* w_rows, const int8_t* a_q, const float* a_scale,
+                       const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y, int64_t ldy,
+                       int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_mpgemm_args(packed, a_q, a_scale, M, K, N, y, ldy, acc_or_null);
     if (rc != VLUT_OK) return rc;
     Plan pl = choose_plan(M, K, N);
@@ -1212,7 +1214,7 @@ int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const f
     LookupParams p;
     std::memset(&p, 0, sizeof(p));
     p.packed = packed; p.a_q = a_q; p.a_scale = a_scale; p.lut = lut_or_null;
-    p.y = y; p.acc = acc_or_null; p.ws = (int32_t*)workspace; p.w_scale = w_scale;
+    p.y = y; p.acc = acc_or_null; p.ws = (int32_t*)workspace; p.w_scale = w_scale; p.w_rows = w_rows;
     p.M = (int)M; p.K = (int)K; p.N = (int)N; p.G = d.G; p.KCn = d.KCn; p.RGtotal = d.RGtotal; p.ldy = (int)ldy;
     p.Jlog = pl.Jlog; p.S = pl.S; p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.RGW = d.RGW;
     p.stages_total = d.stages_total; p.stages_per_split = d.stages_per_split;
@@ -1225,10 +1227,25 @@ int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const f
     if (pl.S > 1) {
         size_t total = (size_t)M * (size_t)N;
         hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                           (const int32_t*)workspace, pl.S, (int)M, (int)N, w_scale, a_scale, y, ldy, acc_or_null);
+                           (const int32_t*)workspace, pl.S, (int)M, (int)N, w_scale, w_rows, a_scale, y, ldy, acc_or_null);
         if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
     }
     return VLUT_OK;
+}
+
+int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale,
+                const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y, int64_t ldy,
+                int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream) {
+    return mpgemm_impl(packed, w_scale, nullptr, a_q, a_scale, lut_or_null, M, K, N, y, ldy, acc_or_null, workspace,
+                       workspace_bytes, stream);
+}
+
+int vlut_mpgemm_rows(const uint8_t* packed, const float* w_scale_rows, const int8_t* a_q, const float* a_scale,
+                     const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y, int64_t ldy,
+                     int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!w_scale_rows) return VLUT_ERR_NULL;
+    return mpgemm_impl(packed, 1.0f, w_scale_rows, a_q, a_scale, lut_or_null, M, K, N, y, ldy, acc_or_null, workspace,
+                       workspace_bytes, stream);
 }
 
 size_t vlut_mfma_workspace_bytes(int64_t M, int64_t K, int64_t N) {

@@ -27,6 +27,7 @@ def L(vlut_lib_path):
     g = [vp, cf, vp, vp, vp, i64, i64, i64, vp, i64, vp, vp, sz, vp]
     lib.vlut_mpgemm.argtypes = g
     lib.vlut_mpgemm_mfma.argtypes = g
+    lib.vlut_mpgemm_rows.argtypes = [vp, vp] + g[2:]
     lib.vlut_set_plan.argtypes = [ci, ci, ci, ci]
     lib.vlut_query_plan.argtypes = [i64, i64, i64, ctypes.POINTER(ci)]
     return lib
@@ -114,6 +115,9 @@ def test_argument_errors_come_before_any_device_call(L):
         assert fn(d, 1.0, d, d, None, 8, 8, 4, d, 7, None, None, 0, None) == -2      # ldy < M
         assert fn(d, 1.0, d, d, None, 8, 7, 4, d, 8, None, None, 0, None) == -2
         assert fn(d, 1.0, d, d, None, 8, 8, 0, d, 8, None, None, 0, None) == -2
+    assert L.vlut_mpgemm_rows(d, None, d, d, None, 8, 8, 4, d, 8, None, None, 0, None) == -1      # row scales are required
+    assert L.vlut_mpgemm_rows(None, d, d, d, None, 8, 8, 4, d, 8, None, None, 0, None) == -1
+    assert L.vlut_mpgemm_rows(d, d, d, d, None, 8, 8, 4, d, 7, None, None, 0, None) == -2
     assert L.vlut_set_plan(3, 0, 0, 0) == -6 and L.vlut_set_plan(0, 13, 0, 0) == -6
     assert L.vlut_set_plan(0, 0, 7, 0) == -6 and L.vlut_set_plan(0, 0, 0, 99) == -6
     assert L.vlut_set_plan(0, 0, 0, 0) == 0

@@ -142,9 +142,11 @@ def test_every_rows_per_wave(B, R):
     M = 48 * R * 2 - 37                                     # two row tiles, the second one ragged
     W, s, x = wl.small_case(20 + R, M, 512, 33)
     run_case(B, W, s, x, plan=(8, R, 0, 1), tag=f"R{R}")
+    run_case(B, W, s, x, plan=(16, R, 0, 1), tag=f"R{R}-J16")   # the 16-sub-table plans have their own epilogue
 
 
-@pytest.mark.parametrize("J,R,S", [(1, 2, 1), (1, 6, 1), (2, 3, 1), (4, 5, 2), (16, 4, 3), (8, 2, 6)])
+@pytest.mark.parametrize("J,R,S", [(1, 2, 1), (1, 6, 1), (2, 3, 1), (4, 5, 2), (16, 4, 3), (8, 2, 6), (16, 3, 1),
+                                   (16, 6, 1)])
 def test_int32_widening_and_split_k(B, J, R, S):
     # K = 4352 -> 1088 groups: more than 64 lookups per lane for small J, so the INT16 blocks get widened
     W, s, x = wl.small_case(30 + J + S, 300, 4352, 40)
@@ -176,6 +178,35 @@ def test_mfma_comparison_path_is_exact_too(B, M, K, N):
     torch.cuda.synchronize()
     assert np.array_equal(acc.cpu().numpy(), acc_ref)
     check_y(y.cpu().numpy(), y_ref)
+
+
+def test_stacked_matrices_with_row_scales(B):
+    # q/k/v-style: three matrices on the same activations, stacked along M, one weight scale per row (Sec. 3.2:
+    # the tables depend on the activations only).  Each block must equal the oracle's result for its own matrix.
+    K, N = 516, 33
+    rows, scales = (130, 70, 71), (0.0159, 0.5, 3.25)
+    Ws = [wl.ternary(60 + i, m, K, 0.4) for i, m in enumerate(rows)]
+    x = wl.activations(61, N, K)
+    W = np.concatenate(Ws, axis=0)
+    M = W.shape[0]
+    w_rows = np.concatenate([np.full(m, sc, np.float32) for m, sc in zip(rows, scales)])
+    for plan in ((0, 0, 0, 0), (16, 2, 0, 3), (4, 3, 0, 1)):
+        print(f"case stacked plan={plan}", flush=True)
+        B.set_plan(*plan)
+        try:
+            packed = B.pack_weights(dev(W))
+            a_q, a_s = B.quantize_act(dev(x))
+            y, acc = B.mpgemm_rows(packed, dev(w_rows), a_q, a_s, M, want_acc=True)
+            torch.cuda.synchronize()
+        finally:
+            B.set_plan(0, 0, 0, 0)
+        y, acc = y.cpu().numpy(), acc.cpu().numpy()
+        r0 = 0
+        for Wi, sc in zip(Ws, scales):
+            _, _, acc_ref, y_ref = O.mpgemm(Wi, np.float32(sc), x)
+            assert np.array_equal(acc[r0:r0 + Wi.shape[0]], acc_ref)
+            check_y(y[:, r0:r0 + Wi.shape[0]], y_ref)
+            r0 += Wi.shape[0]
 
 
 def test_special_weights(B):
