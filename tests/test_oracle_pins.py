@@ -129,6 +129,25 @@ def test_lut_g5():
     assert np.array_equal(T[1].astype(np.int64), pats @ q[5:10].astype(np.int64))
 
 
+def test_lut_g5_structure_and_packing_density():
+    """1.60-bit packing (Sec. 3.3): five weights per byte, 243 rows; the all-zero pattern is row 121, rows mirror
+    around it, the extremes reach 5 * 127 and the INT16 block bound of Sec. 3.4 gives 51 lookups."""
+    rng = np.random.default_rng(55)
+    q = _rand_q(rng, 10, 4)
+    q[:5, 0] = 127
+    T = O.build_lut(q, g=5).astype(np.int64)
+    assert not T[:, 121].any()
+    assert np.array_equal(T[:, ::-1], -T)                                  # T[242 - i] = -T[i]
+    assert np.array_equal(T[0, 242], q[:5].astype(np.int64).sum(axis=0)) and T[0, 242, 0] == 635
+    for j, p3 in enumerate((81, 27, 9, 3, 1)):                             # single non-zero digit -> +-A[j]
+        assert np.array_equal(T[1, 121 + p3], q[5 + j].astype(np.int64))
+        assert np.array_equal(T[1, 121 - p3], -q[5 + j].astype(np.int64))
+    W = _rand_w(rng, 7, 40)
+    idx = O.pack_indices(W, 5)
+    assert idx.size * 8 == 1.6 * W.size and idx.max() < 243
+    assert 32767 // (127 * 5) == 51 and 51 * 635 <= 32767 < 52 * 635
+
+
 # ---------------------------------------------------------------- integer GEMM
 def test_gemm_bruteforce_tiny():
     rng = np.random.default_rng(6)
