@@ -166,6 +166,34 @@ int vlut_mpgemm_rows(const uint8_t* packed, const float* w_scale_rows, const int
                      const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y, int64_t ldy,
                      int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * 1.60-bit packing (g = 5, the paper's I1; Sec. 3.3 "Flexible sub-2-bit weight packing", Fig. 5): five weights per
+ * base-3 byte, idx = sum_j (W[m][5kg+j] + 1) * 3^(4-j) in [0, 243), 243-row sub-tables, INT16 blocks of at most
+ * 51 = floor(32767 / (127 * 5)) lookups (Sec. 3.4).  Shapes: K >= 5 and K % 5 == 0 (g | K); together with
+ * vlut_quantize_act's K % 4 == 0 the whole path needs K % 20 == 0.  The blob has the tile layout of the 2-bit one
+ * with K/5 groups per row: ceil(M/4) * ceil((K/5)/16) * 64 bytes, padded with byte 121 (the all-zero pattern).
+ * Results are the same numbers as vlut_mpgemm's: the packing changes the table, not the product.
+ */
+#define VLUT_GROUP_G5 5
+#define VLUT_ROWS_G5 243
+size_t vlut_packed_weight_bytes_g5(int64_t M, int64_t K);                    /* 0 if the shape is invalid      */
+size_t vlut_packed_offset_g5(int64_t M, int64_t K, int64_t m, int64_t kg);   /* (size_t)-1 if out of range     */
+size_t vlut_workspace_bytes_g5(int64_t M, int64_t K, int64_t N);             /* split-K partial sums; may be 0 */
+/* As vlut_pack_weights, for the 1.60-bit blob (synchronises `stream` to report VLUT_ERR_VALUE). */
+int vlut_pack_weights_g5(const int8_t* w_ternary, int64_t M, int64_t K, uint8_t* packed, size_t packed_bytes,
+                         void* stream);
+/*
+ * As vlut_mpgemm (streamed tables only: there is no materialised-table variant), on a blob written by
+ * vlut_pack_weights_g5.  a_q (8-byte aligned) and a_scale as written by vlut_quantize_act for the same K, N.
+ */
+int vlut_mpgemm_g5(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale, int64_t M, int64_t K,
+                   int64_t N, float* y, int64_t ldy, int32_t* acc_or_null, void* workspace, size_t workspace_bytes,
+                   void* stream);
+/* Tuning hooks of the 1.60-bit kernel: row groups per wave R in {1,2,4,6,9,12,14} and split-K factor (0 = automatic);
+ * out3 (host, 3 ints) = { R, split_k, number of workgroup tiles }. */
+int vlut_set_plan_g5(int R, int split_k);
+int vlut_query_plan_g5(int64_t M, int64_t K, int64_t N, int* out3);
+
 /* Bytes of scratch vlut_mpgemm_mfma needs: a [tokens padded to 16][K padded to 64] INT8 copy of the activations. */
 size_t vlut_mfma_workspace_bytes(int64_t M, int64_t K, int64_t N);
 

@@ -25,6 +25,8 @@ EXPORTS = [
     "vlut_lut_bytes",
     "vlut_workspace_bytes", "vlut_pack_weights", "vlut_quantize_act", "vlut_build_lut", "vlut_mpgemm",
     "vlut_mpgemm_rows", "vlut_mpgemm_mfma", "vlut_mfma_workspace_bytes", "vlut_set_plan", "vlut_query_plan",
+    "vlut_packed_weight_bytes_g5", "vlut_packed_offset_g5", "vlut_workspace_bytes_g5", "vlut_pack_weights_g5",
+    "vlut_mpgemm_g5", "vlut_set_plan_g5", "vlut_query_plan_g5",
 ]
 
 _lib = None
@@ -59,6 +61,13 @@ def lib() -> ctypes.CDLL:
         L.vlut_mpgemm.argtypes, L.vlut_mpgemm.restype = gemm_args, ci
         L.vlut_mpgemm_mfma.argtypes, L.vlut_mpgemm_mfma.restype = gemm_args, ci
         L.vlut_mpgemm_rows.argtypes, L.vlut_mpgemm_rows.restype = [p, p] + list(gemm_args[2:]), ci
+        L.vlut_packed_weight_bytes_g5.argtypes, L.vlut_packed_weight_bytes_g5.restype = [i64, i64], sz
+        L.vlut_packed_offset_g5.argtypes, L.vlut_packed_offset_g5.restype = [i64, i64, i64, i64], sz
+        L.vlut_workspace_bytes_g5.argtypes, L.vlut_workspace_bytes_g5.restype = [i64, i64, i64], sz
+        L.vlut_pack_weights_g5.argtypes, L.vlut_pack_weights_g5.restype = [p, i64, i64, p, sz, p], ci
+        L.vlut_mpgemm_g5.argtypes, L.vlut_mpgemm_g5.restype = [p, cf, p, p, i64, i64, i64, p, i64, p, p, sz, p], ci
+        L.vlut_set_plan_g5.argtypes, L.vlut_set_plan_g5.restype = [ci, ci], ci
+        L.vlut_query_plan_g5.argtypes, L.vlut_query_plan_g5.restype = [i64, i64, i64, ctypes.POINTER(ci)], ci
         L.vlut_set_plan.argtypes, L.vlut_set_plan.restype = [ci, ci, ci, ci], ci
         L.vlut_query_plan.argtypes, L.vlut_query_plan.restype = [i64, i64, i64, ctypes.POINTER(ci)], ci
         _lib = L
@@ -189,4 +198,45 @@ def mpgemm_rows(packed: torch.Tensor, w_scale_rows: torch.Tensor, a_q: torch.Ten
                                 y.stride(0), _ptr(acc), _ptr(workspace),
                                 0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "vlut_mpgemm_rows")
+    return y, acc
+
+
+# ---- 1.60-bit packing (g = 5)
+def pack_weights_g5(w_ternary: torch.Tensor) -> torch.Tensor:
+    """int8 [M][K] (K % 5 == 0) on the GPU -> 1.60-bit packed blob on the GPU."""
+    assert w_ternary.is_cuda and w_ternary.dtype == torch.int8 and w_ternary.is_contiguous()
+    M, K = w_ternary.shape
+    nbytes = lib().vlut_packed_weight_bytes_g5(M, K)
+    if nbytes == 0:
+        raise VlutError(VLUT_ERR_SHAPE, "vlut_packed_weight_bytes_g5")
+    packed = torch.empty(nbytes, dtype=torch.uint8, device=w_ternary.device)
+    _check(lib().vlut_pack_weights_g5(_ptr(w_ternary), M, K, _ptr(packed), nbytes, _stream()), "vlut_pack_weights_g5")
+    return packed
+
+
+def set_plan_g5(R: int = 0, split_k: int = 0) -> None:
+    _check(lib().vlut_set_plan_g5(R, split_k), "vlut_set_plan_g5")
+
+
+def query_plan_g5(M: int, K: int, N: int) -> Tuple[int, int, int]:
+    out = (ctypes.c_int * 3)()
+    _check(lib().vlut_query_plan_g5(M, K, N, out), "vlut_query_plan_g5")
+    return out[0], out[1], out[2]
+
+
+def mpgemm_g5(packed: torch.Tensor, w_scale: float, a_q: torch.Tensor, a_scale: torch.Tensor, M: int,
+              y: Optional[torch.Tensor] = None, want_acc: bool = False, workspace: Optional[torch.Tensor] = None):
+    """Runs vlut_mpgemm_g5.  Returns (y fp32 [N][M], acc int32 [M][N] or None)."""
+    K, N = a_q.shape[1], a_scale.shape[0]
+    dev = a_q.device
+    if y is None:
+        y = torch.empty((N, M), dtype=torch.float32, device=dev)
+    acc = torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None
+    ws_bytes = lib().vlut_workspace_bytes_g5(M, K, N)
+    if workspace is None and ws_bytes:
+        workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    rc = lib().vlut_mpgemm_g5(_ptr(packed), float(w_scale), _ptr(a_q), _ptr(a_scale), M, K, N, _ptr(y), y.stride(0),
+                              _ptr(acc), _ptr(workspace),
+                              0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "vlut_mpgemm_g5")
     return y, acc

@@ -95,6 +95,40 @@ __device__ __forceinline__ int lane_xor16(int x) {
 // Value of lane l ^ 7 (row_half_mirror reverses each group of 8 lanes): a one-instruction partner whose bit 2 differs.
 __device__ __forceinline__ int lane_xor7(int x) { return __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); }
 
+// 16 sub-tables per table row: the 16 lanes of a group hold 16 partial sums of the same 8 tokens (packed INT16 block
+// sums, plus INT32 sums of earlier blocks when WIDE).  Reduce-scatter with partners l^8, l^7, l^2, l^1 (each a
+// single DPP operand): lane l ends with the total of token l >> 1.  The first exchange moves packed INT16 pairs and
+// widens while adding.
+template <bool WIDE>
+__device__ __forceinline__ int reduce16(const s16x2 (&a16)[4], const int (&a32)[8], int l) {
+    const bool hi3 = (l & 8) != 0, hi2 = (l & 4) != 0, hi1 = (l & 2) != 0;
+    int w[4];
+    if constexpr (!WIDE) {
+        const int a0 = __builtin_bit_cast(int, a16[0]), a1 = __builtin_bit_cast(int, a16[1]);
+        const int a2 = __builtin_bit_cast(int, a16[2]), a3 = __builtin_bit_cast(int, a16[3]);
+        const s16x2 kA = __builtin_bit_cast(s16x2, hi3 ? a2 : a0), kB = __builtin_bit_cast(s16x2, hi3 ? a3 : a1);
+        const s16x2 rA = __builtin_bit_cast(s16x2, lane_xor16<8>(hi3 ? a0 : a2));
+        const s16x2 rB = __builtin_bit_cast(s16x2, lane_xor16<8>(hi3 ? a1 : a3));
+        w[0] = (int)kA.x + (int)rA.x;
+        w[1] = (int)kA.y + (int)rA.y;
+        w[2] = (int)kB.x + (int)rB.x;
+        w[3] = (int)kB.y + (int)rB.y;
+    } else {
+        int v[8];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            v[2 * q] = (int)a16[q].x + a32[2 * q];
+            v[2 * q + 1] = (int)a16[q].y + a32[2 * q + 1];
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (hi3 ? v[e + 4] : v[e]) + lane_xor16<8>(hi3 ? v[e] : v[e + 4]);
+    }
+    const int x0 = (hi2 ? w[2] : w[0]) + lane_xor7(hi2 ? w[0] : w[2]);
+    const int x1 = (hi2 ? w[3] : w[1]) + lane_xor7(hi2 ? w[1] : w[3]);
+    const int y1 = (hi1 ? x1 : x0) + lane_xor16<2>(hi1 ? x0 : x1);
+    return y1 + lane_xor16<1>(y1);
+}
+
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global load
 // and store of the wave (vmcnt(0)), which would expose the latency of the weight and activation prefetches at
 // every stage; here a wave only has to finish its own LDS reads/writes before it signals the barrier.
@@ -117,6 +151,7 @@ __device__ __forceinline__ s16x2 unpack_pair(unsigned x, int h) {
 // ---------------------------------------------------------------------------------------------
 __device__ int g_pack_error;
 
+template <int GW>   // GW = weights per byte: 4 (2.00 bits per weight) or 5 (1.60)
 __global__ void pack_kernel(const int8_t* __restrict__ w, int M, int K, int G, int KCn, int RGtotal,
                             uint8_t* __restrict__ packed) {
     size_t total = (size_t)RGtotal * KCn * 64;
@@ -129,13 +164,18 @@ __global__ void pack_kernel(const int8_t* __restrict__ w, int M, int K, int G, i
     int rg = (int)(tile / KCn);
     int m = rg * 4 + r;
     int kg = kc * 16 + b;
-    unsigned v = 40;
+    unsigned v = GW == 4 ? 40u : 121u;      // the all-zero pattern: every digit 1
     if (m < M && kg < G) {
-        const int8_t* p = w + (size_t)m * K + (size_t)kg * 4;
-        int w0 = p[0], w1 = p[1], w2 = p[2], w3 = p[3];
-        bool ok = (w0 >= -1 && w0 <= 1) && (w1 >= -1 && w1 <= 1) && (w2 >= -1 && w2 <= 1) && (w3 >= -1 && w3 <= 1);
+        const int8_t* p = w + (size_t)m * K + (size_t)kg * GW;
+        bool ok = true;
+        v = 0;
+#pragma unroll
+        for (int j = 0; j < GW; ++j) {      // first weight = most significant base-3 digit
+            const int wj = p[j];
+            ok = ok && wj >= -1 && wj <= 1;
+            v = v * 3u + (unsigned)(wj + 1);
+        }
         if (!ok) atomicOr(&g_pack_error, 1);
-        v = (unsigned)((w0 + 1) * 27 + (w1 + 1) * 9 + (w2 + 1) * 3 + (w3 + 1));
     }
     packed[i] = (uint8_t)v;
 }
@@ -685,36 +725,9 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         for (int rr = 0; rr < RC; ++rr) {
             const int r = c0 + rr;
             if (r < R && Jlog == 4) {
-                // 16 sub-tables per table row (the usual plan): the 16 lanes of a group hold 16 partial sums of the
-                // same 8 tokens.  Reduce-scatter with partners l^8, l^7, l^2, l^1 (each a single DPP operand): lane l
-                // ends with the total of token l >> 1.  The first exchange moves packed INT16 pairs and widens while
-                // adding.
-                const bool hi3 = (l & 8) != 0, hi2 = (l & 4) != 0, hi1 = (l & 2) != 0;
-                int w[4];
-                if constexpr (!NEED32) {
-                    const int a0 = as_int(acc16[r][0]), a1 = as_int(acc16[r][1]), a2 = as_int(acc16[r][2]), a3 = as_int(acc16[r][3]);
-                    const s16x2 kA = as_s16x2(hi3 ? a2 : a0), kB = as_s16x2(hi3 ? a3 : a1);
-                    const s16x2 rA = as_s16x2(lane_xor16<8>(hi3 ? a0 : a2)), rB = as_s16x2(lane_xor16<8>(hi3 ? a1 : a3));
-                    w[0] = (int)kA.x + (int)rA.x;
-                    w[1] = (int)kA.y + (int)rA.y;
-                    w[2] = (int)kB.x + (int)rB.x;
-                    w[3] = (int)kB.y + (int)rB.y;
-                } else {
-                    int v[8];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        v[2 * q] = (int)acc16[r][q].x + acc32[r][2 * q];
-                        v[2 * q + 1] = (int)acc16[r][q].y + acc32[r][2 * q + 1];
-                    }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) w[e] = (hi3 ? v[e + 4] : v[e]) + lane_xor16<8>(hi3 ? v[e] : v[e + 4]);
-                }
-                const int x0 = (hi2 ? w[2] : w[0]) + lane_xor7(hi2 ? w[0] : w[2]);
-                const int x1 = (hi2 ? w[3] : w[1]) + lane_xor7(hi2 ? w[1] : w[3]);
-                const int y1 = (hi1 ? x1 : x0) + lane_xor16<2>(hi1 ? x0 : x1);
-                const int z = y1 + lane_xor16<1>(y1);
                 // both lanes of a pair hold the same total and store it to the same place
-                park[(l >> 1) * kParkStride + rr * kRoundRows + lw * 4 + grp] = z;
+                park[(l >> 1) * kParkStride + rr * kRoundRows + lw * 4 + grp] =
+                    reduce16<NEED32>(acc16[r], acc32[NEED32 ? r : 0], l);
             } else if (r < R) {
                 int v[8];
 #pragma unroll
@@ -873,6 +886,272 @@ __global__ void __launch_bounds__(256) mfma_kernel(const MfmaParams p) {
                     if (p.y) p.y[(size_t)n * p.ldy + m] = (float)v * sc;
                     if (p.acc) p.acc[(size_t)m * p.N + n] = v;
                 }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// 1.60-bit packing (g = 5; Sec. 3.3 "Flexible sub-2-bit weight packing"): five weights per byte, 243-row sub-tables.
+// Same roles, same 256-byte table rows (16 sub-tables x 8 tokens) and same hand-over by barriers as lookup_kernel;
+// what changes: a slot is 243 x 256 B = 62 208 B, so two slots are resident and a half-stage is ONE slot, i.e. one
+// byte of the weight dword (bytes 0..3 of a dword use slots 0,1,0,1); a lane builds 9-row groups that share their
+// three leading digits (27 groups per sub-table slice, handed out over the 16 lane groups of the build waves in two
+// passes); the INT16 block is 48 lookups (bound 51 = floor(32767 / (127*5)), Sec. 3.4).
+// ---------------------------------------------------------------------------------------------
+constexpr int kRows5 = 243;
+constexpr int kSlot5Bytes = kRows5 * kRowBytes;          // 62208
+constexpr int kScale5Base = 2 * kSlot5Bytes;             // 124416: output scales of the tile's 8 tokens
+constexpr int kLds5Bytes = kScale5Base + 128 * 4;        // 124928
+constexpr int kBlockLookups5 = 51;
+constexpr int kWidenEvery5 = 12;                         // dword stages between widenings: 48 lookups <= 51
+
+struct Lookup5Params {
+    const uint8_t* packed;
+    const int8_t* a_q;
+    const float* a_scale;
+    float* y;
+    int32_t* acc;
+    int32_t* ws;
+    float w_scale;
+    int M, K, N, G, KCn, RGtotal, ldy;
+    int S, tiles_m, tiles_n, RGW, dstages_total, dstages_per_split, total_tiles, per_xcd;
+};
+
+// Table read of lookup I (= row group I) of the half-stage that uses byte B of the weight dwords (slot B & 1).
+template <int R, int B, int I>
+__device__ __forceinline__ i32x4 lookup5_read(const unsigned (&w)[R], unsigned lanebase) {
+    constexpr unsigned sel = 0x0c0c0000u | ((4u + (unsigned)B) << 8);
+    const unsigned addr = __builtin_amdgcn_perm(w[I], lanebase, sel);   // idx*256 + slice*16
+    return lds_read128<(B & 1) * (kSlot5Bytes / 16)>(addr);
+}
+
+template <int R, int B, int NB, int K0>
+__device__ __forceinline__ void lookup5_batches(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4],
+                                                i32x4 (&cur)[NB]) {
+    if constexpr (K0 < R) {
+        i32x4 nxt[NB];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) nxt[i] = i32x4{0, 0, 0, 0};
+        static_for<0, NB>([&](auto ic_) {
+            constexpr int i = decltype(ic_)::value;
+            if constexpr (K0 + NB + i < R) nxt[i] = lookup5_read<R, B, (K0 + NB + i < R ? K0 + NB + i : 0)>(w, lanebase);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, NB>([&](auto ic_) {
+            constexpr int i = decltype(ic_)::value;
+            if constexpr (K0 + i < R) lookup_accumulate<R, (K0 + i < R ? K0 + i : 0)>(acc16, cur[i]);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+        lookup5_batches<R, B, NB, K0 + NB>(w, lanebase, acc16, nxt);
+    }
+}
+
+// The R lookups of one half-stage (Alg. 1 lines 3-6), software pipelined in batches of four.
+template <int R, int B>
+__device__ __forceinline__ void lookup5_half(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4]) {
+    constexpr int NB = 4;
+    i32x4 first[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) first[i] = i32x4{0, 0, 0, 0};
+    static_for<0, NB>([&](auto ic_) {
+        constexpr int i = decltype(ic_)::value;
+        if constexpr (i < R) first[i] = lookup5_read<R, B, (i < R ? i : 0)>(w, lanebase);
+    });
+    __builtin_amdgcn_sched_barrier(0);
+    lookup5_batches<R, B, NB, 0>(w, lanebase, acc16, first);
+}
+
+template <int R, bool NEED32>
+__global__ void __launch_bounds__(kThreads) lookup5_kernel(const Lookup5Params p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem5[];
+    if (lds_base_of(smem5) != 0u) return;      // table addresses are formed as idx*256 + slice*16 from LDS address 0
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    int L = (int)(blockIdx.x & 7) * p.per_xcd + (int)(blockIdx.x >> 3);      // XCD-aware tile order, as in lookup_kernel
+    if ((int)(blockIdx.x >> 3) >= p.per_xcd || L >= p.total_tiles) return;
+    const int ks = L % p.S;
+    L /= p.S;
+    const int nt = L % p.tiles_n;
+    const int mt = L / p.tiles_n;
+    const int n0 = nt * 8;                      // 8 tokens per workgroup (16 sub-tables per table row)
+    const int rgw0 = mt * p.RGW;
+
+    const int l = lane & 15;                    // slice = sub-table selector
+    const int grp = lane >> 4;
+    const unsigned lanebase = (unsigned)l * 16u;
+    const int ds_begin = ks * p.dstages_per_split;        // a dword stage = 4 half-stages = 64 groups = 320 weights
+    const int ds_end = min(p.dstages_total, ds_begin + p.dstages_per_split);
+    const bool builder = wave < kBuildWaves;
+    const int lw = wave - kBuildWaves;
+
+    typedef __attribute__((address_space(3))) float lds_f32;
+    lds_f32* scale_lds = (lds_f32*)(unsigned)kScale5Base;
+    float my_scale = 0.0f;
+    if (tid < 8 && n0 + tid < p.N) my_scale = p.w_scale * p.a_scale[n0 + tid];
+
+    s16x2 acc16[R][4];
+    int acc32[NEED32 ? R : 1][8];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc16[r][q] = s16x2{0, 0};
+    if (NEED32) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc32[r][e] = 0;
+    }
+
+    if (builder) {
+        __builtin_amdgcn_s_setprio(3);
+        // Tasks of a lane per half-stage: slice l, leading digits (d0,d1,d2) = ua, and = ub when ub < 27.
+        const int ua = 4 * wave + grp, ub = 16 + ua;
+        const bool has_b = ub < 27;
+        const bool tok_valid = n0 < p.N;
+        const int chunk = n0 >> 3;
+        const int hs0 = 4 * ds_begin, hs1 = 4 * ds_end;
+        unsigned actA[5][2], actB[5][2];
+        bool validA = false, validB = false;
+
+        // Half-stage hs = 4*dstage + b holds, in slot b & 1, the sub-tables of groups kg = dstage*64 + 4*slice + b.
+        auto fetch_act = [&](int hs, unsigned (&act)[5][2], bool& valid) {
+            const int kg = (hs >> 2) * 64 + 4 * l + (hs & 3);
+            valid = (hs < hs1) && (kg < p.G) && tok_valid;
+            const int kgc = min(kg, p.G - 1);               // clamped into the tensor; validity applied at use
+            const int cc = tok_valid ? chunk : 0;
+            const i32x2* src = (const i32x2*)(p.a_q + ((size_t)cc * p.K + 5 * (size_t)kgc) * 8);   // 5 rows x 8 tokens
+#pragma unroll
+            for (int c = 0; c < 5; ++c) {
+                const i32x2 v = src[c];
+                act[c][0] = (unsigned)v.x;
+                act[c][1] = (unsigned)v.y;
+            }
+        };
+        // Nine rows that share their three leading digits u: base +- a3 +- a4 (topological order of Sec. 4).
+        auto build_group = [&](unsigned dst, int u, const s16x2 (&a)[5][4]) {
+            const short d0 = (short)(u / 9 - 1), d1 = (short)((u / 3) % 3 - 1), d2 = (short)(u % 3 - 1);
+            const s16x2 m0 = {d0, d0}, m1 = {d1, d1}, m2 = {d2, d2};
+            s16x2 rows[9][4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const s16x2 base = a[0][q] * m0 + a[1][q] * m1 + a[2][q] * m2;
+                const s16x2 lo = base - a[3][q], hi = base + a[3][q];
+                rows[0][q] = lo - a[4][q]; rows[1][q] = lo; rows[2][q] = lo + a[4][q];
+                rows[3][q] = base - a[4][q]; rows[4][q] = base; rows[5][q] = base + a[4][q];
+                rows[6][q] = hi - a[4][q]; rows[7][q] = hi; rows[8][q] = hi + a[4][q];
+            }
+            const unsigned dst9 = dst + (unsigned)(9 * u) * kRowBytes;
+            static_for<0, 9>([&](auto ic_) {
+                constexpr int i = decltype(ic_)::value;
+                lds_write128<i * 16>(dst9, i32x4{as_int(rows[i][0]), as_int(rows[i][1]), as_int(rows[i][2]), as_int(rows[i][3])});
+            });
+        };
+        auto build_half = [&](int hs, unsigned (&act)[5][2], bool valid) {
+            if (!valid) {
+#pragma unroll
+                for (int c = 0; c < 5; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
+            }
+            s16x2 a[5][4];
+#pragma unroll
+            for (int c = 0; c < 5; ++c)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) a[c][q] = unpack_pair(act[c][q >> 1], q & 1);
+            const unsigned dst = (unsigned)(hs & 1) * kSlot5Bytes + (unsigned)l * 16u;
+            build_group(dst, ua, a);
+            if (has_b) build_group(dst, ub, a);
+        };
+        if (hs0 < hs1) {
+            fetch_act(hs0, actA, validA);
+            fetch_act(hs0 + 1, actB, validB);
+            build_half(hs0, actA, validA);
+            fetch_act(hs0 + 2, actA, validA);
+        }
+        wg_barrier_lds();
+        for (int hs = hs0; hs < hs1; hs += 2) {     // hs1 - hs0 is a multiple of 4
+            build_half(hs + 1, actB, validB);       // lookups read slot 0 (hs): fill slot 1
+            fetch_act(hs + 3, actB, validB);
+            wg_barrier_lds();
+            if (hs + 2 < hs1) build_half(hs + 2, actA, validA);   // lookups read slot 1 (hs+1): fill slot 0
+            fetch_act(hs + 4, actA, validA);
+            wg_barrier_lds();
+        }
+        __builtin_amdgcn_s_setprio(0);
+    } else {
+        const unsigned char* wbase[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int rgl = r * kLookupWaves + lw;
+            const int rg = rgw0 + rgl;
+            const bool valid = (rgl < p.RGW) && (rg < p.RGtotal);
+            wbase[r] = p.packed + ((size_t)(valid ? rg : 0) * p.KCn) * 64;
+        }
+        // Dword q = ds*16 + slice of each row, fetched one dword stage ahead.  A tile index past the end of K is
+        // clamped to the last tile and meets tables built from zero activations; rows past M are clamped to row group
+        // 0 and never stored.
+        auto load_weights = [&](int ds, unsigned (&wdst)[R]) {
+            const int q = ds * 16 + l;
+            const int kc = min(q >> 2, p.KCn - 1);
+            const unsigned voff = (unsigned)(kc * 64 + grp * 16 + (q & 3) * 4);
+#pragma unroll
+            for (int r = 0; r < R; ++r) wdst[r] = *(const unsigned*)(wbase[r] + voff);
+        };
+        auto dstage = [&](int ds, unsigned (&w)[R], unsigned (&wnext)[R]) {
+            load_weights(ds + 1, wnext);
+            lookup5_half<R, 0>(w, lanebase, acc16);
+            wg_barrier_lds();
+            lookup5_half<R, 1>(w, lanebase, acc16);
+            wg_barrier_lds();
+            lookup5_half<R, 2>(w, lanebase, acc16);
+            wg_barrier_lds();
+            lookup5_half<R, 3>(w, lanebase, acc16);
+            wg_barrier_lds();
+            if (NEED32 && ((ds - ds_begin) % kWidenEvery5 == kWidenEvery5 - 1)) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        acc32[r][2 * q] += (int)acc16[r][q].x;
+                        acc32[r][2 * q + 1] += (int)acc16[r][q].y;
+                        acc16[r][q] = s16x2{0, 0};
+                    }
+            }
+        };
+        unsigned wa[R], wb[R];
+        load_weights(ds_begin, wa);
+        wg_barrier_lds();                          // slot 0 of the first dword stage is built
+        for (int ds = ds_begin; ds < ds_end; ds += 2) {
+            dstage(ds, wa, wb);
+            if (ds + 1 < ds_end) dstage(ds + 1, wb, wa);
+        }
+    }
+
+    // ---- epilogue: reduce the 16 partial sums per token across the lane group, park as [token][row], store rows.
+    lds_i32* park = (lds_i32*)0u;
+    if (tid < 8) scale_lds[tid] = my_scale;
+    constexpr int kParkStride = R * kRoundRows + 4;
+    const int m0 = rgw0 * 4;
+    const int rows_wg = min(p.RGW * 4, p.M - m0);
+    if (!builder) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            park[(l >> 1) * kParkStride + r * kRoundRows + lw * 4 + grp] = reduce16<NEED32>(acc16[r], acc32[NEED32 ? r : 0], l);
+    }
+    wg_barrier_lds();
+    for (int i = tid; i < R * kRoundRows * 8; i += kThreads) {
+        const int col = i % (R * kRoundRows);
+        const int nl = i / (R * kRoundRows);
+        const int n = n0 + nl;
+        if (col < rows_wg && n < p.N) {
+            const int val = park[nl * kParkStride + col];
+            const int m = m0 + col;
+            if (p.S == 1) {
+                if (p.y) p.y[(size_t)n * p.ldy + m] = (float)val * scale_lds[nl];
+                if (p.acc) p.acc[(size_t)m * p.N + n] = val;
+            } else {
+                p.ws[((size_t)ks * p.N + n) * p.M + m] = val;
             }
         }
     }
@@ -1061,6 +1340,100 @@ int check_mpgemm_args(const uint8_t* packed, const int8_t* a_q, const float* a_s
 
 std::mutex g_pack_mutex;
 
+// ---- 1.60-bit (g = 5) host side
+struct Plan5 {
+    int R, S;
+};
+thread_local Plan5 t_forced5 = {0, 0};
+const int kSupportedR5[] = {1, 2, 4, 6, 9, 12, 14};
+
+bool shape5_ok(int64_t M, int64_t K, int64_t N) {
+    return M >= 1 && N >= 1 && K >= 5 && (K % 5) == 0 && M < kMaxDim && K < kMaxDim && N < kMaxDim;
+}
+
+struct Derived5 {
+    int G, KCn, RGtotal, tiles_n, tiles_m, RGW, dstages_total, dstages_per_split, total, per_xcd;
+    bool need32;
+};
+
+Derived5 derive5(const Plan5& pl, int64_t M, int64_t K, int64_t N) {
+    Derived5 d;
+    d.G = (int)(K / 5);
+    d.KCn = (d.G + 15) / 16;
+    d.RGtotal = (int)((M + 3) / 4);
+    d.tiles_n = (int)((N + 7) / 8);
+    int cap = kLookupWaves * pl.R;
+    d.tiles_m = (d.RGtotal + cap - 1) / cap;
+    d.RGW = (d.RGtotal + d.tiles_m - 1) / d.tiles_m;
+    d.dstages_total = (d.G + 63) / 64;
+    d.dstages_per_split = (d.dstages_total + pl.S - 1) / pl.S;
+    d.total = d.tiles_m * d.tiles_n * pl.S;
+    d.per_xcd = (d.total + 7) / 8;
+    d.need32 = d.dstages_per_split * 4 > kBlockLookups5;
+    return d;
+}
+
+bool plan5_valid(const Plan5& pl, int64_t M, int64_t K, int64_t N) {
+    bool ok = false;
+    for (int v : kSupportedR5) ok = ok || v == pl.R;
+    if (!ok || pl.S < 1 || pl.S > 16) return false;
+    Derived5 d = derive5(pl, M, K, N);
+    if (d.need32 && pl.R > 6) return false;
+    return pl.S <= d.dstages_total;
+}
+
+Plan5 choose_plan5(int64_t M, int64_t K, int64_t N) {
+    Plan5 best = {1, 1};
+    double best_cost = 1e300;
+    const int Ss[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
+    for (int R : kSupportedR5)
+        for (int S : Ss) {
+            Plan5 pl = {t_forced5.R > 0 ? t_forced5.R : R, t_forced5.S > 0 ? t_forced5.S : S};
+            if (!plan5_valid(pl, M, K, N)) continue;
+            Derived5 d = derive5(pl, M, K, N);
+            double rw = (double)((d.RGW + kLookupWaves - 1) / kLookupWaves);
+            // a dword stage = four half-stages; each writes a 62 KB slot and reads it rw times per lookup wave
+            double wg = d.dstages_per_split * 4.0 * (1900.0 + 75.0 * rw) + 5900.0 + 840.0 * rw;
+            double t = (double)((d.total + 255) / 256) * wg;
+            if (pl.S > 1) t += 5000.0 + 600.0 * pl.S;
+            if (t < best_cost) { best_cost = t; best = pl; }
+        }
+    return best;
+}
+
+template <int R, bool NEED32>
+int launch_lookup5_t(const Lookup5Params& p, int grid, hipStream_t stream) {
+    auto kfn = lookup5_kernel<R, NEED32>;
+    static bool attr_done = false;   // benign race: the call is idempotent
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, kLds5Bytes) != hipSuccess)
+            return VLUT_ERR_DEVICE;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), kLds5Bytes, stream, p);
+    return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
+}
+
+template <bool NEED32>
+int launch_lookup5_r(int R, const Lookup5Params& p, int grid, hipStream_t stream) {
+    switch (R) {
+    case 1: return launch_lookup5_t<1, NEED32>(p, grid, stream);
+    case 2: return launch_lookup5_t<2, NEED32>(p, grid, stream);
+    case 4: return launch_lookup5_t<4, NEED32>(p, grid, stream);
+    case 6: return launch_lookup5_t<6, NEED32>(p, grid, stream);
+    default: break;
+    }
+    if constexpr (!NEED32) {
+        switch (R) {
+        case 9: return launch_lookup5_t<9, false>(p, grid, stream);
+        case 12: return launch_lookup5_t<12, false>(p, grid, stream);
+        case 14: return launch_lookup5_t<14, false>(p, grid, stream);
+        default: break;
+        }
+    }
+    return VLUT_ERR_UNSUPPORTED;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1148,7 +1521,7 @@ int vlut_pack_weights(const int8_t* w_ternary, int64_t M, int64_t K, uint8_t* pa
         return VLUT_ERR_DEVICE;
     int G = (int)(K / 4), KCn = (G + 15) / 16, RGtotal = (int)((M + 3) / 4);
     size_t blocks = (need + 255) / 256;
-    hipLaunchKernelGGL(pack_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w_ternary, (int)M, (int)K, G, KCn, RGtotal,
+    hipLaunchKernelGGL(pack_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, s, w_ternary, (int)M, (int)K, G, KCn, RGtotal,
                        packed);
     if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
     int err = 0;
@@ -1246,6 +1619,105 @@ int vlut_mpgemm_rows(const uint8_t* packed, const float* w_scale_rows, const int
     if (!w_scale_rows) return VLUT_ERR_NULL;
     return mpgemm_impl(packed, 1.0f, w_scale_rows, a_q, a_scale, lut_or_null, M, K, N, y, ldy, acc_or_null, workspace,
                        workspace_bytes, stream);
+}
+
+// ---- 1.60-bit packing (g = 5)
+size_t vlut_packed_weight_bytes_g5(int64_t M, int64_t K) {
+    if (!shape5_ok(M, K, 1)) return 0;
+    return (size_t)((M + 3) / 4) * (size_t)((K / 5 + 15) / 16) * 64;
+}
+
+size_t vlut_packed_offset_g5(int64_t M, int64_t K, int64_t m, int64_t kg) {
+    if (!shape5_ok(M, K, 1) || m < 0 || m >= M || kg < 0 || kg >= K / 5) return (size_t)-1;
+    size_t KCn = (size_t)((K / 5 + 15) / 16);
+    return (((size_t)(m / 4) * KCn + (size_t)(kg / 16)) * 64) + (size_t)(m % 4) * 16 + (size_t)(kg % 16);
+}
+
+int vlut_pack_weights_g5(const int8_t* w_ternary, int64_t M, int64_t K, uint8_t* packed, size_t packed_bytes,
+                         void* stream) {
+    if (!shape5_ok(M, K, 1)) return VLUT_ERR_SHAPE;
+    if (!w_ternary || !packed) return VLUT_ERR_NULL;
+    size_t need = vlut_packed_weight_bytes_g5(M, K);
+    if (packed_bytes < need) return VLUT_ERR_SMALL_BUFFER;
+    hipStream_t s = (hipStream_t)stream;
+    std::lock_guard<std::mutex> lock(g_pack_mutex);
+    int zero = 0;
+    if (hipMemcpyToSymbolAsync(HIP_SYMBOL(g_pack_error), &zero, sizeof(int), 0, hipMemcpyHostToDevice, s) != hipSuccess)
+        return VLUT_ERR_DEVICE;
+    int G = (int)(K / 5), KCn = (G + 15) / 16, RGtotal = (int)((M + 3) / 4);
+    size_t blocks = (need + 255) / 256;
+    hipLaunchKernelGGL(pack_kernel<5>, dim3((unsigned)blocks), dim3(256), 0, s, w_ternary, (int)M, (int)K, G, KCn, RGtotal,
+                       packed);
+    if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
+    int err = 0;
+    if (hipMemcpyFromSymbolAsync(&err, HIP_SYMBOL(g_pack_error), sizeof(int), 0, hipMemcpyDeviceToHost, s) != hipSuccess)
+        return VLUT_ERR_DEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess) return VLUT_ERR_DEVICE;
+    return err ? VLUT_ERR_VALUE : VLUT_OK;
+}
+
+size_t vlut_workspace_bytes_g5(int64_t M, int64_t K, int64_t N) {
+    if (!shape5_ok(M, K, N)) return 0;
+    Plan5 pl = choose_plan5(M, K, N);
+    return pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
+}
+
+int vlut_set_plan_g5(int R, int split_k) {
+    if (R != 0) {
+        bool ok = false;
+        for (int v : kSupportedR5) ok = ok || v == R;
+        if (!ok) return VLUT_ERR_UNSUPPORTED;
+    }
+    if (split_k < 0 || split_k > 16) return VLUT_ERR_UNSUPPORTED;
+    t_forced5 = {R, split_k};
+    return VLUT_OK;
+}
+
+int vlut_query_plan_g5(int64_t M, int64_t K, int64_t N, int* out3) {
+    if (!out3) return VLUT_ERR_NULL;
+    if (!shape5_ok(M, K, N)) return VLUT_ERR_SHAPE;
+    Plan5 pl = choose_plan5(M, K, N);
+    Derived5 d = derive5(pl, M, K, N);
+    out3[0] = pl.R; out3[1] = pl.S; out3[2] = d.total;
+    return VLUT_OK;
+}
+
+int vlut_mpgemm_g5(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale, int64_t M, int64_t K,
+                   int64_t N, float* y, int64_t ldy, int32_t* acc_or_null, void* workspace, size_t workspace_bytes,
+                   void* stream) {
+    if (!shape5_ok(M, K, N)) return VLUT_ERR_SHAPE;
+    if (!packed || !a_q || !a_scale) return VLUT_ERR_NULL;
+    if (!y && !acc_or_null) return VLUT_ERR_NULL;
+    if (y && (ldy < M || ldy > INT32_MAX)) return VLUT_ERR_SHAPE;
+    if (((uintptr_t)a_q) % 8 != 0) return VLUT_ERR_UNSUPPORTED;       // 5 rows x 8 tokens are read 8 bytes at a time
+    Plan5 pl = choose_plan5(M, K, N);
+    if (!plan5_valid(pl, M, K, N)) return VLUT_ERR_UNSUPPORTED;
+    Derived5 d = derive5(pl, M, K, N);
+    size_t ws_need = pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
+    if (ws_need > 0) {
+        if (!workspace) return VLUT_ERR_NULL;
+        if (workspace_bytes < ws_need) return VLUT_ERR_SMALL_BUFFER;
+    }
+    Lookup5Params p;
+    std::memset(&p, 0, sizeof(p));
+    p.packed = packed; p.a_q = a_q; p.a_scale = a_scale; p.y = y; p.acc = acc_or_null; p.ws = (int32_t*)workspace;
+    p.w_scale = w_scale;
+    p.M = (int)M; p.K = (int)K; p.N = (int)N; p.G = d.G; p.KCn = d.KCn; p.RGtotal = d.RGtotal; p.ldy = (int)ldy;
+    p.S = pl.S; p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.RGW = d.RGW;
+    p.dstages_total = d.dstages_total; p.dstages_per_split = d.dstages_per_split;
+    p.total_tiles = d.total; p.per_xcd = d.per_xcd;
+    hipStream_t s = (hipStream_t)stream;
+    int grid = d.per_xcd * 8;
+    int rc = d.need32 ? launch_lookup5_r<true>(pl.R, p, grid, s) : launch_lookup5_r<false>(pl.R, p, grid, s);
+    if (rc != VLUT_OK) return rc;
+    if (pl.S > 1) {
+        size_t total = (size_t)M * (size_t)N;
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           (const int32_t*)workspace, pl.S, (int)M, (int)N, w_scale, (const float*)nullptr, a_scale, y, ldy,
+                           acc_or_null);
+        if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
+    }
+    return VLUT_OK;
 }
 
 size_t vlut_mfma_workspace_bytes(int64_t M, int64_t K, int64_t N) {

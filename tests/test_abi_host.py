@@ -29,6 +29,13 @@ def L(vlut_lib_path):
     lib.vlut_mpgemm_mfma.argtypes = g
     lib.vlut_mpgemm_rows.argtypes = [vp, vp] + g[2:]
     lib.vlut_set_plan.argtypes = [ci, ci, ci, ci]
+    lib.vlut_packed_weight_bytes_g5.argtypes, lib.vlut_packed_weight_bytes_g5.restype = [i64, i64], sz
+    lib.vlut_packed_offset_g5.argtypes, lib.vlut_packed_offset_g5.restype = [i64, i64, i64, i64], sz
+    lib.vlut_workspace_bytes_g5.argtypes, lib.vlut_workspace_bytes_g5.restype = [i64, i64, i64], sz
+    lib.vlut_pack_weights_g5.argtypes = [vp, i64, i64, vp, sz, vp]
+    lib.vlut_mpgemm_g5.argtypes = [vp, cf, vp, vp, i64, i64, i64, vp, i64, vp, vp, sz, vp]
+    lib.vlut_set_plan_g5.argtypes = [ci, ci]
+    lib.vlut_query_plan_g5.argtypes = [i64, i64, i64, ctypes.POINTER(ci)]
     lib.vlut_query_plan.argtypes = [i64, i64, i64, ctypes.POINTER(ci)]
     return lib
 
@@ -152,3 +159,42 @@ def test_plans_cover_all_benchmark_shapes(L):
         assert tiles % (tiles_n * S) == 0
         tiles_m = tiles // (tiles_n * S)
         assert tiles_m * 48 * R >= M                                   # every row is covered (12 lookup waves x 4 rows x R)
+
+
+def test_g5_host_logic(L):
+    """1.60-bit packing: sizes (Sec. 3.3: 5 weights per byte, g | K), layout bijection, argument checks, plan coverage."""
+    assert L.vlut_packed_weight_bytes_g5(6912, 2560) == 6912 * 512             # 1.60 bits per weight, no padding needed
+    assert L.vlut_packed_weight_bytes_g5(6912, 2560) * 5 == L.vlut_packed_weight_bytes(6912, 2560) * 4
+    assert L.vlut_packed_weight_bytes_g5(5, 100) == 2 * 2 * 64                 # rows padded to 4, groups to 16
+    assert L.vlut_packed_weight_bytes_g5(8, 64) == 0 and L.vlut_packed_weight_bytes_g5(0, 80) == 0
+    M, K = 10, 100
+    offs = {L.vlut_packed_offset_g5(M, K, m, kg) for m in range(M) for kg in range(K // 5)}
+    assert len(offs) == M * (K // 5) and max(offs) < L.vlut_packed_weight_bytes_g5(M, K)
+    assert L.vlut_packed_offset_g5(M, K, M, 0) == 2 ** 64 - 1 and L.vlut_packed_offset_g5(M, K, 0, K // 5) == 2 ** 64 - 1
+    d = ctypes.c_void_p(0x1000)                                                # never dereferenced: checks come first
+    assert L.vlut_pack_weights_g5(None, 8, 80, d, 1 << 20, None) == -1
+    assert L.vlut_pack_weights_g5(d, 8, 64, d, 1 << 20, None) == -2            # 5 does not divide 64
+    assert L.vlut_pack_weights_g5(d, 8, 80, d, 63, None) == -3
+    assert L.vlut_mpgemm_g5(None, 1.0, d, d, 8, 80, 4, d, 8, None, None, 0, None) == -1
+    assert L.vlut_mpgemm_g5(d, 1.0, d, d, 8, 80, 4, None, 8, None, None, 0, None) == -1
+    assert L.vlut_mpgemm_g5(d, 1.0, d, d, 8, 82, 4, d, 8, None, None, 0, None) == -2
+    assert L.vlut_mpgemm_g5(d, 1.0, d, d, 8, 80, 4, d, 7, None, None, 0, None) == -2
+    assert L.vlut_set_plan_g5(3, 0) == -6 and L.vlut_set_plan_g5(0, 17) == -6
+    out = (ci * 3)()
+    try:
+        assert L.vlut_set_plan_g5(2, 4) == 0
+        need = L.vlut_workspace_bytes_g5(300, 5120, 40)
+        assert need == 4 * 300 * 40 * 4
+        assert L.vlut_mpgemm_g5(d, 1.0, d, d, 300, 5120, 40, d, 300, None, None, 0, None) == -1
+        assert L.vlut_mpgemm_g5(d, 1.0, d, d, 300, 5120, 40, d, 300, None, d, need - 1, None) == -3
+    finally:
+        assert L.vlut_set_plan_g5(0, 0) == 0
+    for (M, K, N) in [(6912, 2560, 128), (8640, 3200, 256), (3200, 8640, 256), (2560, 2560, 1), (640, 2560, 1024)]:
+        assert L.vlut_query_plan_g5(M, K, N, out) == 0
+        R, S, tiles = out[0], out[1], out[2]
+        assert R in (1, 2, 4, 6, 9, 12, 14) and 1 <= S <= 16 and tiles >= 1
+        stages = -(-(K // 5) // 64)
+        per_split = -(-stages // S)
+        assert per_split * 4 <= 51 or R <= 6                                   # INT16 block bound of Sec. 3.4
+        tiles_m = tiles // (S * -(-N // 8))
+        assert tiles_m * 48 * R >= M                                           # the tiles cover every row
