@@ -93,6 +93,23 @@ class Case:
                         self.N, self.y.data_ptr(), self.y.stride(0), None, self.mws.data_ptr(), self.mws.numel())
                        for pk in self.pool]
 
+    def enable_g5(self, B, torch, W, rotate_bytes):
+        """Adds the 1.60-bit blob of the same weights (K % 20 == 0 only) and pre-marshals vlut_mpgemm_g5."""
+        L = B.lib()
+        packed = B.pack_weights_g5(torch.from_numpy(W).cuda())
+        n_pool = 1 if rotate_bytes <= 0 else max(1, min(256, -(-rotate_bytes // packed.numel())))
+        self.pool5 = [packed] + [packed.clone() for _ in range(n_pool - 1)]
+        ws = L.vlut_workspace_bytes_g5(self.M, self.K, self.N)
+        self.ws5 = torch.empty(max(ws, 16), dtype=torch.uint8, device="cuda")
+        self.plan5 = B.query_plan_g5(self.M, self.K, self.N)
+        self._gemm5 = L.vlut_mpgemm_g5
+        self._g5args = [(pk.data_ptr(), self.w_scale, self.a_q.data_ptr(), self.a_s.data_ptr(), self.M, self.K, self.N,
+                         self.y.data_ptr(), self.y.stride(0), None, self.ws5.data_ptr(), self.ws5.numel())
+                        for pk in self.pool5]
+
+    def gemm_g5(self, i, stream):
+        self._check(self._gemm5(*self._g5args[i % len(self._g5args)], stream), "vlut_mpgemm_g5")
+
     def quantize(self, stream):
         self._check(self._quant(*self._qargs, stream), "vlut_quantize_act")
 
@@ -246,6 +263,16 @@ def main():
         sys.exit(4)
 
     ms_mfma = time_mfma(torch, case, args.steps, args.warmup)
+    g5 = None
+    if K % 20 == 0:
+        case.enable_g5(B, torch, W, rotate)
+        _, ms_g5, _ = run_timed(torch, case.gemm_g5, args.steps, args.warmup)
+        if not torch.equal(y_ref, case.y):
+            print("bench.py: the 1.60-bit path disagrees with the 2-bit path", file=sys.stderr)
+            sys.exit(4)
+        g5 = {"what": "vlut_mpgemm_g5 on the same weights packed 5 per byte (1.60 bits per weight, 243-row tables)",
+              "ms": ms_g5, "plan": {"R": case.plan5[0], "split_k": case.plan5[1], "workgroups": case.plan5[2]},
+              "packed_weight_bytes": case.pool5[0].numel(), "time_over_2bit": ms_g5 / ms_kernel}
     ops = 2.0 * M * K * N
     adds = M * (K // 4) * N                      # one INT16 add (= 2 table bytes) per (row, group, token)
     gops = ops / (ms_step * 1e-3) / 1e9
@@ -264,6 +291,7 @@ def main():
         "mfma_comparison": {"what": "vlut_mpgemm_mfma on the same inputs (unpack to INT8 + v_mfma_i32_16x16x64_i8), "
                                     "GPU ms per call incl. its activation re-layout kernel",
                             "ms": ms_mfma, "lut_over_mfma_time": ms_kernel / ms_mfma},
+        "g5_packing": g5,
         "roofline": {
             "kernel": "lookup_kernel (fused LDS table build + lookup-accumulate + epilogue)",
             "bound": "alu", "achieved": achieved_tadds, "peak": ALU_PEAK_TADDS, "unit": "TOP/s",
@@ -360,17 +388,21 @@ def main():
                     st, km, _ = time_case(B, torch, c, max(20, args.steps // 4), 5)
                     mf = time_mfma(torch, c, max(20, args.steps // 4), 5)
                     mm, kk = Wm.shape
+                    g5us = float("nan")
+                    if kk % 20 == 0:
+                        c.enable_g5(B, torch, Wm, rotate)
+                        g5us = run_timed(torch, c.gemm_g5, max(20, args.steps // 4), 5)[1] * 1e3
                     a = mm * (kk // 4) * n
                     rows.append((name, linr.name, mm, kk, n, c.plan, st * 1e3, km * 1e3,
                                  2.0 * mm * kk * n / (st * 1e-3) / 1e12, a / (km * 1e-3) / 1e12 / ALU_PEAK_TADDS,
-                                 wl.algorithmic_bytes(mm, kk, n) / (km * 1e-3) / 1e9 / HBM_PEAK_GBS, mf * 1e3))
+                                 wl.algorithmic_bytes(mm, kk, n) / (km * 1e-3) / 1e9 / HBM_PEAK_GBS, mf * 1e3, g5us))
                     del c
                     torch.cuda.empty_cache()
         print(f"{'workload':18s} {'lin':7s} {'M':>6s} {'K':>6s} {'N':>5s} {'plan(J,R,S,WG)':>18s} {'step us':>9s} "
-              f"{'mpgemm us':>9s} {'TOPS':>7s} {'alu/lds frac':>12s} {'hbm frac':>8s} {'mfma us':>8s}", file=sys.stderr)
+              f"{'mpgemm us':>9s} {'TOPS':>7s} {'alu/lds frac':>12s} {'hbm frac':>8s} {'mfma us':>8s} {'g5 us':>8s}", file=sys.stderr)
         for r in rows:
             print(f"{r[0]:18s} {r[1]:7s} {r[2]:6d} {r[3]:6d} {r[4]:5d} {str(r[5]):>18s} {r[6]:9.1f} {r[7]:9.1f} "
-                  f"{r[8]:7.1f} {r[9]:12.3f} {r[10]:8.3f} {r[11]:8.1f}", file=sys.stderr)
+                  f"{r[8]:7.1f} {r[9]:12.3f} {r[10]:8.3f} {r[11]:8.1f} {r[12]:8.1f}", file=sys.stderr)
 
     print(json.dumps(out))
 
