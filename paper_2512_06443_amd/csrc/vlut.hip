@@ -863,14 +863,31 @@ __global__ void __launch_bounds__(256) mfma_kernel(const MfmaParams p) {
     i32x4 acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = i32x4{0, 0, 0, 0};
-    for (int ks = 0; ks < p.KCn; ++ks) {
-        const unsigned w = *(const unsigned*)(arow + (size_t)ks * 64);
+    // Operands of the next two K steps are in flight while one step is multiplied (loads are clamped to the last
+    // step instead of branching; the surplus loads are never used).
+    auto load_w = [&](int ks) { return *(const unsigned*)(arow + (size_t)min(ks, p.KCn - 1) * 64); };
+    auto load_b = [&](int ks, i32x4 (&b)[NT]) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) b[t] = *(const i32x4*)(brow[t] + (size_t)min(ks, p.KCn - 1) * 64);
+    };
+    auto mul = [&](unsigned w, const i32x4 (&b)[NT]) {
         const i32x4 a = {(int)dec[w & 0xffu], (int)dec[(w >> 8) & 0xffu], (int)dec[(w >> 16) & 0xffu], (int)dec[w >> 24]};
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const i32x4 b = *(const i32x4*)(brow[t] + (size_t)ks * 64);
-            acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[t], 0, 0, 0);
-        }
+        for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b[t], acc[t], 0, 0, 0);
+    };
+    unsigned w0 = load_w(0), w1 = load_w(1), w2;
+    i32x4 b0[NT], b1[NT], b2[NT];
+    load_b(0, b0);
+    load_b(1, b1);
+    for (int ks = 0; ks < p.KCn; ks += 3) {
+        w2 = load_w(ks + 2); load_b(ks + 2, b2);
+        mul(w0, b0);
+        if (ks + 1 >= p.KCn) break;
+        w0 = load_w(ks + 3); load_b(ks + 3, b0);
+        mul(w1, b1);
+        if (ks + 2 >= p.KCn) break;
+        w1 = load_w(ks + 4); load_b(ks + 4, b1);
+        mul(w2, b2);
     }
     // C tile: lane (column = token i, row block kblk) holds rows 4*kblk .. 4*kblk+3
 #pragma unroll
@@ -1745,9 +1762,12 @@ int vlut_mpgemm_mfma(const uint8_t* packed, float w_scale, const int8_t* a_q, co
                        p.Kp, (int8_t*)workspace);
     if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
     const unsigned gx = (unsigned)((M + 63) / 64);
-    if (N <= 16) hipLaunchKernelGGL(mfma_kernel<1>, dim3(gx, (unsigned)(p.Npad / 16)), dim3(256), 0, s, p);
-    else if (N <= 32) hipLaunchKernelGGL(mfma_kernel<2>, dim3(gx, (unsigned)((p.Npad + 31) / 32)), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL(mfma_kernel<4>, dim3(gx, (unsigned)((p.Npad + 63) / 64)), dim3(256), 0, s, p);
+    // Tokens per workgroup (16, 32 or 64): the widest tile that still gives about four workgroups per CU, since the
+    // kernel hides memory latency with resident waves only.
+    const unsigned g64 = (unsigned)((p.Npad + 63) / 64), g32 = (unsigned)((p.Npad + 31) / 32), g16 = (unsigned)(p.Npad / 16);
+    if (N > 32 && (size_t)gx * g64 >= 1024) hipLaunchKernelGGL(mfma_kernel<4>, dim3(gx, g64), dim3(256), 0, s, p);
+    else if (N > 16 && (size_t)gx * g32 >= 1024) hipLaunchKernelGGL(mfma_kernel<2>, dim3(gx, g32), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(mfma_kernel<1>, dim3(gx, g16), dim3(256), 0, s, p);
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
 
