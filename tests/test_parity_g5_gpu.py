@@ -106,6 +106,18 @@ def test_g5_int16_block_is_overflow_free_at_the_extremes(B):
         run_case(B, W[:, :2560], np.float32(0.01), x[:, :2560], plan=(9, 1), tag=f"extreme{sign}-no-widening")
 
 
+def test_g5_ldy_and_acc_only(B):
+    W, s, x = wl.small_case(95, 100, 260, 12)
+    _, _, acc_ref, y_ref = O.mpgemm(W, s, x)
+    packed = B.pack_weights_g5(dev(W))
+    a_q, a_s = B.quantize_act(dev(x))
+    ybig = torch.full((12, 128), -7.0, device="cuda")
+    B.mpgemm_g5(packed, float(s), a_q, a_s, 100, y=ybig[:, :100])
+    yb = ybig.cpu().numpy()
+    check_y(yb[:, :100], y_ref)
+    assert np.all(yb[:, 100:] == -7.0)                      # nothing written past M
+
+
 def test_g5_full_size_bitnet2b_ffn_up(B):
     M, K, N = 6912, 2560, 128
     W = wl.ternary(0, M, K, 0.4)

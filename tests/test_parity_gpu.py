@@ -251,6 +251,19 @@ def test_acc_only_and_ldy(B):
     assert np.all(yb[:, 100:] == -7.0)                      # nothing written past M
 
 
+def test_smallest_shape_many_token_tiles_and_a_side_stream(B):
+    W, s, x = wl.small_case(81, 1, 4, 1)                    # M = 1, K = g, N = 1: one lookup in all
+    run_case(B, W, s, x, tag="1x4x1")
+    W, s, x = wl.small_case(82, 9, 64, 1030)                # 129 token tiles of 8, the last one ragged
+    run_case(B, W, s, x, plan=(16, 1, 0, 1), tag="n1030")
+    run_case(B, W, s, x, plan=(1, 1, 0, 1), tag="n1030-J1")
+    side = torch.cuda.Stream()                              # the calls only enqueue on the stream they are given
+    with torch.cuda.stream(side):
+        W, s, x = wl.small_case(83, 300, 1024, 40)
+        run_case(B, W, s, x, tag="side stream")
+    side.synchronize()
+
+
 def test_run_to_run_determinism(B):
     w = wl.WORKLOADS["bitnet2b_ffn_up"]
     W, s, x = wl.small_case(90, 1000, 2560, 128)
