@@ -264,6 +264,44 @@ def test_smallest_shape_many_token_tiles_and_a_side_stream(B):
     side.synchronize()
 
 
+def test_hip_graph_replays_match_eager(B):
+    """quantise + mpgemm (a split-K plan, so two kernels and the workspace) captured once and replayed on changing
+    inputs, with eager launches and synchronisations in between; every replay must equal the eager result."""
+    M, K, N = 300, 1024, 24
+    W = wl.ternary(85, M, K, 0.4)
+    packed = B.pack_weights(dev(W))
+    x_dev = torch.empty((N, K), dtype=torch.float32, device="cuda")
+    a_q = torch.empty(((N + 7) // 8, K, 8), dtype=torch.int8, device="cuda")
+    a_s = torch.empty(N, dtype=torch.float32, device="cuda")
+    y = torch.empty((N, M), dtype=torch.float32, device="cuda")
+    B.set_plan(16, 2, 0, 4)
+    try:
+        ws = torch.empty(max(B.workspace_bytes(M, K, N), 16), dtype=torch.uint8, device="cuda")
+        side = torch.cuda.Stream()
+        x_dev.copy_(dev(wl.activations(86, N, K)))
+        with torch.cuda.stream(side):                       # warm-up outside the capture
+            B.quantize_act(x_dev, a_q, a_s)
+            B.mpgemm(packed, 0.02, a_q, a_s, M, y=y, workspace=ws)
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            B.quantize_act(x_dev, a_q, a_s)
+            B.mpgemm(packed, 0.02, a_q, a_s, M, y=y, workspace=ws)
+        for seed in (87, 88, 89):
+            x = wl.activations(seed, N, K)
+            x_dev.copy_(dev(x))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            y_graph = y.clone()
+            y_eager, _ = B.mpgemm(packed, 0.02, *B.quantize_act(dev(x)), M)   # eager work between the replays
+            torch.cuda.synchronize()
+            assert torch.equal(y_graph, y_eager)
+            check_y(y_graph.cpu().numpy(), O.mpgemm(W, np.float32(0.02), x)[3])
+    finally:
+        B.set_plan(0, 0, 0, 0)
+
+
 def test_run_to_run_determinism(B):
     w = wl.WORKLOADS["bitnet2b_ffn_up"]
     W, s, x = wl.small_case(90, 1000, 2560, 128)
