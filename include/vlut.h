@@ -148,6 +148,8 @@ int vlut_build_lut(const int8_t* a_q, int64_t K, int64_t N, int16_t* lut, size_t
  *   acc_or_null   dev or NULL, int32 [M][N] raw accumulators (token-contiguous)
  *   workspace     dev, workspace_bytes >= vlut_workspace_bytes(M, K, N); may be
  *                 NULL when that size is 0
+ * For one or two tokens (N <= 2, streamed tables, no plan override) a kernel specialised for that case runs
+ * instead; the results are the same numbers.
  */
 int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale,
                 const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y, int64_t ldy,
@@ -221,6 +223,8 @@ int vlut_set_plan(int J, int R, int waves, int split_k);
 /*
  * Reports the launch plan vlut_mpgemm would use for this shape (after any vlut_set_plan override of the
  * calling thread): out4 (host, 4 ints) = { J, R, split_k, number of workgroup tiles }.
+ * With N <= 2 and no override, vlut_mpgemm uses a kernel of its own (table entries of one dword, every workgroup
+ * sweeps all of K, no workspace); it is reported as { 0, rows per workgroup, 1, number of workgroups }.
  */
 int vlut_query_plan(int64_t M, int64_t K, int64_t N, int* out4);
 

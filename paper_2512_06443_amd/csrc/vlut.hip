@@ -1174,6 +1174,169 @@ __global__ void __launch_bounds__(kThreads) lookup5_kernel(const Lookup5Params p
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// N <= 2 (one or two parallel tokens: decoding).  A table entry is then one dword (two INT16 sums), the tables of a
+// 256-group chunk of K take 86 KB, and a workgroup can sweep all of K by itself: no split-K partial sums, no second
+// kernel, one barrier pair per chunk.  All 16 waves build a chunk together, then all 16 look it up.
+//   Tables: sub-table kg of the chunk = three blocks (leading digit d0 = 0,1,2) of 27 entries padded to 28 dwords:
+//           entry idx lives at kg*336 + (idx + idx/27)*4.  A build lane (kg, d0) owns one block = 7 aligned 16-byte
+//           stores at 112*tid, which is free of bank conflicts.
+//   Lookups: wave w reads the packed tile w of the chunk (16 groups); a lane owns an output row and 16/PARTS of the
+//           tile's groups (PARTS lanes per row), RR rows one after the other; INT16 sums inside a chunk (at most 16
+//           lookups), INT32 across chunks; the 16*PARTS partial sums per row are added through LDS at the end.
+// ---------------------------------------------------------------------------------------------
+constexpr int kNarrowChunk = 256;                        // k-groups per chunk = 16 packed tiles, one per wave
+constexpr int kNarrowSubBytes = 336;                     // 3 blocks x 28 dwords
+constexpr int kNarrowLdsBytes = kNarrowChunk * kNarrowSubBytes;   // 86016
+
+struct NarrowParams {
+    const uint8_t* packed;
+    const int8_t* a_q;
+    const float* a_scale;
+    const float* w_rows;
+    float* y;
+    int32_t* acc;
+    float w_scale;
+    int M, K, N, G, KCn, RGtotal, ldy, chunks;
+};
+
+template <int PARTS, int RR>
+__global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_n[];
+    if (lds_base_of(smem_n) != 0u) return;               // table addresses below are absolute LDS addresses
+    constexpr int RPW = 64 / PARTS;                       // rows of one pass of a wave
+    constexpr int ROWS = RPW * RR;                        // rows of the workgroup
+    constexpr int NBYTES = 16 / PARTS;                    // groups (= bytes of the packed tile row) per lane
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m0 = blockIdx.x * ROWS;
+
+    // ---- build geometry: thread tid < 768 owns block tid = (k-group tid/3, leading digit tid%3) of every chunk
+    const bool builds = tid < 3 * kNarrowChunk;
+    const int kg_b = tid / 3, d0 = tid - 3 * kg_b;
+    // ---- lookup geometry
+    const int part = lane / RPW, row_l = lane % RPW;
+    const unsigned lane_tab = (unsigned)(wave * 16 + part * NBYTES) * kNarrowSubBytes;   // first sub-table of this lane
+    const unsigned char* wrow[RR];
+    bool row_ok[RR];
+#pragma unroll
+    for (int rr = 0; rr < RR; ++rr) {
+        const int m = m0 + rr * RPW + row_l;
+        row_ok[rr] = m < p.M;
+        const int mc = row_ok[rr] ? m : 0;
+        wrow[rr] = p.packed + ((size_t)(mc >> 2) * p.KCn) * 64 + (mc & 3) * 16 + part * NBYTES;
+    }
+    int acc32[RR][2];
+#pragma unroll
+    for (int rr = 0; rr < RR; ++rr) { acc32[rr][0] = 0; acc32[rr][1] = 0; }
+
+    // activations of tokens 0,1 for the four rows of a k-group: bytes 0,1 of a_q[0][4kg + j][*] (chunk 0 of tokens)
+    auto fetch_act = [&](int c, unsigned (&a)[4]) {
+        const int kg = min(c * kNarrowChunk + kg_b, p.G - 1);          // clamped; validity applied at use
+        const unsigned short* src = (const unsigned short*)(p.a_q + (size_t)(4 * kg) * 8);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] = src[4 * j];                 // 8 bytes per activation row
+    };
+    typedef unsigned wvec __attribute__((ext_vector_type(4)));
+    auto fetch_w = [&](int c, wvec (&w)[RR]) {
+        const int tile = min(c * 16 + wave, p.KCn - 1);                // clamped tile meets all-zero tables
+#pragma unroll
+        for (int rr = 0; rr < RR; ++rr) {
+            const unsigned char* src = wrow[rr] + (size_t)tile * 64;
+            if constexpr (PARTS == 1) {
+                const i32x4 v = *(const i32x4*)src;
+                w[rr] = wvec{(unsigned)v.x, (unsigned)v.y, (unsigned)v.z, (unsigned)v.w};
+            } else if constexpr (PARTS == 2) {
+                const i32x2 v = *(const i32x2*)src;
+                w[rr] = wvec{(unsigned)v.x, (unsigned)v.y, 0u, 0u};
+            } else {
+                w[rr] = wvec{*(const unsigned*)src, 0u, 0u, 0u};
+            }
+        }
+    };
+
+    unsigned act_cur[4] = {0, 0, 0, 0}, act_nxt[4] = {0, 0, 0, 0};
+    wvec w_cur[RR], w_nxt[RR];
+    if (builds) fetch_act(0, act_cur);
+    fetch_w(0, w_cur);
+    for (int c = 0; c < p.chunks; ++c) {
+        // ---------------- build the chunk's tables (topological order of Sec. 4: one add per entry)
+        if (builds) {
+            const bool valid = c * kNarrowChunk + kg_b < p.G;
+            s16x2 a[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const unsigned v = valid ? act_cur[j] : 0u;
+                a[j] = s16x2{(short)(signed char)(v & 0xffu), (short)(signed char)((v >> 8) & 0xffu)};
+            }
+            const short s0 = (short)(d0 - 1);
+            const s16x2 base = a[0] * s16x2{s0, s0};
+            const unsigned dst = (unsigned)tid * 112u;
+            int blk[28];
+#pragma unroll
+            for (int d1 = 0; d1 < 3; ++d1) {
+                const s16x2 b1 = d1 == 0 ? base - a[1] : (d1 == 1 ? base : base + a[1]);
+#pragma unroll
+                for (int d2 = 0; d2 < 3; ++d2) {
+                    const s16x2 b2 = d2 == 0 ? b1 - a[2] : (d2 == 1 ? b1 : b1 + a[2]);
+                    blk[9 * d1 + 3 * d2 + 0] = as_int(b2 - a[3]);
+                    blk[9 * d1 + 3 * d2 + 1] = as_int(b2);
+                    blk[9 * d1 + 3 * d2 + 2] = as_int(b2 + a[3]);
+                }
+            }
+            blk[27] = 0;
+            static_for<0, 7>([&](auto qc) {
+                constexpr int q = decltype(qc)::value;
+                lds_write128<q>(dst, i32x4{blk[4 * q], blk[4 * q + 1], blk[4 * q + 2], blk[4 * q + 3]});
+            });
+            fetch_act(c + 1, act_nxt);
+        }
+        fetch_w(c + 1, w_nxt);
+        wg_barrier_lds();
+        // ---------------- look the chunk up
+#pragma unroll
+        for (int rr = 0; rr < RR; ++rr) {
+            s16x2 acc16 = {0, 0};
+            static_for<0, NBYTES>([&](auto bc) {
+                constexpr int b = decltype(bc)::value;
+                const unsigned idx = (w_cur[rr][b >> 2] >> (8 * (b & 3))) & 0xffu;
+                const unsigned slot = idx + ((idx * 19u) >> 9);            // idx + idx/27 for idx < 81
+                const unsigned addr = lane_tab + slot * 4u;
+                acc16 += as_s16x2(((const lds_i32*)addr)[b * (kNarrowSubBytes / 4)]);
+            });
+            acc32[rr][0] += (int)acc16.x;
+            acc32[rr][1] += (int)acc16.y;
+        }
+        wg_barrier_lds();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) act_cur[j] = act_nxt[j];
+#pragma unroll
+        for (int rr = 0; rr < RR; ++rr) w_cur[rr] = w_nxt[rr];
+    }
+
+    // ---------------- add the 16*PARTS partial sums of every (row, token) through LDS, scale, store
+    lds_i32* red = (lds_i32*)0u;                          // [16*PARTS][ROWS][2], reuses the table space
+#pragma unroll
+    for (int rr = 0; rr < RR; ++rr) {
+        const int ri = rr * RPW + row_l;
+        const int pi = wave * PARTS + part;
+        red[(pi * ROWS + ri) * 2 + 0] = acc32[rr][0];
+        red[(pi * ROWS + ri) * 2 + 1] = acc32[rr][1];
+    }
+    wg_barrier_lds();
+    for (int i = tid; i < ROWS * 2; i += kThreads) {
+        const int ri = i >> 1, n = i & 1;
+        const int m = m0 + ri;
+        if (m < p.M && n < p.N) {
+            int v = 0;
+            for (int pi = 0; pi < 16 * PARTS; ++pi) v += red[(pi * ROWS + ri) * 2 + n];
+            if (p.y) p.y[(size_t)n * p.ldy + m] = (float)v * ((p.w_rows ? p.w_rows[m] : p.w_scale) * p.a_scale[n]);
+            if (p.acc) p.acc[(size_t)m * p.N + n] = v;
+        }
+    }
+}
+
 // Sum of the split-K partials (any order is exact: integers) + scale step.
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const int32_t* __restrict__ ws, int S, int M, int N,
                                                             float w_scale, const float* __restrict__ w_rows,
@@ -1355,6 +1518,49 @@ int check_mpgemm_args(const uint8_t* packed, const int8_t* a_q, const float* a_s
     return VLUT_OK;
 }
 
+// ---- N <= 2 kernel: rows per workgroup (16..256) so that the grid is about one workgroup per CU
+struct NarrowPlan {
+    int parts, rr, rows, grid, chunks;
+};
+
+bool narrow_applies(int64_t N, const void* lut) {
+    return N <= 2 && lut == nullptr && t_forced.Jlog < 0 && t_forced.R == 0 && t_forced.S == 0;
+}
+
+NarrowPlan narrow_plan(int64_t M, int64_t K) {
+    const int64_t want = (M + 255) / 256;
+    NarrowPlan np;
+    if (want <= 16) np = {4, 1, 16, 0, 0};
+    else if (want <= 32) np = {2, 1, 32, 0, 0};
+    else if (want <= 64) np = {1, 1, 64, 0, 0};
+    else if (want <= 128) np = {1, 2, 128, 0, 0};
+    else np = {1, 4, 256, 0, 0};
+    np.grid = (int)((M + np.rows - 1) / np.rows);
+    np.chunks = (int)((K / 4 + kNarrowChunk - 1) / kNarrowChunk);
+    return np;
+}
+
+template <int PARTS, int RR>
+int launch_narrow_t(const NarrowParams& p, int grid, hipStream_t stream) {
+    auto kfn = narrow_kernel<PARTS, RR>;
+    static bool attr_done = false;   // benign race: the call is idempotent
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, kNarrowLdsBytes) != hipSuccess)
+            return VLUT_ERR_DEVICE;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), kNarrowLdsBytes, stream, p);
+    return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
+}
+
+int launch_narrow(const NarrowPlan& np, const NarrowParams& p, hipStream_t stream) {
+    if (np.parts == 4) return launch_narrow_t<4, 1>(p, np.grid, stream);
+    if (np.parts == 2) return launch_narrow_t<2, 1>(p, np.grid, stream);
+    if (np.rr == 1) return launch_narrow_t<1, 1>(p, np.grid, stream);
+    if (np.rr == 2) return launch_narrow_t<1, 2>(p, np.grid, stream);
+    return launch_narrow_t<1, 4>(p, np.grid, stream);
+}
+
 std::mutex g_pack_mutex;
 
 // ---- 1.60-bit (g = 5) host side
@@ -1493,6 +1699,7 @@ size_t vlut_lut_bytes(int64_t K, int64_t N) {
 
 size_t vlut_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     if (!shape_ok(M, K, N)) return 0;
+    if (narrow_applies(N, nullptr)) return 0;
     Plan pl = choose_plan(M, K, N);
     return pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
 }
@@ -1516,6 +1723,11 @@ int vlut_set_plan(int J, int R, int waves, int split_k) {
 int vlut_query_plan(int64_t M, int64_t K, int64_t N, int* out4) {
     if (!out4) return VLUT_ERR_NULL;
     if (!shape_ok(M, K, N)) return VLUT_ERR_SHAPE;
+    if (narrow_applies(N, nullptr)) {          // the N <= 2 kernel: J reported as 0, R = rows per workgroup
+        const NarrowPlan np = narrow_plan(M, K);
+        out4[0] = 0; out4[1] = np.rows; out4[2] = 1; out4[3] = np.grid;
+        return VLUT_OK;
+    }
     Plan pl = choose_plan(M, K, N);
     Derived d = derive(pl, M, K, N);
     out4[0] = 1 << pl.Jlog;
@@ -1590,8 +1802,17 @@ static int mpgemm_impl(const uint8_t* packed, float w_scale, const float* w_rows
                        int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_mpgemm_args(packed, a_q, a_scale, M, K, N, y, ldy, acc_or_null);
     if (rc != VLUT_OK) return rc;
-    Plan pl = choose_plan(M, K, N);
     if (((uintptr_t)a_q) % 16 != 0) return VLUT_ERR_UNSUPPORTED;      // the [N/8][K][8] blocks are read 16 bytes at a time
+    if (narrow_applies(N, lut_or_null)) {      // one or two tokens: the workgroups sweep all of K, no workspace
+        const NarrowPlan np = narrow_plan(M, K);
+        NarrowParams q;
+        std::memset(&q, 0, sizeof(q));
+        q.packed = packed; q.a_q = a_q; q.a_scale = a_scale; q.w_rows = w_rows; q.y = y; q.acc = acc_or_null;
+        q.w_scale = w_scale; q.M = (int)M; q.K = (int)K; q.N = (int)N; q.G = (int)(K / 4);
+        q.KCn = (int)((K / 4 + 15) / 16); q.RGtotal = (int)((M + 3) / 4); q.ldy = (int)ldy; q.chunks = np.chunks;
+        return launch_narrow(np, q, (hipStream_t)stream);
+    }
+    Plan pl = choose_plan(M, K, N);
     const bool al = lut_or_null && (N % 8 == 0) && (((uintptr_t)lut_or_null) % 16 == 0);
     const int mode = lut_or_null ? kFromGlobal : kFast;
     if (mode != kFast) pl.R = pl.R >= 4 ? 4 : (pl.R >= 2 ? 2 : 1);   // the general-purpose kernels are built for these R only

@@ -190,8 +190,10 @@ def test_stacked_matrices_with_row_scales(B):
     W = np.concatenate(Ws, axis=0)
     M = W.shape[0]
     w_rows = np.concatenate([np.full(m, sc, np.float32) for m, sc in zip(rows, scales)])
-    for plan in ((0, 0, 0, 0), (16, 2, 0, 3), (4, 3, 0, 1)):
-        print(f"case stacked plan={plan}", flush=True)
+    xs = {33: x, 2: wl.activations(62, 2, K)}
+    for plan, N in (((0, 0, 0, 0), 33), ((16, 2, 0, 3), 33), ((4, 3, 0, 1), 33), ((0, 0, 0, 0), 2)):
+        x = xs[N]
+        print(f"case stacked plan={plan} N={N}", flush=True)
         B.set_plan(*plan)
         try:
             packed = B.pack_weights(dev(W))
@@ -225,6 +227,17 @@ def test_gemv_and_other_n(B):
     for N in (1, 2, 15, 16, 17, 64):
         W, s, x = wl.small_case(50 + N, 640, 2560, N)
         run_case(B, W, s, x, tag=f"N{N}")
+
+
+@pytest.mark.parametrize("M", [100, 5000, 10000, 20000, 40000])
+def test_one_or_two_tokens_every_tile_shape(B, M):
+    # N <= 2 runs a kernel of its own; M picks its rows per workgroup (16, 32, 64, 128, 256)
+    for N, K in ((1, 260), (2, 1028)):                      # K = 1028: two chunks of 256 groups, the second ragged
+        W, s, x = wl.small_case(300 + M % 97 + N, M, K, N)
+        assert B.query_plan(M, K, N)[0] == 0
+        run_case(B, W, s, x, tag=f"narrow M{M} N{N}")
+    W, s, x = wl.small_case(301, 300, 4352, 2)
+    run_case(B, W, s, x, plan=(16, 2, 0, 3), tag="general kernel at N=2 when a plan is forced")
 
 
 def test_unstreamed_table_variant(B):
