@@ -93,6 +93,18 @@ class Case:
                         self.N, self.y.data_ptr(), self.y.stride(0), None, self.mws.data_ptr(), self.mws.numel())
                        for pk in self.pool]
 
+        # quantisation fused into the lookup kernel: fp32 activations in, one launch per step
+        self._f32 = L.vlut_mpgemm_f32
+        self.ws32 = torch.empty(max(L.vlut_workspace_bytes_f32(self.M, self.K, self.N), 16), dtype=torch.uint8, device="cuda")
+        self.plan32 = B.query_plan_f32(self.M, self.K, self.N)
+        rows_ptr = None if self.w_rows is None else self.w_rows.data_ptr()
+        self._fargs = [(pk.data_ptr(), self.w_scale, rows_ptr, self.x.data_ptr(), self.x.stride(0), self.M, self.K, self.N,
+                        self.y.data_ptr(), self.y.stride(0), None, None, self.ws32.data_ptr(), self.ws32.numel())
+                       for pk in self.pool]
+
+    def step_fused(self, i, stream):
+        self._check(self._f32(*self._fargs[i % len(self._fargs)], stream), "vlut_mpgemm_f32")
+
     def enable_g5(self, B, torch, W, rotate_bytes):
         """Adds the 1.60-bit blob of the same weights (K % 20 == 0 only) and pre-marshals vlut_mpgemm_g5."""
         L = B.lib()

@@ -169,6 +169,31 @@ int vlut_mpgemm_rows(const uint8_t* packed, const float* w_scale_rows, const int
                      int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Quantisation and mpGeMM in one call, from fp32 activations: the steps of vlut_quantize_act (Sec. 3.4 first
+ * paragraph: per-token absmax INT8) and of vlut_mpgemm / vlut_mpgemm_rows (Alg. 1, Eq. 2) with the same readings and
+ * the same numbers, but the workgroups of the lookup kernel quantise the tokens of their own tile themselves (absmax
+ * over the whole row, codes kept in LDS), so that neither the INT8 activations nor a second launch are needed.
+ *   x             dev, fp32 [N][ldx], ldx >= K (16-byte aligned rows are read as float4)
+ *   w_scale / w_scale_rows_or_null   per-tensor scale, or (non-NULL) dev fp32 [M] per-row scales as in
+ *                 vlut_mpgemm_rows (w_scale is then ignored)
+ *   y, ldy, acc_or_null              as in vlut_mpgemm
+ *   a_scale_out_or_null              dev or NULL, fp32 [N]: receives the token scales s_n = amax_n / 127
+ *   workspace     dev, 16-byte aligned, workspace_bytes >= vlut_workspace_bytes_f32(M, K, N); may be NULL when that
+ *                 size is 0
+ * Shapes the fused kernels do not cover (a K range of more than 8704 per workgroup after the split of K, a launch
+ * plan forced to fewer than 16 sub-tables per table row, more than 37888 values of K for one or two tokens) are run
+ * as vlut_quantize_act into the workspace followed by the ordinary path (with that call's own limit on K, reported as
+ * VLUT_ERR_UNSUPPORTED); vlut_query_plan_f32 tells which:
+ *   out5 = {J, R, split_k, workgroups, fused (1) or two launches (0)}  (J, R as in vlut_query_plan)
+ * Errors as in vlut_mpgemm; VLUT_ERR_SHAPE also for ldx < K.
+ */
+size_t vlut_workspace_bytes_f32(int64_t M, int64_t K, int64_t N);            /* 0 if the shape is invalid      */
+int vlut_query_plan_f32(int64_t M, int64_t K, int64_t N, int* out5);
+int vlut_mpgemm_f32(const uint8_t* packed, float w_scale, const float* w_scale_rows_or_null, const float* x, int64_t ldx,
+                    int64_t M, int64_t K, int64_t N, float* y, int64_t ldy, int32_t* acc_or_null,
+                    float* a_scale_out_or_null, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * 1.60-bit packing (g = 5, the paper's I1; Sec. 3.3 "Flexible sub-2-bit weight packing", Fig. 5): five weights per
  * base-3 byte, idx = sum_j (W[m][5kg+j] + 1) * 3^(4-j) in [0, 243), 243-row sub-tables, INT16 blocks of at most
  * 51 = floor(32767 / (127 * 5)) lookups (Sec. 3.4).  Shapes: K >= 5 and K % 5 == 0 (g | K); together with

@@ -27,6 +27,7 @@ EXPORTS = [
     "vlut_mpgemm_rows", "vlut_mpgemm_mfma", "vlut_mfma_workspace_bytes", "vlut_set_plan", "vlut_query_plan",
     "vlut_packed_weight_bytes_g5", "vlut_packed_offset_g5", "vlut_workspace_bytes_g5", "vlut_pack_weights_g5",
     "vlut_mpgemm_g5", "vlut_set_plan_g5", "vlut_query_plan_g5",
+    "vlut_workspace_bytes_f32", "vlut_query_plan_f32", "vlut_mpgemm_f32",
 ]
 
 _lib = None
@@ -68,6 +69,10 @@ def lib() -> ctypes.CDLL:
         L.vlut_mpgemm_g5.argtypes, L.vlut_mpgemm_g5.restype = [p, cf, p, p, i64, i64, i64, p, i64, p, p, sz, p], ci
         L.vlut_set_plan_g5.argtypes, L.vlut_set_plan_g5.restype = [ci, ci], ci
         L.vlut_query_plan_g5.argtypes, L.vlut_query_plan_g5.restype = [i64, i64, i64, ctypes.POINTER(ci)], ci
+        L.vlut_workspace_bytes_f32.argtypes, L.vlut_workspace_bytes_f32.restype = [i64, i64, i64], sz
+        L.vlut_query_plan_f32.argtypes, L.vlut_query_plan_f32.restype = [i64, i64, i64, ctypes.POINTER(ci)], ci
+        L.vlut_mpgemm_f32.argtypes = [p, cf, p, p, i64, i64, i64, i64, p, i64, p, p, p, sz, p]
+        L.vlut_mpgemm_f32.restype = ci
         L.vlut_set_plan.argtypes, L.vlut_set_plan.restype = [ci, ci, ci, ci], ci
         L.vlut_query_plan.argtypes, L.vlut_query_plan.restype = [i64, i64, i64, ctypes.POINTER(ci)], ci
         _lib = L
@@ -199,6 +204,37 @@ def mpgemm_rows(packed: torch.Tensor, w_scale_rows: torch.Tensor, a_q: torch.Ten
                                 0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "vlut_mpgemm_rows")
     return y, acc
+
+
+def query_plan_f32(M: int, K: int, N: int) -> Tuple[int, int, int, int, bool]:
+    """(J, R, split_k, workgroups, fused) that vlut_mpgemm_f32 uses for this shape."""
+    out = (ctypes.c_int * 5)()
+    _check(lib().vlut_query_plan_f32(M, K, N, out), "vlut_query_plan_f32")
+    return out[0], out[1], out[2], out[3], bool(out[4])
+
+
+def mpgemm_f32(packed: torch.Tensor, w_scale, x: torch.Tensor, M: int, y: Optional[torch.Tensor] = None,
+               want_acc: bool = False, want_scales: bool = False, workspace: Optional[torch.Tensor] = None):
+    """Runs vlut_mpgemm_f32 on fp32 activations x [N][K] (row stride >= K).  w_scale: a float, or an fp32 [M]
+    tensor on the GPU with one weight scale per output row.  Returns (y [N][M], acc or None, a_scale or None)."""
+    assert x.is_cuda and x.dtype == torch.float32 and x.dim() == 2 and x.stride(1) == 1
+    N, K = x.shape
+    dev = x.device
+    rows = w_scale if isinstance(w_scale, torch.Tensor) else None
+    if rows is not None:
+        assert rows.is_cuda and rows.dtype == torch.float32 and rows.numel() == M
+    if y is None:
+        y = torch.empty((N, M), dtype=torch.float32, device=dev)
+    acc = torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None
+    scales = torch.empty(N, dtype=torch.float32, device=dev) if want_scales else None
+    ws_bytes = lib().vlut_workspace_bytes_f32(M, K, N)
+    if workspace is None and ws_bytes:
+        workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    rc = lib().vlut_mpgemm_f32(_ptr(packed), 1.0 if rows is not None else float(w_scale), _ptr(rows), _ptr(x), x.stride(0),
+                               M, K, N, _ptr(y), y.stride(0), _ptr(acc), _ptr(scales), _ptr(workspace),
+                               0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "vlut_mpgemm_f32")
+    return y, acc, scales
 
 
 # ---- 1.60-bit packing (g = 5)

@@ -38,6 +38,16 @@ constexpr int kSlotBytes = kRows * kRowBytes;  // 20736
 constexpr int kStageSlots = 4;               // slots resident per stage (one weight dword = 4 lookups)
 constexpr int kTableBytes = kStageSlots * kSlotBytes;  // 82944
 constexpr int kLdsBytes = kTableBytes + 128 * 4;    // + the output scales of the tile's tokens
+// Fused quantisation: behind the tables and the scales, 16 x 8 partial absmax values, then the INT8 codes of the
+// tile's 8 tokens for the workgroup's K range.  A stage (64 k-groups) is 8 blocks (slot of the stage x activation
+// row pair) of 16 sub-tables x 16 bytes, pitched 288 bytes so that both the quantiser's dword stores and the build
+// waves' 16-byte reads are free of bank conflicts.
+constexpr int kFusedRedBase = kLdsBytes;
+constexpr int kFusedAqBase = kFusedRedBase + 16 * 8 * 4;
+constexpr int kFusedBlockPitch = 288;
+constexpr int kFusedStageBytes = 8 * kFusedBlockPitch;           // 2304
+constexpr int kFusedMaxLds = 160 * 1024;
+constexpr int kFusedMaxStages = (kFusedMaxLds - kFusedAqBase) / kFusedStageBytes;   // 34 stages = 8704 values of K
 constexpr int kWaves = 16;                   // waves per workgroup
 constexpr int kThreads = kWaves * 64;
 constexpr unsigned kZeroIdx4 = 0x28282828u;  // four copies of index 40 (the all-zero pattern)
@@ -57,6 +67,11 @@ struct LookupParams {
     int M, K, N, G, KCn, RGtotal, ldy;
     int Jlog, S, tiles_m, tiles_n, RGW, stages_total, stages_per_split, total_tiles, per_xcd;
     int aligned8;
+    // fused quantisation (MODE kFusedQuant): fp32 activations [N][ldx] instead of a_q / a_scale
+    const float* x;
+    float* a_scale_out;       // optional: the token scales, written by the workgroups of the first row tile
+    int64_t ldx;
+    int x_vec;                // rows can be read as float4
 };
 
 __device__ __forceinline__ unsigned lds_base_of(void* p) {
@@ -182,26 +197,58 @@ __global__ void pack_kernel(const int8_t* __restrict__ w, int M, int K, int G, i
 
 // ---------------------------------------------------------------------------------------------
 // Activation quantisation + transposition (Sec. 3.4 first paragraph, Sec. 3.3).
-// One workgroup handles one chunk of 8 consecutive tokens over all K: 128 threads per token read the
-// token's row with 16-byte loads, the 8 codes of every k are gathered in LDS as the chunk's [K][8]
-// block, which is contiguous in the token-chunked layout and leaves with 16-byte stores.
+// One workgroup handles one chunk of 8 consecutive tokens over all K.  A wave reads 8 consecutive float4 of each
+// of the 8 tokens per pass (lane = token + 8 * quad): 128 contiguous bytes per token.  The four codes a lane makes
+// (4 consecutive k of one token) are transposed inside its quad of lanes, so that every lane leaves with one dword
+// of the chunk's [K][8] block (4 tokens of one k) and a wave's LDS store is 256 contiguous bytes, free of bank
+// conflicts; the block is contiguous in the token-chunked layout and leaves with 16-byte stores.
 //   NV  float4 values per thread kept in registers between the absmax pass and the rounding pass
 //       (0: x is read twice, for large K)
 //   VEC true when rows can be read as float4 (x and ldx 16-byte aligned)
 // ---------------------------------------------------------------------------------------------
 constexpr int kQuantThreads = 1024;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Absmax quantiser of one token row, decided in fp32: inv = 127 / amax (IEEE division, 0 for an all-zero row),
+// code = clamp(rint(x * inv), -127, 127) with ties to even.
+// Four values at once, code of v[c] in byte c.  |v * inv| <= 127 (1 + 2^-23) for finite rows, so the rounded value r
+// is an integer of [-127, 127], r + 128 is exact and fits a byte: one saturating float -> byte conversion per value
+// writes it in place, and flipping the top bits afterwards subtracts the 128 again.  The lower clamp stays as an
+// instruction (an overflowing inv = 127 / amax for rows below 4e-37 can make r = -inf); the upper one is the
+// conversion's saturation.
+__device__ __forceinline__ unsigned quant_codes4(const f32x4 v, float inv) {
+    unsigned d = 0u;
+    d = __builtin_amdgcn_cvt_pk_u8_f32(fmaxf(rintf(v.x * inv), -127.0f) + 128.0f, 0u, d);
+    d = __builtin_amdgcn_cvt_pk_u8_f32(fmaxf(rintf(v.y * inv), -127.0f) + 128.0f, 1u, d);
+    d = __builtin_amdgcn_cvt_pk_u8_f32(fmaxf(rintf(v.z * inv), -127.0f) + 128.0f, 2u, d);
+    d = __builtin_amdgcn_cvt_pk_u8_f32(fmaxf(rintf(v.w * inv), -127.0f) + 128.0f, 3u, d);
+    return d ^ 0x80808080u;
+}
+// The lane holds the codes of k = 4q .. 4q+3 of token `tok` (byte c = k offset c); the four lanes of a quad hold
+// four consecutive tokens of the same q.  Returns, for the lane with tok % 4 == c, the codes of those four tokens
+// at k = 4q + c (byte e = token 4*(tok/4) + e).
+__device__ __forceinline__ unsigned quad_transpose_codes(unsigned d, int tok) {
+    const unsigned d0 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)d, 0x00, 0xF, 0xF, false);
+    const unsigned d1 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)d, 0x55, 0xF, 0xF, false);
+    const unsigned d2 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)d, 0xAA, 0xF, 0xF, false);
+    const unsigned d3 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)d, 0xFF, 0xF, 0xF, false);
+    const unsigned c = (unsigned)tok & 3u;
+    const unsigned lo = __builtin_amdgcn_perm(d1, d0, 0x0c0c0000u | ((4u + c) << 8) | c);
+    const unsigned hi = __builtin_amdgcn_perm(d3, d2, 0x00000c0cu | ((4u + c) << 24) | (c << 16));
+    return lo | hi;
+}
 
 template <int NV, bool VEC>
 __global__ void __launch_bounds__(kQuantThreads) quantize_kernel(const float* __restrict__ x, int N, int K, int64_t ldx,
                                                                  int8_t* __restrict__ a_q, float* __restrict__ a_scale) {
     extern __shared__ __attribute__((aligned(16))) unsigned char q_lds[];   // [K][8] codes
-    __shared__ float red[kQuantThreads / 64];
+    __shared__ float red[kQuantThreads / 64][8];
     __shared__ float s_inv[8];
-    typedef float f32x4 __attribute__((ext_vector_type(4)));
     const int chunk = blockIdx.x;
     const int tid = threadIdx.x;
-    const int t = tid >> 7;                    // token of the chunk
-    const int kq = tid & 127;                  // this thread handles k = 4*(kq + 128*i) .. +3
+    const int lane = tid & 63, wave = tid >> 6;
+    const int t = lane & 7;                    // token of the chunk
+    const int kq = wave * 8 + (lane >> 3);     // this thread handles k = 4*(kq + 128*i) .. +3
     const int n = chunk * 8 + t;
     const bool live = n < N;
     const float* row = x + (size_t)(live ? n : 0) * ldx;
@@ -221,43 +268,52 @@ __global__ void __launch_bounds__(kQuantThreads) quantize_kernel(const float* __
             xv[i] = (live && qi < nquad) ? load4(qi) : f32x4{0.f, 0.f, 0.f, 0.f};
             amax = fmaxf(fmaxf(amax, fmaxf(fabsf(xv[i].x), fabsf(xv[i].y))), fmaxf(fabsf(xv[i].z), fabsf(xv[i].w)));
         }
-    } else if (live) {
-        for (int qi = kq; qi < nquad; qi += 128) {
-            const f32x4 v = load4(qi);
-            amax = fmaxf(fmaxf(amax, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+    } else {
+        // eight loads in flight per thread and pass (a plain loop would wait for every load in turn)
+        for (int q0 = 0; q0 < nquad; q0 += 128 * 8) {
+            f32x4 tv[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int qi = q0 + kq + 128 * i;
+                tv[i] = (live && qi < nquad) ? load4(qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                amax = fmaxf(fmaxf(amax, fmaxf(fabsf(tv[i].x), fabsf(tv[i].y))), fmaxf(fabsf(tv[i].z), fabsf(tv[i].w)));
         }
     }
-    for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
-    if ((tid & 63) == 0) red[tid >> 6] = amax;
+    for (int off = 32; off >= 8; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));   // lanes of the same token
+    if (lane < 8) red[wave][lane] = amax;
     __syncthreads();
     if (tid < 8) {
-        const float v = fmaxf(red[2 * tid], red[2 * tid + 1]);   // the two waves of token tid
+        float v = 0.0f;
+        for (int w = 0; w < kQuantThreads / 64; ++w) v = fmaxf(v, red[w][tid]);
         // IEEE-correct fp32 divisions (the default for HIP); no reciprocal approximation.
         s_inv[tid] = (v > 0.0f) ? 127.0f / v : 0.0f;
         if (chunk * 8 + tid < N) a_scale[chunk * 8 + tid] = v / 127.0f;
     }
     __syncthreads();
     const float inv = s_inv[t];
-    auto code = [&](float v) -> unsigned char {
-        float r = rintf(v * inv);                 // one rounded multiply, ties to even
-        r = fminf(fmaxf(r, -127.0f), 127.0f);
-        return (unsigned char)(int)r;             // tokens past N: x = 0 -> code 0
-    };
-    auto emit = [&](int qi, const f32x4 v) {
-        unsigned char* d = q_lds + (size_t)qi * 32 + t;
-        d[0] = code(v.x);
-        d[8] = code(v.y);
-        d[16] = code(v.z);
-        d[24] = code(v.w);
+    // The quad transpose uses all four lanes of a quad; they share qi, so the bounds test is uniform per quad.
+    auto emit = [&](int qi, const f32x4 v) {       // tokens past N: x = 0 -> code 0
+        const unsigned e = quad_transpose_codes(quant_codes4(v, inv), t);
+        if (qi < nquad) *(unsigned*)(q_lds + (size_t)qi * 32 + (t & 3) * 8 + (t >> 2) * 4) = e;
     };
     if (NV > 0) {
 #pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            const int qi = kq + 128 * i;
-            if (qi < nquad) emit(qi, xv[i]);
-        }
+        for (int i = 0; i < NV; ++i) emit(kq + 128 * i, xv[i]);
     } else {
-        for (int qi = kq; qi < nquad; qi += 128) emit(qi, live ? load4(qi) : f32x4{0.f, 0.f, 0.f, 0.f});
+        // every lane runs the same number of passes (the quad exchange needs its partner lanes)
+        for (int q0 = 0; q0 < nquad; q0 += 128 * 8) {
+            f32x4 tv[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int qi = q0 + kq + 128 * i;
+                tv[i] = (live && qi < nquad) ? load4(qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) emit(q0 + kq + 128 * i, tv[i]);
+        }
     }
     __syncthreads();
     i32x4* dst = (i32x4*)(a_q + (size_t)chunk * K * 8);
@@ -308,6 +364,8 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const int8_t* __restrict
 //   R       row groups (of 4 output rows) per lookup wave; workgroup tile = up to 48*R rows
 //   NEED32  more than 64 lookups per lane: widen INT16 block sums into INT32 every 16 stages
 //   MODE    kFast: tables built in LDS from the token-chunked INT8 activations (streamed, the hot path)
+//           kFusedQuant: as kFast, but the workgroup first quantises its 8 tokens itself (fp32 rows -> absmax ->
+//                        INT8 codes kept in LDS); needs 16 sub-tables per row (8-token tiles)
 //           kFromGlobal: LDS slots are filled from a table materialised by vlut_build_lut
 // ---------------------------------------------------------------------------------------------
 template <int V> using ic = std::integral_constant<int, V>;
@@ -319,7 +377,7 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
-enum { kFast = 0, kFromGlobal = 2 };
+enum { kFast = 0, kFusedQuant = 1, kFromGlobal = 2 };
 constexpr int kBuildWaves = 4;
 constexpr int kLookupWaves = kWaves - kBuildWaves;     // 12
 constexpr int kRoundRows = kLookupWaves * 4;           // 48 output rows per row-group round of the workgroup
@@ -422,7 +480,8 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     asm volatile("" ::"s"(p.per_xcd), "s"(p.total_tiles), "s"(p.S), "s"(p.tiles_n), "s"(p.Jlog), "s"(p.RGW),
                  "s"(p.stages_per_split), "s"(p.stages_total), "s"(p.K), "s"(p.N), "s"(p.G), "s"(p.KCn), "s"(p.RGtotal),
                  "s"(p.M), "s"(p.ldy), "s"(p.w_scale), "s"(p.packed), "s"(p.a_q), "s"(p.a_scale), "s"(p.y), "s"(p.acc),
-                 "s"(p.ws), "s"(p.lut), "s"(p.aligned8), "s"(p.w_rows));
+                 "s"(p.ws), "s"(p.lut), "s"(p.aligned8), "s"(p.w_rows), "s"(p.x), "s"(p.a_scale_out), "s"(p.ldx),
+                 "s"(p.x_vec));
 
     // ---- which tile (XCD-aware: the 8 XCDs take contiguous ranges of the tile list, so the
     //      workgroups that share a weight tile also share an L2)
@@ -456,7 +515,86 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     lds_f32* scale_lds = (lds_f32*)(unsigned)kTableBytes;
     // Loaded now, stored to LDS only when the K loop is over: nothing at the start of the kernel waits for it.
     float my_scale = 0.0f;
-    if (tid < n_tile && n0 + tid < p.N) my_scale = p.w_rows ? p.a_scale[n0 + tid] : p.w_scale * p.a_scale[n0 + tid];
+    if (MODE != kFusedQuant && tid < n_tile && n0 + tid < p.N)
+        my_scale = p.w_rows ? p.a_scale[n0 + tid] : p.w_scale * p.a_scale[n0 + tid];
+
+    // Fused quantisation (all 16 waves; called once by either role, after its first loads are on their way): lane =
+    // token + 8 * quad, a wave reads 8 consecutive float4 of each of the 8 rows per pass.  Absmax over all of K
+    // (also when K is split: every split needs the same scale), codes only for this workgroup's K range.
+    auto quantise_tile = [&]() {
+        typedef __attribute__((address_space(3))) unsigned lds_u32;
+        lds_f32* red = (lds_f32*)(unsigned)kFusedRedBase;      // [wave][token]
+        const int tok = lane & 7;
+        const int kq = wave * 8 + (lane >> 3);
+        const int n = n0 + tok;
+        const bool live = n < p.N;
+        const float* row = p.x + (size_t)(live ? n : 0) * p.ldx;
+        const int nquad = p.G;                                 // a float4 of a row = one k-group
+        const int q_lo = st_begin * 64, q_hi = min(st_end * 64, nquad);
+        auto load4 = [&](int qi) -> f32x4 {
+            const float* src = row + 4 * (size_t)qi;
+            if (p.x_vec) return *(const f32x4*)src;
+            return f32x4{src[0], src[1], src[2], src[3]};
+        };
+        auto absmax4 = [](float m, const f32x4 v) {
+            return fmaxf(fmaxf(m, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+        };
+        constexpr int NVC = 8;                                 // float4 per thread kept in registers (K <= 4096)
+        f32x4 xv[NVC];
+        float amax = 0.0f;
+#pragma unroll
+        for (int i = 0; i < NVC; ++i) {
+            const int qi = kq + 128 * i;
+            xv[i] = (live && qi < nquad) ? load4(qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+            amax = absmax4(amax, xv[i]);
+        }
+        for (int q0 = 128 * NVC; q0 < nquad; q0 += 128 * NVC) {   // longer rows: NVC loads in flight per pass
+            f32x4 tv[NVC];
+#pragma unroll
+            for (int i = 0; i < NVC; ++i) {
+                const int qi = q0 + kq + 128 * i;
+                tv[i] = (live && qi < nquad) ? load4(qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int i = 0; i < NVC; ++i) amax = absmax4(amax, tv[i]);
+        }
+        for (int off = 32; off >= 8; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));   // lanes of the same token
+        if (lane < 8) red[wave * 8 + lane] = amax;
+        wg_barrier_lds();
+        float v = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) v = fmaxf(v, red[w * 8 + tok]);
+        const float inv = (v > 0.0f) ? 127.0f / v : 0.0f;      // IEEE divisions, as in quantize_kernel
+        const float sc = v / 127.0f;
+        if (tid < 8) {                                         // lane = token here
+            my_scale = live ? (p.w_rows ? sc : p.w_scale * sc) : 0.0f;
+            if (live && mt == 0 && ks == 0 && p.a_scale_out) p.a_scale_out[n] = sc;
+        }
+        // LDS address of the lane's dword for k-group kq; the address is affine in the k-group (128 groups = 2 stages)
+        const int ql0 = kq - q_lo;
+        const int a0 = kFusedAqBase + (ql0 >> 6) * kFusedStageBytes +
+                       ((ql0 & 3) * 2 + ((tok & 3) >> 1)) * kFusedBlockPitch +   // (slot of the stage, row pair)
+                       ((ql0 >> 2) & 15) * 16 + (tok & 1) * 8 + (tok >> 2) * 4;
+        auto emit = [&](int qi, const f32x4 xq, int addr) {
+            const unsigned e = quad_transpose_codes(quant_codes4(xq, inv), tok);   // 4 tokens of row tok % 4 of the group
+            if (qi >= q_lo && qi < q_hi) *(lds_u32*)(unsigned)addr = e;
+        };
+#pragma unroll
+        for (int i = 0; i < NVC; ++i) emit(kq + 128 * i, xv[i], a0 + i * 2 * kFusedStageBytes);
+        // the rest of the range is read again; every lane runs the same passes (the quad exchange needs its partners)
+        for (int q0 = max(128 * NVC, q_lo & ~127); q0 < q_hi; q0 += 128 * NVC) {
+            f32x4 tv[NVC];
+#pragma unroll
+            for (int i = 0; i < NVC; ++i) {
+                const int qi = q0 + kq + 128 * i;
+                tv[i] = (live && qi >= q_lo && qi < q_hi) ? load4(qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int i = 0; i < NVC; ++i)
+                emit(q0 + kq + 128 * i, tv[i], a0 + ((q0 >> 6) + 2 * i) * kFusedStageBytes);
+        }
+        wg_barrier_lds();
+    };
 
     s16x2 acc16[R][4];
     int acc32[NEED32 ? R : 1][8];
@@ -486,6 +624,17 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         auto fetch_act = [&](int hs, unsigned (&act)[4][2], bool& valid) {
             const int kg = (hs >> 1) * 4 * J + 4 * j + 2 * (hs & 1) + s2;
             valid = (hs < 2 * st_end) && (kg < p.G) && (nb < p.N);
+            if (MODE == kFusedQuant) {
+                // the codes this workgroup made itself: rows 0,1 and rows 2,3 of the group, 16 bytes each
+                const int stl = min((hs >> 1) - st_begin, p.stages_per_split - 1);   // prefetches run past the end
+                const unsigned a0 = (unsigned)(kFusedAqBase + stl * kFusedStageBytes +
+                                               (2 * (hs & 1) + s2) * 2 * kFusedBlockPitch + j * 16);
+                const i32x4 v0 = lds_read128<0>(a0), v1 = lds_read128<kFusedBlockPitch / 16>(a0);
+                act[0][0] = (unsigned)v0.x; act[0][1] = (unsigned)v0.y;
+                act[1][0] = (unsigned)v0.z; act[1][1] = (unsigned)v0.w;
+                act[2][0] = (unsigned)v1.x; act[2][1] = (unsigned)v1.y;
+                act[3][0] = (unsigned)v1.z; act[3][1] = (unsigned)v1.w;
+            }
             if (MODE == kFast) {
                 // 4 activation rows x 8 tokens = 32 contiguous bytes of the token-chunked layout; branch-free
                 // (address clamped into the tensor, validity applied at use) so nothing waits on the data early.
@@ -559,6 +708,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         };
 
         const int hs0 = 2 * st_begin, hs1 = 2 * st_end;
+        if constexpr (MODE == kFusedQuant) quantise_tile();
         if constexpr (MODE == kFromGlobal) {
             if (hs0 < hs1) build_half(hs0, actA, validA);
             wg_barrier_lds();
@@ -694,12 +844,13 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         };
         unsigned wa[R], wb[R];
         load_weights(st_begin, wa);
+        if constexpr (MODE == kFusedQuant) quantise_tile();
         wg_barrier_lds();                      // half-stage 0 of the first stage is built
         for (int st = st_begin; st < st_end; st += 2) {
             stage(st, wa, wb);
             if (st + 1 < st_end) {
                 stage(st + 1, wb, wa);
-            } else if (MODE == kFast) {
+            } else if (MODE != kFromGlobal) {
                 wg_barrier_lds();              // the build waves run in units of two stages
                 wg_barrier_lds();
             }
@@ -1198,9 +1349,17 @@ struct NarrowParams {
     int32_t* acc;
     float w_scale;
     int M, K, N, G, KCn, RGtotal, ldy, chunks;
+    // fused quantisation (FUSED): fp32 activations [N][ldx] instead of a_q / a_scale
+    const float* x;
+    float* a_scale_out;       // optional: the token scales, written by workgroup 0
+    int64_t ldx;
+    int x_vec;
 };
+// FUSED keeps, behind the tables, two dwords per k-group (the four codes of token 0 and of token 1) and the 16 x 2
+// partial absmax values.
+constexpr int kNarrowFusedMaxChunks = (160 * 1024 - kNarrowLdsBytes - 128) / (kNarrowChunk * 8);   // 37 -> K <= 37888
 
-template <int PARTS, int RR>
+template <int PARTS, int RR, bool FUSED>
 __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_n[];
     if (lds_base_of(smem_n) != 0u) return;               // table addresses below are absolute LDS addresses
@@ -1234,9 +1393,16 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
     // activations of tokens 0,1 for the four rows of a k-group: bytes 0,1 of a_q[0][4kg + j][*] (chunk 0 of tokens)
     auto fetch_act = [&](int c, unsigned (&a)[4]) {
         const int kg = min(c * kNarrowChunk + kg_b, p.G - 1);          // clamped; validity applied at use
-        const unsigned short* src = (const unsigned short*)(p.a_q + (size_t)(4 * kg) * 8);
+        if constexpr (FUSED) {
+            const i32x2 d = *(const __attribute__((address_space(3))) i32x2*)(unsigned)(kNarrowLdsBytes + kg * 8);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) a[j] = src[4 * j];                 // 8 bytes per activation row
+            for (int j = 0; j < 4; ++j)                                // {code of token 0, code of token 1} of row j
+                a[j] = __builtin_amdgcn_perm((unsigned)d.y, (unsigned)d.x, 0x0c0c0000u | ((4u + j) << 8) | (unsigned)j);
+        } else {
+            const unsigned short* src = (const unsigned short*)(p.a_q + (size_t)(4 * kg) * 8);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a[j] = src[4 * j];             // 8 bytes per activation row
+        }
     };
     typedef unsigned wvec __attribute__((ext_vector_type(4)));
     auto fetch_w = [&](int c, wvec (&w)[RR]) {
@@ -1258,8 +1424,82 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
 
     unsigned act_cur[4] = {0, 0, 0, 0}, act_nxt[4] = {0, 0, 0, 0};
     wvec w_cur[RR], w_nxt[RR];
-    if (builds) fetch_act(0, act_cur);
     fetch_w(0, w_cur);
+    float sc[2] = {0.0f, 0.0f};                                        // token scales (FUSED)
+    if constexpr (FUSED) {
+        // Quantise the one or two rows of x over all of K: thread tid takes the float4 (= k-group) tid + 1024 i.
+        typedef __attribute__((address_space(3))) float lds_f32;
+        typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
+        lds_f32* red = (lds_f32*)(unsigned)(kNarrowLdsBytes + p.chunks * kNarrowChunk * 8);   // [wave][token]
+        lds_i32x2* aq = (lds_i32x2*)(unsigned)kNarrowLdsBytes;
+        const int nquad = p.G;
+        auto load4 = [&](int n, int qi) -> f32x4 {
+            const float* src = p.x + (size_t)n * p.ldx + 4 * (size_t)qi;
+            if (p.x_vec) return *(const f32x4*)src;
+            return f32x4{src[0], src[1], src[2], src[3]};
+        };
+        auto absmax4 = [](float m, const f32x4 v) {
+            return fmaxf(fmaxf(m, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+        };
+        auto codes4 = [](const f32x4 v, float inv) { return (int)quant_codes4(v, inv); };
+        constexpr int NVC = 4;                                         // float4 per thread and token kept (K <= 16384)
+        f32x4 xv[2][NVC];
+        float amax[2] = {0.0f, 0.0f};
+#pragma unroll
+        for (int n = 0; n < 2; ++n) {
+#pragma unroll
+            for (int i = 0; i < NVC; ++i) {
+                const int qi = tid + kThreads * i;
+                xv[n][i] = (n < p.N && qi < nquad) ? load4(n, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+                amax[n] = absmax4(amax[n], xv[n][i]);
+            }
+            if (n < p.N)
+                for (int q0 = kThreads * NVC; q0 < nquad; q0 += kThreads * NVC) {   // NVC loads in flight per pass
+                    f32x4 tv[NVC];
+#pragma unroll
+                    for (int i = 0; i < NVC; ++i) {
+                        const int qi = q0 + tid + kThreads * i;
+                        tv[i] = qi < nquad ? load4(n, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+#pragma unroll
+                    for (int i = 0; i < NVC; ++i) amax[n] = absmax4(amax[n], tv[i]);
+                }
+            for (int off = 32; off > 0; off >>= 1) amax[n] = fmaxf(amax[n], __shfl_xor(amax[n], off));
+        }
+        if (lane == 0) { red[wave * 2] = amax[0]; red[wave * 2 + 1] = amax[1]; }
+        wg_barrier_lds();
+        float inv[2];
+#pragma unroll
+        for (int n = 0; n < 2; ++n) {
+            float v = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) v = fmaxf(v, red[w * 2 + n]);
+            inv[n] = (v > 0.0f) ? 127.0f / v : 0.0f;                   // IEEE divisions, as in quantize_kernel
+            sc[n] = v / 127.0f;
+        }
+        if (blockIdx.x == 0 && tid < p.N && p.a_scale_out) p.a_scale_out[tid] = tid == 0 ? sc[0] : sc[1];
+#pragma unroll
+        for (int i = 0; i < NVC; ++i) {
+            const int qi = tid + kThreads * i;
+            if (qi < nquad) aq[qi] = i32x2{codes4(xv[0][i], inv[0]), codes4(xv[1][i], inv[1])};
+        }
+        for (int q0 = kThreads * NVC; q0 < nquad; q0 += kThreads * NVC) {
+            f32x4 tv[2][NVC];
+#pragma unroll
+            for (int i = 0; i < NVC; ++i) {
+                const int qi = q0 + tid + kThreads * i;
+                tv[0][i] = qi < nquad ? load4(0, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+                tv[1][i] = (p.N > 1 && qi < nquad) ? load4(1, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int i = 0; i < NVC; ++i) {
+                const int qi = q0 + tid + kThreads * i;
+                if (qi < nquad) aq[qi] = i32x2{codes4(tv[0][i], inv[0]), codes4(tv[1][i], inv[1])};
+            }
+        }
+        wg_barrier_lds();
+    }
+    if (builds) fetch_act(0, act_cur);
     for (int c = 0; c < p.chunks; ++c) {
         // ---------------- build the chunk's tables (topological order of Sec. 4: one add per entry)
         if (builds) {
@@ -1331,7 +1571,8 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
         if (m < p.M && n < p.N) {
             int v = 0;
             for (int pi = 0; pi < 16 * PARTS; ++pi) v += red[(pi * ROWS + ri) * 2 + n];
-            if (p.y) p.y[(size_t)n * p.ldy + m] = (float)v * ((p.w_rows ? p.w_rows[m] : p.w_scale) * p.a_scale[n]);
+            const float s_n = FUSED ? (n ? sc[1] : sc[0]) : p.a_scale[n];
+            if (p.y) p.y[(size_t)n * p.ldy + m] = (float)v * ((p.w_rows ? p.w_rows[m] : p.w_scale) * s_n);
             if (p.acc) p.acc[(size_t)m * p.N + n] = v;
         }
     }
@@ -1441,6 +1682,27 @@ Plan search_plan(int64_t M, int64_t K, int64_t N) {
     return best;
 }
 
+// Fused quantisation needs 8-token tiles (16 sub-tables per row) and the codes of the workgroup's K range in LDS.
+bool fused_plan_valid(const Plan& pl, int64_t M, int64_t K, int64_t N) {
+    if (pl.Jlog != 4 || !plan_valid(pl, M, K, N)) return false;
+    return derive(pl, M, K, N).stages_per_split <= kFusedMaxStages;
+}
+
+bool search_fused_plan(int64_t M, int64_t K, int64_t N, Plan* out) {
+    if (t_forced.Jlog >= 0 && t_forced.Jlog != 4) return false;
+    bool found = false;
+    double best_cost = 1e300;
+    const int Ss[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
+    for (int R : kSupportedR)
+        for (int S : Ss) {
+            Plan pl = {4, t_forced.R > 0 ? t_forced.R : R, t_forced.S > 0 ? t_forced.S : S};
+            if (!fused_plan_valid(pl, M, K, N)) continue;
+            double c = plan_cost(pl, M, K, N);
+            if (c < best_cost) { best_cost = c; *out = pl; found = true; }
+        }
+    return found;
+}
+
 // The search above costs microseconds of host time; a launch-bound caller repeats a handful of shapes, so the
 // last few answers are kept per thread (invalidated by vlut_set_plan).
 struct PlanCacheEntry {
@@ -1460,16 +1722,42 @@ Plan choose_plan(int64_t M, int64_t K, int64_t N) {
     return pl;
 }
 
+struct FusedCacheEntry {
+    int64_t M, K, N;
+    Plan plan;
+    bool found;
+};
+thread_local FusedCacheEntry t_fcache[8];
+thread_local int t_fcache_used = 0, t_fcache_next = 0;
+
+bool choose_fused_plan(int64_t M, int64_t K, int64_t N, Plan* out) {
+    for (int i = 0; i < t_fcache_used; ++i)
+        if (t_fcache[i].M == M && t_fcache[i].K == K && t_fcache[i].N == N) {
+            *out = t_fcache[i].plan;
+            return t_fcache[i].found;
+        }
+    Plan pl = {4, 1, 1};
+    const bool found = search_fused_plan(M, K, N, &pl);
+    t_fcache[t_fcache_next] = {M, K, N, pl, found};
+    t_fcache_next = (t_fcache_next + 1) % 8;
+    if (t_fcache_used < 8) ++t_fcache_used;
+    *out = pl;
+    return found;
+}
+
 template <int R, bool NEED32, int MODE>
 int launch_lookup_t(const LookupParams& p, int grid, hipStream_t stream) {
     auto kfn = lookup_kernel<R, NEED32, MODE>;
+    constexpr int max_lds = MODE == kFusedQuant ? kFusedMaxLds : kLdsBytes;
+    const int lds = MODE == kFusedQuant ? kFusedAqBase + p.stages_per_split * kFusedStageBytes : kLdsBytes;
+    if (lds > max_lds) return VLUT_ERR_UNSUPPORTED;
     static bool attr_done = false;   // benign race: the call is idempotent
     if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
+        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds) != hipSuccess)
             return VLUT_ERR_DEVICE;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), kLdsBytes, stream, p);
+    hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), lds, stream, p);
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
 
@@ -1477,6 +1765,30 @@ int launch_lookup_t(const LookupParams& p, int grid, hipStream_t stream) {
 // small R (the launcher maps R down).
 template <bool NEED32>
 int launch_lookup_r(int R, int mode, const LookupParams& p, int grid, hipStream_t stream) {
+    if (mode == kFusedQuant) {
+        switch (R) {
+        case 1: return launch_lookup_t<1, NEED32, kFusedQuant>(p, grid, stream);
+        case 2: return launch_lookup_t<2, NEED32, kFusedQuant>(p, grid, stream);
+        case 3: return launch_lookup_t<3, NEED32, kFusedQuant>(p, grid, stream);
+        case 4: return launch_lookup_t<4, NEED32, kFusedQuant>(p, grid, stream);
+        case 5: return launch_lookup_t<5, NEED32, kFusedQuant>(p, grid, stream);
+        case 6: return launch_lookup_t<6, NEED32, kFusedQuant>(p, grid, stream);
+        default: break;
+        }
+        if constexpr (!NEED32) {
+            switch (R) {
+            case 7: return launch_lookup_t<7, false, kFusedQuant>(p, grid, stream);
+            case 8: return launch_lookup_t<8, false, kFusedQuant>(p, grid, stream);
+            case 9: return launch_lookup_t<9, false, kFusedQuant>(p, grid, stream);
+            case 10: return launch_lookup_t<10, false, kFusedQuant>(p, grid, stream);
+            case 11: return launch_lookup_t<11, false, kFusedQuant>(p, grid, stream);
+            case 12: return launch_lookup_t<12, false, kFusedQuant>(p, grid, stream);
+            case 14: return launch_lookup_t<14, false, kFusedQuant>(p, grid, stream);
+            default: break;
+            }
+        }
+        return VLUT_ERR_UNSUPPORTED;
+    }
     if (mode == kFast) {
         switch (R) {
         case 1: return launch_lookup_t<1, NEED32, kFast>(p, grid, stream);
@@ -1540,28 +1852,76 @@ NarrowPlan narrow_plan(int64_t M, int64_t K) {
     return np;
 }
 
-template <int PARTS, int RR>
+template <int PARTS, int RR, bool FUSED>
 int launch_narrow_t(const NarrowParams& p, int grid, hipStream_t stream) {
-    auto kfn = narrow_kernel<PARTS, RR>;
+    auto kfn = narrow_kernel<PARTS, RR, FUSED>;
+    constexpr int max_lds = FUSED ? 160 * 1024 : kNarrowLdsBytes;
+    const int lds = FUSED ? kNarrowLdsBytes + p.chunks * kNarrowChunk * 8 + 128 : kNarrowLdsBytes;
+    if (lds > max_lds) return VLUT_ERR_UNSUPPORTED;
     static bool attr_done = false;   // benign race: the call is idempotent
     if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, kNarrowLdsBytes) != hipSuccess)
+        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds) != hipSuccess)
             return VLUT_ERR_DEVICE;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), kNarrowLdsBytes, stream, p);
+    hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), lds, stream, p);
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
 
+template <bool FUSED>
 int launch_narrow(const NarrowPlan& np, const NarrowParams& p, hipStream_t stream) {
-    if (np.parts == 4) return launch_narrow_t<4, 1>(p, np.grid, stream);
-    if (np.parts == 2) return launch_narrow_t<2, 1>(p, np.grid, stream);
-    if (np.rr == 1) return launch_narrow_t<1, 1>(p, np.grid, stream);
-    if (np.rr == 2) return launch_narrow_t<1, 2>(p, np.grid, stream);
-    return launch_narrow_t<1, 4>(p, np.grid, stream);
+    if (np.parts == 4) return launch_narrow_t<4, 1, FUSED>(p, np.grid, stream);
+    if (np.parts == 2) return launch_narrow_t<2, 1, FUSED>(p, np.grid, stream);
+    if (np.rr == 1) return launch_narrow_t<1, 1, FUSED>(p, np.grid, stream);
+    if (np.rr == 2) return launch_narrow_t<1, 2, FUSED>(p, np.grid, stream);
+    return launch_narrow_t<1, 4, FUSED>(p, np.grid, stream);
 }
 
 std::mutex g_pack_mutex;
+
+// ---- vlut_mpgemm_f32: which kernels run and how the caller's workspace is divided
+enum { kF32Narrow = 0, kF32Fused = 1, kF32TwoLaunches = 2 };
+struct F32Layout {
+    int kind;
+    Plan plan;                                   // kF32Fused
+    size_t off_scale, off_aq, off_ws, total;     // byte offsets into the workspace
+};
+
+size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+F32Layout f32_layout(int64_t M, int64_t K, int64_t N) {
+    F32Layout L;
+    std::memset(&L, 0, sizeof(L));
+    const size_t scale_bytes = round256((size_t)N * sizeof(float));
+    if (narrow_applies(N, nullptr) && narrow_plan(M, K).chunks <= kNarrowFusedMaxChunks) {
+        L.kind = kF32Narrow;
+        return L;
+    }
+    // Fused, every workgroup pays for the quantisation of its tile (measured: ~3.6 us per round of 256 workgroups);
+    // apart, one more kernel runs ahead of the lookups (~6.3 us).  Large shapes with several rounds are better off apart.
+    bool fused = choose_fused_plan(M, K, N, &L.plan);
+    if (fused && !narrow_applies(N, nullptr)) {
+        const Derived df = derive(L.plan, M, K, N);
+        const double cost_fused = plan_cost(L.plan, M, K, N) + 7500.0 * (double)((df.total + 255) / 256);
+        const double cost_apart = plan_cost(choose_plan(M, K, N), M, K, N) + 13000.0;
+        fused = cost_fused <= cost_apart;
+    }
+    if (fused) {
+        L.kind = kF32Fused;
+        if (L.plan.S > 1) {                      // the second kernel reads the scales from memory
+            L.off_ws = scale_bytes;
+            L.total = L.off_ws + (size_t)L.plan.S * (size_t)M * (size_t)N * sizeof(int32_t);
+        }
+        return L;
+    }
+    L.kind = kF32TwoLaunches;                    // quantise into the workspace, then the ordinary path
+    L.off_aq = scale_bytes;
+    L.off_ws = L.off_aq + round256((size_t)((N + 7) / 8) * (size_t)K * 8);
+    const bool narrow = narrow_applies(N, nullptr);
+    const Plan pl = narrow ? Plan{4, 1, 1} : choose_plan(M, K, N);
+    L.total = L.off_ws + (pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0);
+    return L;
+}
 
 // ---- 1.60-bit (g = 5) host side
 struct Plan5 {
@@ -1717,6 +2077,8 @@ int vlut_set_plan(int J, int R, int waves, int split_k) {
     t_forced = {Jlog, R, split_k};
     t_cache_used = 0;
     t_cache_next = 0;
+    t_fcache_used = 0;
+    t_fcache_next = 0;
     return VLUT_OK;
 }
 
@@ -1782,6 +2144,7 @@ int vlut_quantize_act(const float* x, int64_t N, int64_t K, int64_t ldx, int8_t*
     if (vec) {
         if (nquad_per_thread <= 5) return launch(quantize_kernel<5, true>);
         if (nquad_per_thread <= 8) return launch(quantize_kernel<8, true>);
+        if (nquad_per_thread <= 16) return launch(quantize_kernel<16, true>);
         return launch(quantize_kernel<0, true>);
     }
     return launch(quantize_kernel<0, false>);
@@ -1810,7 +2173,7 @@ static int mpgemm_impl(const uint8_t* packed, float w_scale, const float* w_rows
         q.packed = packed; q.a_q = a_q; q.a_scale = a_scale; q.w_rows = w_rows; q.y = y; q.acc = acc_or_null;
         q.w_scale = w_scale; q.M = (int)M; q.K = (int)K; q.N = (int)N; q.G = (int)(K / 4);
         q.KCn = (int)((K / 4 + 15) / 16); q.RGtotal = (int)((M + 3) / 4); q.ldy = (int)ldy; q.chunks = np.chunks;
-        return launch_narrow(np, q, (hipStream_t)stream);
+        return launch_narrow<false>(np, q, (hipStream_t)stream);
     }
     Plan pl = choose_plan(M, K, N);
     const bool al = lut_or_null && (N % 8 == 0) && (((uintptr_t)lut_or_null) % 16 == 0);
@@ -1857,6 +2220,88 @@ int vlut_mpgemm_rows(const uint8_t* packed, const float* w_scale_rows, const int
     if (!w_scale_rows) return VLUT_ERR_NULL;
     return mpgemm_impl(packed, 1.0f, w_scale_rows, a_q, a_scale, lut_or_null, M, K, N, y, ldy, acc_or_null, workspace,
                        workspace_bytes, stream);
+}
+
+size_t vlut_workspace_bytes_f32(int64_t M, int64_t K, int64_t N) {
+    if (!shape_ok(M, K, N)) return 0;
+    return f32_layout(M, K, N).total;
+}
+
+int vlut_query_plan_f32(int64_t M, int64_t K, int64_t N, int* out5) {
+    if (!out5) return VLUT_ERR_NULL;
+    if (!shape_ok(M, K, N)) return VLUT_ERR_SHAPE;
+    const F32Layout L = f32_layout(M, K, N);
+    out5[4] = L.kind == kF32TwoLaunches ? 0 : 1;
+    if (L.kind == kF32Fused) {
+        const Derived d = derive(L.plan, M, K, N);
+        out5[0] = 1 << L.plan.Jlog; out5[1] = L.plan.R; out5[2] = L.plan.S; out5[3] = d.total;
+        return VLUT_OK;
+    }
+    return vlut_query_plan(M, K, N, out5);
+}
+
+int vlut_mpgemm_f32(const uint8_t* packed, float w_scale, const float* w_scale_rows_or_null, const float* x, int64_t ldx,
+                    int64_t M, int64_t K, int64_t N, float* y, int64_t ldy, int32_t* acc_or_null,
+                    float* a_scale_out_or_null, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!shape_ok(M, K, N)) return VLUT_ERR_SHAPE;
+    if (!packed || !x) return VLUT_ERR_NULL;
+    if (!y && !acc_or_null) return VLUT_ERR_NULL;
+    if (y && (ldy < M || ldy > INT32_MAX)) return VLUT_ERR_SHAPE;
+    if (ldx < K) return VLUT_ERR_SHAPE;
+    const F32Layout L = f32_layout(M, K, N);
+    if (L.total > 0) {
+        if (!workspace) return VLUT_ERR_NULL;
+        if (workspace_bytes < L.total) return VLUT_ERR_SMALL_BUFFER;
+        if (((uintptr_t)workspace) % 16 != 0) return VLUT_ERR_UNSUPPORTED;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const int x_vec = ((((uintptr_t)x) % 16 == 0) && (ldx % 4 == 0)) ? 1 : 0;
+    const float* w_rows = w_scale_rows_or_null;
+    const float w_one = w_rows ? 1.0f : w_scale;
+    char* ws = (char*)workspace;
+
+    if (L.kind == kF32Narrow) {
+        const NarrowPlan np = narrow_plan(M, K);
+        NarrowParams q;
+        std::memset(&q, 0, sizeof(q));
+        q.packed = packed; q.w_rows = w_rows; q.y = y; q.acc = acc_or_null; q.w_scale = w_one;
+        q.M = (int)M; q.K = (int)K; q.N = (int)N; q.G = (int)(K / 4);
+        q.KCn = (int)((K / 4 + 15) / 16); q.RGtotal = (int)((M + 3) / 4); q.ldy = (int)ldy; q.chunks = np.chunks;
+        q.x = x; q.ldx = ldx; q.x_vec = x_vec; q.a_scale_out = a_scale_out_or_null;
+        return launch_narrow<true>(np, q, s);
+    }
+    if (L.kind == kF32TwoLaunches) {
+        float* scales = a_scale_out_or_null ? a_scale_out_or_null : (float*)(ws + L.off_scale);
+        int8_t* a_q = (int8_t*)(ws + L.off_aq);
+        int rc = vlut_quantize_act(x, N, K, ldx, a_q, scales, stream);
+        if (rc != VLUT_OK) return rc;
+        return mpgemm_impl(packed, w_one, w_rows, a_q, scales, nullptr, M, K, N, y, ldy, acc_or_null, ws + L.off_ws,
+                           L.total - L.off_ws, stream);
+    }
+    const Plan pl = L.plan;
+    const Derived d = derive(pl, M, K, N);
+    float* scales = a_scale_out_or_null;
+    if (pl.S > 1 && !scales) scales = (float*)(ws + L.off_scale);
+    LookupParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.packed = packed; p.x = x; p.ldx = ldx; p.x_vec = x_vec; p.a_scale_out = scales;
+    p.y = y; p.acc = acc_or_null; p.ws = (int32_t*)(ws + L.off_ws); p.w_scale = w_one; p.w_rows = w_rows;
+    p.M = (int)M; p.K = (int)K; p.N = (int)N; p.G = d.G; p.KCn = d.KCn; p.RGtotal = d.RGtotal; p.ldy = (int)ldy;
+    p.Jlog = pl.Jlog; p.S = pl.S; p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.RGW = d.RGW;
+    p.stages_total = d.stages_total; p.stages_per_split = d.stages_per_split;
+    p.total_tiles = d.total; p.per_xcd = d.per_xcd;
+    const int grid = d.per_xcd * 8;
+    int rc = d.need32 ? launch_lookup_r<true>(pl.R, kFusedQuant, p, grid, s)
+                      : launch_lookup_r<false>(pl.R, kFusedQuant, p, grid, s);
+    if (rc != VLUT_OK) return rc;
+    if (pl.S > 1) {
+        size_t total = (size_t)M * (size_t)N;
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                           (const int32_t*)(ws + L.off_ws), pl.S, (int)M, (int)N, w_one, w_rows, (const float*)scales, y,
+                           ldy, acc_or_null);
+        if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
+    }
+    return VLUT_OK;
 }
 
 // ---- 1.60-bit packing (g = 5)
