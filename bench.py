@@ -2,8 +2,10 @@
 """Benchmark of the vector-LUT ternary x INT8 mpGeMM hot path on one MI355X.
 
 One step = one pass of the whole hot path over one batch of synthetic input that is already
-resident in HBM: vlut_quantize_act (fp32 [N][K] -> INT8 [K][N] + scales) followed by vlut_mpgemm
-(streamed LDS table build + lookup-accumulate + scale epilogue).  Weight packing is the paper's
+resident in HBM: per-token INT8 quantisation of the fp32 activations, streamed LDS table build,
+lookup-accumulate and scale epilogue, through vlut_mpgemm_f32 (which runs the quantisation inside the
+lookup kernel or as a kernel of its own ahead of it, whichever its cost model prefers for the shape; the
+two-call form vlut_quantize_act + vlut_mpgemm is timed next to it).  Weight packing is the paper's
 offline stage and is not timed.  The packed weights rotate through a pool larger than the last-level
 cache, so every step streams its weights from HBM.
 
@@ -181,11 +183,15 @@ def run_timed(torch, fn, count, warmup):
 
 
 def time_case(B, torch, case, steps, warmup):
-    """(wall ms per whole step, GPU ms per mpgemm launch, launch mode).  The second figure comes from a timed region
-    that holds only the vlut_mpgemm launches (HIP events on their stream), after quantising once."""
-    ms_step, _, mode = run_timed(torch, case.step, steps, warmup)
+    """(wall ms per whole step through vlut_mpgemm_f32, GPU ms per launch of the dominant kernel, launch mode, wall ms
+    per step of the two-call form, GPU ms per vlut_mpgemm launch).  The dominant kernel is the lookup kernel: when
+    the step is one fused launch its time is the step's own GPU time (HIP events on the launch stream), otherwise it
+    comes from a timed region that holds only the vlut_mpgemm launches, after quantising once."""
+    ms_step, ms_step_gpu, mode = run_timed(torch, case.step_fused, steps, warmup)
+    ms_two, _, _ = run_timed(torch, case.step, steps, warmup)
     _, ms_gemm, _ = run_timed(torch, case.gemm, steps, warmup)
-    return ms_step, ms_gemm, mode
+    one_launch = case.plan32[4] and case.plan32[2] == 1
+    return ms_step, (ms_step_gpu if one_launch else ms_gemm), mode, ms_two, ms_gemm
 
 
 def time_mfma(torch, case, steps, warmup):
@@ -269,7 +275,13 @@ def main():
     case.step(0, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     y_ref.copy_(case.y)
-    ms_step, ms_kernel, mode = time_case(B, torch, case, args.steps, args.warmup)
+    case.y.zero_()
+    case.step_fused(0, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    if not torch.equal(y_ref, case.y):
+        print("bench.py: vlut_mpgemm_f32 disagrees with vlut_quantize_act + vlut_mpgemm", file=sys.stderr)
+        sys.exit(4)
+    ms_step, ms_kernel, mode, ms_two_call, ms_gemm = time_case(B, torch, case, args.steps, args.warmup)
     if not torch.equal(y_ref, case.y):   # every pool buffer holds the same weights, so every step writes the same y
         print("bench.py: output of the timed region differs from the reference launch", file=sys.stderr)
         sys.exit(4)
@@ -284,7 +296,7 @@ def main():
             sys.exit(4)
         g5 = {"what": "vlut_mpgemm_g5 on the same weights packed 5 per byte (1.60 bits per weight, 243-row tables)",
               "ms": ms_g5, "plan": {"R": case.plan5[0], "split_k": case.plan5[1], "workgroups": case.plan5[2]},
-              "packed_weight_bytes": case.pool5[0].numel(), "time_over_2bit": ms_g5 / ms_kernel}
+              "packed_weight_bytes": case.pool5[0].numel(), "time_over_2bit": ms_g5 / ms_gemm}
     ops = 2.0 * M * K * N
     adds = M * (K // 4) * N                      # one INT16 add (= 2 table bytes) per (row, group, token)
     gops = ops / (ms_step * 1e-3) / 1e9
@@ -295,17 +307,23 @@ def main():
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int16/int32 (INT8 activations, ternary weights)", "data": "synthetic",
         "config": {"workload": f"{w.name}: M={M} K={K} N={N}, ternary P(0)={w.p_zero}, INT8 per-token absmax "
-                               f"activations from N(0,1); step = quantize_act + mpgemm",
-                   "plan": {"J": case.plan[0], "R": case.plan[1], "split_k": case.plan[2], "workgroups": case.plan[3]},
+                               f"activations from N(0,1); step = vlut_mpgemm_f32 (quantise + table build + lookup + scale)",
+                   "plan": {"J": case.plan32[0], "R": case.plan32[1], "split_k": case.plan32[2],
+                            "workgroups": case.plan32[3],
+                            "quantisation": "inside the lookup kernel" if case.plan32[4] else "kernel of its own"},
                    "weight_pool_buffers": len(case.pool), "launch": mode},
         "weight_stream_GBs": (M * K / 4) / (ms_step * 1e-3) / 1e9,
         "algorithmic_GBs": wl.algorithmic_bytes(M, K, N) / (ms_step * 1e-3) / 1e9,
+        "two_call_form": {"what": "vlut_quantize_act + vlut_mpgemm on the same inputs", "ms_per_step": ms_two_call,
+                          "mpgemm_kernel_ms": ms_gemm},
         "mfma_comparison": {"what": "vlut_mpgemm_mfma on the same inputs (unpack to INT8 + v_mfma_i32_16x16x64_i8), "
                                     "GPU ms per call incl. its activation re-layout kernel",
-                            "ms": ms_mfma, "lut_over_mfma_time": ms_kernel / ms_mfma},
+                            "ms": ms_mfma, "lut_over_mfma_time": ms_gemm / ms_mfma},
         "g5_packing": g5,
         "roofline": {
-            "kernel": "lookup_kernel (fused LDS table build + lookup-accumulate + epilogue)",
+            "kernel": ("lookup_kernel, quantising variant (absmax + INT8 codes, LDS table build, lookup-accumulate, "
+                       "epilogue in one launch)") if (case.plan32[4] and case.plan32[2] == 1) else
+                      "lookup_kernel (LDS table build + lookup-accumulate + epilogue)",
             "bound": "alu", "achieved": achieved_tadds, "peak": ALU_PEAK_TADDS, "unit": "TOP/s",
             "frac": achieved_tadds / ALU_PEAK_TADDS,
             "kernel_ms": ms_kernel,
@@ -373,21 +391,32 @@ def main():
                         c.gemm(i, stream)
                 return fn
 
+            def run_all_steps(cases, f32):
+                def fn(i, stream):
+                    for c in cases:
+                        (c.step_fused if f32 else c.step)(i, stream)
+                return fn
+
             cnt = max(10, args.steps // 8)
             _, t_single, _ = run_timed(torch, run_all(single), cnt, 3)
             _, t_fused, _ = run_timed(torch, run_all(fused), cnt, 3)
+            # the same four launches from fp32 inputs: quantisation included, as a decoder layer needs them
+            _, t_f32, _ = run_timed(torch, run_all_steps(fused, True), cnt, 3)
+            _, t_two, _ = run_timed(torch, run_all_steps(fused, False), cnt, 3)
             wbytes = sum(c.M * c.K // 4 for c in single)
             layer_rows.append({"N": n, "launches_single": 7, "single_ms": t_single, "launches_stacked": 4,
-                               "stacked_ms": t_fused, "packed_weight_MB": wbytes / 1e6,
+                               "stacked_ms": t_fused, "stacked_from_fp32_ms": t_f32,
+                               "stacked_from_fp32_two_call_ms": t_two, "packed_weight_MB": wbytes / 1e6,
                                "weight_stream_GBs_stacked": wbytes / (t_fused * 1e-3) / 1e9,
                                "hbm_frac_stacked": wbytes / (t_fused * 1e-3) / 1e9 / HBM_PEAK_GBS})
             del single, fused
             torch.cuda.empty_cache()
         out["layer_linears"] = layer_rows
-        print(f"{'N':>5s} {'7 launches us':>14s} {'4 stacked us':>13s} {'weights MB':>11s} {'GB/s stacked':>13s} {'hbm frac':>9s}",
-              file=sys.stderr)
+        print(f"{'N':>5s} {'7 launches us':>14s} {'4 stacked us':>13s} {'4 from fp32 us':>15s} {'4 x (quant+gemm) us':>20s} "
+              f"{'weights MB':>11s} {'GB/s stacked':>13s} {'hbm frac':>9s}", file=sys.stderr)
         for r in layer_rows:
-            print(f"{r['N']:5d} {r['single_ms'] * 1e3:14.1f} {r['stacked_ms'] * 1e3:13.1f} {r['packed_weight_MB']:11.2f} "
+            print(f"{r['N']:5d} {r['single_ms'] * 1e3:14.1f} {r['stacked_ms'] * 1e3:13.1f} {r['stacked_from_fp32_ms'] * 1e3:15.1f} "
+                  f"{r['stacked_from_fp32_two_call_ms'] * 1e3:20.1f} {r['packed_weight_MB']:11.2f} "
                   f"{r['weight_stream_GBs_stacked']:13.1f} {r['hbm_frac_stacked']:9.3f}", file=sys.stderr)
 
     if args.all:
@@ -397,7 +426,7 @@ def main():
                 for n in wk.N:
                     Wm, ws_, xm = wl.make_case(wk, linr, n, wk.seeds[0])
                     c = Case(B, torch, wl, Wm, ws_, xm, rotate)
-                    st, km, _ = time_case(B, torch, c, max(20, args.steps // 4), 5)
+                    st, _, _, st2, km = time_case(B, torch, c, max(20, args.steps // 4), 5)
                     mf = time_mfma(torch, c, max(20, args.steps // 4), 5)
                     mm, kk = Wm.shape
                     g5us = float("nan")
@@ -405,16 +434,17 @@ def main():
                         c.enable_g5(B, torch, Wm, rotate)
                         g5us = run_timed(torch, c.gemm_g5, max(20, args.steps // 4), 5)[1] * 1e3
                     a = mm * (kk // 4) * n
-                    rows.append((name, linr.name, mm, kk, n, c.plan, st * 1e3, km * 1e3,
+                    rows.append((name, linr.name, mm, kk, n, c.plan32, st * 1e3, st2 * 1e3, km * 1e3,
                                  2.0 * mm * kk * n / (st * 1e-3) / 1e12, a / (km * 1e-3) / 1e12 / ALU_PEAK_TADDS,
                                  wl.algorithmic_bytes(mm, kk, n) / (km * 1e-3) / 1e9 / HBM_PEAK_GBS, mf * 1e3, g5us))
                     del c
                     torch.cuda.empty_cache()
-        print(f"{'workload':18s} {'lin':7s} {'M':>6s} {'K':>6s} {'N':>5s} {'plan(J,R,S,WG)':>18s} {'step us':>9s} "
-              f"{'mpgemm us':>9s} {'TOPS':>7s} {'alu/lds frac':>12s} {'hbm frac':>8s} {'mfma us':>8s} {'g5 us':>8s}", file=sys.stderr)
+        print(f"{'workload':18s} {'lin':7s} {'M':>6s} {'K':>6s} {'N':>5s} {'plan(J,R,S,WG,fused)':>26s} {'step us':>9s} "
+              f"{'2-call us':>9s} {'mpgemm us':>9s} {'TOPS':>7s} {'alu/lds frac':>12s} {'hbm frac':>8s} {'mfma us':>8s} "
+              f"{'g5 us':>8s}", file=sys.stderr)
         for r in rows:
-            print(f"{r[0]:18s} {r[1]:7s} {r[2]:6d} {r[3]:6d} {r[4]:5d} {str(r[5]):>18s} {r[6]:9.1f} {r[7]:9.1f} "
-                  f"{r[8]:7.1f} {r[9]:12.3f} {r[10]:8.3f} {r[11]:8.1f} {r[12]:8.1f}", file=sys.stderr)
+            print(f"{r[0]:18s} {r[1]:7s} {r[2]:6d} {r[3]:6d} {r[4]:5d} {str(r[5]):>26s} {r[6]:9.1f} {r[7]:9.1f} {r[8]:9.1f} "
+                  f"{r[9]:7.1f} {r[10]:12.3f} {r[11]:8.3f} {r[12]:8.1f} {r[13]:8.1f}", file=sys.stderr)
 
     print(json.dumps(out))
 

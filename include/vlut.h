@@ -171,8 +171,11 @@ int vlut_mpgemm_rows(const uint8_t* packed, const float* w_scale_rows, const int
 /*
  * Quantisation and mpGeMM in one call, from fp32 activations: the steps of vlut_quantize_act (Sec. 3.4 first
  * paragraph: per-token absmax INT8) and of vlut_mpgemm / vlut_mpgemm_rows (Alg. 1, Eq. 2) with the same readings and
- * the same numbers, but the workgroups of the lookup kernel quantise the tokens of their own tile themselves (absmax
- * over the whole row, codes kept in LDS), so that neither the INT8 activations nor a second launch are needed.
+ * the same numbers.  For one or two tokens (decoding) it is one launch: the workgroups quantise the rows themselves
+ * (absmax over the whole row, codes kept in LDS), so that neither the INT8 activations nor a second kernel are
+ * needed.  For more tokens the quantiser runs as a kernel of its own into the workspace, ahead of the lookup kernel
+ * (measured to be the faster arrangement); a lookup kernel that quantises the 8 tokens of its tile itself exists as
+ * well and is taken when vlut_set_plan forces a plan with J = 16 whose K range per workgroup is at most 8704.
  *   x             dev, fp32 [N][ldx], ldx >= K (16-byte aligned rows are read as float4)
  *   w_scale / w_scale_rows_or_null   per-tensor scale, or (non-NULL) dev fp32 [M] per-row scales as in
  *                 vlut_mpgemm_rows (w_scale is then ignored)
@@ -180,10 +183,7 @@ int vlut_mpgemm_rows(const uint8_t* packed, const float* w_scale_rows, const int
  *   a_scale_out_or_null              dev or NULL, fp32 [N]: receives the token scales s_n = amax_n / 127
  *   workspace     dev, 16-byte aligned, workspace_bytes >= vlut_workspace_bytes_f32(M, K, N); may be NULL when that
  *                 size is 0
- * Shapes the fused kernels do not cover (a K range of more than 8704 per workgroup after the split of K, a launch
- * plan forced to fewer than 16 sub-tables per table row, more than 37888 values of K for one or two tokens) are run
- * as vlut_quantize_act into the workspace followed by the ordinary path (with that call's own limit on K, reported as
- * VLUT_ERR_UNSUPPORTED); vlut_query_plan_f32 tells which:
+ * vlut_query_plan_f32 tells which form a shape takes:
  *   out5 = {J, R, split_k, workgroups, fused (1) or two launches (0)}  (J, R as in vlut_query_plan)
  * Errors as in vlut_mpgemm; VLUT_ERR_SHAPE also for ldx < K.
  */

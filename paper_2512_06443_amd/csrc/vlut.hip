@@ -321,6 +321,83 @@ __global__ void __launch_bounds__(kQuantThreads) quantize_kernel(const float* __
     for (int i = tid; i < K / 2; i += kQuantThreads) dst[i] = src[i];   // 16 bytes = 2 k-rows of 8 codes
 }
 
+// The same quantiser with one workgroup (256 threads) per token, for long rows or many tokens: the chunk kernel above
+// lets one CU pull 8 whole rows twice, which takes 20 us at K = 8640, while here every CU reads one row once.  The
+// price is the store: a token owns one byte in every 8 of its chunk's [K][8] block, so the codes leave as single
+// bytes (distinct bytes written by different workgroups: no race).  Tokens past N (padding of the last chunk) are
+// written as zeros.  Blocks are numbered so that the 8 tokens of a chunk sit 8 blocks apart (same XCD under
+// round-robin dispatch, so their partial lines meet in one L2); this is a matter of speed only.
+//   NV  float4 values per thread kept in registers between the two passes (0: x is read twice)
+constexpr int kTokThreads = 256;
+
+template <int NV, bool VEC>
+__global__ void __launch_bounds__(kTokThreads) quantize_token_kernel(const float* __restrict__ x, int N, int K, int64_t ldx,
+                                                                     int8_t* __restrict__ a_q,
+                                                                     float* __restrict__ a_scale, int chunks) {
+    __shared__ float red[kTokThreads / 64];
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x;
+    const int chunk = (b >> 6) * 8 + (b & 7);
+    const int t = (b >> 3) & 7;
+    if (chunk >= chunks) return;
+    const int n = chunk * 8 + t;
+    const bool live = n < N;
+    const float* row = x + (size_t)(live ? n : 0) * ldx;
+    const int nquad = K >> 2;
+    auto load4 = [&](int qi) -> f32x4 {
+        const float* src = row + 4 * (size_t)qi;
+        if (VEC) return *(const f32x4*)src;
+        return f32x4{src[0], src[1], src[2], src[3]};
+    };
+    auto absmax4 = [](float m, const f32x4 v) {
+        return fmaxf(fmaxf(m, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+    };
+    constexpr int NB = NV > 0 ? NV : 8;            // loads in flight per thread and pass
+    f32x4 xv[NB];
+    float amax = 0.0f;
+    if (live) {
+        for (int q0 = 0; q0 < (NV > 0 ? 1 : nquad); q0 += kTokThreads * NB) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const int qi = q0 + tid + kTokThreads * i;
+                xv[i] = qi < nquad ? load4(qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int i = 0; i < NB; ++i) amax = absmax4(amax, xv[i]);
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+    if ((tid & 63) == 0) red[tid >> 6] = amax;
+    __syncthreads();
+    float v = 0.0f;
+#pragma unroll
+    for (int w = 0; w < kTokThreads / 64; ++w) v = fmaxf(v, red[w]);
+    const float inv = (v > 0.0f) ? 127.0f / v : 0.0f;      // IEEE divisions
+    if (tid == 0 && live) a_scale[n] = v / 127.0f;
+    int8_t* dst = a_q + (size_t)chunk * K * 8 + t;
+    auto store4 = [&](int qi, unsigned d) {
+        int8_t* o = dst + (size_t)qi * 32;
+        o[0] = (int8_t)(d & 0xffu);
+        o[8] = (int8_t)((d >> 8) & 0xffu);
+        o[16] = (int8_t)((d >> 16) & 0xffu);
+        o[24] = (int8_t)(d >> 24);
+    };
+    for (int q0 = 0; q0 < (NV > 0 ? 1 : nquad); q0 += kTokThreads * NB) {
+        if (NV == 0 && live) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const int qi = q0 + tid + kTokThreads * i;
+                xv[i] = qi < nquad ? load4(qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int qi = q0 + tid + kTokThreads * i;
+            if (qi < nquad) store4(qi, live ? quant_codes4(xv[i], inv) : 0u);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Whole table in global memory (Alg. 1 Precompute / Eq. 1), topological order of Sec. 4:
 // every row is one add/sub away from an earlier one.  One thread per (group, token).
@@ -1897,15 +1974,12 @@ F32Layout f32_layout(int64_t M, int64_t K, int64_t N) {
         L.kind = kF32Narrow;
         return L;
     }
-    // Fused, every workgroup pays for the quantisation of its tile (measured: ~3.6 us per round of 256 workgroups);
-    // apart, one more kernel runs ahead of the lookups (~6.3 us).  Large shapes with several rounds are better off apart.
-    bool fused = choose_fused_plan(M, K, N, &L.plan);
-    if (fused && !narrow_applies(N, nullptr)) {
-        const Derived df = derive(L.plan, M, K, N);
-        const double cost_fused = plan_cost(L.plan, M, K, N) + 7500.0 * (double)((df.total + 255) / 256);
-        const double cost_apart = plan_cost(choose_plan(M, K, N), M, K, N) + 13000.0;
-        fused = cost_fused <= cost_apart;
-    }
+    // More than two tokens: measured, quantising inside the lookup kernel loses against a kernel of its own ahead of
+    // it (every workgroup reads the whole rows of its 8 tokens and 16 row tiles repeat the work: +5.6 us on the
+    // lookup kernel at M = 6912, K = 2560, N = 128, against 3.2 us + the gap between two kernels).  The fused form
+    // is therefore only taken when a launch plan is forced (an override selects the kernel too).
+    const bool forced = t_forced.Jlog >= 0 || t_forced.R > 0 || t_forced.S > 0;
+    const bool fused = forced && choose_fused_plan(M, K, N, &L.plan);
     if (fused) {
         L.kind = kF32Fused;
         if (L.plan.S > 1) {                      // the second kernel reads the scales from memory
@@ -2122,25 +2196,44 @@ int vlut_pack_weights(const int8_t* w_ternary, int64_t M, int64_t K, uint8_t* pa
     return err ? VLUT_ERR_VALUE : VLUT_OK;
 }
 
+#ifndef VLUT_QUANT_PER_TOKEN
+// measured: the per-token kernel is the faster one except for more than ~2M values in short rows, where its
+// single-byte stores cost more than the chunk kernel's serial reads
+#define VLUT_QUANT_PER_TOKEN(N, K) (!((N) * (K) >= 2000000 && (K) <= 4096))
+#endif
 int vlut_quantize_act(const float* x, int64_t N, int64_t K, int64_t ldx, int8_t* a_q, float* a_scale,
                       void* stream) {
     if (!shape_ok(1, K, N)) return VLUT_ERR_SHAPE;
     if (ldx < K) return VLUT_ERR_SHAPE;
     if (!x || !a_q || !a_scale) return VLUT_ERR_NULL;
     if (((uintptr_t)a_q) % 16 != 0) return VLUT_ERR_UNSUPPORTED;
-    if (K * 8 > 160 * 1024 - 1024) return VLUT_ERR_UNSUPPORTED;   // the chunk's [K][8] block is staged in LDS
     hipStream_t s = (hipStream_t)stream;
     const unsigned chunks = (unsigned)((N + 7) / 8);
     const bool vec = (((uintptr_t)x) % 16 == 0) && (ldx % 4 == 0);
     const size_t lds = (size_t)K * 8;
     const int nquad_per_thread = (int)((K / 4 + 127) / 128);
     auto launch = [&](auto kfn) -> int {
+        if (lds > 160 * 1024 - 1024) return VLUT_ERR_UNSUPPORTED;   // the chunk's [K][8] block is staged in LDS
         if (lds > 48 * 1024 &&
             hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return VLUT_ERR_DEVICE;
         hipLaunchKernelGGL(kfn, dim3(chunks), dim3(kQuantThreads), lds, s, x, (int)N, (int)K, ldx, a_q, a_scale);
         return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
     };
+    // One workgroup per token (every CU reads one row once) unless the byte stores would dominate
+    if (VLUT_QUANT_PER_TOKEN(N, K)) {
+        const unsigned blocks = ((chunks + 7) / 8) * 64;
+        const int per_thread = (int)((K / 4 + kTokThreads - 1) / kTokThreads);
+        auto launch_tok = [&](auto kfn) -> int {
+            hipLaunchKernelGGL(kfn, dim3(blocks), dim3(kTokThreads), 0, s, x, (int)N, (int)K, ldx, a_q, a_scale, (int)chunks);
+            return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
+        };
+        if (!vec) return launch_tok(quantize_token_kernel<0, false>);
+        if (per_thread <= 4) return launch_tok(quantize_token_kernel<4, true>);
+        if (per_thread <= 10) return launch_tok(quantize_token_kernel<10, true>);
+        if (per_thread <= 16) return launch_tok(quantize_token_kernel<16, true>);
+        return launch_tok(quantize_token_kernel<0, true>);
+    }
     if (vec) {
         if (nquad_per_thread <= 5) return launch(quantize_kernel<5, true>);
         if (nquad_per_thread <= 8) return launch(quantize_kernel<8, true>);

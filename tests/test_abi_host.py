@@ -37,6 +37,9 @@ def L(vlut_lib_path):
     lib.vlut_set_plan_g5.argtypes = [ci, ci]
     lib.vlut_query_plan_g5.argtypes = [i64, i64, i64, ctypes.POINTER(ci)]
     lib.vlut_query_plan.argtypes = [i64, i64, i64, ctypes.POINTER(ci)]
+    lib.vlut_workspace_bytes_f32.argtypes, lib.vlut_workspace_bytes_f32.restype = [i64, i64, i64], sz
+    lib.vlut_query_plan_f32.argtypes = [i64, i64, i64, ctypes.POINTER(ci)]
+    lib.vlut_mpgemm_f32.argtypes = [vp, cf, vp, vp, i64, i64, i64, i64, vp, i64, vp, vp, vp, sz, vp]
     return lib
 
 
@@ -202,3 +205,48 @@ def test_g5_host_logic(L):
         assert per_split * 4 <= 51 or R <= 6                                   # INT16 block bound of Sec. 3.4
         tiles_m = tiles // (S * -(-N // 8))
         assert tiles_m * 48 * R >= M                                           # the tiles cover every row
+
+
+def test_f32_entry_host_logic(L):
+    """vlut_mpgemm_f32: which kernels it picks, what workspace that needs, and argument errors before any device call."""
+    out = (ci * 5)()
+    # one or two tokens: the kernel that sweeps all of K, quantising inside; no workspace
+    for (M, K, N) in [(6912, 2560, 1), (2560, 6912, 2), (640, 2560, 1)]:
+        assert L.vlut_query_plan_f32(M, K, N, out) == 0
+        assert out[0] == 0 and out[2] == 1 and out[4] == 1
+        assert L.vlut_workspace_bytes_f32(M, K, N) == 0
+    # more tokens: quantised once, by a kernel of its own ahead of the lookups; the workspace then holds the scales,
+    # the INT8 activations and the split-K partial sums of the ordinary path
+    for (M, K, N) in [(6912, 2560, 128), (14336, 4096, 512), (4096, 14336, 512), (3200, 8640, 256), (6912, 2560, 3)]:
+        assert L.vlut_query_plan_f32(M, K, N, out) == 0
+        assert out[4] == 0
+        r256 = lambda v: (v + 255) // 256 * 256
+        assert L.vlut_workspace_bytes_f32(M, K, N) == r256(4 * N) + r256(L.vlut_act_bytes(K, N)) + L.vlut_workspace_bytes(M, K, N)
+    # a forced plan with 16 sub-tables per table row selects the fused kernel when the K range fits next to the
+    # tables (34 stages of 256 values), with the scales in front of the split-K partial sums
+    try:
+        assert L.vlut_set_plan(16, 2, 0, 4) == 0
+        assert L.vlut_query_plan_f32(300, 14336, 40, out) == 0 and tuple(out) == (16, 2, 4, 4 * 4 * 5, 1)
+        assert L.vlut_workspace_bytes_f32(300, 14336, 40) == 256 + 4 * 300 * 40 * 4
+        assert L.vlut_set_plan(16, 2, 0, 1) == 0
+        assert L.vlut_query_plan_f32(300, 14336, 40, out) == 0 and out[4] == 0     # 56 stages in one range
+        assert L.vlut_set_plan(8, 2, 0, 1) == 0
+        assert L.vlut_query_plan_f32(300, 2560, 40, out) == 0 and out[4] == 0      # 16-token tiles
+    finally:
+        assert L.vlut_set_plan(0, 0, 0, 0) == 0
+    d = ctypes.c_void_p(0x1000)                                                # never dereferenced: checks come first
+    ok = [d, 1.0, None, d, 2560, 6912, 2560, 1, d, 6912, None, None, None, 0, None]
+    def call(**kw):
+        names = ["packed", "w_scale", "rows", "x", "ldx", "M", "K", "N", "y", "ldy", "acc", "scales", "ws", "ws_bytes", "stream"]
+        a = list(ok)
+        for k, v in kw.items():
+            a[names.index(k)] = v
+        return L.vlut_mpgemm_f32(*a)
+    assert call(packed=None) == -1 and call(x=None) == -1 and call(y=None) == -1
+    assert call(ldx=2559) == -2 and call(ldy=6911) == -2 and call(K=2562) == -2 and call(N=0) == -2
+    assert call(M=14336, K=4096, N=512, ldx=4096, ldy=14336) == -1             # needs a workspace
+    need = L.vlut_workspace_bytes_f32(14336, 4096, 512)
+    assert call(M=14336, K=4096, N=512, ldx=4096, ldy=14336, ws=d, ws_bytes=need - 1) == -3
+    assert call(M=14336, K=4096, N=512, ldx=4096, ldy=14336, ws=ctypes.c_void_p(0x1004), ws_bytes=need) == -6
+    assert L.vlut_query_plan_f32(8, 8, 8, None) == -1 and L.vlut_query_plan_f32(8, 6, 8, out) == -2
+    assert L.vlut_workspace_bytes_f32(8, 6, 8) == 0

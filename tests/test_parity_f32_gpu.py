@@ -37,7 +37,9 @@ def check_y(y_gpu, y_ref):
     assert np.all(y_gpu[y_ref == 0.0] == 0.0)
 
 
-def run_f32(B, W, w_scale, x, plan=None, fused=True, tag="", x_dev=None):
+def run_f32(B, W, w_scale, x, plan=None, fused=None, tag="", x_dev=None):
+    """fused: None = the library's own choice (by cost), True/False = what the call must report.  A forced plan with
+    16 sub-tables per table row always takes the fused kernel when the shape fits it."""
     M, K = W.shape
     N = x.shape[0]
     print(f"f32 case {tag} M={M} K={K} N={N} plan={plan}", flush=True)
@@ -45,7 +47,7 @@ def run_f32(B, W, w_scale, x, plan=None, fused=True, tag="", x_dev=None):
     B.set_plan(*(plan or (0, 0, 0, 0)))
     try:
         qp = B.query_plan_f32(M, K, N)
-        assert qp[4] == fused, qp
+        assert fused is None or qp[4] == fused, qp
         packed = B.pack_weights(dev(W))
         y, acc, sc = B.mpgemm_f32(packed, float(w_scale), dev(x) if x_dev is None else x_dev, M, want_acc=True,
                                   want_scales=True)
@@ -74,7 +76,7 @@ def test_tiny_and_ragged(B):
 def test_every_rows_per_wave(B, R):
     M = 48 * R * 2 - 37
     W, s, x = wl.small_case(420 + R, M, 512, 33)
-    qp = run_f32(B, W, s, x, plan=(16, R, 0, 1), tag=f"R{R}")
+    qp = run_f32(B, W, s, x, plan=(16, R, 0, 1), fused=True, tag=f"R{R}")
     assert qp[:3] == (16, R, 1)
 
 
@@ -83,21 +85,22 @@ def test_int32_widening_split_k_and_long_rows(B, R, S):
     # K = 4352: 17 stages; with S = 1 a lane does 68 > 64 lookups, so the INT16 blocks get widened (R <= 6); the
     # rows are longer than the 4096 values a thread keeps in registers, so the tail is read twice
     W, s, x = wl.small_case(430 + R + S, 300, 4352, 40)
-    run_f32(B, W, s, x, plan=(16, R, 0, S), tag=f"widen R{R} S{S}")
+    run_f32(B, W, s, x, plan=(16, R, 0, S), fused=True, tag=f"widen R{R} S{S}")
 
 
 def test_split_k_ranges_past_the_register_cache(B):
     # K = 8640 in three ranges: the second and third range lie entirely in the part of the row that is read again
     W, s, x = wl.small_case(440, 200, 8640, 19)
-    run_f32(B, W, s, x, plan=(16, 2, 0, 3), tag="K8640 S3")
-    run_f32(B, W, s, x, plan=(16, 4, 0, 1), tag="K8640 S1 (34 stages: the largest range that fits)")
+    run_f32(B, W, s, x, plan=(16, 2, 0, 3), fused=True, tag="K8640 S3")
+    run_f32(B, W, s, x, plan=(16, 4, 0, 1), fused=True, tag="K8640 S1 (34 stages: the largest range that fits)")
 
 
 def test_shapes_the_fused_kernels_do_not_cover_take_two_launches(B):
     W, s, x = wl.small_case(450, 100, 9216, 12)             # 36 stages in one range do not fit next to the tables
     run_f32(B, W, s, x, plan=(16, 2, 0, 1), fused=False, tag="K9216 S1")
     run_f32(B, W, s, x, plan=(4, 2, 0, 1), fused=False, tag="J=4 forced")
-    run_f32(B, W, s, x, tag="K9216 free plan")              # the search splits K instead
+    run_f32(B, W, s, x, plan=(16, 2, 0, 2), fused=True, tag="K9216 S2")
+    run_f32(B, W, s, x, fused=False, tag="K9216 free plan")   # rows this long are cheaper to quantise once, ahead
 
 
 def test_extremes_zero_tokens_and_outliers(B):
@@ -134,20 +137,22 @@ def test_row_stride_and_unaligned_rows(B):
 def test_one_or_two_tokens_every_tile_shape(B, M):
     for N, K in ((1, 260), (2, 1028)):
         W, s, x = wl.small_case(470 + M % 97 + N, M, K, N)
-        qp = run_f32(B, W, s, x, tag=f"narrow M{M} N{N}")
+        qp = run_f32(B, W, s, x, fused=True, tag=f"narrow M{M} N{N}")
         assert qp[0] == 0                                   # the one-or-two-token kernel
 
 
 def test_one_or_two_tokens_long_rows(B):
     for N, K in ((1, 2560), (2, 6912), (2, 9216), (1, 14336)):   # beyond 8192 the tail of a row is read twice
         W, s, x = wl.small_case(480 + N, 130, K, N)
-        run_f32(B, W, s, x, tag=f"narrow K{K}")
+        run_f32(B, W, s, x, fused=True, tag=f"narrow K{K}")
     W, s, x = wl.small_case(483, 40, 36864, 2)              # 36 of at most 37 chunks of codes next to the tables
-    run_f32(B, W, s, x, tag="narrow K36864")
-    # past that the general kernel takes over, with K split into ranges whose codes fit
+    run_f32(B, W, s, x, fused=True, tag="narrow K36864")
+    # past that: two launches (the one-or-two-token kernel on the INT8 codes), or the general kernel with K split
+    # into ranges whose codes fit when a plan asks for it
     W, s, x = wl.small_case(484, 40, 40000, 2)
-    qp = run_f32(B, W, s, x, tag="K40000 at two tokens")
-    assert qp[0] == 16 and qp[2] > 1
+    run_f32(B, W, s, x, fused=False, tag="K40000 at two tokens")
+    qp = run_f32(B, W, s, x, plan=(16, 1, 0, 5), fused=True, tag="K40000 at two tokens, general kernel")
+    assert qp[:3] == (16, 1, 5)
 
 
 def test_stacked_matrices_with_row_scales(B):
@@ -196,7 +201,8 @@ def test_argument_errors(B):
     L = B.lib()
     y = torch.empty((4, 64), device="cuda")
     args = lambda **kw: [kw.get("packed", packed.data_ptr()), 1.0, None, kw.get("x", xd.data_ptr()), kw.get("ldx", 64),
-                         64, kw.get("K", 64), 4, kw.get("y", y.data_ptr()), kw.get("ldy", 64), None, None, None, 0, None]
+                         64, kw.get("K", 64), kw.get("N", 2), kw.get("y", y.data_ptr()), kw.get("ldy", 64), None, None,
+                         None, 0, None]
     assert L.vlut_mpgemm_f32(*args()) == B.VLUT_OK
     assert L.vlut_mpgemm_f32(*args(x=None)) == B.VLUT_ERR_NULL
     assert L.vlut_mpgemm_f32(*args(packed=None)) == B.VLUT_ERR_NULL
@@ -204,6 +210,7 @@ def test_argument_errors(B):
     assert L.vlut_mpgemm_f32(*args(ldx=60)) == B.VLUT_ERR_SHAPE
     assert L.vlut_mpgemm_f32(*args(ldy=63)) == B.VLUT_ERR_SHAPE
     assert L.vlut_mpgemm_f32(*args(K=62)) == B.VLUT_ERR_SHAPE
+    assert L.vlut_mpgemm_f32(*args(N=4)) == B.VLUT_ERR_NULL    # more than two tokens: the INT8 codes need a workspace
     torch.cuda.synchronize()
     # split-K needs the workspace
     B.set_plan(16, 1, 0, 2)

@@ -89,7 +89,9 @@ def test_pack_bytes_match_oracle_and_padding(B):
 def test_quantize_bit_exact(B):
     cases = [wl.activations(0, 8, 256), wl.activations(1, 37, 100, 0.05), wl.activations(2, 130, 2560),
              wl.activations(3, 1, 64), wl.activations(4, 300, 512, 0.01), wl.activations(5, 1030, 128),
-             wl.activations(7, 9, 6912), wl.activations(8, 5, 14336, 0.01)]
+             wl.activations(7, 9, 6912), wl.activations(8, 5, 14336, 0.01),
+             # more than 2M values in short rows take the kernel with one workgroup per 8 tokens
+             wl.activations(9, 1030, 2048), wl.activations(10, 520, 4096), wl.activations(11, 801, 2560)]
     z = wl.activations(6, 5, 64)
     z[2] = 0.0                                              # a zero token
     z[3, :] = 3.25                                          # all-equal token
@@ -108,6 +110,14 @@ def test_quantize_bit_exact(B):
     a_q, a_s = B.quantize_act(xb)
     q_ref, s_ref = O.quantize(cases[1])
     assert np.array_equal(codes_kn(B, a_q, 37), q_ref) and np.array_equal(a_s.cpu().numpy(), s_ref)
+    # rows that start at addresses that are no multiple of 16 (scalar loads), in both kernels
+    for N, K in ((37, 100), (1030, 2048)):
+        x = wl.activations(12, N, K)
+        odd = np.full((N, K + 3), 1e9, np.float32)
+        odd[:, 1:K + 1] = x
+        a_q, a_s = B.quantize_act(dev(odd)[:, 1:K + 1])
+        q_ref, s_ref = O.quantize(x)
+        assert np.array_equal(codes_kn(B, a_q, N), q_ref) and np.array_equal(a_s.cpu().numpy(), s_ref)
 
 
 def test_build_lut_matches_alg1(B, golden):
