@@ -1403,19 +1403,25 @@ __global__ void __launch_bounds__(kThreads) lookup5_kernel(const Lookup5Params p
 }
 
 // ---------------------------------------------------------------------------------------------
-// N <= 2 (one or two parallel tokens: decoding).  A table entry is then one dword (two INT16 sums), the tables of a
-// 256-group chunk of K take 86 KB, and a workgroup can sweep all of K by itself: no split-K partial sums, no second
-// kernel, one barrier pair per chunk.  All 16 waves build a chunk together, then all 16 look it up.
-//   Tables: sub-table kg of the chunk = three blocks (leading digit d0 = 0,1,2) of 27 entries padded to 28 dwords:
-//           entry idx lives at kg*336 + (idx + idx/27)*4.  A build lane (kg, d0) owns one block = 7 aligned 16-byte
-//           stores at 112*tid, which is free of bank conflicts.
+// N <= 2 (one or two parallel tokens: decoding).  The tables of a 256-group chunk of K then take 83 KB (two tokens: an
+// entry is one dword = two INT16 sums) or 42 KB (one token: an entry is one INT16), and a workgroup can sweep all of K
+// by itself: no split-K partial sums, no second kernel, one barrier pair per chunk.  The waves build a chunk
+// together, then all 16 look it up.
+//   Tables: NTOK = 2: sub-table kg of the chunk = 81 dwords at kg*324 + idx*4; a build lane (kg, leading digit d0)
+//           makes 27 entries and stores them as single dwords.  NTOK = 1: sub-table = 81 INT16 + 1 pad = 41 dwords at
+//           kg*164 + idx*2; a build lane owns a whole sub-table.  Consecutive lanes are 27 or 41 dwords apart: odd, so
+//           every store of a wave is free of bank conflicts.
 //   Lookups: wave w reads the packed tile w of the chunk (16 groups); a lane owns an output row and 16/PARTS of the
-//           tile's groups (PARTS lanes per row), RR rows one after the other; INT16 sums inside a chunk (at most 16
-//           lookups), INT32 across chunks; the 16*PARTS partial sums per row are added through LDS at the end.
+//           tile's groups (PARTS lanes per row), RR rows one after the other.  Address = lane constant + idx * entry
+//           size, the group's offset is an immediate: 3 VALU instructions per lookup.  With PARTS = 1 all lanes of a
+//           read look into the same sub-table, whose dwords lie in distinct banks (equal bank = equal address =
+//           broadcast).  Two tokens: INT16 sums inside a chunk (at most 16 lookups), INT32 across chunks; one token:
+//           INT32 throughout.  The 16*PARTS partial sums per row are added through LDS at the end.
+//   Tiles past the end of K are neither built nor looked up.
 // ---------------------------------------------------------------------------------------------
 constexpr int kNarrowChunk = 256;                        // k-groups per chunk = 16 packed tiles, one per wave
-constexpr int kNarrowSubBytes = 336;                     // 3 blocks x 28 dwords
-constexpr int kNarrowLdsBytes = kNarrowChunk * kNarrowSubBytes;   // 86016
+constexpr int narrow_sub_bytes(int ntok) { return ntok == 2 ? 324 : 164; }
+constexpr int narrow_tab_bytes(int ntok) { return kNarrowChunk * narrow_sub_bytes(ntok); }   // 82944 / 41984
 
 struct NarrowParams {
     const uint8_t* packed;
@@ -1434,26 +1440,34 @@ struct NarrowParams {
 };
 // FUSED keeps, behind the tables, two dwords per k-group (the four codes of token 0 and of token 1) and the 16 x 2
 // partial absmax values.
-constexpr int kNarrowFusedMaxChunks = (160 * 1024 - kNarrowLdsBytes - 128) / (kNarrowChunk * 8);   // 37 -> K <= 37888
+constexpr int narrow_fused_lds_bytes(int ntok, int chunks) { return narrow_tab_bytes(ntok) + chunks * kNarrowChunk * 8 + 128; }
+constexpr int narrow_fused_max_chunks(int ntok) {        // 39 (K <= 39936) for two tokens, 59 for one
+    return (160 * 1024 - narrow_tab_bytes(ntok) - 128) / (kNarrowChunk * 8);
+}
 
-template <int PARTS, int RR, bool FUSED>
+template <int NTOK, int PARTS, int RR, bool FUSED>
 __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_n[];
     if (lds_base_of(smem_n) != 0u) return;               // table addresses below are absolute LDS addresses
+    constexpr int SUB = narrow_sub_bytes(NTOK);           // bytes per sub-table
+    constexpr int TAB = narrow_tab_bytes(NTOK);
     constexpr int RPW = 64 / PARTS;                       // rows of one pass of a wave
     constexpr int ROWS = RPW * RR;                        // rows of the workgroup
     constexpr int NBYTES = 16 / PARTS;                    // groups (= bytes of the packed tile row) per lane
+    typedef __attribute__((address_space(3))) short lds_i16;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m0 = blockIdx.x * ROWS;
 
-    // ---- build geometry: thread tid < 768 owns block tid = (k-group tid/3, leading digit tid%3) of every chunk
-    const bool builds = tid < 3 * kNarrowChunk;
-    const int kg_b = tid / 3, d0 = tid - 3 * kg_b;
+    // ---- build geometry.  Two tokens: thread tid < 768 owns (k-group tid/3, leading digit tid%3) of every chunk;
+    //      one token: thread tid < 256 owns k-group tid.
+    const bool builds = tid < (NTOK == 2 ? 3 : 1) * kNarrowChunk;
+    const int kg_b = NTOK == 2 ? tid / 3 : tid;
+    const int d0 = tid - 3 * kg_b;                        // NTOK == 2 only
     // ---- lookup geometry
     const int part = lane / RPW, row_l = lane % RPW;
-    const unsigned lane_tab = (unsigned)(wave * 16 + part * NBYTES) * kNarrowSubBytes;   // first sub-table of this lane
+    const unsigned lane_tab = (unsigned)(wave * 16 + part * NBYTES) * SUB;   // first sub-table of this lane
     const unsigned char* wrow[RR];
     bool row_ok[RR];
 #pragma unroll
@@ -1471,7 +1485,7 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
     auto fetch_act = [&](int c, unsigned (&a)[4]) {
         const int kg = min(c * kNarrowChunk + kg_b, p.G - 1);          // clamped; validity applied at use
         if constexpr (FUSED) {
-            const i32x2 d = *(const __attribute__((address_space(3))) i32x2*)(unsigned)(kNarrowLdsBytes + kg * 8);
+            const i32x2 d = *(const __attribute__((address_space(3))) i32x2*)(unsigned)(TAB + kg * 8);
 #pragma unroll
             for (int j = 0; j < 4; ++j)                                // {code of token 0, code of token 1} of row j
                 a[j] = __builtin_amdgcn_perm((unsigned)d.y, (unsigned)d.x, 0x0c0c0000u | ((4u + j) << 8) | (unsigned)j);
@@ -1483,7 +1497,7 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
     };
     typedef unsigned wvec __attribute__((ext_vector_type(4)));
     auto fetch_w = [&](int c, wvec (&w)[RR]) {
-        const int tile = min(c * 16 + wave, p.KCn - 1);                // clamped tile meets all-zero tables
+        const int tile = min(c * 16 + wave, p.KCn - 1);                // clamped; tiles past the end are not looked up
 #pragma unroll
         for (int rr = 0; rr < RR; ++rr) {
             const unsigned char* src = wrow[rr] + (size_t)tile * 64;
@@ -1507,8 +1521,8 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
         // Quantise the one or two rows of x over all of K: thread tid takes the float4 (= k-group) tid + 1024 i.
         typedef __attribute__((address_space(3))) float lds_f32;
         typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
-        lds_f32* red = (lds_f32*)(unsigned)(kNarrowLdsBytes + p.chunks * kNarrowChunk * 8);   // [wave][token]
-        lds_i32x2* aq = (lds_i32x2*)(unsigned)kNarrowLdsBytes;
+        lds_f32* red = (lds_f32*)(unsigned)(TAB + p.chunks * kNarrowChunk * 8);   // [wave][token]
+        lds_i32x2* aq = (lds_i32x2*)(unsigned)TAB;
         const int nquad = p.G;
         auto load4 = [&](int n, int qi) -> f32x4 {
             const float* src = p.x + (size_t)n * p.ldx + 4 * (size_t)qi;
@@ -1520,10 +1534,11 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
         };
         auto codes4 = [](const f32x4 v, float inv) { return (int)quant_codes4(v, inv); };
         constexpr int NVC = 4;                                         // float4 per thread and token kept (K <= 16384)
-        f32x4 xv[2][NVC];
-        float amax[2] = {0.0f, 0.0f};
+        f32x4 xv[NTOK][NVC];
+        float amax[NTOK];
 #pragma unroll
-        for (int n = 0; n < 2; ++n) {
+        for (int n = 0; n < NTOK; ++n) {
+            amax[n] = 0.0f;
 #pragma unroll
             for (int i = 0; i < NVC; ++i) {
                 const int qi = tid + kThreads * i;
@@ -1543,11 +1558,14 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
                 }
             for (int off = 32; off > 0; off >>= 1) amax[n] = fmaxf(amax[n], __shfl_xor(amax[n], off));
         }
-        if (lane == 0) { red[wave * 2] = amax[0]; red[wave * 2 + 1] = amax[1]; }
-        wg_barrier_lds();
-        float inv[2];
+        if (lane == 0) {
 #pragma unroll
-        for (int n = 0; n < 2; ++n) {
+            for (int n = 0; n < NTOK; ++n) red[wave * 2 + n] = amax[n];
+        }
+        wg_barrier_lds();
+        float inv[NTOK];
+#pragma unroll
+        for (int n = 0; n < NTOK; ++n) {
             float v = 0.0f;
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) v = fmaxf(v, red[w * 2 + n]);
@@ -1558,72 +1576,110 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
 #pragma unroll
         for (int i = 0; i < NVC; ++i) {
             const int qi = tid + kThreads * i;
-            if (qi < nquad) aq[qi] = i32x2{codes4(xv[0][i], inv[0]), codes4(xv[1][i], inv[1])};
+            if (qi < nquad) aq[qi] = i32x2{codes4(xv[0][i], inv[0]), NTOK == 2 ? codes4(xv[NTOK - 1][i], inv[NTOK - 1]) : 0};
         }
         for (int q0 = kThreads * NVC; q0 < nquad; q0 += kThreads * NVC) {
-            f32x4 tv[2][NVC];
+            f32x4 tv[NTOK][NVC];
 #pragma unroll
             for (int i = 0; i < NVC; ++i) {
                 const int qi = q0 + tid + kThreads * i;
-                tv[0][i] = qi < nquad ? load4(0, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
-                tv[1][i] = (p.N > 1 && qi < nquad) ? load4(1, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int n = 0; n < NTOK; ++n)
+                    tv[n][i] = (n < p.N && qi < nquad) ? load4(n, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
             }
 #pragma unroll
             for (int i = 0; i < NVC; ++i) {
                 const int qi = q0 + tid + kThreads * i;
-                if (qi < nquad) aq[qi] = i32x2{codes4(tv[0][i], inv[0]), codes4(tv[1][i], inv[1])};
+                if (qi < nquad)
+                    aq[qi] = i32x2{codes4(tv[0][i], inv[0]), NTOK == 2 ? codes4(tv[NTOK - 1][i], inv[NTOK - 1]) : 0};
             }
         }
         wg_barrier_lds();
     }
     if (builds) fetch_act(0, act_cur);
     for (int c = 0; c < p.chunks; ++c) {
-        // ---------------- build the chunk's tables (topological order of Sec. 4: one add per entry)
+        // ---------------- build the chunk's tables (topological order of Sec. 4: one add per entry); only the groups
+        //                  of real tiles: the padding groups of the last tile get all-zero tables
         if (builds) {
-            const bool valid = c * kNarrowChunk + kg_b < p.G;
-            s16x2 a[4];
+            const int kgg = c * kNarrowChunk + kg_b;
+            if (kgg < p.KCn * 16) {
+                const bool valid = kgg < p.G;
+                if constexpr (NTOK == 2) {
+                    s16x2 a[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const unsigned v = valid ? act_cur[j] : 0u;
-                a[j] = s16x2{(short)(signed char)(v & 0xffu), (short)(signed char)((v >> 8) & 0xffu)};
-            }
-            const short s0 = (short)(d0 - 1);
-            const s16x2 base = a[0] * s16x2{s0, s0};
-            const unsigned dst = (unsigned)tid * 112u;
-            int blk[28];
+                    for (int j = 0; j < 4; ++j) {
+                        const unsigned v = valid ? act_cur[j] : 0u;
+                        a[j] = s16x2{(short)(signed char)(v & 0xffu), (short)(signed char)((v >> 8) & 0xffu)};
+                    }
+                    const short s0 = (short)(d0 - 1);
+                    const s16x2 base = a[0] * s16x2{s0, s0};
+                    lds_i32* dst = (lds_i32*)(unsigned)(kg_b * SUB + d0 * 108);
+                    static_for<0, 3>([&](auto c1) {
+                        constexpr int d1 = decltype(c1)::value;
+                        const s16x2 b1 = d1 == 0 ? base - a[1] : (d1 == 1 ? base : base + a[1]);
+                        static_for<0, 3>([&](auto c2) {
+                            constexpr int d2 = decltype(c2)::value;
+                            const s16x2 b2 = d2 == 0 ? b1 - a[2] : (d2 == 1 ? b1 : b1 + a[2]);
+                            dst[9 * d1 + 3 * d2 + 0] = as_int(b2 - a[3]);
+                            dst[9 * d1 + 3 * d2 + 1] = as_int(b2);
+                            dst[9 * d1 + 3 * d2 + 2] = as_int(b2 + a[3]);
+                        });
+                    });
+                } else {
+                    int a[4];
 #pragma unroll
-            for (int d1 = 0; d1 < 3; ++d1) {
-                const s16x2 b1 = d1 == 0 ? base - a[1] : (d1 == 1 ? base : base + a[1]);
-#pragma unroll
-                for (int d2 = 0; d2 < 3; ++d2) {
-                    const s16x2 b2 = d2 == 0 ? b1 - a[2] : (d2 == 1 ? b1 : b1 + a[2]);
-                    blk[9 * d1 + 3 * d2 + 0] = as_int(b2 - a[3]);
-                    blk[9 * d1 + 3 * d2 + 1] = as_int(b2);
-                    blk[9 * d1 + 3 * d2 + 2] = as_int(b2 + a[3]);
+                    for (int j = 0; j < 4; ++j) a[j] = valid ? (int)(signed char)(act_cur[j] & 0xffu) : 0;
+                    int e[82];
+                    static_for<0, 3>([&](auto c0) {
+                        constexpr int e0 = decltype(c0)::value;
+                        const int b0 = e0 == 0 ? -a[0] : (e0 == 1 ? 0 : a[0]);
+                        static_for<0, 3>([&](auto c1) {
+                            constexpr int d1 = decltype(c1)::value;
+                            const int b1 = d1 == 0 ? b0 - a[1] : (d1 == 1 ? b0 : b0 + a[1]);
+                            static_for<0, 3>([&](auto c2) {
+                                constexpr int d2 = decltype(c2)::value;
+                                const int b2 = d2 == 0 ? b1 - a[2] : (d2 == 1 ? b1 : b1 + a[2]);
+                                e[27 * e0 + 9 * d1 + 3 * d2 + 0] = b2 - a[3];
+                                e[27 * e0 + 9 * d1 + 3 * d2 + 1] = b2;
+                                e[27 * e0 + 9 * d1 + 3 * d2 + 2] = b2 + a[3];
+                            });
+                        });
+                    });
+                    e[81] = 0;
+                    lds_i32* dst = (lds_i32*)(unsigned)(kg_b * SUB);
+                    static_for<0, 41>([&](auto ci) {
+                        constexpr int i = decltype(ci)::value;      // entries 2i (low half) and 2i + 1 (high half)
+                        dst[i] = (int)__builtin_amdgcn_perm((unsigned)e[2 * i + 1], (unsigned)e[2 * i], 0x05040100u);
+                    });
                 }
             }
-            blk[27] = 0;
-            static_for<0, 7>([&](auto qc) {
-                constexpr int q = decltype(qc)::value;
-                lds_write128<q>(dst, i32x4{blk[4 * q], blk[4 * q + 1], blk[4 * q + 2], blk[4 * q + 3]});
-            });
             fetch_act(c + 1, act_nxt);
         }
         fetch_w(c + 1, w_nxt);
         wg_barrier_lds();
         // ---------------- look the chunk up
+        if (c * 16 + wave < p.KCn) {                                   // wave-uniform
 #pragma unroll
-        for (int rr = 0; rr < RR; ++rr) {
-            s16x2 acc16 = {0, 0};
-            static_for<0, NBYTES>([&](auto bc) {
-                constexpr int b = decltype(bc)::value;
-                const unsigned idx = (w_cur[rr][b >> 2] >> (8 * (b & 3))) & 0xffu;
-                const unsigned slot = idx + ((idx * 19u) >> 9);            // idx + idx/27 for idx < 81
-                const unsigned addr = lane_tab + slot * 4u;
-                acc16 += as_s16x2(((const lds_i32*)addr)[b * (kNarrowSubBytes / 4)]);
-            });
-            acc32[rr][0] += (int)acc16.x;
-            acc32[rr][1] += (int)acc16.y;
+            for (int rr = 0; rr < RR; ++rr) {
+                if constexpr (NTOK == 2) {
+                    s16x2 acc16 = {0, 0};
+                    static_for<0, NBYTES>([&](auto bc) {
+                        constexpr int b = decltype(bc)::value;
+                        const unsigned idx = (w_cur[rr][b >> 2] >> (8 * (b & 3))) & 0xffu;
+                        const unsigned addr = lane_tab + idx * 4u;
+                        acc16 += as_s16x2(((const lds_i32*)addr)[b * (SUB / 4)]);
+                    });
+                    acc32[rr][0] += (int)acc16.x;
+                    acc32[rr][1] += (int)acc16.y;
+                } else {
+                    static_for<0, NBYTES>([&](auto bc) {
+                        constexpr int b = decltype(bc)::value;
+                        const unsigned idx = (w_cur[rr][b >> 2] >> (8 * (b & 3))) & 0xffu;
+                        const unsigned addr = lane_tab + idx * 2u;
+                        acc32[rr][0] += (int)((const lds_i16*)addr)[b * (SUB / 2)];
+                    });
+                }
+            }
         }
         wg_barrier_lds();
 #pragma unroll
@@ -1929,11 +1985,11 @@ NarrowPlan narrow_plan(int64_t M, int64_t K) {
     return np;
 }
 
-template <int PARTS, int RR, bool FUSED>
+template <int NTOK, int PARTS, int RR, bool FUSED>
 int launch_narrow_t(const NarrowParams& p, int grid, hipStream_t stream) {
-    auto kfn = narrow_kernel<PARTS, RR, FUSED>;
-    constexpr int max_lds = FUSED ? 160 * 1024 : kNarrowLdsBytes;
-    const int lds = FUSED ? kNarrowLdsBytes + p.chunks * kNarrowChunk * 8 + 128 : kNarrowLdsBytes;
+    auto kfn = narrow_kernel<NTOK, PARTS, RR, FUSED>;
+    constexpr int max_lds = FUSED ? 160 * 1024 : narrow_tab_bytes(NTOK);
+    const int lds = FUSED ? narrow_fused_lds_bytes(NTOK, p.chunks) : narrow_tab_bytes(NTOK);
     if (lds > max_lds) return VLUT_ERR_UNSUPPORTED;
     static bool attr_done = false;   // benign race: the call is idempotent
     if (!attr_done) {
@@ -1945,13 +2001,18 @@ int launch_narrow_t(const NarrowParams& p, int grid, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
 
+template <int NTOK, bool FUSED>
+int launch_narrow_n(const NarrowPlan& np, const NarrowParams& p, hipStream_t stream) {
+    if (np.parts == 4) return launch_narrow_t<NTOK, 4, 1, FUSED>(p, np.grid, stream);
+    if (np.parts == 2) return launch_narrow_t<NTOK, 2, 1, FUSED>(p, np.grid, stream);
+    if (np.rr == 1) return launch_narrow_t<NTOK, 1, 1, FUSED>(p, np.grid, stream);
+    if (np.rr == 2) return launch_narrow_t<NTOK, 1, 2, FUSED>(p, np.grid, stream);
+    return launch_narrow_t<NTOK, 1, 4, FUSED>(p, np.grid, stream);
+}
+
 template <bool FUSED>
 int launch_narrow(const NarrowPlan& np, const NarrowParams& p, hipStream_t stream) {
-    if (np.parts == 4) return launch_narrow_t<4, 1, FUSED>(p, np.grid, stream);
-    if (np.parts == 2) return launch_narrow_t<2, 1, FUSED>(p, np.grid, stream);
-    if (np.rr == 1) return launch_narrow_t<1, 1, FUSED>(p, np.grid, stream);
-    if (np.rr == 2) return launch_narrow_t<1, 2, FUSED>(p, np.grid, stream);
-    return launch_narrow_t<1, 4, FUSED>(p, np.grid, stream);
+    return p.N == 1 ? launch_narrow_n<1, FUSED>(np, p, stream) : launch_narrow_n<2, FUSED>(np, p, stream);
 }
 
 std::mutex g_pack_mutex;
@@ -1970,7 +2031,7 @@ F32Layout f32_layout(int64_t M, int64_t K, int64_t N) {
     F32Layout L;
     std::memset(&L, 0, sizeof(L));
     const size_t scale_bytes = round256((size_t)N * sizeof(float));
-    if (narrow_applies(N, nullptr) && narrow_plan(M, K).chunks <= kNarrowFusedMaxChunks) {
+    if (narrow_applies(N, nullptr) && narrow_plan(M, K).chunks <= narrow_fused_max_chunks((int)N)) {
         L.kind = kF32Narrow;
         return L;
     }
