@@ -1513,9 +1513,14 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
         }
     };
 
-    unsigned act_cur[4] = {0, 0, 0, 0}, act_nxt[4] = {0, 0, 0, 0};
-    wvec w_cur[RR], w_nxt[RR];
-    fetch_w(0, w_cur);
+    // The loop streams the packed weights from HBM and a chunk takes less than the latency of a load, so the weights
+    // are fetched WD chunks ahead (a ring of WD + 1 register sets; fewer for more rows per lane), the activations two.
+    constexpr int WD = RR == 1 ? 4 : (RR == 2 ? 2 : 1);
+    unsigned act_cur[4] = {0, 0, 0, 0}, act_nxt[4] = {0, 0, 0, 0}, act_nx2[4] = {0, 0, 0, 0};
+    wvec w_ring[WD + 1][RR];                               // w_ring[0] = the chunk being looked up
+    wvec (&w_cur)[RR] = w_ring[0];
+#pragma unroll
+    for (int d = 0; d < WD; ++d) fetch_w(d, w_ring[d]);
     float sc[2] = {0.0f, 0.0f};                                        // token scales (FUSED)
     if constexpr (FUSED) {
         // Quantise the one or two rows of x over all of K: thread tid takes the float4 (= k-group) tid + 1024 i.
@@ -1596,8 +1601,10 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
         }
         wg_barrier_lds();
     }
-    if (builds) fetch_act(0, act_cur);
+    if (builds) { fetch_act(0, act_cur); fetch_act(1, act_nxt); }
     for (int c = 0; c < p.chunks; ++c) {
+        fetch_w(c + WD, w_ring[WD]);
+        if (builds) fetch_act(c + 2, act_nx2);
         // ---------------- build the chunk's tables (topological order of Sec. 4: one add per entry); only the groups
         //                  of real tiles: the padding groups of the last tile get all-zero tables
         if (builds) {
@@ -1653,9 +1660,7 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
                     });
                 }
             }
-            fetch_act(c + 1, act_nxt);
         }
-        fetch_w(c + 1, w_nxt);
         wg_barrier_lds();
         // ---------------- look the chunk up
         if (c * 16 + wave < p.KCn) {                                   // wave-uniform
@@ -1683,9 +1688,11 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
         }
         wg_barrier_lds();
 #pragma unroll
-        for (int j = 0; j < 4; ++j) act_cur[j] = act_nxt[j];
+        for (int j = 0; j < 4; ++j) { act_cur[j] = act_nxt[j]; act_nxt[j] = act_nx2[j]; }
 #pragma unroll
-        for (int rr = 0; rr < RR; ++rr) w_cur[rr] = w_nxt[rr];
+        for (int d = 0; d < WD; ++d)
+#pragma unroll
+            for (int rr = 0; rr < RR; ++rr) w_ring[d][rr] = w_ring[d + 1][rr];
     }
 
     // ---------------- add the 16*PARTS partial sums of every (row, token) through LDS, scale, store
