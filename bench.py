@@ -205,8 +205,9 @@ def time_mfma(torch, case, steps, warmup):
 
 def time_ablation(B, torch, case, steps, warmup):
     """Streamed (tables built in LDS on the fly) against materialised (whole table written to HBM, then read back
-    tile by tile), the ablation of Sec. 5.6.  Returns GPU ms per call: streamed mpgemm, build_lut + mpgemm(lut),
-    mpgemm(lut) alone."""
+    tile by tile), and the materialised table token-contiguous (the method's layout) against token-outermost (one
+    table per token, one value per lookup): the ablations of Sec. 5.6.  Returns GPU ms per call: streamed mpgemm,
+    build_lut + mpgemm(lut), mpgemm(lut) alone, build + mpgemm on the token-outermost table, that mpgemm alone."""
     L = B.lib()
     lut = torch.empty(L.vlut_lut_bytes(case.K, case.N) // 2, dtype=torch.int16, device="cuda")
     bargs = (case.a_q.data_ptr(), case.K, case.N, lut.data_ptr(), lut.numel() * 2)
@@ -231,7 +232,27 @@ def time_ablation(B, torch, case, steps, warmup):
         print("bench.py: the un-streamed variant disagrees with the streamed one", file=sys.stderr)
         sys.exit(4)
     _, t_lut, _ = run_timed(torch, gemm_lut, steps, warmup)
-    return t_stream, t_both, t_lut
+
+    oargs = [(a[0], a[1], case.a_s.data_ptr(), lut.data_ptr(), case.M, case.K, case.N, case.y.data_ptr(), case.y.stride(0),
+              None) for a in case._gargs]
+
+    def build_outer(i, stream):
+        case._check(L.vlut_build_lut_token_outer(*bargs, stream), "vlut_build_lut_token_outer")
+
+    def gemm_outer(i, stream):
+        case._check(L.vlut_mpgemm_token_outer(*oargs[i % len(oargs)], stream), "vlut_mpgemm_token_outer")
+
+    def both_outer(i, stream):
+        build_outer(i, stream)
+        gemm_outer(i, stream)
+
+    few = max(5, steps // 4)                      # the slow leg: fewer repetitions
+    _, t_both_outer, _ = run_timed(torch, both_outer, few, 2)
+    if not torch.equal(y_streamed, case.y):
+        print("bench.py: the token-outermost table disagrees with the streamed path", file=sys.stderr)
+        sys.exit(4)
+    _, t_outer, _ = run_timed(torch, gemm_outer, few, 2)
+    return t_stream, t_both, t_lut, t_both_outer, t_outer
 
 
 def cpu_baseline(wl, W, w_scale, x):
@@ -354,20 +375,24 @@ def main():
             linr = [l_ for l_ in wk.linears if l_.name == lname][0]
             Wm, ws_, xm = wl.make_case(wk, linr, n, wk.seeds[0])
             c = Case(B, torch, wl, Wm, ws_, xm, rotate)
-            ts, tb, tl = time_ablation(B, torch, c, max(20, args.steps // 4), 5)
+            ts, tb, tl, tbo, to = time_ablation(B, torch, c, max(20, args.steps // 4), 5)
             abl.append({"workload": wname, "linear": lname, "M": c.M, "K": c.K, "N": n,
                         "lut_MB": B.lib().vlut_lut_bytes(c.K, n) / 1e6, "streamed_ms": ts,
                         "build_lut_plus_mpgemm_ms": tb, "mpgemm_on_materialised_ms": tl,
-                        "streaming_gain": tb / ts})
+                        "streaming_gain": tb / ts,
+                        "token_outer_build_plus_mpgemm_ms": tbo, "token_outer_mpgemm_ms": to,
+                        "layout_gain": tbo / tb})
             del c
             torch.cuda.empty_cache()
         out["ablation_streamed_vs_materialised"] = abl
         print(f"{'workload':18s} {'lin':5s} {'N':>5s} {'table MB':>9s} {'streamed us':>12s} {'build+gemm us':>14s} "
-              f"{'gemm(lut) us':>13s} {'gain':>6s}", file=sys.stderr)
+              f"{'gemm(lut) us':>13s} {'gain':>6s} {'outer build+gemm us':>20s} {'outer gemm us':>14s} {'layout gain':>12s}",
+              file=sys.stderr)
         for a in abl:
             print(f"{a['workload']:18s} {a['linear']:5s} {a['N']:5d} {a['lut_MB']:9.1f} {a['streamed_ms'] * 1e3:12.1f} "
                   f"{a['build_lut_plus_mpgemm_ms'] * 1e3:14.1f} {a['mpgemm_on_materialised_ms'] * 1e3:13.1f} "
-                  f"{a['streaming_gain']:6.2f}", file=sys.stderr)
+                  f"{a['streaming_gain']:6.2f} {a['token_outer_build_plus_mpgemm_ms'] * 1e3:20.1f} "
+                  f"{a['token_outer_mpgemm_ms'] * 1e3:14.1f} {a['layout_gain']:12.2f}", file=sys.stderr)
 
     if args.layer:
         import numpy as np

@@ -132,6 +132,18 @@ int vlut_build_lut(const int8_t* a_q, int64_t K, int64_t N, int16_t* lut, size_t
                    void* stream);
 
 /*
+ * Layout ablation (Sec. 5.6 "Vector LUT-centric tensor layout", Sec. 3.3): the same table with the token index
+ * outermost, lut[n][kg][i] (one table per token, the scalar-LUT arrangement; vlut_lut_bytes(K, N) bytes), and the
+ * mpGeMM on it, where every lookup yields one value for one token.  Same numbers as vlut_mpgemm; arguments as there
+ * (no workspace; N <= 262140).  These two calls exist to measure what the token-contiguous layout buys.
+ */
+int vlut_build_lut_token_outer(const int8_t* a_q, int64_t K, int64_t N, int16_t* lut, size_t lut_bytes,
+                               void* stream);
+int vlut_mpgemm_token_outer(const uint8_t* packed, float w_scale, const float* a_scale, const int16_t* lut,
+                            int64_t M, int64_t K, int64_t N, float* y, int64_t ldy, int32_t* acc_or_null,
+                            void* stream);
+
+/*
  * The mpGeMM itself (Alg. 1 main loop, Eq. 2; Sec. 3.4): for every packed byte
  * one lookup of an 81-row sub-table row and a vector add over the tokens,
  * INT16 inside blocks of at most 64 lookups, INT32 across blocks, then the

@@ -28,6 +28,7 @@ EXPORTS = [
     "vlut_packed_weight_bytes_g5", "vlut_packed_offset_g5", "vlut_workspace_bytes_g5", "vlut_pack_weights_g5",
     "vlut_mpgemm_g5", "vlut_set_plan_g5", "vlut_query_plan_g5",
     "vlut_workspace_bytes_f32", "vlut_query_plan_f32", "vlut_mpgemm_f32",
+    "vlut_build_lut_token_outer", "vlut_mpgemm_token_outer",
 ]
 
 _lib = None
@@ -69,6 +70,9 @@ def lib() -> ctypes.CDLL:
         L.vlut_mpgemm_g5.argtypes, L.vlut_mpgemm_g5.restype = [p, cf, p, p, i64, i64, i64, p, i64, p, p, sz, p], ci
         L.vlut_set_plan_g5.argtypes, L.vlut_set_plan_g5.restype = [ci, ci], ci
         L.vlut_query_plan_g5.argtypes, L.vlut_query_plan_g5.restype = [i64, i64, i64, ctypes.POINTER(ci)], ci
+        L.vlut_build_lut_token_outer.argtypes, L.vlut_build_lut_token_outer.restype = [p, i64, i64, p, sz, p], ci
+        L.vlut_mpgemm_token_outer.argtypes = [p, cf, p, p, i64, i64, i64, p, i64, p, p]
+        L.vlut_mpgemm_token_outer.restype = ci
         L.vlut_workspace_bytes_f32.argtypes, L.vlut_workspace_bytes_f32.restype = [i64, i64, i64], sz
         L.vlut_query_plan_f32.argtypes, L.vlut_query_plan_f32.restype = [i64, i64, i64, ctypes.POINTER(ci)], ci
         L.vlut_mpgemm_f32.argtypes = [p, cf, p, p, i64, i64, i64, i64, p, i64, p, p, p, sz, p]
@@ -203,6 +207,27 @@ def mpgemm_rows(packed: torch.Tensor, w_scale_rows: torch.Tensor, a_q: torch.Ten
                                 y.stride(0), _ptr(acc), _ptr(workspace),
                                 0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "vlut_mpgemm_rows")
+    return y, acc
+
+
+def build_lut_token_outer(a_q: torch.Tensor, N: int) -> torch.Tensor:
+    """The table with the token index outermost, int16 [N][K/4][81] (layout ablation)."""
+    assert a_q.is_cuda and a_q.dtype == torch.int8 and a_q.is_contiguous() and a_q.dim() == 3
+    K = a_q.shape[1]
+    lut = torch.empty((N, K // 4, 81), dtype=torch.int16, device=a_q.device)
+    _check(lib().vlut_build_lut_token_outer(_ptr(a_q), K, N, _ptr(lut), lut.numel() * 2, _stream()),
+           "vlut_build_lut_token_outer")
+    return lut
+
+
+def mpgemm_token_outer(packed: torch.Tensor, w_scale: float, a_scale: torch.Tensor, lut: torch.Tensor, M: int,
+                       want_acc: bool = False):
+    """Runs vlut_mpgemm_token_outer on a table from build_lut_token_outer.  Returns (y [N][M], acc or None)."""
+    N, G, _ = lut.shape
+    y = torch.empty((N, M), dtype=torch.float32, device=lut.device)
+    acc = torch.empty((M, N), dtype=torch.int32, device=lut.device) if want_acc else None
+    _check(lib().vlut_mpgemm_token_outer(_ptr(packed), float(w_scale), _ptr(a_scale), _ptr(lut), M, 4 * G, N, _ptr(y),
+                                         y.stride(0), _ptr(acc), _stream()), "vlut_mpgemm_token_outer")
     return y, acc
 
 

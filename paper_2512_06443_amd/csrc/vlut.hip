@@ -402,6 +402,9 @@ __global__ void __launch_bounds__(kTokThreads) quantize_token_kernel(const float
 // Whole table in global memory (Alg. 1 Precompute / Eq. 1), topological order of Sec. 4:
 // every row is one add/sub away from an earlier one.  One thread per (group, token).
 // ---------------------------------------------------------------------------------------------
+//   TOKEN_OUTER false: lut[kg][i][n], tokens contiguous (Sec. 3.3, the layout of the method)
+//               true:  lut[n][kg][i], one table per token (the scalar-LUT arrangement; layout ablation of Sec. 5.6)
+template <bool TOKEN_OUTER>
 __global__ void __launch_bounds__(256) build_lut_kernel(const int8_t* __restrict__ a_q, int G, int N,
                                                         int16_t* __restrict__ lut) {
     size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
@@ -410,7 +413,8 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const int8_t* __restrict
     int kg = (int)(i / N);
     const int8_t* a = a_q + ((size_t)(n >> 3) * (4 * G) + 4 * kg) * 8 + (n & 7);   // [N/8][K][8]
     int a0 = a[0], a1 = a[8], a2 = a[16], a3 = a[24];
-    int16_t* t = lut + ((size_t)kg * kRows) * N + n;
+    int16_t* t = TOKEN_OUTER ? lut + ((size_t)n * G + kg) * kRows : lut + ((size_t)kg * kRows) * N + n;
+    const size_t row_stride = TOKEN_OUTER ? 1 : (size_t)N;
     int v0 = -a0 - a1 - a2 - a3;                       // row 0, then walk the digits
     for (int d0 = 0; d0 < 3; ++d0) {
         int v1 = v0;
@@ -419,7 +423,7 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const int8_t* __restrict
             for (int d2 = 0; d2 < 3; ++d2) {
                 int v3 = v2;
                 for (int d3 = 0; d3 < 3; ++d3) {
-                    t[(size_t)(27 * d0 + 9 * d1 + 3 * d2 + d3) * N] = (int16_t)v3;
+                    t[(size_t)(27 * d0 + 9 * d1 + 3 * d2 + d3) * row_stride] = (int16_t)v3;
                     v3 += a3;
                 }
                 v2 += a2;
@@ -1718,6 +1722,39 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Layout ablation (Sec. 5.6, Sec. 3.3): the mpGeMM on a table with the token index outermost, lut[n][kg][i].  A
+// lookup then yields one value for one token (1 -> 1), so every (row, group, token) is a 2-byte gather.  A wave takes
+// 64 rows of one token (its lanes gather from the 162 bytes of one sub-table at a time); INT32 accumulation.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) token_outer_lookup_kernel(const uint8_t* __restrict__ packed,
+                                                                 const int16_t* __restrict__ lut, int M, int N, int G,
+                                                                 int KCn, float w_scale, const float* __restrict__ a_scale,
+                                                                 float* __restrict__ y, int64_t ldy,
+                                                                 int32_t* __restrict__ acc) {
+    const int m = blockIdx.x * 64 + (threadIdx.x & 63);
+    const int n = blockIdx.y * 4 + (threadIdx.x >> 6);          // uniform per wave
+    if (n >= N) return;
+    const int mc = m < M ? m : 0;
+    const unsigned char* wrow = packed + ((size_t)(mc >> 2) * KCn) * 64 + (mc & 3) * 16;
+    const int16_t* tab = lut + (size_t)n * G * kRows;
+    int sum = 0;
+    for (int kc = 0; kc < KCn; ++kc) {
+        const i32x4 w = *(const i32x4*)(wrow + (size_t)kc * 64);   // 16 groups of this row
+        const unsigned wd[4] = {(unsigned)w.x, (unsigned)w.y, (unsigned)w.z, (unsigned)w.w};
+#pragma unroll
+        for (int b = 0; b < 16; ++b) {
+            const int kg = kc * 16 + b;
+            const unsigned idx = (wd[b >> 2] >> (8 * (b & 3))) & 0xffu;
+            if (kg < G) sum += tab[(size_t)kg * kRows + min(idx, (unsigned)(kRows - 1))];   // padding groups (index 40) have no table
+        }
+    }
+    if (m < M) {
+        if (y) y[(size_t)n * ldy + m] = (float)sum * (w_scale * a_scale[n]);
+        if (acc) acc[(size_t)m * N + n] = sum;
+    }
+}
+
 // Sum of the split-K partials (any order is exact: integers) + scale step.
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const int32_t* __restrict__ ws, int S, int M, int N,
                                                             float w_scale, const float* __restrict__ w_rows,
@@ -2316,8 +2353,32 @@ int vlut_build_lut(const int8_t* a_q, int64_t K, int64_t N, int16_t* lut, size_t
     if (!a_q || !lut) return VLUT_ERR_NULL;
     if (lut_bytes < vlut_lut_bytes(K, N)) return VLUT_ERR_SMALL_BUFFER;
     size_t total = (size_t)(K / 4) * (size_t)N;
-    hipLaunchKernelGGL(build_lut_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream, a_q,
-                       (int)(K / 4), (int)N, lut);
+    hipLaunchKernelGGL(build_lut_kernel<false>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       a_q, (int)(K / 4), (int)N, lut);
+    return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
+}
+
+int vlut_build_lut_token_outer(const int8_t* a_q, int64_t K, int64_t N, int16_t* lut, size_t lut_bytes, void* stream) {
+    if (!shape_ok(1, K, N)) return VLUT_ERR_SHAPE;
+    if (!a_q || !lut) return VLUT_ERR_NULL;
+    if (lut_bytes < vlut_lut_bytes(K, N)) return VLUT_ERR_SMALL_BUFFER;
+    size_t total = (size_t)(K / 4) * (size_t)N;
+    hipLaunchKernelGGL(build_lut_kernel<true>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       a_q, (int)(K / 4), (int)N, lut);
+    return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
+}
+
+int vlut_mpgemm_token_outer(const uint8_t* packed, float w_scale, const float* a_scale, const int16_t* lut, int64_t M,
+                            int64_t K, int64_t N, float* y, int64_t ldy, int32_t* acc_or_null, void* stream) {
+    if (!shape_ok(M, K, N)) return VLUT_ERR_SHAPE;
+    if (!packed || !a_scale || !lut) return VLUT_ERR_NULL;
+    if (!y && !acc_or_null) return VLUT_ERR_NULL;
+    if (y && (ldy < M || ldy > INT32_MAX)) return VLUT_ERR_SHAPE;
+    const int G = (int)(K / 4), KCn = (G + 15) / 16;
+    const dim3 grid((unsigned)((M + 63) / 64), (unsigned)((N + 3) / 4));
+    if (grid.y > 65535u) return VLUT_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(token_outer_lookup_kernel, grid, dim3(256), 0, (hipStream_t)stream, packed, lut, (int)M, (int)N, G,
+                       KCn, w_scale, a_scale, y, ldy, acc_or_null);
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
 

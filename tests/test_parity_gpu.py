@@ -256,6 +256,23 @@ def test_unstreamed_table_variant(B):
         run_case(B, W, s, x, plan=plan, use_lut=True, tag="unstreamed")
 
 
+def test_token_outer_table_layout(B):
+    # layout ablation (Sec. 5.6): the table with the token index outermost is the same table, and the mpGeMM that
+    # reads it one value per lookup gives the same numbers
+    for (M, K, N) in [(257, 260, 130), (64, 64, 1), (70, 1024, 7), (300, 2560, 33)]:
+        print(f"case token-outer M={M} K={K} N={N}", flush=True)
+        W, s, x = wl.small_case(90 + N, M, K, N)
+        q_ref, s_ref, acc_ref, y_ref = O.mpgemm(W, s, x)
+        packed = B.pack_weights(dev(W))
+        a_q, a_s = B.quantize_act(dev(x))
+        lut = B.build_lut_token_outer(a_q, N)
+        assert np.array_equal(lut.cpu().numpy(), np.ascontiguousarray(O.build_lut(q_ref).transpose(2, 0, 1)))
+        y, acc = B.mpgemm_token_outer(packed, float(s), a_s, lut, M, want_acc=True)
+        torch.cuda.synchronize()
+        assert np.array_equal(acc.cpu().numpy(), acc_ref)
+        check_y(y.cpu().numpy(), y_ref)
+
+
 def test_outlier_channels(B):
     W = wl.ternary(70, 512, 1024, 0.35)
     x = wl.activations(70, 48, 1024, outlier_frac=0.01)
