@@ -121,6 +121,21 @@ class Case:
                          self.y.data_ptr(), self.y.stride(0), None, self.ws5.data_ptr(), self.ws5.numel())
                         for pk in self.pool5]
 
+    def enable_mixed(self, B, torch, W, rotate_bytes):
+        """Adds the blob of the mixed 1.60-bit / 2-bit packing of the same weights and pre-marshals vlut_mpgemm_mixed."""
+        L = B.lib()
+        packed = B.pack_weights_mixed(torch.from_numpy(W).cuda())
+        n_pool = 1 if rotate_bytes <= 0 else max(1, min(256, -(-rotate_bytes // packed.numel())))
+        self.poolx = [packed] + [packed.clone() for _ in range(n_pool - 1)]
+        self.wsx = torch.empty(max(L.vlut_workspace_bytes_mixed(self.M, self.K, self.N), 16), dtype=torch.uint8, device="cuda")
+        self._gemmx = L.vlut_mpgemm_mixed
+        self._gxargs = [(pk.data_ptr(), self.w_scale, self.a_q.data_ptr(), self.a_s.data_ptr(), self.M, self.K, self.N,
+                         self.y.data_ptr(), self.y.stride(0), None, self.wsx.data_ptr(), self.wsx.numel())
+                        for pk in self.poolx]
+
+    def gemm_mixed(self, i, stream):
+        self._check(self._gemmx(*self._gxargs[i % len(self._gxargs)], stream), "vlut_mpgemm_mixed")
+
     def gemm_g5(self, i, stream):
         self._check(self._gemm5(*self._g5args[i % len(self._g5args)], stream), "vlut_mpgemm_g5")
 
@@ -461,6 +476,9 @@ def main():
                     if kk % 20 == 0:
                         c.enable_g5(B, torch, Wm, rotate)
                         g5us = run_timed(torch, c.gemm_g5, max(20, args.steps // 4), 5)[1] * 1e3
+                    else:                                   # other K: the mixed 1.60-bit / 2-bit packing
+                        c.enable_mixed(B, torch, Wm, rotate)
+                        g5us = run_timed(torch, c.gemm_mixed, max(20, args.steps // 4), 5)[1] * 1e3
                     a = mm * (kk // 4) * n
                     rows.append((name, linr.name, mm, kk, n, c.plan32, st * 1e3, st2 * 1e3, km * 1e3,
                                  2.0 * mm * kk * n / (st * 1e-3) / 1e12, a / (km * 1e-3) / 1e12 / ALU_PEAK_TADDS,
@@ -469,7 +487,7 @@ def main():
                     torch.cuda.empty_cache()
         print(f"{'workload':18s} {'lin':7s} {'M':>6s} {'K':>6s} {'N':>5s} {'plan(J,R,S,WG,fused)':>26s} {'step us':>9s} "
               f"{'2-call us':>9s} {'mpgemm us':>9s} {'TOPS':>7s} {'alu/lds frac':>12s} {'hbm frac':>8s} {'mfma us':>8s} "
-              f"{'g5 us':>8s}", file=sys.stderr)
+              f"{'g5|mix us':>9s}", file=sys.stderr)
         for r in rows:
             print(f"{r[0]:18s} {r[1]:7s} {r[2]:6d} {r[3]:6d} {r[4]:5d} {str(r[5]):>26s} {r[6]:9.1f} {r[7]:9.1f} {r[8]:9.1f} "
                   f"{r[9]:7.1f} {r[10]:12.3f} {r[11]:8.3f} {r[12]:8.1f} {r[13]:8.1f}", file=sys.stderr)

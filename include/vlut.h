@@ -233,6 +233,27 @@ int vlut_mpgemm_g5(const uint8_t* packed, float w_scale, const int8_t* a_q, cons
 int vlut_set_plan_g5(int R, int split_k);
 int vlut_query_plan_g5(int64_t M, int64_t K, int64_t N, int* out3);
 
+/*
+ * Mixed 1.60-bit / 2-bit packing (Sec. 3.3 "Flexible sub-2-bit weight packing": different packings for different
+ * groups of weights, so that almost any K is served at close to 1.6 bits per weight).  Here: the first
+ * K5 = 20 * floor(K / 20) input features of every row are packed five per byte, the remaining K - K5 < 20 (a multiple
+ * of 4, as the quantiser's K % 4 == 0 demands) four per byte; K5 = 0 or K - K5 = 0 leave one part empty.
+ *   blob = [vlut_pack_weights_g5 blob of W[:, :K5]] [vlut_pack_weights blob of W[:, K5:]]
+ *   vlut_mixed_k5(K)            K5, or -1 if K is not a positive multiple of 4
+ * vlut_mpgemm_mixed runs each part through its kernel in partial-sum mode (a_q: the part's range of activation rows)
+ * and adds the parts with the split-K parts in one exact INT32 pass before the scale step: the same numbers as
+ * vlut_mpgemm.  The workspace (vlut_workspace_bytes_mixed, never 0) is required; other arguments and errors as in
+ * vlut_mpgemm (streamed tables only).
+ */
+int64_t vlut_mixed_k5(int64_t K);
+size_t vlut_packed_weight_bytes_mixed(int64_t M, int64_t K);                 /* 0 if the shape is invalid      */
+size_t vlut_workspace_bytes_mixed(int64_t M, int64_t K, int64_t N);
+int vlut_pack_weights_mixed(const int8_t* w_ternary, int64_t M, int64_t K, uint8_t* packed, size_t packed_bytes,
+                            void* stream);
+int vlut_mpgemm_mixed(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale, int64_t M,
+                      int64_t K, int64_t N, float* y, int64_t ldy, int32_t* acc_or_null, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
 /* Bytes of scratch vlut_mpgemm_mfma needs: a [tokens padded to 16][K padded to 64] INT8 copy of the activations. */
 size_t vlut_mfma_workspace_bytes(int64_t M, int64_t K, int64_t N);
 

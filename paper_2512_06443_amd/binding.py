@@ -29,6 +29,8 @@ EXPORTS = [
     "vlut_mpgemm_g5", "vlut_set_plan_g5", "vlut_query_plan_g5",
     "vlut_workspace_bytes_f32", "vlut_query_plan_f32", "vlut_mpgemm_f32",
     "vlut_build_lut_token_outer", "vlut_mpgemm_token_outer",
+    "vlut_mixed_k5", "vlut_packed_weight_bytes_mixed", "vlut_workspace_bytes_mixed", "vlut_pack_weights_mixed",
+    "vlut_mpgemm_mixed",
 ]
 
 _lib = None
@@ -70,6 +72,11 @@ def lib() -> ctypes.CDLL:
         L.vlut_mpgemm_g5.argtypes, L.vlut_mpgemm_g5.restype = [p, cf, p, p, i64, i64, i64, p, i64, p, p, sz, p], ci
         L.vlut_set_plan_g5.argtypes, L.vlut_set_plan_g5.restype = [ci, ci], ci
         L.vlut_query_plan_g5.argtypes, L.vlut_query_plan_g5.restype = [i64, i64, i64, ctypes.POINTER(ci)], ci
+        L.vlut_mixed_k5.argtypes, L.vlut_mixed_k5.restype = [i64], i64
+        L.vlut_packed_weight_bytes_mixed.argtypes, L.vlut_packed_weight_bytes_mixed.restype = [i64, i64], sz
+        L.vlut_workspace_bytes_mixed.argtypes, L.vlut_workspace_bytes_mixed.restype = [i64, i64, i64], sz
+        L.vlut_pack_weights_mixed.argtypes, L.vlut_pack_weights_mixed.restype = [p, i64, i64, p, sz, p], ci
+        L.vlut_mpgemm_mixed.argtypes, L.vlut_mpgemm_mixed.restype = [p, cf, p, p, i64, i64, i64, p, i64, p, p, sz, p], ci
         L.vlut_build_lut_token_outer.argtypes, L.vlut_build_lut_token_outer.restype = [p, i64, i64, p, sz, p], ci
         L.vlut_mpgemm_token_outer.argtypes = [p, cf, p, p, i64, i64, i64, p, i64, p, p]
         L.vlut_mpgemm_token_outer.restype = ci
@@ -273,6 +280,32 @@ def pack_weights_g5(w_ternary: torch.Tensor) -> torch.Tensor:
     packed = torch.empty(nbytes, dtype=torch.uint8, device=w_ternary.device)
     _check(lib().vlut_pack_weights_g5(_ptr(w_ternary), M, K, _ptr(packed), nbytes, _stream()), "vlut_pack_weights_g5")
     return packed
+
+
+def pack_weights_mixed(w_ternary: torch.Tensor) -> torch.Tensor:
+    """int8 [M][K] (K % 4 == 0) on the GPU -> blob of the mixed 1.60-bit / 2-bit packing on the GPU."""
+    assert w_ternary.is_cuda and w_ternary.dtype == torch.int8 and w_ternary.is_contiguous()
+    M, K = w_ternary.shape
+    nbytes = lib().vlut_packed_weight_bytes_mixed(M, K)
+    if nbytes == 0:
+        raise VlutError(VLUT_ERR_SHAPE, "vlut_packed_weight_bytes_mixed")
+    packed = torch.empty(nbytes, dtype=torch.uint8, device=w_ternary.device)
+    _check(lib().vlut_pack_weights_mixed(_ptr(w_ternary), M, K, _ptr(packed), nbytes, _stream()), "vlut_pack_weights_mixed")
+    return packed
+
+
+def mpgemm_mixed(packed: torch.Tensor, w_scale: float, a_q: torch.Tensor, a_scale: torch.Tensor, M: int,
+                 y: Optional[torch.Tensor] = None, want_acc: bool = False):
+    """Runs vlut_mpgemm_mixed on a blob from pack_weights_mixed.  Returns (y [N][M], acc or None)."""
+    K, N = a_q.shape[1], a_scale.shape[0]
+    dev = a_q.device
+    if y is None:
+        y = torch.empty((N, M), dtype=torch.float32, device=dev)
+    acc = torch.empty((M, N), dtype=torch.int32, device=dev) if want_acc else None
+    ws = torch.empty(max(lib().vlut_workspace_bytes_mixed(M, K, N), 16), dtype=torch.uint8, device=dev)
+    _check(lib().vlut_mpgemm_mixed(_ptr(packed), float(w_scale), _ptr(a_q), _ptr(a_scale), M, K, N, _ptr(y), y.stride(0),
+                                   _ptr(acc), _ptr(ws), ws.numel(), _stream()), "vlut_mpgemm_mixed")
+    return y, acc
 
 
 def set_plan_g5(R: int = 0, split_k: int = 0) -> None:

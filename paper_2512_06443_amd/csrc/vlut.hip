@@ -67,6 +67,10 @@ struct LookupParams {
     int M, K, N, G, KCn, RGtotal, ldy;
     int Jlog, S, tiles_m, tiles_n, RGW, stages_total, stages_per_split, total_tiles, per_xcd;
     int aligned8;
+    // a_q may be a range of activation rows of a longer tensor: Ka = rows per token chunk of that tensor (0: K)
+    int Ka;
+    // partial-sum mode (mixed packing): write INT32 sums to ws slots slot0 + ks also when K is not split
+    int partial, slot0;
     // fused quantisation (MODE kFusedQuant): fp32 activations [N][ldx] instead of a_q / a_scale
     const float* x;
     float* a_scale_out;       // optional: the token scales, written by the workgroups of the first row tile
@@ -167,7 +171,7 @@ __device__ __forceinline__ s16x2 unpack_pair(unsigned x, int h) {
 __device__ int g_pack_error;
 
 template <int GW>   // GW = weights per byte: 4 (2.00 bits per weight) or 5 (1.60)
-__global__ void pack_kernel(const int8_t* __restrict__ w, int M, int K, int G, int KCn, int RGtotal,
+__global__ void pack_kernel(const int8_t* __restrict__ w, int M, int64_t ldw, int G, int KCn, int RGtotal,
                             uint8_t* __restrict__ packed) {
     size_t total = (size_t)RGtotal * KCn * 64;
     size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
@@ -181,7 +185,7 @@ __global__ void pack_kernel(const int8_t* __restrict__ w, int M, int K, int G, i
     int kg = kc * 16 + b;
     unsigned v = GW == 4 ? 40u : 121u;      // the all-zero pattern: every digit 1
     if (m < M && kg < G) {
-        const int8_t* p = w + (size_t)m * K + (size_t)kg * GW;
+        const int8_t* p = w + (size_t)m * (size_t)ldw + (size_t)kg * GW;
         bool ok = true;
         v = 0;
 #pragma unroll
@@ -721,7 +725,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                 // (address clamped into the tensor, validity applied at use) so nothing waits on the data early.
                 const int kgc = min(kg, p.G - 1);
                 const int cc = (nb < p.N) ? chunk_b : 0;
-                const i32x4* src = (const i32x4*)(p.a_q + ((size_t)cc * p.K + 4 * kgc) * 8);
+                const i32x4* src = (const i32x4*)(p.a_q + ((size_t)cc * p.Ka + 4 * kgc) * 8);
                 const i32x4 v0 = src[0], v1 = src[1];
                 act[0][0] = (unsigned)v0.x; act[0][1] = (unsigned)v0.y;
                 act[1][0] = (unsigned)v0.z; act[1][1] = (unsigned)v0.w;
@@ -1021,11 +1025,11 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
             if (mrow < rows_wg && mrow < R * kRoundRows && n < p.N) {
                 const int val = park[nl * kParkStride + col];
                 const int m = m0 + mrow;
-                if (p.S == 1) {
+                if (p.S == 1 && !p.partial) {
                     if (p.y) p.y[(size_t)n * p.ldy + m] = (float)val * (p.w_rows ? p.w_rows[m] * scale_lds[nl] : scale_lds[nl]);
                     if (p.acc) p.acc[(size_t)m * p.N + n] = val;
                 } else {
-                    p.ws[((size_t)ks * p.N + n) * p.M + m] = val;
+                    p.ws[((size_t)(p.slot0 + ks) * p.N + n) * p.M + m] = val;
                 }
             }
         }
@@ -1165,6 +1169,8 @@ struct Lookup5Params {
     float w_scale;
     int M, K, N, G, KCn, RGtotal, ldy;
     int S, tiles_m, tiles_n, RGW, dstages_total, dstages_per_split, total_tiles, per_xcd;
+    int Ka;        // rows per token chunk of the activation tensor a_q points into
+    int partial;   // mixed packing: write INT32 sums to ws slots ks also when K is not split
 };
 
 // Table read of lookup I (= row group I) of the half-stage that uses byte B of the weight dwords (slot B & 1).
@@ -1271,7 +1277,7 @@ __global__ void __launch_bounds__(kThreads) lookup5_kernel(const Lookup5Params p
             valid = (hs < hs1) && (kg < p.G) && tok_valid;
             const int kgc = min(kg, p.G - 1);               // clamped into the tensor; validity applied at use
             const int cc = tok_valid ? chunk : 0;
-            const i32x2* src = (const i32x2*)(p.a_q + ((size_t)cc * p.K + 5 * (size_t)kgc) * 8);   // 5 rows x 8 tokens
+            const i32x2* src = (const i32x2*)(p.a_q + ((size_t)cc * p.Ka + 5 * (size_t)kgc) * 8);   // 5 rows x 8 tokens
 #pragma unroll
             for (int c = 0; c < 5; ++c) {
                 const i32x2 v = src[c];
@@ -1396,7 +1402,7 @@ __global__ void __launch_bounds__(kThreads) lookup5_kernel(const Lookup5Params p
         if (col < rows_wg && n < p.N) {
             const int val = park[nl * kParkStride + col];
             const int m = m0 + col;
-            if (p.S == 1) {
+            if (p.S == 1 && !p.partial) {
                 if (p.y) p.y[(size_t)n * p.ldy + m] = (float)val * scale_lds[nl];
                 if (p.acc) p.acc[(size_t)m * p.N + n] = val;
             } else {
@@ -2291,7 +2297,7 @@ int vlut_pack_weights(const int8_t* w_ternary, int64_t M, int64_t K, uint8_t* pa
         return VLUT_ERR_DEVICE;
     int G = (int)(K / 4), KCn = (G + 15) / 16, RGtotal = (int)((M + 3) / 4);
     size_t blocks = (need + 255) / 256;
-    hipLaunchKernelGGL(pack_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, s, w_ternary, (int)M, (int)K, G, KCn, RGtotal,
+    hipLaunchKernelGGL(pack_kernel<4>, dim3((unsigned)blocks), dim3(256), 0, s, w_ternary, (int)M, K, G, KCn, RGtotal,
                        packed);
     if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
     int err = 0;
@@ -2416,6 +2422,7 @@ static int mpgemm_impl(const uint8_t* packed, float w_scale, const float* w_rows
     p.stages_total = d.stages_total; p.stages_per_split = d.stages_per_split;
     p.total_tiles = d.total; p.per_xcd = d.per_xcd;
     p.aligned8 = al ? 1 : 0;
+    p.Ka = (int)K;
     hipStream_t s = (hipStream_t)stream;
     int grid = d.per_xcd * 8;
     rc = d.need32 ? launch_lookup_r<true>(pl.R, mode, p, grid, s) : launch_lookup_r<false>(pl.R, mode, p, grid, s);
@@ -2506,7 +2513,7 @@ int vlut_mpgemm_f32(const uint8_t* packed, float w_scale, const float* w_scale_r
     if (pl.S > 1 && !scales) scales = (float*)(ws + L.off_scale);
     LookupParams p;
     std::memset(&p, 0, sizeof(p));
-    p.packed = packed; p.x = x; p.ldx = ldx; p.x_vec = x_vec; p.a_scale_out = scales;
+    p.packed = packed; p.x = x; p.ldx = ldx; p.x_vec = x_vec; p.a_scale_out = scales; p.Ka = (int)K;
     p.y = y; p.acc = acc_or_null; p.ws = (int32_t*)(ws + L.off_ws); p.w_scale = w_one; p.w_rows = w_rows;
     p.M = (int)M; p.K = (int)K; p.N = (int)N; p.G = d.G; p.KCn = d.KCn; p.RGtotal = d.RGtotal; p.ldy = (int)ldy;
     p.Jlog = pl.Jlog; p.S = pl.S; p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.RGW = d.RGW;
@@ -2551,7 +2558,7 @@ int vlut_pack_weights_g5(const int8_t* w_ternary, int64_t M, int64_t K, uint8_t*
         return VLUT_ERR_DEVICE;
     int G = (int)(K / 5), KCn = (G + 15) / 16, RGtotal = (int)((M + 3) / 4);
     size_t blocks = (need + 255) / 256;
-    hipLaunchKernelGGL(pack_kernel<5>, dim3((unsigned)blocks), dim3(256), 0, s, w_ternary, (int)M, (int)K, G, KCn, RGtotal,
+    hipLaunchKernelGGL(pack_kernel<5>, dim3((unsigned)blocks), dim3(256), 0, s, w_ternary, (int)M, K, G, KCn, RGtotal,
                        packed);
     if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
     int err = 0;
@@ -2611,6 +2618,7 @@ int vlut_mpgemm_g5(const uint8_t* packed, float w_scale, const int8_t* a_q, cons
     p.S = pl.S; p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.RGW = d.RGW;
     p.dstages_total = d.dstages_total; p.dstages_per_split = d.dstages_per_split;
     p.total_tiles = d.total; p.per_xcd = d.per_xcd;
+    p.Ka = (int)K;
     hipStream_t s = (hipStream_t)stream;
     int grid = d.per_xcd * 8;
     int rc = d.need32 ? launch_lookup5_r<true>(pl.R, p, grid, s) : launch_lookup5_r<false>(pl.R, p, grid, s);
@@ -2623,6 +2631,124 @@ int vlut_mpgemm_g5(const uint8_t* packed, float w_scale, const int8_t* a_q, cons
         if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
     }
     return VLUT_OK;
+}
+
+// ---- mixed 1.60-bit / 2-bit packing (Sec. 3.3 "Flexible sub-2-bit weight packing")
+int64_t vlut_mixed_k5(int64_t K) {
+    if (K < 4 || (K % 4) != 0) return -1;
+    return (K / 20) * 20;
+}
+
+size_t vlut_packed_weight_bytes_mixed(int64_t M, int64_t K) {
+    if (!shape_ok(M, K, 1)) return 0;
+    const int64_t K5 = vlut_mixed_k5(K), K4 = K - K5;
+    return (K5 > 0 ? vlut_packed_weight_bytes_g5(M, K5) : 0) + (K4 > 0 ? vlut_packed_weight_bytes(M, K4) : 0);
+}
+
+int vlut_pack_weights_mixed(const int8_t* w_ternary, int64_t M, int64_t K, uint8_t* packed, size_t packed_bytes,
+                            void* stream) {
+    if (!shape_ok(M, K, 1)) return VLUT_ERR_SHAPE;
+    if (!w_ternary || !packed) return VLUT_ERR_NULL;
+    if (packed_bytes < vlut_packed_weight_bytes_mixed(M, K)) return VLUT_ERR_SMALL_BUFFER;
+    const int64_t K5 = vlut_mixed_k5(K), K4 = K - K5;
+    const size_t bytes5 = K5 > 0 ? vlut_packed_weight_bytes_g5(M, K5) : 0;
+    const size_t bytes4 = K4 > 0 ? vlut_packed_weight_bytes(M, K4) : 0;
+    hipStream_t s = (hipStream_t)stream;
+    std::lock_guard<std::mutex> lock(g_pack_mutex);
+    int zero = 0;
+    if (hipMemcpyToSymbolAsync(HIP_SYMBOL(g_pack_error), &zero, sizeof(int), 0, hipMemcpyHostToDevice, s) != hipSuccess)
+        return VLUT_ERR_DEVICE;
+    const int RGtotal = (int)((M + 3) / 4);
+    if (K5 > 0) {
+        const int G = (int)(K5 / 5), KCn = (G + 15) / 16;
+        hipLaunchKernelGGL(pack_kernel<5>, dim3((unsigned)((bytes5 + 255) / 256)), dim3(256), 0, s, w_ternary, (int)M, K, G,
+                           KCn, RGtotal, packed);
+        if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
+    }
+    if (K4 > 0) {
+        const int G = (int)(K4 / 4), KCn = (G + 15) / 16;
+        hipLaunchKernelGGL(pack_kernel<4>, dim3((unsigned)((bytes4 + 255) / 256)), dim3(256), 0, s, w_ternary + K5, (int)M, K,
+                           G, KCn, RGtotal, packed + bytes5);
+        if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
+    }
+    int err = 0;
+    if (hipMemcpyFromSymbolAsync(&err, HIP_SYMBOL(g_pack_error), sizeof(int), 0, hipMemcpyDeviceToHost, s) != hipSuccess)
+        return VLUT_ERR_DEVICE;
+    if (hipStreamSynchronize(s) != hipSuccess) return VLUT_ERR_DEVICE;
+    return err ? VLUT_ERR_VALUE : VLUT_OK;
+}
+
+// The two parts as launches of the kernels above in partial-sum mode, then one exact INT32 sum + scale step.
+// Workspace: [S5 + S4][N][M] INT32.
+static bool mixed_plans(int64_t M, int64_t K, int64_t N, Plan5* p5, Plan* p4) {
+    const int64_t K5 = vlut_mixed_k5(K), K4 = K - K5;
+    if (K5 > 0) {
+        *p5 = choose_plan5(M, K5, N);
+        if (!plan5_valid(*p5, M, K5, N)) return false;
+    } else {
+        *p5 = Plan5{0, 0};
+    }
+    *p4 = K4 > 0 ? choose_plan(M, K4, N) : Plan{0, 0, 0};
+    return true;
+}
+
+size_t vlut_workspace_bytes_mixed(int64_t M, int64_t K, int64_t N) {
+    if (!shape_ok(M, K, N)) return 0;
+    Plan5 p5;
+    Plan p4;
+    if (!mixed_plans(M, K, N, &p5, &p4)) return 0;
+    return (size_t)(p5.S + p4.S) * (size_t)M * (size_t)N * sizeof(int32_t);
+}
+
+int vlut_mpgemm_mixed(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale, int64_t M, int64_t K,
+                      int64_t N, float* y, int64_t ldy, int32_t* acc_or_null, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+    int rc = check_mpgemm_args(packed, a_q, a_scale, M, K, N, y, ldy, acc_or_null);
+    if (rc != VLUT_OK) return rc;
+    if (((uintptr_t)a_q) % 16 != 0) return VLUT_ERR_UNSUPPORTED;
+    const int64_t K5 = vlut_mixed_k5(K), K4 = K - K5;
+    Plan5 pl5;
+    Plan pl4;
+    if (!mixed_plans(M, K, N, &pl5, &pl4)) return VLUT_ERR_UNSUPPORTED;
+    const size_t need = (size_t)(pl5.S + pl4.S) * (size_t)M * (size_t)N * sizeof(int32_t);
+    if (!workspace) return VLUT_ERR_NULL;
+    if (workspace_bytes < need) return VLUT_ERR_SMALL_BUFFER;
+    hipStream_t s = (hipStream_t)stream;
+    if (K5 > 0) {
+        const Derived5 d = derive5(pl5, M, K5, N);
+        Lookup5Params p;
+        std::memset(&p, 0, sizeof(p));
+        p.packed = packed; p.a_q = a_q; p.a_scale = a_scale; p.ws = (int32_t*)workspace; p.w_scale = w_scale;
+        p.M = (int)M; p.K = (int)K5; p.N = (int)N; p.G = d.G; p.KCn = d.KCn; p.RGtotal = d.RGtotal; p.ldy = (int)ldy;
+        p.S = pl5.S; p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.RGW = d.RGW;
+        p.dstages_total = d.dstages_total; p.dstages_per_split = d.dstages_per_split;
+        p.total_tiles = d.total; p.per_xcd = d.per_xcd;
+        p.Ka = (int)K; p.partial = 1;
+        const int grid = d.per_xcd * 8;
+        rc = d.need32 ? launch_lookup5_r<true>(pl5.R, p, grid, s) : launch_lookup5_r<false>(pl5.R, p, grid, s);
+        if (rc != VLUT_OK) return rc;
+    }
+    if (K4 > 0) {
+        const Derived d = derive(pl4, M, K4, N);
+        LookupParams p;
+        std::memset(&p, 0, sizeof(p));
+        p.packed = packed + (K5 > 0 ? vlut_packed_weight_bytes_g5(M, K5) : 0);
+        p.a_q = a_q + (size_t)K5 * 8;                      // activation rows K5 .. K-1 of every token chunk
+        p.a_scale = a_scale; p.ws = (int32_t*)workspace; p.w_scale = w_scale;
+        p.M = (int)M; p.K = (int)K4; p.N = (int)N; p.G = d.G; p.KCn = d.KCn; p.RGtotal = d.RGtotal; p.ldy = (int)ldy;
+        p.Jlog = pl4.Jlog; p.S = pl4.S; p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.RGW = d.RGW;
+        p.stages_total = d.stages_total; p.stages_per_split = d.stages_per_split;
+        p.total_tiles = d.total; p.per_xcd = d.per_xcd;
+        p.Ka = (int)K; p.partial = 1; p.slot0 = pl5.S;
+        const int grid = d.per_xcd * 8;
+        rc = d.need32 ? launch_lookup_r<true>(pl4.R, kFast, p, grid, s) : launch_lookup_r<false>(pl4.R, kFast, p, grid, s);
+        if (rc != VLUT_OK) return rc;
+    }
+    const size_t total = (size_t)M * (size_t)N;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+                       (const int32_t*)workspace, pl5.S + pl4.S, (int)M, (int)N, w_scale, (const float*)nullptr, a_scale, y,
+                       ldy, acc_or_null);
+    return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
 
 size_t vlut_mfma_workspace_bytes(int64_t M, int64_t K, int64_t N) {

@@ -37,6 +37,11 @@ def L(vlut_lib_path):
     lib.vlut_set_plan_g5.argtypes = [ci, ci]
     lib.vlut_query_plan_g5.argtypes = [i64, i64, i64, ctypes.POINTER(ci)]
     lib.vlut_query_plan.argtypes = [i64, i64, i64, ctypes.POINTER(ci)]
+    lib.vlut_mixed_k5.argtypes, lib.vlut_mixed_k5.restype = [i64], i64
+    lib.vlut_packed_weight_bytes_mixed.argtypes, lib.vlut_packed_weight_bytes_mixed.restype = [i64, i64], sz
+    lib.vlut_workspace_bytes_mixed.argtypes, lib.vlut_workspace_bytes_mixed.restype = [i64, i64, i64], sz
+    lib.vlut_pack_weights_mixed.argtypes = [vp, i64, i64, vp, sz, vp]
+    lib.vlut_mpgemm_mixed.argtypes = [vp, cf, vp, vp, i64, i64, i64, vp, i64, vp, vp, sz, vp]
     lib.vlut_workspace_bytes_f32.argtypes, lib.vlut_workspace_bytes_f32.restype = [i64, i64, i64], sz
     lib.vlut_query_plan_f32.argtypes = [i64, i64, i64, ctypes.POINTER(ci)]
     lib.vlut_mpgemm_f32.argtypes = [vp, cf, vp, vp, i64, i64, i64, i64, vp, i64, vp, vp, vp, sz, vp]
@@ -250,3 +255,28 @@ def test_f32_entry_host_logic(L):
     assert call(M=14336, K=4096, N=512, ldx=4096, ldy=14336, ws=ctypes.c_void_p(0x1004), ws_bytes=need) == -6
     assert L.vlut_query_plan_f32(8, 8, 8, None) == -1 and L.vlut_query_plan_f32(8, 6, 8, out) == -2
     assert L.vlut_workspace_bytes_f32(8, 6, 8) == 0
+
+
+def test_mixed_packing_host_logic(L):
+    """Mixed 1.60-bit / 2-bit packing (Sec. 3.3): how K is divided, blob sizes, bits per weight, argument checks."""
+    assert [L.vlut_mixed_k5(K) for K in (4, 16, 20, 36, 2560, 4096, 6912, 14336)] == [0, 0, 20, 20, 2560, 4080, 6900, 14320]
+    assert L.vlut_mixed_k5(0) == -1 and L.vlut_mixed_k5(18) == -1
+    for (M, K) in [(6912, 2560), (14336, 4096), (4096, 14336), (2560, 6912), (8, 16), (8, 36)]:
+        K5 = L.vlut_mixed_k5(K)
+        want = (L.vlut_packed_weight_bytes_g5(M, K5) if K5 else 0) + (L.vlut_packed_weight_bytes(M, K - K5) if K > K5 else 0)
+        assert L.vlut_packed_weight_bytes_mixed(M, K) == want
+        if K >= 2560:                                      # "near-1.6-bit" (Sec. 3.3): the 2-bit part is one tile column
+            assert 1.6 <= want * 8 / (M * K) < 1.65
+            assert want < L.vlut_packed_weight_bytes(M, K) * 0.82
+        assert L.vlut_workspace_bytes_mixed(M, K, 8) >= (1 + (K > K5 > 0)) * M * 8 * 4
+    assert L.vlut_packed_weight_bytes_mixed(8, 18) == 0 and L.vlut_workspace_bytes_mixed(8, 18, 8) == 0
+    d = ctypes.c_void_p(0x1000)                                                # never dereferenced: checks come first
+    assert L.vlut_pack_weights_mixed(None, 8, 36, d, 1 << 20, None) == -1
+    assert L.vlut_pack_weights_mixed(d, 8, 18, d, 1 << 20, None) == -2
+    assert L.vlut_pack_weights_mixed(d, 8, 36, d, 100, None) == -3
+    assert L.vlut_mpgemm_mixed(None, 1.0, d, d, 8, 36, 4, d, 8, None, d, 1 << 20, None) == -1
+    assert L.vlut_mpgemm_mixed(d, 1.0, d, d, 8, 36, 4, None, 8, None, d, 1 << 20, None) == -1
+    assert L.vlut_mpgemm_mixed(d, 1.0, d, d, 8, 38, 4, d, 8, None, d, 1 << 20, None) == -2
+    assert L.vlut_mpgemm_mixed(d, 1.0, d, d, 8, 36, 4, d, 7, None, d, 1 << 20, None) == -2
+    assert L.vlut_mpgemm_mixed(d, 1.0, d, d, 8, 36, 4, d, 8, None, None, 0, None) == -1        # the workspace is required
+    assert L.vlut_mpgemm_mixed(d, 1.0, d, d, 8, 36, 4, d, 8, None, d, 16, None) == -3

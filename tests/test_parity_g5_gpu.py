@@ -135,3 +135,46 @@ def test_g5_full_size_bitnet2b_ffn_up(B):
     check_y(y.cpu().numpy()[:, rows], O.epilogue(acc_ref, w_scale, s_ref))
     colsum = W.astype(np.int64).sum(0) @ q_ref.astype(np.int64)
     assert np.array_equal(acc.cpu().numpy().astype(np.int64).sum(0), colsum)
+
+
+# ------------------------------------------------------------------ mixed 1.60-bit / 2-bit packing (Sec. 3.3)
+def test_mixed_packing_blob_is_the_two_blobs(B):
+    L = B.lib()
+    for (M, K) in [(10, 116), (257, 4096), (33, 16), (64, 2560)]:
+        W = wl.ternary(700 + M + K, M, K, 0.4)
+        K5 = L.vlut_mixed_k5(K)
+        assert K5 == (K // 20) * 20
+        blob = B.pack_weights_mixed(dev(W)).cpu().numpy()
+        b5 = L.vlut_packed_weight_bytes_g5(M, K5) if K5 else 0
+        b4 = L.vlut_packed_weight_bytes(M, K - K5) if K > K5 else 0
+        assert blob.size == b5 + b4 == L.vlut_packed_weight_bytes_mixed(M, K)
+        if K5:                                              # bytes of the first part against the oracle's indices
+            idx = O.pack_indices(np.ascontiguousarray(W[:, :K5]), 5)
+            offs = np.array([[L.vlut_packed_offset_g5(M, K5, m, kg) for kg in range(K5 // 5)] for m in range(M)])
+            assert np.array_equal(blob[:b5][offs], idx)
+        if K > K5:
+            idx = O.pack_indices(np.ascontiguousarray(W[:, K5:]), 4)
+            offs = np.array([[L.vlut_packed_offset(M, K - K5, m, kg) for kg in range((K - K5) // 4)] for m in range(M)])
+            assert np.array_equal(blob[b5:][offs], idx)
+    with pytest.raises(B.VlutError) as e:
+        bad = wl.ternary(1, 8, 36, 0.4)
+        bad[3, 33] = 2                                      # in the 2-bit part
+        B.pack_weights_mixed(dev(bad))
+    assert e.value.status == B.VLUT_ERR_VALUE
+
+
+@pytest.mark.parametrize("M,K,N", [(257, 116, 33), (300, 4096, 40), (64, 16, 8), (130, 2560, 17), (640, 6912, 1),
+                                    (100, 14336, 9), (48, 36, 130)])
+def test_mixed_packing_mpgemm(B, M, K, N):
+    print(f"mixed case M={M} K={K} N={N}", flush=True)
+    W, s, x = wl.small_case(710 + M + N, M, K, N)
+    _, _, acc_ref, y_ref = O.mpgemm(W, s, x)
+    blob = B.pack_weights_mixed(dev(W))
+    a_q, a_s = B.quantize_act(dev(x))
+    y, acc = B.mpgemm_mixed(blob, float(s), a_q, a_s, M, want_acc=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy(), acc_ref)
+    check_y(y.cpu().numpy(), y_ref)
+    # close to 1.6 bits per weight for long rows: the 2-bit part is at most 16 features (one 16-byte tile row)
+    if K >= 2560 and M % 4 == 0:
+        assert blob.numel() * 8 / (M * K) < 1.65
