@@ -21,7 +21,9 @@ HIPCC_FLAGS = [
 def build(force: bool = True) -> str:
     """Compiles the library; returns its path.  force=False only builds when the .so is missing or stale."""
     if not force and os.path.exists(LIB):
-        newest = max(os.path.getmtime(SRC), os.path.getmtime(os.path.join(INCLUDE, "vlut.h")))
+        csrc = os.path.dirname(SRC)     # vlut.hip includes the kernel headers next to it
+        sources = [os.path.join(csrc, f) for f in os.listdir(csrc)] + [os.path.join(INCLUDE, "vlut.h")]
+        newest = max(os.path.getmtime(f) for f in sources)
         if os.path.getmtime(LIB) >= newest:
             return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

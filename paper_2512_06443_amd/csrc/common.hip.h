@@ -1,0 +1,148 @@
+// Types, constants, launch parameters of the main lookup kernel and the small device helpers (LDS access, DPP
+// lane exchanges, the LDS-only barrier) shared by the kernels.
+// Part of the single translation unit vlut.hip (included there, in this order).
+#pragma once
+
+namespace {
+
+
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) i32x4 lds_i32x4;
+typedef __attribute__((address_space(3))) int lds_i32;
+
+constexpr int kRows = 81;                    // 3^4 rows per sub-table
+constexpr int kRowBytes = 256;               // LDS bytes per table row (16 slices x 16 B)
+constexpr int kSlotBytes = kRows * kRowBytes;  // 20736
+constexpr int kStageSlots = 4;               // slots resident per stage (one weight dword = 4 lookups)
+constexpr int kTableBytes = kStageSlots * kSlotBytes;  // 82944
+constexpr int kLdsBytes = kTableBytes + 128 * 4;    // + the output scales of the tile's tokens
+// Fused quantisation: behind the tables and the scales, 16 x 8 partial absmax values, then the INT8 codes of the
+// tile's 8 tokens for the workgroup's K range.  A stage (64 k-groups) is 8 blocks (slot of the stage x activation
+// row pair) of 16 sub-tables x 16 bytes, pitched 288 bytes so that both the quantiser's dword stores and the build
+// waves' 16-byte reads are free of bank conflicts.
+constexpr int kFusedRedBase = kLdsBytes;
+constexpr int kFusedAqBase = kFusedRedBase + 16 * 8 * 4;
+constexpr int kFusedBlockPitch = 288;
+constexpr int kFusedStageBytes = 8 * kFusedBlockPitch;           // 2304
+constexpr int kFusedMaxLds = 160 * 1024;
+constexpr int kFusedMaxStages = (kFusedMaxLds - kFusedAqBase) / kFusedStageBytes;   // 34 stages = 8704 values of K
+constexpr int kWaves = 16;                   // waves per workgroup
+constexpr int kThreads = kWaves * 64;
+constexpr unsigned kZeroIdx4 = 0x28282828u;  // four copies of index 40 (the all-zero pattern)
+constexpr int kMaxDim = 1 << 24;
+constexpr int kBlockLookups = 64;            // INT16 block size B for g = 4 (Sec. 3.4)
+
+struct LookupParams {
+    const uint8_t* packed;
+    const int8_t* a_q;
+    const float* a_scale;
+    const float* w_rows;      // per-output-row weight scales (stacked matrices) or null: w_scale for all rows
+    const int16_t* lut;
+    float* y;
+    int32_t* acc;
+    int32_t* ws;
+    float w_scale;
+    int M, K, N, G, KCn, RGtotal, ldy;
+    int Jlog, S, tiles_m, tiles_n, RGW, stages_total, stages_per_split, total_tiles, per_xcd;
+    int aligned8;
+    // a_q may be a range of activation rows of a longer tensor: Ka = rows per token chunk of that tensor (0: K)
+    int Ka;
+    // partial-sum mode (mixed packing): write INT32 sums to ws slots slot0 + ks also when K is not split
+    int partial, slot0;
+    // fused quantisation (MODE kFusedQuant): fp32 activations [N][ldx] instead of a_q / a_scale
+    const float* x;
+    float* a_scale_out;       // optional: the token scales, written by the workgroups of the first row tile
+    int64_t ldx;
+    int x_vec;                // rows can be read as float4
+};
+
+__device__ __forceinline__ unsigned lds_base_of(void* p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (unsigned)(__attribute__((address_space(3))) char*)p;
+#else
+    (void)p;
+    return 0u;   // host pass of the single-source compile; never executed
+#endif
+}
+
+// addr is a byte address inside LDS; OFF16 is a compile-time offset in units of 16 bytes, kept apart so that it
+// lands in the instruction's immediate offset field instead of costing a VALU add.
+template <int OFF16>
+__device__ __forceinline__ i32x4 lds_read128(unsigned addr) {
+    return ((const lds_i32x4*)addr)[OFF16];
+}
+template <int OFF16>
+__device__ __forceinline__ void lds_write128(unsigned addr, i32x4 v) {
+    ((lds_i32x4*)addr)[OFF16] = v;
+}
+
+// Value of x held by the lane whose index differs in bit MASK (1, 2, 4 or 8), inside each row of 16 lanes: data
+// parallel primitives (no LDS traffic).  row_ror:8 swaps the halves of a row; for 4 the two directions are written
+// under complementary bank masks; 2 and 1 are quad permutes.
+template <int MASK>
+__device__ __forceinline__ int lane_xor16(int x) {
+    if (MASK == 8) return __builtin_amdgcn_update_dpp(0, x, 0x128, 0xF, 0xF, false);
+    if (MASK == 4) {
+        int t = __builtin_amdgcn_update_dpp(0, x, 0x104, 0xF, 0x5, false);   // lanes 0-3, 8-11 <- lane + 4
+        return __builtin_amdgcn_update_dpp(t, x, 0x114, 0xF, 0xA, false);     // lanes 4-7, 12-15 <- lane - 4
+    }
+    if (MASK == 2) return __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false);
+    return __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false);
+}
+// Value of lane l ^ 7 (row_half_mirror reverses each group of 8 lanes): a one-instruction partner whose bit 2 differs.
+__device__ __forceinline__ int lane_xor7(int x) { return __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); }
+
+// 16 sub-tables per table row: the 16 lanes of a group hold 16 partial sums of the same 8 tokens (packed INT16 block
+// sums, plus INT32 sums of earlier blocks when WIDE).  Reduce-scatter with partners l^8, l^7, l^2, l^1 (each a
+// single DPP operand): lane l ends with the total of token l >> 1.  The first exchange moves packed INT16 pairs and
+// widens while adding.
+template <bool WIDE>
+__device__ __forceinline__ int reduce16(const s16x2 (&a16)[4], const int (&a32)[8], int l) {
+    const bool hi3 = (l & 8) != 0, hi2 = (l & 4) != 0, hi1 = (l & 2) != 0;
+    int w[4];
+    if constexpr (!WIDE) {
+        const int a0 = __builtin_bit_cast(int, a16[0]), a1 = __builtin_bit_cast(int, a16[1]);
+        const int a2 = __builtin_bit_cast(int, a16[2]), a3 = __builtin_bit_cast(int, a16[3]);
+        const s16x2 kA = __builtin_bit_cast(s16x2, hi3 ? a2 : a0), kB = __builtin_bit_cast(s16x2, hi3 ? a3 : a1);
+        const s16x2 rA = __builtin_bit_cast(s16x2, lane_xor16<8>(hi3 ? a0 : a2));
+        const s16x2 rB = __builtin_bit_cast(s16x2, lane_xor16<8>(hi3 ? a1 : a3));
+        w[0] = (int)kA.x + (int)rA.x;
+        w[1] = (int)kA.y + (int)rA.y;
+        w[2] = (int)kB.x + (int)rB.x;
+        w[3] = (int)kB.y + (int)rB.y;
+    } else {
+        int v[8];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            v[2 * q] = (int)a16[q].x + a32[2 * q];
+            v[2 * q + 1] = (int)a16[q].y + a32[2 * q + 1];
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (hi3 ? v[e + 4] : v[e]) + lane_xor16<8>(hi3 ? v[e] : v[e + 4]);
+    }
+    const int x0 = (hi2 ? w[2] : w[0]) + lane_xor7(hi2 ? w[0] : w[2]);
+    const int x1 = (hi2 ? w[3] : w[1]) + lane_xor7(hi2 ? w[1] : w[3]);
+    const int y1 = (hi1 ? x1 : x0) + lane_xor16<2>(hi1 ? x0 : x1);
+    return y1 + lane_xor16<1>(y1);
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every outstanding global load
+// and store of the wave (vmcnt(0)), which would expose the latency of the weight and activation prefetches at
+// every stage; here a wave only has to finish its own LDS reads/writes before it signals the barrier.
+__device__ __forceinline__ void wg_barrier_lds() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__device__ __forceinline__ s16x2 as_s16x2(int v) { return __builtin_bit_cast(s16x2, v); }
+__device__ __forceinline__ int as_int(s16x2 v) { return __builtin_bit_cast(int, v); }
+
+// Two INT8 values (bytes 2h and 2h+1 of x) -> sign-extended packed INT16 pair.
+__device__ __forceinline__ s16x2 unpack_pair(unsigned x, int h) {
+    unsigned sel = h ? 0x070c060cu : 0x050c040cu;   // {0, byte, 0, byte}: value in the high byte of each half
+    s16x2 v = as_s16x2((int)__builtin_amdgcn_perm(x, 0u, sel));
+    return v >> (short)8;                            // arithmetic shift per half
+}
+
+}  // namespace

@@ -1,0 +1,609 @@
+// The main kernel: streamed LDS table build + lookup-accumulate + scale epilogue for g = 4 (Alg. 1, Sec. 3.4).
+// Part of the single translation unit vlut.hip (included there, in this order).
+#pragma once
+
+namespace {
+
+// ---------------------------------------------------------------------------------------------
+// The lookup kernel (Alg. 1 main loop + streamed Precompute, Sec. 3.4).
+//
+// Roles inside the 16-wave workgroup: waves 0..3 (one per SIMD) only BUILD tables, waves 4..15 only LOOK UP.
+// The four LDS slots are used as two halves of two slots each: while the lookup waves read one half, the build
+// waves fill the other half with the next two sub-table sets, and one barrier per half-stage hands the halves over.
+// The lookups are bound by VALU issue (one address permute + four packed adds per 16-byte table read), the build
+// by LDS write bandwidth, so the two overlap well.
+//   R       row groups (of 4 output rows) per lookup wave; workgroup tile = up to 48*R rows
+//   NEED32  more than 64 lookups per lane: widen INT16 block sums into INT32 every 16 stages
+//   MODE    kFast: tables built in LDS from the token-chunked INT8 activations (streamed, the hot path)
+//           kFusedQuant: as kFast, but the workgroup first quantises its 8 tokens itself (fp32 rows -> absmax ->
+//                        INT8 codes kept in LDS); needs 16 sub-tables per row (8-token tiles)
+//           kFromGlobal: LDS slots are filled from a table materialised by vlut_build_lut
+// ---------------------------------------------------------------------------------------------
+template <int V> using ic = std::integral_constant<int, V>;
+template <int I0, int I1, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I0 < I1) {
+        f(ic<I0>{});
+        static_for<I0 + 1, I1>(f);
+    }
+}
+
+enum { kFast = 0, kFusedQuant = 1, kFromGlobal = 2 };
+constexpr int kBuildWaves = 4;
+constexpr int kLookupWaves = kWaves - kBuildWaves;     // 12
+constexpr int kRoundRows = kLookupWaves * 4;           // 48 output rows per row-group round of the workgroup
+
+// Issues the table read of lookup number I of half-stage HALF (b-major: I = b*R + r, b = 0,1).  Byte 2*HALF + b of
+// the row group's weight dword is the row of slot 2*HALF + b; the lane reads its 16-byte slice (8 INT16 entries).
+template <int R, int HALF, int I>
+__device__ __forceinline__ i32x4 lookup_read(const unsigned (&w)[R], unsigned lanebase) {
+    constexpr int slot = 2 * HALF + I / R, r = I % R;
+    constexpr unsigned sel = 0x0c0c0000u | ((4u + (unsigned)slot) << 8);
+    const unsigned addr = __builtin_amdgcn_perm(w[r], lanebase, sel);   // idx*256 + slice*16
+    return lds_read128<slot * (kSlotBytes / 16)>(addr);
+}
+
+template <int R, int I>
+__device__ __forceinline__ void lookup_accumulate(s16x2 (&acc16)[R][4], const i32x4 v) {
+    constexpr int r = I % R;
+    // Written as instructions with the accumulator tied to one register ("+v"): left to the register allocator, the
+    // unrolled copies of the stage keep the accumulators in alternating register sets, which doubles their
+    // footprint and caps the row groups a wave can hold.
+    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][0]) : "v"(v.x));
+    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][1]) : "v"(v.y));
+    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][2]) : "v"(v.z));
+    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][3]) : "v"(v.w));
+}
+
+// The 2*R lookups of a half-stage, software pipelined in batches of NB: the reads of batch k+1 are in flight while
+// the packed INT16 adds of batch k issue (Alg. 1 lines 3-6: one shared index, one vector add over the tokens).
+template <int R, int HALF, int NB, int K0>
+__device__ __forceinline__ void lookup_batches(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4],
+                                               i32x4 (&cur)[NB]) {
+    constexpr int total = 2 * R;
+    if constexpr (K0 < total) {
+        i32x4 nxt[NB];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) nxt[i] = i32x4{0, 0, 0, 0};
+        if constexpr (K0 + NB + 0 < total && NB > 0) nxt[0] = lookup_read<R, HALF, (K0 + NB + 0 < total ? K0 + NB + 0 : 0)>(w, lanebase);
+        if constexpr (K0 + NB + 1 < total && NB > 1) nxt[1] = lookup_read<R, HALF, (K0 + NB + 1 < total ? K0 + NB + 1 : 0)>(w, lanebase);
+        if constexpr (K0 + NB + 2 < total && NB > 2) nxt[2] = lookup_read<R, HALF, (K0 + NB + 2 < total ? K0 + NB + 2 : 0)>(w, lanebase);
+        if constexpr (K0 + NB + 3 < total && NB > 3) nxt[3] = lookup_read<R, HALF, (K0 + NB + 3 < total ? K0 + NB + 3 : 0)>(w, lanebase);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (K0 + 0 < total && NB > 0) lookup_accumulate<R, (K0 + 0 < total ? K0 + 0 : 0)>(acc16, cur[0]);
+        if constexpr (K0 + 1 < total && NB > 1) lookup_accumulate<R, (K0 + 1 < total ? K0 + 1 : 0)>(acc16, cur[1]);
+        if constexpr (K0 + 2 < total && NB > 2) lookup_accumulate<R, (K0 + 2 < total ? K0 + 2 : 0)>(acc16, cur[2]);
+        if constexpr (K0 + 3 < total && NB > 3) lookup_accumulate<R, (K0 + 3 < total ? K0 + 3 : 0)>(acc16, cur[3]);
+        __builtin_amdgcn_sched_barrier(0);
+        lookup_batches<R, HALF, NB, K0 + NB>(w, lanebase, acc16, nxt);
+    }
+}
+
+template <int R, int HALF>
+__device__ __forceinline__ void lookup_half(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4]) {
+    constexpr int NB = 4;
+    constexpr int total = 2 * R;
+    i32x4 first[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) first[i] = i32x4{0, 0, 0, 0};
+    first[0] = lookup_read<R, HALF, 0>(w, lanebase);
+    if constexpr (total > 1) first[1] = lookup_read<R, HALF, 1>(w, lanebase);
+    if constexpr (total > 2) first[2] = lookup_read<R, HALF, (total > 2 ? 2 : 0)>(w, lanebase);
+    if constexpr (total > 3) first[3] = lookup_read<R, HALF, (total > 3 ? 3 : 0)>(w, lanebase);
+    __builtin_amdgcn_sched_barrier(0);
+    lookup_batches<R, HALF, NB, 0>(w, lanebase, acc16, first);
+}
+
+// Nine table rows that share their two leading digits (b1 = their common part): the third and fourth digits add or
+// subtract a2 and a3.  Row offsets 0..8 from dst.
+__device__ __forceinline__ void build_rows9(unsigned dst, const s16x2 (&b1)[4], const s16x2 (&a2)[4],
+                                            const s16x2 (&a3)[4]) {
+    s16x2 u[4], lo[4], hi[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { u[q] = b1[q] - a2[q]; lo[q] = u[q] - a3[q]; hi[q] = u[q] + a3[q]; }
+    lds_write128<0 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
+    lds_write128<1 * 16>(dst, i32x4{as_int(u[0]), as_int(u[1]), as_int(u[2]), as_int(u[3])});
+    lds_write128<2 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { lo[q] = b1[q] - a3[q]; hi[q] = b1[q] + a3[q]; }
+    lds_write128<3 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
+    lds_write128<4 * 16>(dst, i32x4{as_int(b1[0]), as_int(b1[1]), as_int(b1[2]), as_int(b1[3])});
+    lds_write128<5 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { u[q] = b1[q] + a2[q]; lo[q] = u[q] - a3[q]; hi[q] = u[q] + a3[q]; }
+    lds_write128<6 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
+    lds_write128<7 * 16>(dst, i32x4{as_int(u[0]), as_int(u[1]), as_int(u[2]), as_int(u[3])});
+    lds_write128<8 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
+}
+
+template <int R, bool NEED32, int MODE>
+__global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    // The kernel has no static LDS, so the dynamic segment starts at LDS address 0; table addresses are formed
+    // as idx*256 + slice*16 by a byte permute and rely on that.
+    if (lds_base_of(smem) != 0u) return;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction
+
+    // Fetch every launch parameter now, in one batch of scalar loads.  Left alone, the compiler loads only what the
+    // early exit below needs and the rest after it, so each workgroup would wait for the argument buffer twice.
+    asm volatile("" ::"s"(p.per_xcd), "s"(p.total_tiles), "s"(p.S), "s"(p.tiles_n), "s"(p.Jlog), "s"(p.RGW),
+                 "s"(p.stages_per_split), "s"(p.stages_total), "s"(p.K), "s"(p.N), "s"(p.G), "s"(p.KCn), "s"(p.RGtotal),
+                 "s"(p.M), "s"(p.ldy), "s"(p.w_scale), "s"(p.packed), "s"(p.a_q), "s"(p.a_scale), "s"(p.y), "s"(p.acc),
+                 "s"(p.ws), "s"(p.lut), "s"(p.aligned8), "s"(p.w_rows), "s"(p.x), "s"(p.a_scale_out), "s"(p.ldx),
+                 "s"(p.x_vec));
+
+    // ---- which tile (XCD-aware: the 8 XCDs take contiguous ranges of the tile list, so the
+    //      workgroups that share a weight tile also share an L2)
+    int L = (int)(blockIdx.x & 7) * p.per_xcd + (int)(blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= p.per_xcd || L >= p.total_tiles) return;
+    const int ks = L % p.S;
+    L /= p.S;
+    const int nt = L % p.tiles_n;
+    const int mt = L / p.tiles_n;
+
+    const int Jlog = p.Jlog;
+    const int J = 1 << Jlog;
+    const int TClog = 4 - Jlog;          // log2(token chunks per sub-table)
+    const int n_tile = 128 >> Jlog;
+    const int n0 = nt * n_tile;
+    const int rgw0 = mt * p.RGW;          // first row group of this workgroup
+
+    const int l = lane & 15;             // 16-byte slice of the table rows this lane reads or writes
+    const int grp = lane >> 4;
+    const int j = l >> TClog;            // sub-table selector of the slice
+    const int t = l & ((1 << TClog) - 1);   // 8-token chunk of the slice
+    const unsigned lanebase = (unsigned)l * 16u;
+
+    const int st_begin = ks * p.stages_per_split;
+    const int st_end = min(p.stages_total, st_begin + p.stages_per_split);
+    const bool builder = wave < kBuildWaves;          // scalar condition
+    const int lw = wave - kBuildWaves;                // index among the lookup waves
+
+    // Output scale of every token of the tile, parked behind the tables (read in the epilogue).
+    typedef __attribute__((address_space(3))) float lds_f32;
+    lds_f32* scale_lds = (lds_f32*)(unsigned)kTableBytes;
+    // Loaded now, stored to LDS only when the K loop is over: nothing at the start of the kernel waits for it.
+    float my_scale = 0.0f;
+    if (MODE != kFusedQuant && tid < n_tile && n0 + tid < p.N)
+        my_scale = p.w_rows ? p.a_scale[n0 + tid] : p.w_scale * p.a_scale[n0 + tid];
+
+    // Fused quantisation (all 16 waves; called once by either role, after its first loads are on their way): lane =
+    // token + 8 * quad, a wave reads 8 consecutive float4 of each of the 8 rows per pass.  Absmax over all of K
+    // (also when K is split: every split needs the same scale), codes only for this workgroup's K range.
+    auto quantise_tile = [&]() {
+        typedef __attribute__((address_space(3))) unsigned lds_u32;
+        lds_f32* red = (lds_f32*)(unsigned)kFusedRedBase;      // [wave][token]
+        const int tok = lane & 7;
+        const int kq = wave * 8 + (lane >> 3);
+        const int n = n0 + tok;
+        const bool live = n < p.N;
+        const float* row = p.x + (size_t)(live ? n : 0) * p.ldx;
+        const int nquad = p.G;                                 // a float4 of a row = one k-group
+        const int q_lo = st_begin * 64, q_hi = min(st_end * 64, nquad);
+        auto load4 = [&](int qi) -> f32x4 {
+            const float* src = row + 4 * (size_t)qi;
+            if (p.x_vec) return *(const f32x4*)src;
+            return f32x4{src[0], src[1], src[2], src[3]};
+        };
+        auto absmax4 = [](float m, const f32x4 v) {
+            return fmaxf(fmaxf(m, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+        };
+        constexpr int NVC = 8;                                 // float4 per thread kept in registers (K <= 4096)
+        f32x4 xv[NVC];
+        float amax = 0.0f;
+#pragma unroll
+        for (int i = 0; i < NVC; ++i) {
+            const int qi = kq + 128 * i;
+            xv[i] = (live && qi < nquad) ? load4(qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+            amax = absmax4(amax, xv[i]);
+        }
+        for (int q0 = 128 * NVC; q0 < nquad; q0 += 128 * NVC) {   // longer rows: NVC loads in flight per pass
+            f32x4 tv[NVC];
+#pragma unroll
+            for (int i = 0; i < NVC; ++i) {
+                const int qi = q0 + kq + 128 * i;
+                tv[i] = (live && qi < nquad) ? load4(qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int i = 0; i < NVC; ++i) amax = absmax4(amax, tv[i]);
+        }
+        for (int off = 32; off >= 8; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));   // lanes of the same token
+        if (lane < 8) red[wave * 8 + lane] = amax;
+        wg_barrier_lds();
+        float v = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) v = fmaxf(v, red[w * 8 + tok]);
+        const float inv = (v > 0.0f) ? 127.0f / v : 0.0f;      // IEEE divisions, as in quantize_kernel
+        const float sc = v / 127.0f;
+        if (tid < 8) {                                         // lane = token here
+            my_scale = live ? (p.w_rows ? sc : p.w_scale * sc) : 0.0f;
+            if (live && mt == 0 && ks == 0 && p.a_scale_out) p.a_scale_out[n] = sc;
+        }
+        // LDS address of the lane's dword for k-group kq; the address is affine in the k-group (128 groups = 2 stages)
+        const int ql0 = kq - q_lo;
+        const int a0 = kFusedAqBase + (ql0 >> 6) * kFusedStageBytes +
+                       ((ql0 & 3) * 2 + ((tok & 3) >> 1)) * kFusedBlockPitch +   // (slot of the stage, row pair)
+                       ((ql0 >> 2) & 15) * 16 + (tok & 1) * 8 + (tok >> 2) * 4;
+        auto emit = [&](int qi, const f32x4 xq, int addr) {
+            const unsigned e = quad_transpose_codes(quant_codes4(xq, inv), tok);   // 4 tokens of row tok % 4 of the group
+            if (qi >= q_lo && qi < q_hi) *(lds_u32*)(unsigned)addr = e;
+        };
+#pragma unroll
+        for (int i = 0; i < NVC; ++i) emit(kq + 128 * i, xv[i], a0 + i * 2 * kFusedStageBytes);
+        // the rest of the range is read again; every lane runs the same passes (the quad exchange needs its partners)
+        for (int q0 = max(128 * NVC, q_lo & ~127); q0 < q_hi; q0 += 128 * NVC) {
+            f32x4 tv[NVC];
+#pragma unroll
+            for (int i = 0; i < NVC; ++i) {
+                const int qi = q0 + kq + 128 * i;
+                tv[i] = (live && qi >= q_lo && qi < q_hi) ? load4(qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int i = 0; i < NVC; ++i)
+                emit(q0 + kq + 128 * i, tv[i], a0 + ((q0 >> 6) + 2 * i) * kFusedStageBytes);
+        }
+        wg_barrier_lds();
+    };
+
+    s16x2 acc16[R][4];
+    int acc32[NEED32 ? R : 1][8];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc16[r][q] = s16x2{0, 0};
+    if (NEED32) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc32[r][e] = 0;
+    }
+
+    if (builder) {
+        // ================================ build role ================================
+        // Task of a lane for one half-stage: slot s2 of the half (0/1), slice l, leading digits hh = u (table rows
+        // 9u .. 9u+8); the ninth digit pair (rows 72..80) is shared out one row per lane, lane u = 0 takes two.
+        const int u = (wave * 4 + grp) & 7;
+        const int s2 = (wave * 4 + grp) >> 3;
+        const int nb = n0 + 8 * t;                   // first token of the slice
+        const int chunk_b = nb >> 3;
+        unsigned actA[4][2], actB[4][2];
+        bool validA = false, validB = false;
+
+        // Half-stage hs = 2*stage + half holds slots 2*half, 2*half+1 = sub-tables kg = stage*4J + 4j + slot.
+        auto fetch_act = [&](int hs, unsigned (&act)[4][2], bool& valid) {
+            const int kg = (hs >> 1) * 4 * J + 4 * j + 2 * (hs & 1) + s2;
+            valid = (hs < 2 * st_end) && (kg < p.G) && (nb < p.N);
+            if (MODE == kFusedQuant) {
+                // the codes this workgroup made itself: rows 0,1 and rows 2,3 of the group, 16 bytes each
+                const int stl = min((hs >> 1) - st_begin, p.stages_per_split - 1);   // prefetches run past the end
+                const unsigned a0 = (unsigned)(kFusedAqBase + stl * kFusedStageBytes +
+                                               (2 * (hs & 1) + s2) * 2 * kFusedBlockPitch + j * 16);
+                const i32x4 v0 = lds_read128<0>(a0), v1 = lds_read128<kFusedBlockPitch / 16>(a0);
+                act[0][0] = (unsigned)v0.x; act[0][1] = (unsigned)v0.y;
+                act[1][0] = (unsigned)v0.z; act[1][1] = (unsigned)v0.w;
+                act[2][0] = (unsigned)v1.x; act[2][1] = (unsigned)v1.y;
+                act[3][0] = (unsigned)v1.z; act[3][1] = (unsigned)v1.w;
+            }
+            if (MODE == kFast) {
+                // 4 activation rows x 8 tokens = 32 contiguous bytes of the token-chunked layout; branch-free
+                // (address clamped into the tensor, validity applied at use) so nothing waits on the data early.
+                const int kgc = min(kg, p.G - 1);
+                const int cc = (nb < p.N) ? chunk_b : 0;
+                const i32x4* src = (const i32x4*)(p.a_q + ((size_t)cc * p.Ka + 4 * kgc) * 8);
+                const i32x4 v0 = src[0], v1 = src[1];
+                act[0][0] = (unsigned)v0.x; act[0][1] = (unsigned)v0.y;
+                act[1][0] = (unsigned)v0.z; act[1][1] = (unsigned)v0.w;
+                act[2][0] = (unsigned)v1.x; act[2][1] = (unsigned)v1.y;
+                act[3][0] = (unsigned)v1.z; act[3][1] = (unsigned)v1.w;
+            }
+        };
+
+        auto build_half = [&](int hs, unsigned (&act)[4][2], bool valid) {
+            const unsigned slot = (unsigned)(2 * (hs & 1) + s2);
+            const unsigned dst = slot * kSlotBytes + (unsigned)l * 16u;
+            if (MODE == kFromGlobal) {
+                const int kg = (hs >> 1) * 4 * J + 4 * j + 2 * (hs & 1) + s2;
+                auto copy_row = [&](int row) {
+                    i32x4 v = {0, 0, 0, 0};
+                    if (kg < p.G && nb < p.N) {
+                        const int16_t* src = p.lut + ((size_t)kg * kRows + row) * p.N + nb;
+                        if (p.aligned8 && nb + 8 <= p.N) {
+                            v = *(const i32x4*)src;
+                        } else {
+                            int tmp[4] = {0, 0, 0, 0};
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                unsigned hw = (nb + e < p.N) ? (unsigned)(uint16_t)src[e] : 0u;
+                                tmp[e >> 1] |= (int)(hw << (16 * (e & 1)));
+                            }
+                            v = i32x4{tmp[0], tmp[1], tmp[2], tmp[3]};
+                        }
+                    }
+                    lds_write128<0>(dst + (unsigned)row * kRowBytes, v);
+                };
+#pragma unroll
+                for (int i = 0; i < 9; ++i) copy_row(9 * u + i);
+                copy_row(72 + u);
+                if (u == 0) copy_row(80);
+            } else {
+                // Every row is one packed add/sub away from an earlier one (topological order, Sec. 4).
+                if (!valid) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
+                }
+                const short s0 = (short)(u / 3 - 1), s1 = (short)(u % 3 - 1);
+                const s16x2 m0 = {s0, s0}, m1 = {s1, s1};
+                const short e2 = (short)(u / 3 - 1), e3 = (short)(u % 3 - 1);    // digits (d2,d3) of the extra row 72+u
+                const s16x2 x2 = {e2, e2}, x3 = {e3, e3};
+                s16x2 a2[4], a3[4], b1[4], ex[4], top[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const s16x2 a0 = unpack_pair(act[0][q >> 1], q & 1);
+                    const s16x2 a1 = unpack_pair(act[1][q >> 1], q & 1);
+                    a2[q] = unpack_pair(act[2][q >> 1], q & 1);
+                    a3[q] = unpack_pair(act[3][q >> 1], q & 1);
+                    b1[q] = a0 * m0 + a1 * m1;
+                    top[q] = a0 + a1;                               // leading digits (2,2)
+                    ex[q] = top[q] + a2[q] * x2 + a3[q] * x3;       // row 72 + 3*d2 + d3 with (d2,d3) = (u/3, u%3)
+                }
+                build_rows9(dst + (unsigned)(9 * u) * kRowBytes, b1, a2, a3);
+                lds_write128<0>(dst + (unsigned)(72 + u) * kRowBytes,
+                                i32x4{as_int(ex[0]), as_int(ex[1]), as_int(ex[2]), as_int(ex[3])});
+                if (u == 0) {
+                    lds_write128<80 * 16>(dst, i32x4{as_int(top[0] + a2[0] + a3[0]), as_int(top[1] + a2[1] + a3[1]),
+                                                      as_int(top[2] + a2[2] + a3[2]), as_int(top[3] + a2[3] + a3[3])});
+                }
+            }
+        };
+
+        const int hs0 = 2 * st_begin, hs1 = 2 * st_end;
+        if constexpr (MODE == kFusedQuant) quantise_tile();
+        if constexpr (MODE == kFromGlobal) {
+            if (hs0 < hs1) build_half(hs0, actA, validA);
+            wg_barrier_lds();
+            for (int hs = hs0; hs < hs1; hs += 2) {
+                build_half(hs + 1, actB, validB);     // lookups read half 0 now: fill half 1
+                wg_barrier_lds();
+                if (hs + 2 < hs1) build_half(hs + 2, actA, validA);   // lookups read half 1 now: fill half 0
+                wg_barrier_lds();
+            }
+        } else {
+            // The build waves are few and every barrier waits for them: let them issue first.
+            __builtin_amdgcn_s_setprio(3);
+            // Rows are computed one half-stage ahead: after a barrier a build wave only has to issue its eleven
+            // LDS writes, and it computes the next half-stage's rows while those writes drain.  Activations are
+            // fetched four half-stages ahead of their use.
+            struct Rows { s16x2 r[9][4], ex[4], last[4]; };
+            unsigned act2[4][2], act3[4][2];
+            bool valid2 = false, valid3 = false;
+            auto compute_rows = [&](unsigned (&act)[4][2], bool valid, Rows& rw) {
+                if (!valid) {
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
+                }
+                const short d0 = (short)(u / 3 - 1), d1 = (short)(u % 3 - 1);   // leading digits of rows 9u..9u+8,
+                const s16x2 m0 = {d0, d0}, m1 = {d1, d1};                         // and digits (d2,d3) of row 72+u
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const s16x2 a0 = unpack_pair(act[0][q >> 1], q & 1);
+                    const s16x2 a1 = unpack_pair(act[1][q >> 1], q & 1);
+                    const s16x2 a2 = unpack_pair(act[2][q >> 1], q & 1);
+                    const s16x2 a3 = unpack_pair(act[3][q >> 1], q & 1);
+                    const s16x2 b1 = a0 * m0 + a1 * m1;
+                    const s16x2 top = a0 + a1;                          // leading digits (2,2)
+                    const s16x2 lo = b1 - a2, hi = b1 + a2;
+                    rw.r[0][q] = lo - a3; rw.r[1][q] = lo; rw.r[2][q] = lo + a3;
+                    rw.r[3][q] = b1 - a3; rw.r[4][q] = b1; rw.r[5][q] = b1 + a3;
+                    rw.r[6][q] = hi - a3; rw.r[7][q] = hi; rw.r[8][q] = hi + a3;
+                    rw.ex[q] = top + a2 * m0 + a3 * m1;                 // row 72 + 3*d2 + d3 with (d2,d3) = (u/3, u%3)
+                    rw.last[q] = top + a2 + a3;                         // row 80
+                }
+                // Pin the finished rows in registers here, so that the arithmetic stays where it is written
+                // (between the LDS writes of one half-stage and the barrier) instead of sinking below the barrier.
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                    for (int i = 0; i < 9; ++i) asm volatile("" : "+v"(rw.r[i][q]));
+                    asm volatile("" : "+v"(rw.ex[q]));
+                    asm volatile("" : "+v"(rw.last[q]));
+                }
+            };
+            auto write_rows = [&](int hs, const Rows& rw) {
+                const unsigned dst = (unsigned)(2 * (hs & 1) + s2) * kSlotBytes + (unsigned)l * 16u;
+                const unsigned dst9 = dst + (unsigned)(9 * u) * kRowBytes;
+                static_for<0, 9>([&](auto ic_) {
+                    constexpr int i = decltype(ic_)::value;
+                    lds_write128<i * 16>(dst9, i32x4{as_int(rw.r[i][0]), as_int(rw.r[i][1]), as_int(rw.r[i][2]), as_int(rw.r[i][3])});
+                });
+                lds_write128<0>(dst + (unsigned)(72 + u) * kRowBytes,
+                                i32x4{as_int(rw.ex[0]), as_int(rw.ex[1]), as_int(rw.ex[2]), as_int(rw.ex[3])});
+                if (u == 0) {
+                    lds_write128<80 * 16>(dst, i32x4{as_int(rw.last[0]), as_int(rw.last[1]), as_int(rw.last[2]), as_int(rw.last[3])});
+                }
+            };
+            Rows rows;
+            // One half-stage: write the rows computed earlier (half-stage hs, if it exists), compute the rows of
+            // half-stage hs + 1 from `act_next`, refill that activation buffer, and meet the lookup waves.
+            auto step = [&](int hs, unsigned (&act_next)[4][2], bool& valid_next) {
+                if (hs < hs1) write_rows(hs, rows);
+                compute_rows(act_next, valid_next, rows);
+                fetch_act(hs + 5, act_next, valid_next);
+                wg_barrier_lds();
+            };
+            if (hs0 < hs1) {
+                fetch_act(hs0, actA, validA);
+                fetch_act(hs0 + 1, actB, validB);
+                fetch_act(hs0 + 2, act2, valid2);
+                fetch_act(hs0 + 3, act3, valid3);
+                compute_rows(actA, validA, rows);
+                fetch_act(hs0 + 4, actA, validA);
+            }
+            // half 0 of the first stage: hand it over as soon as it is written, compute the next rows afterwards
+            if (hs0 < hs1) write_rows(hs0, rows);
+            wg_barrier_lds();
+            compute_rows(actB, validB, rows);
+            fetch_act(hs0 + 5, actB, validB);
+            for (int hs = hs0; hs < hs1; hs += 4) {
+                step(hs + 1, act2, valid2);           // lookups read half 0 (hs): fill half 1
+                step(hs + 2, act3, valid3);           // lookups read half 1 (hs+1): fill half 0
+                step(hs + 3, actA, validA);           // (with an odd number of stages the last two steps only meet
+                                                      //  the lookup waves at their two matching barriers)
+                step(hs + 4, actB, validB);
+            }
+            __builtin_amdgcn_s_setprio(0);
+        }
+    } else {
+        // ================================ lookup role ================================
+        // Row group r of this wave: its packed tiles start at a wave-uniform address (scalar registers); the lane
+        // adds its row (grp) and, per stage, the tile and dword it needs.
+        const unsigned char* wbase[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int rgl = r * kLookupWaves + lw;   // r-major: round r of the epilogue covers 48 consecutive rows
+            const int rg = rgw0 + rgl;
+            const bool valid = (rgl < p.RGW) && (rg < p.RGtotal);
+            wbase[r] = p.packed + ((size_t)(valid ? rg : 0) * p.KCn) * 64;
+        }
+        // Weight dwords (4 lookups each) are fetched one whole stage ahead.  Dword q = st*J + j of each row.
+        // Out-of-range cases need no masking: a tile index past the end of K is clamped to the last tile and meets
+        // tables built from zero activations, and rows past M are clamped to row group 0 and never stored.
+        auto load_weights = [&](int st, unsigned (&wdst)[R]) {
+            const int q = st * J + j;
+            const int kc = min(q >> 2, p.KCn - 1);
+            const unsigned voff = (unsigned)(kc * 64 + grp * 16 + (q & 3) * 4);
+#pragma unroll
+            for (int r = 0; r < R; ++r) wdst[r] = *(const unsigned*)(wbase[r] + voff);
+        };
+        auto stage = [&](int st, unsigned (&w)[R], unsigned (&wnext)[R]) {
+            load_weights(st + 1, wnext);
+            lookup_half<R, 0>(w, lanebase, acc16);
+            wg_barrier_lds();
+            lookup_half<R, 1>(w, lanebase, acc16);
+            wg_barrier_lds();
+            if (NEED32 && (((st - st_begin) & 15) == 15)) {   // 16 stages x 4 lookups = block of 64 (Sec. 3.4)
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        acc32[r][2 * q] += (int)acc16[r][q].x;
+                        acc32[r][2 * q + 1] += (int)acc16[r][q].y;
+                        acc16[r][q] = s16x2{0, 0};
+                    }
+            }
+        };
+        unsigned wa[R], wb[R];
+        load_weights(st_begin, wa);
+        if constexpr (MODE == kFusedQuant) quantise_tile();
+        wg_barrier_lds();                      // half-stage 0 of the first stage is built
+        for (int st = st_begin; st < st_end; st += 2) {
+            stage(st, wa, wb);
+            if (st + 1 < st_end) {
+                stage(st + 1, wb, wa);
+            } else if (MODE != kFromGlobal) {
+                wg_barrier_lds();              // the build waves run in units of two stages
+                wg_barrier_lds();
+            }
+        }
+    }
+
+    // ---- epilogue.  Per row group: widen to INT32, add the J partial sums of each token across the 16 lanes of
+    // the group with a reduce-scatter (each step halves the tokens a lane keeps), park the sums in LDS as
+    // [token][row] and let the whole workgroup write consecutive output rows per token.
+    lds_i32* park = (lds_i32*)0u;
+    if (tid < n_tile) scale_lds[tid] = my_scale;     // visible after the first barrier below
+    const int m0 = rgw0 * 4;
+    const int rows_wg = min(p.RGW * 4, p.M - m0);
+    // RC = row-group rounds parked per pass.  All R at once when the tile has few tokens (the R independent
+    // reduction chains then overlap); two at a time when [tokens][rows] would not fit in LDS.
+    auto epilogue = [&](auto rc_tag) {
+    constexpr int RC = decltype(rc_tag)::value;
+    constexpr int kParkStride = RC * kRoundRows + 4;        // ints per parked token; +4 keeps the writes conflict-free
+#pragma unroll
+    for (int c0 = 0; c0 < R; c0 += RC) {
+        if (!builder) {
+#pragma unroll
+        for (int rr = 0; rr < RC; ++rr) {
+            const int r = c0 + rr;
+            if (r < R && Jlog == 4) {
+                // both lanes of a pair hold the same total and store it to the same place
+                park[(l >> 1) * kParkStride + rr * kRoundRows + lw * 4 + grp] =
+                    reduce16<NEED32>(acc16[r], acc32[NEED32 ? r : 0], l);
+            } else if (r < R) {
+                int v[8];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    v[2 * q] = (int)acc16[r][q].x + (NEED32 ? acc32[r][2 * q] : 0);
+                    v[2 * q + 1] = (int)acc16[r][q].y + (NEED32 ? acc32[r][2 * q + 1] : 0);
+                }
+                // Reduce-scatter over the sub-table selector j (the top Jlog bits of the lane's slice index): each
+                // step exchanges half of the remaining tokens with the lane whose index differs in one bit.
+                int tokoff = 0;
+                bool owner = true;
+                if (Jlog > 0) {
+                    const bool hi = (l & 8) != 0;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int send = hi ? v[e] : v[e + 4];
+                        const int keep = hi ? v[e + 4] : v[e];
+                        v[e] = keep + lane_xor16<8>(send);
+                    }
+                    tokoff += hi ? 4 : 0;
+                }
+                if (Jlog > 1) {
+                    const bool hi = (l & 4) != 0;
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const int send = hi ? v[e] : v[e + 2];
+                        const int keep = hi ? v[e + 2] : v[e];
+                        v[e] = keep + lane_xor16<4>(send);
+                    }
+                    tokoff += hi ? 2 : 0;
+                }
+                if (Jlog > 2) {
+                    const bool hi = (l & 2) != 0;
+                    const int send = hi ? v[0] : v[1];
+                    const int keep = hi ? v[1] : v[0];
+                    v[0] = keep + lane_xor16<2>(send);
+                    tokoff += hi ? 1 : 0;
+                }
+                if (Jlog > 3) {
+                    v[0] += lane_xor16<1>(v[0]);
+                    owner = (l & 1) == 0;
+                }
+                const int cnt = 8 >> min(Jlog, 3);
+                if (owner) {
+                    const int col = rr * kRoundRows + lw * 4 + grp;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (e < cnt) park[(8 * t + tokoff + e) * kParkStride + col] = v[e];
+                }
+            }
+        }
+        }
+        wg_barrier_lds();
+        for (int i = tid; i < RC * kRoundRows * n_tile; i += kThreads) {
+            const int col = i % (RC * kRoundRows);
+            const int nl = i / (RC * kRoundRows);
+            const int mrow = c0 * kRoundRows + col;         // row inside the workgroup tile
+            const int n = n0 + nl;
+            if (mrow < rows_wg && mrow < R * kRoundRows && n < p.N) {
+                const int val = park[nl * kParkStride + col];
+                const int m = m0 + mrow;
+                if (p.S == 1 && !p.partial) {
+                    if (p.y) p.y[(size_t)n * p.ldy + m] = (float)val * (p.w_rows ? p.w_rows[m] * scale_lds[nl] : scale_lds[nl]);
+                    if (p.acc) p.acc[(size_t)m * p.N + n] = val;
+                } else {
+                    p.ws[((size_t)(p.slot0 + ks) * p.N + n) * p.M + m] = val;
+                }
+            }
+        }
+        wg_barrier_lds();
+    }
+    };
+    if (n_tile * (R * kRoundRows + 4) * 4 <= kTableBytes) epilogue(std::integral_constant<int, R>{});
+    else epilogue(std::integral_constant<int, (R > 1 ? 2 : 1)>{});
+}
+
+}  // namespace

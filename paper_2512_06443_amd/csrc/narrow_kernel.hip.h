@@ -1,0 +1,323 @@
+// The kernel for one or two tokens (decoding).
+// Part of the single translation unit vlut.hip (included there, in this order).
+#pragma once
+
+namespace {
+
+// ---------------------------------------------------------------------------------------------
+// N <= 2 (one or two parallel tokens: decoding).  The tables of a 256-group chunk of K then take 83 KB (two tokens: an
+// entry is one dword = two INT16 sums) or 42 KB (one token: an entry is one INT16), and a workgroup can sweep all of K
+// by itself: no split-K partial sums, no second kernel, one barrier pair per chunk.  The waves build a chunk
+// together, then all 16 look it up.
+//   Tables: NTOK = 2: sub-table kg of the chunk = 81 dwords at kg*324 + idx*4; a build lane (kg, leading digit d0)
+//           makes 27 entries and stores them as single dwords.  NTOK = 1: sub-table = 81 INT16 + 1 pad = 41 dwords at
+//           kg*164 + idx*2; a build lane owns a whole sub-table.  Consecutive lanes are 27 or 41 dwords apart: odd, so
+//           every store of a wave is free of bank conflicts.
+//   Lookups: wave w reads the packed tile w of the chunk (16 groups); a lane owns an output row and 16/PARTS of the
+//           tile's groups (PARTS lanes per row), RR rows one after the other.  Address = lane constant + idx * entry
+//           size, the group's offset is an immediate: 3 VALU instructions per lookup.  With PARTS = 1 all lanes of a
+//           read look into the same sub-table, whose dwords lie in distinct banks (equal bank = equal address =
+//           broadcast).  Two tokens: INT16 sums inside a chunk (at most 16 lookups), INT32 across chunks; one token:
+//           INT32 throughout.  The 16*PARTS partial sums per row are added through LDS at the end.
+//   Tiles past the end of K are neither built nor looked up.
+// ---------------------------------------------------------------------------------------------
+constexpr int kNarrowChunk = 256;                        // k-groups per chunk = 16 packed tiles, one per wave
+constexpr int narrow_sub_bytes(int ntok) { return ntok == 2 ? 324 : 164; }
+constexpr int narrow_tab_bytes(int ntok) { return kNarrowChunk * narrow_sub_bytes(ntok); }   // 82944 / 41984
+
+struct NarrowParams {
+    const uint8_t* packed;
+    const int8_t* a_q;
+    const float* a_scale;
+    const float* w_rows;
+    float* y;
+    int32_t* acc;
+    float w_scale;
+    int M, K, N, G, KCn, RGtotal, ldy, chunks;
+    // fused quantisation (FUSED): fp32 activations [N][ldx] instead of a_q / a_scale
+    const float* x;
+    float* a_scale_out;       // optional: the token scales, written by workgroup 0
+    int64_t ldx;
+    int x_vec;
+};
+// FUSED keeps, behind the tables, two dwords per k-group (the four codes of token 0 and of token 1) and the 16 x 2
+// partial absmax values.
+constexpr int narrow_fused_lds_bytes(int ntok, int chunks) { return narrow_tab_bytes(ntok) + chunks * kNarrowChunk * 8 + 128; }
+constexpr int narrow_fused_max_chunks(int ntok) {        // 39 (K <= 39936) for two tokens, 59 for one
+    return (160 * 1024 - narrow_tab_bytes(ntok) - 128) / (kNarrowChunk * 8);
+}
+
+template <int NTOK, int PARTS, int RR, bool FUSED>
+__global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_n[];
+    if (lds_base_of(smem_n) != 0u) return;               // table addresses below are absolute LDS addresses
+    constexpr int SUB = narrow_sub_bytes(NTOK);           // bytes per sub-table
+    constexpr int TAB = narrow_tab_bytes(NTOK);
+    constexpr int RPW = 64 / PARTS;                       // rows of one pass of a wave
+    constexpr int ROWS = RPW * RR;                        // rows of the workgroup
+    constexpr int NBYTES = 16 / PARTS;                    // groups (= bytes of the packed tile row) per lane
+    typedef __attribute__((address_space(3))) short lds_i16;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m0 = blockIdx.x * ROWS;
+
+    // ---- build geometry.  Two tokens: thread tid < 768 owns (k-group tid/3, leading digit tid%3) of every chunk;
+    //      one token: thread tid < 256 owns k-group tid.
+    const bool builds = tid < (NTOK == 2 ? 3 : 1) * kNarrowChunk;
+    const int kg_b = NTOK == 2 ? tid / 3 : tid;
+    const int d0 = tid - 3 * kg_b;                        // NTOK == 2 only
+    // ---- lookup geometry
+    const int part = lane / RPW, row_l = lane % RPW;
+    const unsigned lane_tab = (unsigned)(wave * 16 + part * NBYTES) * SUB;   // first sub-table of this lane
+    const unsigned char* wrow[RR];
+    bool row_ok[RR];
+#pragma unroll
+    for (int rr = 0; rr < RR; ++rr) {
+        const int m = m0 + rr * RPW + row_l;
+        row_ok[rr] = m < p.M;
+        const int mc = row_ok[rr] ? m : 0;
+        wrow[rr] = p.packed + ((size_t)(mc >> 2) * p.KCn) * 64 + (mc & 3) * 16 + part * NBYTES;
+    }
+    int acc32[RR][2];
+#pragma unroll
+    for (int rr = 0; rr < RR; ++rr) { acc32[rr][0] = 0; acc32[rr][1] = 0; }
+
+    // activations of tokens 0,1 for the four rows of a k-group: bytes 0,1 of a_q[0][4kg + j][*] (chunk 0 of tokens)
+    auto fetch_act = [&](int c, unsigned (&a)[4]) {
+        const int kg = min(c * kNarrowChunk + kg_b, p.G - 1);          // clamped; validity applied at use
+        if constexpr (FUSED) {
+            const i32x2 d = *(const __attribute__((address_space(3))) i32x2*)(unsigned)(TAB + kg * 8);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)                                // {code of token 0, code of token 1} of row j
+                a[j] = __builtin_amdgcn_perm((unsigned)d.y, (unsigned)d.x, 0x0c0c0000u | ((4u + j) << 8) | (unsigned)j);
+        } else {
+            const unsigned short* src = (const unsigned short*)(p.a_q + (size_t)(4 * kg) * 8);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a[j] = src[4 * j];             // 8 bytes per activation row
+        }
+    };
+    typedef unsigned wvec __attribute__((ext_vector_type(4)));
+    auto fetch_w = [&](int c, wvec (&w)[RR]) {
+        const int tile = min(c * 16 + wave, p.KCn - 1);                // clamped; tiles past the end are not looked up
+#pragma unroll
+        for (int rr = 0; rr < RR; ++rr) {
+            const unsigned char* src = wrow[rr] + (size_t)tile * 64;
+            if constexpr (PARTS == 1) {
+                const i32x4 v = *(const i32x4*)src;
+                w[rr] = wvec{(unsigned)v.x, (unsigned)v.y, (unsigned)v.z, (unsigned)v.w};
+            } else if constexpr (PARTS == 2) {
+                const i32x2 v = *(const i32x2*)src;
+                w[rr] = wvec{(unsigned)v.x, (unsigned)v.y, 0u, 0u};
+            } else {
+                w[rr] = wvec{*(const unsigned*)src, 0u, 0u, 0u};
+            }
+        }
+    };
+
+    // The loop streams the packed weights from HBM and a chunk takes less than the latency of a load, so the weights
+    // are fetched WD chunks ahead (a ring of WD + 1 register sets; fewer for more rows per lane), the activations two.
+    constexpr int WD = RR == 1 ? 4 : (RR == 2 ? 2 : 1);
+    unsigned act_cur[4] = {0, 0, 0, 0}, act_nxt[4] = {0, 0, 0, 0}, act_nx2[4] = {0, 0, 0, 0};
+    wvec w_ring[WD + 1][RR];                               // w_ring[0] = the chunk being looked up
+    wvec (&w_cur)[RR] = w_ring[0];
+#pragma unroll
+    for (int d = 0; d < WD; ++d) fetch_w(d, w_ring[d]);
+    float sc[2] = {0.0f, 0.0f};                                        // token scales (FUSED)
+    if constexpr (FUSED) {
+        // Quantise the one or two rows of x over all of K: thread tid takes the float4 (= k-group) tid + 1024 i.
+        typedef __attribute__((address_space(3))) float lds_f32;
+        typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
+        lds_f32* red = (lds_f32*)(unsigned)(TAB + p.chunks * kNarrowChunk * 8);   // [wave][token]
+        lds_i32x2* aq = (lds_i32x2*)(unsigned)TAB;
+        const int nquad = p.G;
+        auto load4 = [&](int n, int qi) -> f32x4 {
+            const float* src = p.x + (size_t)n * p.ldx + 4 * (size_t)qi;
+            if (p.x_vec) return *(const f32x4*)src;
+            return f32x4{src[0], src[1], src[2], src[3]};
+        };
+        auto absmax4 = [](float m, const f32x4 v) {
+            return fmaxf(fmaxf(m, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
+        };
+        auto codes4 = [](const f32x4 v, float inv) { return (int)quant_codes4(v, inv); };
+        constexpr int NVC = 4;                                         // float4 per thread and token kept (K <= 16384)
+        f32x4 xv[NTOK][NVC];
+        float amax[NTOK];
+#pragma unroll
+        for (int n = 0; n < NTOK; ++n) {
+            amax[n] = 0.0f;
+#pragma unroll
+            for (int i = 0; i < NVC; ++i) {
+                const int qi = tid + kThreads * i;
+                xv[n][i] = (n < p.N && qi < nquad) ? load4(n, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+                amax[n] = absmax4(amax[n], xv[n][i]);
+            }
+            if (n < p.N)
+                for (int q0 = kThreads * NVC; q0 < nquad; q0 += kThreads * NVC) {   // NVC loads in flight per pass
+                    f32x4 tv[NVC];
+#pragma unroll
+                    for (int i = 0; i < NVC; ++i) {
+                        const int qi = q0 + tid + kThreads * i;
+                        tv[i] = qi < nquad ? load4(n, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+#pragma unroll
+                    for (int i = 0; i < NVC; ++i) amax[n] = absmax4(amax[n], tv[i]);
+                }
+            for (int off = 32; off > 0; off >>= 1) amax[n] = fmaxf(amax[n], __shfl_xor(amax[n], off));
+        }
+        if (lane == 0) {
+#pragma unroll
+            for (int n = 0; n < NTOK; ++n) red[wave * 2 + n] = amax[n];
+        }
+        wg_barrier_lds();
+        float inv[NTOK];
+#pragma unroll
+        for (int n = 0; n < NTOK; ++n) {
+            float v = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) v = fmaxf(v, red[w * 2 + n]);
+            inv[n] = (v > 0.0f) ? 127.0f / v : 0.0f;                   // IEEE divisions, as in quantize_kernel
+            sc[n] = v / 127.0f;
+        }
+        if (blockIdx.x == 0 && tid < p.N && p.a_scale_out) p.a_scale_out[tid] = tid == 0 ? sc[0] : sc[1];
+#pragma unroll
+        for (int i = 0; i < NVC; ++i) {
+            const int qi = tid + kThreads * i;
+            if (qi < nquad) aq[qi] = i32x2{codes4(xv[0][i], inv[0]), NTOK == 2 ? codes4(xv[NTOK - 1][i], inv[NTOK - 1]) : 0};
+        }
+        for (int q0 = kThreads * NVC; q0 < nquad; q0 += kThreads * NVC) {
+            f32x4 tv[NTOK][NVC];
+#pragma unroll
+            for (int i = 0; i < NVC; ++i) {
+                const int qi = q0 + tid + kThreads * i;
+#pragma unroll
+                for (int n = 0; n < NTOK; ++n)
+                    tv[n][i] = (n < p.N && qi < nquad) ? load4(n, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int i = 0; i < NVC; ++i) {
+                const int qi = q0 + tid + kThreads * i;
+                if (qi < nquad)
+                    aq[qi] = i32x2{codes4(tv[0][i], inv[0]), NTOK == 2 ? codes4(tv[NTOK - 1][i], inv[NTOK - 1]) : 0};
+            }
+        }
+        wg_barrier_lds();
+    }
+    if (builds) { fetch_act(0, act_cur); fetch_act(1, act_nxt); }
+    for (int c = 0; c < p.chunks; ++c) {
+        fetch_w(c + WD, w_ring[WD]);
+        if (builds) fetch_act(c + 2, act_nx2);
+        // ---------------- build the chunk's tables (topological order of Sec. 4: one add per entry); only the groups
+        //                  of real tiles: the padding groups of the last tile get all-zero tables
+        if (builds) {
+            const int kgg = c * kNarrowChunk + kg_b;
+            if (kgg < p.KCn * 16) {
+                const bool valid = kgg < p.G;
+                if constexpr (NTOK == 2) {
+                    s16x2 a[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const unsigned v = valid ? act_cur[j] : 0u;
+                        a[j] = s16x2{(short)(signed char)(v & 0xffu), (short)(signed char)((v >> 8) & 0xffu)};
+                    }
+                    const short s0 = (short)(d0 - 1);
+                    const s16x2 base = a[0] * s16x2{s0, s0};
+                    lds_i32* dst = (lds_i32*)(unsigned)(kg_b * SUB + d0 * 108);
+                    static_for<0, 3>([&](auto c1) {
+                        constexpr int d1 = decltype(c1)::value;
+                        const s16x2 b1 = d1 == 0 ? base - a[1] : (d1 == 1 ? base : base + a[1]);
+                        static_for<0, 3>([&](auto c2) {
+                            constexpr int d2 = decltype(c2)::value;
+                            const s16x2 b2 = d2 == 0 ? b1 - a[2] : (d2 == 1 ? b1 : b1 + a[2]);
+                            dst[9 * d1 + 3 * d2 + 0] = as_int(b2 - a[3]);
+                            dst[9 * d1 + 3 * d2 + 1] = as_int(b2);
+                            dst[9 * d1 + 3 * d2 + 2] = as_int(b2 + a[3]);
+                        });
+                    });
+                } else {
+                    int a[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) a[j] = valid ? (int)(signed char)(act_cur[j] & 0xffu) : 0;
+                    int e[82];
+                    static_for<0, 3>([&](auto c0) {
+                        constexpr int e0 = decltype(c0)::value;
+                        const int b0 = e0 == 0 ? -a[0] : (e0 == 1 ? 0 : a[0]);
+                        static_for<0, 3>([&](auto c1) {
+                            constexpr int d1 = decltype(c1)::value;
+                            const int b1 = d1 == 0 ? b0 - a[1] : (d1 == 1 ? b0 : b0 + a[1]);
+                            static_for<0, 3>([&](auto c2) {
+                                constexpr int d2 = decltype(c2)::value;
+                                const int b2 = d2 == 0 ? b1 - a[2] : (d2 == 1 ? b1 : b1 + a[2]);
+                                e[27 * e0 + 9 * d1 + 3 * d2 + 0] = b2 - a[3];
+                                e[27 * e0 + 9 * d1 + 3 * d2 + 1] = b2;
+                                e[27 * e0 + 9 * d1 + 3 * d2 + 2] = b2 + a[3];
+                            });
+                        });
+                    });
+                    e[81] = 0;
+                    lds_i32* dst = (lds_i32*)(unsigned)(kg_b * SUB);
+                    static_for<0, 41>([&](auto ci) {
+                        constexpr int i = decltype(ci)::value;      // entries 2i (low half) and 2i + 1 (high half)
+                        dst[i] = (int)__builtin_amdgcn_perm((unsigned)e[2 * i + 1], (unsigned)e[2 * i], 0x05040100u);
+                    });
+                }
+            }
+        }
+        wg_barrier_lds();
+        // ---------------- look the chunk up
+        if (c * 16 + wave < p.KCn) {                                   // wave-uniform
+#pragma unroll
+            for (int rr = 0; rr < RR; ++rr) {
+                if constexpr (NTOK == 2) {
+                    s16x2 acc16 = {0, 0};
+                    static_for<0, NBYTES>([&](auto bc) {
+                        constexpr int b = decltype(bc)::value;
+                        const unsigned idx = (w_cur[rr][b >> 2] >> (8 * (b & 3))) & 0xffu;
+                        const unsigned addr = lane_tab + idx * 4u;
+                        acc16 += as_s16x2(((const lds_i32*)addr)[b * (SUB / 4)]);
+                    });
+                    acc32[rr][0] += (int)acc16.x;
+                    acc32[rr][1] += (int)acc16.y;
+                } else {
+                    static_for<0, NBYTES>([&](auto bc) {
+                        constexpr int b = decltype(bc)::value;
+                        const unsigned idx = (w_cur[rr][b >> 2] >> (8 * (b & 3))) & 0xffu;
+                        const unsigned addr = lane_tab + idx * 2u;
+                        acc32[rr][0] += (int)((const lds_i16*)addr)[b * (SUB / 2)];
+                    });
+                }
+            }
+        }
+        wg_barrier_lds();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { act_cur[j] = act_nxt[j]; act_nxt[j] = act_nx2[j]; }
+#pragma unroll
+        for (int d = 0; d < WD; ++d)
+#pragma unroll
+            for (int rr = 0; rr < RR; ++rr) w_ring[d][rr] = w_ring[d + 1][rr];
+    }
+
+    // ---------------- add the 16*PARTS partial sums of every (row, token) through LDS, scale, store
+    lds_i32* red = (lds_i32*)0u;                          // [16*PARTS][ROWS][2], reuses the table space
+#pragma unroll
+    for (int rr = 0; rr < RR; ++rr) {
+        const int ri = rr * RPW + row_l;
+        const int pi = wave * PARTS + part;
+        red[(pi * ROWS + ri) * 2 + 0] = acc32[rr][0];
+        red[(pi * ROWS + ri) * 2 + 1] = acc32[rr][1];
+    }
+    wg_barrier_lds();
+    for (int i = tid; i < ROWS * 2; i += kThreads) {
+        const int ri = i >> 1, n = i & 1;
+        const int m = m0 + ri;
+        if (m < p.M && n < p.N) {
+            int v = 0;
+            for (int pi = 0; pi < 16 * PARTS; ++pi) v += red[(pi * ROWS + ri) * 2 + n];
+            const float s_n = FUSED ? (n ? sc[1] : sc[0]) : p.a_scale[n];
+            if (p.y) p.y[(size_t)n * p.ldy + m] = (float)v * ((p.w_rows ? p.w_rows[m] : p.w_scale) * s_n);
+            if (p.acc) p.acc[(size_t)m * p.N + n] = v;
+        }
+    }
+}
+
+}  // namespace
