@@ -290,8 +290,8 @@ def cpu_baseline(wl, W, w_scale, x):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (the path shards over tokens with no exchange; "
-              "see DESIGN.md). Re-run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU only (the path shards over tokens with no exchange: every GPU "
+              "would run this same kernel on its share of the tokens). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2512_06443_amd import binding as B
