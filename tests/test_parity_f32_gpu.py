@@ -227,3 +227,34 @@ def test_argument_errors(B):
         torch.cuda.synchronize()
     finally:
         B.set_plan(0, 0, 0, 0)
+
+
+@pytest.mark.parametrize("N", [1, 2, 24])
+def test_hip_graph_replays_match_eager(B, N):
+    """vlut_mpgemm_f32 captured once (one kernel for one or two tokens, quantiser + split-K lookup + sum otherwise)
+    and replayed on changing inputs, with eager launches and synchronisations in between."""
+    M, K = 300, 1024
+    W = wl.ternary(585, M, K, 0.4)
+    packed = B.pack_weights(dev(W))
+    x_dev = torch.empty((N, K), dtype=torch.float32, device="cuda")
+    y = torch.empty((N, M), dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(B.lib().vlut_workspace_bytes_f32(M, K, N), 16), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    x_dev.copy_(dev(wl.activations(586, N, K)))
+    with torch.cuda.stream(side):                           # warm-up outside the capture
+        B.mpgemm_f32(packed, 0.02, x_dev, M, y=y, workspace=ws)
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        B.mpgemm_f32(packed, 0.02, x_dev, M, y=y, workspace=ws)
+    for seed in (587, 588, 589):
+        x = wl.activations(seed, N, K)
+        x_dev.copy_(dev(x))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        y_graph = y.clone()
+        y_eager, _, _ = B.mpgemm_f32(packed, 0.02, dev(x), M)   # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(y_graph, y_eager)
+        check_y(y_graph.cpu().numpy(), O.mpgemm(W, np.float32(0.02), x)[3])
