@@ -342,6 +342,19 @@ def test_hip_graph_replays_match_eager(B):
         B.set_plan(0, 0, 0, 0)
 
 
+def test_split_k_repeated_and_many_tiles(B):
+    """K split over several workgroups, the same shape twice in a row and other tile counts in between (nothing may
+    carry over from one call to the next), up to 16 splits, and a shape with 4200 output tiles."""
+    shapes = [((300, 4352, 40), (16, 4, 0, 3)), ((300, 4352, 40), (16, 4, 0, 3)), ((1000, 2560, 70), (16, 2, 0, 5)),
+              ((257, 1028, 130), (4, 2, 0, 2)), ((300, 4352, 40), (16, 6, 0, 6)), ((70, 8192, 9), (16, 1, 0, 16)),
+              ((100, 2048, 1030), (16, 1, 0, 2))]
+    for (M, K, N), plan in shapes:
+        W, s, x = wl.small_case(600 + M + N, M, K, N)
+        run_case(B, W, s, x, plan=plan, tag="split-K")
+    W, s, x = wl.small_case(601, 3360, 512, 480)            # 70 row tiles x 60 token tiles
+    run_case(B, W, s, x, plan=(16, 1, 0, 2), tag="split-K, 4200 output tiles")
+
+
 def test_run_to_run_determinism(B):
     w = wl.WORKLOADS["bitnet2b_ffn_up"]
     W, s, x = wl.small_case(90, 1000, 2560, 128)
