@@ -33,7 +33,10 @@ ALU_PEAK_TADDS = CUS * 64 * 2 * CLOCK_GHZ / 1e3          # 78.64 T INT16 adds/s
 LDS_PEAK_GBS = CUS * 256 * CLOCK_GHZ                      # 157286 GB/s
 
 # HBM bytes per launch of the lookup kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), see profiles/
-MEASURED_TRAFFIC_BYTES = {"bitnet2b_ffn_up": 10.95e6}   # profiles/lookup_kernel_bitnet2b_ffn_up_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = {
+    "bitnet2b_ffn_up/up/128": 10.95e6,     # profiles/lookup_kernel_bitnet2b_ffn_up_hbm_traffic.md
+    "layer2b4_nsweep/gate/1": 4.62e6,      # profiles/narrow_kernel_layer2b4_gate_n1_stats_and_hbm_traffic.md
+}
 
 
 def parse_args():
@@ -42,6 +45,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="bitnet2b_ffn_up")
+    ap.add_argument("--linear", default="", help="linear of the workload (default: its first)")
+    ap.add_argument("--tokens", type=int, default=0, help="N of the workload's sweep (default: its first)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rotate", action="store_true", help="keep one weight buffer (cache-warm weights)")
     ap.add_argument("--all", action="store_true", help="also time every benchmark shape (table on stderr)")
@@ -305,7 +310,9 @@ def main():
         B.set_plan(j, r, 0, s)
 
     w = wl.WORKLOADS[args.workload]
-    lin, N, seed = w.linears[0], w.N[0], w.seeds[0]
+    lin = ([l_ for l_ in w.linears if l_.name == args.linear] or [w.linears[0]])[0]
+    N = args.tokens if args.tokens in w.N else w.N[0]
+    seed = w.seeds[w.N.index(N)] if len(w.seeds) == len(w.N) else w.seeds[0]
     W, w_scale, x = wl.make_case(w, lin, N, seed)
     M, K = W.shape
     rotate = 0 if args.no_rotate else 600 << 20
@@ -336,6 +343,13 @@ def main():
         g5 = {"what": "vlut_mpgemm_g5 on the same weights packed 5 per byte (1.60 bits per weight, 243-row tables)",
               "ms": ms_g5, "plan": {"R": case.plan5[0], "split_k": case.plan5[1], "workgroups": case.plan5[2]},
               "packed_weight_bytes": case.pool5[0].numel(), "time_over_2bit": ms_g5 / ms_gemm}
+    if case.plan32[0] == 0:
+        kernel_name = "narrow_kernel (one or two tokens: quantisation, table build, lookups and scale in one launch)"
+    elif case.plan32[4] and case.plan32[2] == 1:
+        kernel_name = ("lookup_kernel, quantising variant (absmax + INT8 codes, LDS table build, lookup-accumulate, "
+                       "epilogue in one launch)")
+    else:
+        kernel_name = "lookup_kernel (LDS table build + lookup-accumulate + epilogue)"
     ops = 2.0 * M * K * N
     adds = M * (K // 4) * N                      # one INT16 add (= 2 table bytes) per (row, group, token)
     gops = ops / (ms_step * 1e-3) / 1e9
@@ -360,18 +374,22 @@ def main():
                             "ms": ms_mfma, "lut_over_mfma_time": ms_gemm / ms_mfma},
         "g5_packing": g5,
         "roofline": {
-            "kernel": ("lookup_kernel, quantising variant (absmax + INT8 codes, LDS table build, lookup-accumulate, "
-                       "epilogue in one launch)") if (case.plan32[4] and case.plan32[2] == 1) else
-                      "lookup_kernel (LDS table build + lookup-accumulate + epilogue)",
+            "kernel": kernel_name,
             "bound": "alu", "achieved": achieved_tadds, "peak": ALU_PEAK_TADDS, "unit": "TOP/s",
             "frac": achieved_tadds / ALU_PEAK_TADDS,
             "kernel_ms": ms_kernel,
             "lds_lookup_GBs": 2.0 * adds / (ms_kernel * 1e-3) / 1e9, "lds_peak_GBs": LDS_PEAK_GBS,
             "lds_frac": 2.0 * adds / (ms_kernel * 1e-3) / 1e9 / LDS_PEAK_GBS,
             "hbm_frac": wl.algorithmic_bytes(M, K, N) / (ms_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+            "traffic": MEASURED_TRAFFIC_BYTES.get(f"{w.name}/{lin.name}/{N}"),
         },
     }
+    if N <= 16:
+        # few tokens: the packed weights dominate the traffic and HBM is the roof (8 TB/s)
+        alg = wl.algorithmic_bytes(M, K, N)
+        r = out["roofline"]
+        r.update({"bound": "hbm", "achieved": alg / (ms_kernel * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                  "frac": alg / (ms_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS, "alu_frac": achieved_tadds / ALU_PEAK_TADDS})
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, W, w_scale, x)
 
