@@ -19,6 +19,7 @@
 
 #include <cstdint>
 #include <cstring>
+#include <atomic>
 #include <mutex>
 #include <type_traits>
 
@@ -39,6 +40,17 @@ namespace {
 // ---------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------
+// Raises a kernel's dynamic LDS limit once per device (the limit is a property of the kernel on one device).
+bool allow_dynamic_lds(const void* kfn, int bytes, std::atomic<unsigned>& done_mask) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    const unsigned bit = (dev >= 0 && dev < 32) ? (1u << dev) : 0u;
+    if (bit && (done_mask.load(std::memory_order_relaxed) & bit)) return true;
+    if (hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return false;
+    done_mask.fetch_or(bit, std::memory_order_relaxed);
+    return true;
+}
+
 struct Plan {
     int Jlog, R, S;
 };
@@ -193,12 +205,8 @@ int launch_lookup_t(const LookupParams& p, int grid, hipStream_t stream) {
     constexpr int max_lds = MODE == kFusedQuant ? kFusedMaxLds : kLdsBytes;
     const int lds = MODE == kFusedQuant ? kFusedAqBase + p.stages_per_split * kFusedStageBytes : kLdsBytes;
     if (lds > max_lds) return VLUT_ERR_UNSUPPORTED;
-    static bool attr_done = false;   // benign race: the call is idempotent
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds) != hipSuccess)
-            return VLUT_ERR_DEVICE;
-        attr_done = true;
-    }
+    static std::atomic<unsigned> attr_done{0};   // one bit per device: the attribute belongs to the device's copy
+    if (!allow_dynamic_lds((const void*)kfn, max_lds, attr_done)) return VLUT_ERR_DEVICE;
     hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), lds, stream, p);
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
@@ -300,12 +308,8 @@ int launch_narrow_t(const NarrowParams& p, int grid, hipStream_t stream) {
     constexpr int max_lds = FUSED ? 160 * 1024 : narrow_tab_bytes(NTOK);
     const int lds = FUSED ? narrow_fused_lds_bytes(NTOK, p.chunks) : narrow_tab_bytes(NTOK);
     if (lds > max_lds) return VLUT_ERR_UNSUPPORTED;
-    static bool attr_done = false;   // benign race: the call is idempotent
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds) != hipSuccess)
-            return VLUT_ERR_DEVICE;
-        attr_done = true;
-    }
+    static std::atomic<unsigned> attr_done{0};   // one bit per device: the attribute belongs to the device's copy
+    if (!allow_dynamic_lds((const void*)kfn, max_lds, attr_done)) return VLUT_ERR_DEVICE;
     hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), lds, stream, p);
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
@@ -431,12 +435,8 @@ Plan5 choose_plan5(int64_t M, int64_t K, int64_t N) {
 template <int R, bool NEED32>
 int launch_lookup5_t(const Lookup5Params& p, int grid, hipStream_t stream) {
     auto kfn = lookup5_kernel<R, NEED32>;
-    static bool attr_done = false;   // benign race: the call is idempotent
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, kLds5Bytes) != hipSuccess)
-            return VLUT_ERR_DEVICE;
-        attr_done = true;
-    }
+    static std::atomic<unsigned> attr_done{0};   // one bit per device: the attribute belongs to the device's copy
+    if (!allow_dynamic_lds((const void*)kfn, kLds5Bytes, attr_done)) return VLUT_ERR_DEVICE;
     hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), kLds5Bytes, stream, p);
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
