@@ -7,8 +7,9 @@ namespace {
 // ---------------------------------------------------------------------------------------------
 // N <= 2 (one or two parallel tokens: decoding).  The tables of a 256-group chunk of K then take 83 KB (two tokens: an
 // entry is one dword = two INT16 sums) or 42 KB (one token: an entry is one INT16), and a workgroup can sweep all of K
-// by itself: no split-K partial sums, no second kernel, one barrier pair per chunk.  The waves build a chunk
-// together, then all 16 look it up.
+// by itself: no split-K partial sums, no second kernel.  Two tokens: the waves build a chunk, barrier, all 16 look it
+// up, barrier.  One token: the tables fit twice, so the build waves fill chunk c + 1 and then join the others in
+// looking chunk c up, one barrier per chunk.
 //   Tables: NTOK = 2: sub-table kg of the chunk = 81 dwords at kg*324 + idx*4; a build lane (kg, leading digit d0)
 //           makes 27 entries and stores them as single dwords.  NTOK = 1: sub-table = 81 INT16 + 1 pad = 41 dwords at
 //           kg*164 + idx*2; a build lane owns a whole sub-table.  Consecutive lanes are 27 or 41 dwords apart: odd, so
@@ -23,7 +24,8 @@ namespace {
 // ---------------------------------------------------------------------------------------------
 constexpr int kNarrowChunk = 256;                        // k-groups per chunk = 16 packed tiles, one per wave
 constexpr int narrow_sub_bytes(int ntok) { return ntok == 2 ? 324 : 164; }
-constexpr int narrow_tab_bytes(int ntok) { return kNarrowChunk * narrow_sub_bytes(ntok); }   // 82944 / 41984
+constexpr int narrow_buffers(int ntok) { return ntok == 2 ? 1 : 2; }
+constexpr int narrow_tab_bytes(int ntok) { return narrow_buffers(ntok) * kNarrowChunk * narrow_sub_bytes(ntok); }   // 82944 / 83968
 
 struct NarrowParams {
     const uint8_t* packed;
@@ -43,7 +45,7 @@ struct NarrowParams {
 // FUSED keeps, behind the tables, two dwords per k-group (the four codes of token 0 and of token 1) and the 16 x 2
 // partial absmax values.
 constexpr int narrow_fused_lds_bytes(int ntok, int chunks) { return narrow_tab_bytes(ntok) + chunks * kNarrowChunk * 8 + 128; }
-constexpr int narrow_fused_max_chunks(int ntok) {        // 39 (K <= 39936) for two tokens, 59 for one
+constexpr int narrow_fused_max_chunks(int ntok) {        // 39 (K <= 39936) for two tokens, 38 for one
     return (160 * 1024 - narrow_tab_bytes(ntok) - 128) / (kNarrowChunk * 8);
 }
 
@@ -52,6 +54,8 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_n[];
     if (lds_base_of(smem_n) != 0u) return;               // table addresses below are absolute LDS addresses
     constexpr int SUB = narrow_sub_bytes(NTOK);           // bytes per sub-table
+    constexpr int BUFS = narrow_buffers(NTOK);            // table buffers: one token's tables fit twice
+    constexpr int BUF = kNarrowChunk * SUB;               // bytes of one buffer
     constexpr int TAB = narrow_tab_bytes(NTOK);
     constexpr int RPW = 64 / PARTS;                       // rows of one pass of a wave
     constexpr int ROWS = RPW * RR;                        // rows of the workgroup
@@ -203,98 +207,133 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
         }
         wg_barrier_lds();
     }
-    if (builds) { fetch_act(0, act_cur); fetch_act(1, act_nxt); }
-    for (int c = 0; c < p.chunks; ++c) {
-        fetch_w(c + WD, w_ring[WD]);
-        if (builds) fetch_act(c + 2, act_nx2);
-        // ---------------- build the chunk's tables (topological order of Sec. 4: one add per entry); only the groups
-        //                  of real tiles: the padding groups of the last tile get all-zero tables
-        if (builds) {
-            const int kgg = c * kNarrowChunk + kg_b;
-            if (kgg < p.KCn * 16) {
-                const bool valid = kgg < p.G;
-                if constexpr (NTOK == 2) {
-                    s16x2 a[4];
+    // ---------------- build the tables of chunk cb (topological order of Sec. 4: one add per entry); only the groups
+    //                  of real tiles: the padding groups of the last tile get all-zero tables
+    auto do_build = [&](int cb, const unsigned (&act)[4]) {
+        const int kgg = cb * kNarrowChunk + kg_b;
+        if (kgg >= p.KCn * 16) return;
+        const bool valid = kgg < p.G;
+        const unsigned buf = (unsigned)((cb & (BUFS - 1)) * BUF);
+        if constexpr (NTOK == 2) {
+            s16x2 a[4];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const unsigned v = valid ? act_cur[j] : 0u;
-                        a[j] = s16x2{(short)(signed char)(v & 0xffu), (short)(signed char)((v >> 8) & 0xffu)};
-                    }
-                    const short s0 = (short)(d0 - 1);
-                    const s16x2 base = a[0] * s16x2{s0, s0};
-                    lds_i32* dst = (lds_i32*)(unsigned)(kg_b * SUB + d0 * 108);
-                    static_for<0, 3>([&](auto c1) {
-                        constexpr int d1 = decltype(c1)::value;
-                        const s16x2 b1 = d1 == 0 ? base - a[1] : (d1 == 1 ? base : base + a[1]);
-                        static_for<0, 3>([&](auto c2) {
-                            constexpr int d2 = decltype(c2)::value;
-                            const s16x2 b2 = d2 == 0 ? b1 - a[2] : (d2 == 1 ? b1 : b1 + a[2]);
-                            dst[9 * d1 + 3 * d2 + 0] = as_int(b2 - a[3]);
-                            dst[9 * d1 + 3 * d2 + 1] = as_int(b2);
-                            dst[9 * d1 + 3 * d2 + 2] = as_int(b2 + a[3]);
-                        });
-                    });
-                } else {
-                    int a[4];
+            for (int j = 0; j < 4; ++j) {
+                const unsigned v = valid ? act[j] : 0u;
+                a[j] = s16x2{(short)(signed char)(v & 0xffu), (short)(signed char)((v >> 8) & 0xffu)};
+            }
+            const short s0 = (short)(d0 - 1);
+            const s16x2 base = a[0] * s16x2{s0, s0};
+            lds_i32* dst = (lds_i32*)(buf + (unsigned)(kg_b * SUB + d0 * 108));
+            static_for<0, 3>([&](auto c1) {
+                constexpr int d1 = decltype(c1)::value;
+                const s16x2 b1 = d1 == 0 ? base - a[1] : (d1 == 1 ? base : base + a[1]);
+                static_for<0, 3>([&](auto c2) {
+                    constexpr int d2 = decltype(c2)::value;
+                    const s16x2 b2 = d2 == 0 ? b1 - a[2] : (d2 == 1 ? b1 : b1 + a[2]);
+                    dst[9 * d1 + 3 * d2 + 0] = as_int(b2 - a[3]);
+                    dst[9 * d1 + 3 * d2 + 1] = as_int(b2);
+                    dst[9 * d1 + 3 * d2 + 2] = as_int(b2 + a[3]);
+                });
+            });
+        } else {
+            int a[4];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) a[j] = valid ? (int)(signed char)(act_cur[j] & 0xffu) : 0;
-                    int e[82];
-                    static_for<0, 3>([&](auto c0) {
-                        constexpr int e0 = decltype(c0)::value;
-                        const int b0 = e0 == 0 ? -a[0] : (e0 == 1 ? 0 : a[0]);
-                        static_for<0, 3>([&](auto c1) {
-                            constexpr int d1 = decltype(c1)::value;
-                            const int b1 = d1 == 0 ? b0 - a[1] : (d1 == 1 ? b0 : b0 + a[1]);
-                            static_for<0, 3>([&](auto c2) {
-                                constexpr int d2 = decltype(c2)::value;
-                                const int b2 = d2 == 0 ? b1 - a[2] : (d2 == 1 ? b1 : b1 + a[2]);
-                                e[27 * e0 + 9 * d1 + 3 * d2 + 0] = b2 - a[3];
-                                e[27 * e0 + 9 * d1 + 3 * d2 + 1] = b2;
-                                e[27 * e0 + 9 * d1 + 3 * d2 + 2] = b2 + a[3];
-                            });
-                        });
+            for (int j = 0; j < 4; ++j) a[j] = valid ? (int)(signed char)(act[j] & 0xffu) : 0;
+            int e[82];
+            static_for<0, 3>([&](auto c0) {
+                constexpr int e0 = decltype(c0)::value;
+                const int b0 = e0 == 0 ? -a[0] : (e0 == 1 ? 0 : a[0]);
+                static_for<0, 3>([&](auto c1) {
+                    constexpr int d1 = decltype(c1)::value;
+                    const int b1 = d1 == 0 ? b0 - a[1] : (d1 == 1 ? b0 : b0 + a[1]);
+                    static_for<0, 3>([&](auto c2) {
+                        constexpr int d2 = decltype(c2)::value;
+                        const int b2 = d2 == 0 ? b1 - a[2] : (d2 == 1 ? b1 : b1 + a[2]);
+                        e[27 * e0 + 9 * d1 + 3 * d2 + 0] = b2 - a[3];
+                        e[27 * e0 + 9 * d1 + 3 * d2 + 1] = b2;
+                        e[27 * e0 + 9 * d1 + 3 * d2 + 2] = b2 + a[3];
                     });
-                    e[81] = 0;
-                    lds_i32* dst = (lds_i32*)(unsigned)(kg_b * SUB);
-                    static_for<0, 41>([&](auto ci) {
-                        constexpr int i = decltype(ci)::value;      // entries 2i (low half) and 2i + 1 (high half)
-                        dst[i] = (int)__builtin_amdgcn_perm((unsigned)e[2 * i + 1], (unsigned)e[2 * i], 0x05040100u);
-                    });
-                }
+                });
+            });
+            e[81] = 0;
+            lds_i32* dst = (lds_i32*)(buf + (unsigned)(kg_b * SUB));
+            static_for<0, 41>([&](auto ci) {
+                constexpr int i = decltype(ci)::value;      // entries 2i (low half) and 2i + 1 (high half)
+                dst[i] = (int)__builtin_amdgcn_perm((unsigned)e[2 * i + 1], (unsigned)e[2 * i], 0x05040100u);
+            });
+        }
+    };
+    // ---------------- look chunk c up (the weights in w_cur)
+    auto do_lookup = [&](int c) {
+        if (c * 16 + wave >= p.KCn) return;                            // wave-uniform
+        const unsigned tab = lane_tab + (unsigned)((c & (BUFS - 1)) * BUF);
+#pragma unroll
+        for (int rr = 0; rr < RR; ++rr) {
+            if constexpr (NTOK == 2) {
+                s16x2 acc16 = {0, 0};
+                static_for<0, NBYTES>([&](auto bc) {
+                    constexpr int b = decltype(bc)::value;
+                    const unsigned idx = (w_cur[rr][b >> 2] >> (8 * (b & 3))) & 0xffu;
+                    const unsigned addr = tab + idx * 4u;
+                    acc16 += as_s16x2(((const lds_i32*)addr)[b * (SUB / 4)]);
+                });
+                acc32[rr][0] += (int)acc16.x;
+                acc32[rr][1] += (int)acc16.y;
+            } else {
+                static_for<0, NBYTES>([&](auto bc) {
+                    constexpr int b = decltype(bc)::value;
+                    const unsigned idx = (w_cur[rr][b >> 2] >> (8 * (b & 3))) & 0xffu;
+                    const unsigned addr = tab + idx * 2u;
+                    acc32[rr][0] += (int)((const lds_i16*)addr)[b * (SUB / 2)];
+                });
             }
         }
-        wg_barrier_lds();
-        // ---------------- look the chunk up
-        if (c * 16 + wave < p.KCn) {                                   // wave-uniform
-#pragma unroll
-            for (int rr = 0; rr < RR; ++rr) {
-                if constexpr (NTOK == 2) {
-                    s16x2 acc16 = {0, 0};
-                    static_for<0, NBYTES>([&](auto bc) {
-                        constexpr int b = decltype(bc)::value;
-                        const unsigned idx = (w_cur[rr][b >> 2] >> (8 * (b & 3))) & 0xffu;
-                        const unsigned addr = lane_tab + idx * 4u;
-                        acc16 += as_s16x2(((const lds_i32*)addr)[b * (SUB / 4)]);
-                    });
-                    acc32[rr][0] += (int)acc16.x;
-                    acc32[rr][1] += (int)acc16.y;
-                } else {
-                    static_for<0, NBYTES>([&](auto bc) {
-                        constexpr int b = decltype(bc)::value;
-                        const unsigned idx = (w_cur[rr][b >> 2] >> (8 * (b & 3))) & 0xffu;
-                        const unsigned addr = lane_tab + idx * 2u;
-                        acc32[rr][0] += (int)((const lds_i16*)addr)[b * (SUB / 2)];
-                    });
-                }
-            }
-        }
-        wg_barrier_lds();
+    };
+    auto rotate = [&]() {
 #pragma unroll
         for (int j = 0; j < 4; ++j) { act_cur[j] = act_nxt[j]; act_nxt[j] = act_nx2[j]; }
+    };
+    auto rotate_w = [&]() {
 #pragma unroll
         for (int d = 0; d < WD; ++d)
 #pragma unroll
             for (int rr = 0; rr < RR; ++rr) w_ring[d][rr] = w_ring[d + 1][rr];
+    };
+
+    if (builds) { fetch_act(0, act_cur); fetch_act(1, act_nxt); }
+    if constexpr (BUFS == 2) {
+        // One token: two table buffers, so the build waves fill chunk c + 1 while every wave (they too, afterwards)
+        // looks chunk c up: one barrier per chunk.  act_cur always belongs to the next chunk to build.
+        if (builds) {
+            fetch_act(2, act_nx2);
+            do_build(0, act_cur);
+            rotate();
+        }
+        wg_barrier_lds();
+        for (int c = 0; c < p.chunks; ++c) {
+            fetch_w(c + WD, w_ring[WD]);
+            if (builds) {
+                fetch_act(c + 3, act_nx2);
+                if (c + 1 < p.chunks) do_build(c + 1, act_cur);
+                rotate();
+            }
+            do_lookup(c);
+            wg_barrier_lds();                  // chunk c + 1 is built, and nobody reads chunk c any more
+            rotate_w();
+        }
+    } else {
+        for (int c = 0; c < p.chunks; ++c) {
+            fetch_w(c + WD, w_ring[WD]);
+            if (builds) {
+                fetch_act(c + 2, act_nx2);
+                do_build(c, act_cur);
+            }
+            wg_barrier_lds();
+            do_lookup(c);
+            wg_barrier_lds();
+            rotate();
+            rotate_w();
+        }
     }
 
     // ---------------- add the 16*PARTS partial sums of every (row, token) through LDS, scale, store
