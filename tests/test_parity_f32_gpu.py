@@ -258,3 +258,25 @@ def test_hip_graph_replays_match_eager(B, N):
         torch.cuda.synchronize()
         assert torch.equal(y_graph, y_eager)
         check_y(y_graph.cpu().numpy(), O.mpgemm(W, np.float32(0.02), x)[3])
+
+
+@pytest.mark.parametrize("M,K,N", [(1, 4, 1), (1, 4, 2), (1, 4, 3), (3, 8, 1), (5, 1024, 2), (1, 2560, 1), (2, 6912, 2),
+                                    (7, 260, 1), (1, 4, 9), (4097, 4, 1), (33, 12, 2), (640, 2560, 3), (640, 2560, 8),
+                                    (640, 2560, 9)])
+def test_degenerate_shapes_through_every_entry_point(B, M, K, N):
+    """Single rows, the smallest K, token counts next to the kernels' switch-over points: the one-call form, the
+    two-call form and the mixed packing all give the oracle's numbers, and the first two the same bits."""
+    print(f"degenerate case M={M} K={K} N={N}", flush=True)
+    W, s, x = wl.small_case(900 + M + K + N, M, K, N)
+    _, s_ref, acc_ref, y_ref = O.mpgemm(W, s, x)
+    packed = B.pack_weights(dev(W))
+    y1, acc1, sc = B.mpgemm_f32(packed, float(s), dev(x), M, want_acc=True, want_scales=True)
+    a_q, a_s = B.quantize_act(dev(x))
+    y2, acc2 = B.mpgemm(packed, float(s), a_q, a_s, M, want_acc=True)
+    ym, accm = B.mpgemm_mixed(B.pack_weights_mixed(dev(W)), float(s), a_q, a_s, M, want_acc=True)
+    torch.cuda.synchronize()
+    for acc in (acc1, acc2, accm):
+        assert np.array_equal(acc.cpu().numpy(), acc_ref)
+    assert np.array_equal(sc.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
+    assert torch.equal(y1, y2) and torch.equal(ym, y2)
+    check_y(y1.cpu().numpy(), y_ref)
