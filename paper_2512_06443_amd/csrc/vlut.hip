@@ -57,7 +57,7 @@ struct Plan {
 
 thread_local Plan t_forced = {-1, 0, 0};
 
-const int kSupportedR[] = {1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 14};
+const int kSupportedR[] = {1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14};
 
 bool r_supported(int R) {
     for (int v : kSupportedR)
@@ -233,6 +233,7 @@ int launch_lookup_r(int R, int mode, const LookupParams& p, int grid, hipStream_
             case 10: return launch_lookup_t<10, false, kFusedQuant>(p, grid, stream);
             case 11: return launch_lookup_t<11, false, kFusedQuant>(p, grid, stream);
             case 12: return launch_lookup_t<12, false, kFusedQuant>(p, grid, stream);
+            case 13: return launch_lookup_t<13, false, kFusedQuant>(p, grid, stream);
             case 14: return launch_lookup_t<14, false, kFusedQuant>(p, grid, stream);
             default: break;
             }
@@ -257,6 +258,7 @@ int launch_lookup_r(int R, int mode, const LookupParams& p, int grid, hipStream_
             case 10: return launch_lookup_t<10, false, kFast>(p, grid, stream);
             case 11: return launch_lookup_t<11, false, kFast>(p, grid, stream);
             case 12: return launch_lookup_t<12, false, kFast>(p, grid, stream);
+            case 13: return launch_lookup_t<13, false, kFast>(p, grid, stream);
             case 14: return launch_lookup_t<14, false, kFast>(p, grid, stream);
             default: break;
             }

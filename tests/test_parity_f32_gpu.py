@@ -72,7 +72,7 @@ def test_tiny_and_ragged(B):
     run_f32(B, W, s, x, tag="k4")
 
 
-@pytest.mark.parametrize("R", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 14])
+@pytest.mark.parametrize("R", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14])
 def test_every_rows_per_wave(B, R):
     M = 48 * R * 2 - 37
     W, s, x = wl.small_case(420 + R, M, 512, 33)
