@@ -161,7 +161,7 @@ class Case:
         self.gemm(i, stream)
 
 
-def run_timed(torch, fn, count, warmup):
+def run_timed(torch, fn, count, warmup, use_graph=True):
     """Times `count` calls of fn(i, stream) that are enqueued back to back.
 
     The calls are captured once into a HIP graph (so the host's launch cost is not part of the GPU timeline) and the
@@ -175,13 +175,16 @@ def run_timed(torch, fn, count, warmup):
     side.synchronize()
     graph = None
     try:
+        if not use_graph:
+            raise RuntimeError("stream launches requested")
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g, stream=side):
             for i in range(count):
                 fn(i, torch.cuda.current_stream().cuda_stream)
         graph = g
     except Exception as e:  # noqa: BLE001 - fall back to plain stream launches
-        print(f"bench.py: graph capture unavailable ({type(e).__name__}: {e}); timing stream launches", file=sys.stderr)
+        if use_graph:
+            print(f"bench.py: graph capture unavailable ({type(e).__name__}: {e}); timing stream launches", file=sys.stderr)
     reps = int(os.environ.get("VLUT_BENCH_REPS", "1"))
     best_wall, best_gpu = float("inf"), float("inf")
     with torch.cuda.stream(side):
@@ -335,6 +338,8 @@ def main():
         print("bench.py: output of the timed region differs from the reference launch", file=sys.stderr)
         sys.exit(4)
 
+    # the same step enqueued call by call from this process (host launch cost included), beside the graph figure
+    ms_step_stream, _, _ = run_timed(torch, case.step_fused, args.steps, args.warmup, use_graph=False)
     ms_mfma = time_mfma(torch, case, args.steps, args.warmup)
     g5 = None
     if K % 20 == 0:
@@ -370,6 +375,8 @@ def main():
                    "weight_pool_buffers": len(case.pool), "launch": mode},
         "weight_stream_GBs": (M * K / 4) / (ms_step * 1e-3) / 1e9,
         "algorithmic_GBs": wl.algorithmic_bytes(M, K, N) / (ms_step * 1e-3) / 1e9,
+        "per_call_stream_launches": {"what": "the same steps enqueued one call at a time from Python (ctypes), no graph",
+                                     "ms_per_step": ms_step_stream},
         "two_call_form": {"what": "vlut_quantize_act + vlut_mpgemm on the same inputs", "ms_per_step": ms_two_call,
                           "mpgemm_kernel_ms": ms_gemm},
         "mfma_comparison": {"what": "vlut_mpgemm_mfma on the same inputs (unpack to INT8 + v_mfma_i32_16x16x64_i8), "
