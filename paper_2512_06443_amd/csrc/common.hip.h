@@ -27,6 +27,7 @@ constexpr int kFusedAqBase = kFusedRedBase + 16 * 8 * 4;
 constexpr int kFusedBlockPitch = 288;
 constexpr int kFusedStageBytes = 8 * kFusedBlockPitch;           // 2304
 constexpr int kFusedMaxLds = 160 * 1024;
+constexpr int kFusedMaxR = 14;   // the quantising variant holds more live state per wave
 constexpr int kFusedMaxStages = (kFusedMaxLds - kFusedAqBase) / kFusedStageBytes;   // 34 stages = 8704 values of K
 constexpr int kWaves = 16;                   // waves per workgroup
 constexpr int kThreads = kWaves * 64;

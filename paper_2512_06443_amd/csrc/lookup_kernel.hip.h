@@ -81,15 +81,15 @@ __device__ __forceinline__ void lookup_batches(const unsigned (&w)[R], unsigned 
 
 template <int R, int HALF>
 __device__ __forceinline__ void lookup_half(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4]) {
-    constexpr int NB = 4;
+    constexpr int NB = R > 14 ? 2 : 4;   // table reads in flight; the widest instances have no registers for four
     constexpr int total = 2 * R;
     i32x4 first[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) first[i] = i32x4{0, 0, 0, 0};
     first[0] = lookup_read<R, HALF, 0>(w, lanebase);
     if constexpr (total > 1) first[1] = lookup_read<R, HALF, 1>(w, lanebase);
-    if constexpr (total > 2) first[2] = lookup_read<R, HALF, (total > 2 ? 2 : 0)>(w, lanebase);
-    if constexpr (total > 3) first[3] = lookup_read<R, HALF, (total > 3 ? 3 : 0)>(w, lanebase);
+    if constexpr (total > 2 && NB > 2) first[2] = lookup_read<R, HALF, (total > 2 ? 2 : 0)>(w, lanebase);
+    if constexpr (total > 3 && NB > 3) first[3] = lookup_read<R, HALF, (total > 3 ? 3 : 0)>(w, lanebase);
     __builtin_amdgcn_sched_barrier(0);
     lookup_batches<R, HALF, NB, 0>(w, lanebase, acc16, first);
 }

@@ -57,7 +57,7 @@ struct Plan {
 
 thread_local Plan t_forced = {-1, 0, 0};
 
-const int kSupportedR[] = {1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14};
+const int kSupportedR[] = {1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16};
 
 bool r_supported(int R) {
     for (int v : kSupportedR)
@@ -138,7 +138,7 @@ Plan search_plan(int64_t M, int64_t K, int64_t N) {
 
 // Fused quantisation needs 8-token tiles (16 sub-tables per row) and the codes of the workgroup's K range in LDS.
 bool fused_plan_valid(const Plan& pl, int64_t M, int64_t K, int64_t N) {
-    if (pl.Jlog != 4 || !plan_valid(pl, M, K, N)) return false;
+    if (pl.Jlog != 4 || pl.R > kFusedMaxR || !plan_valid(pl, M, K, N)) return false;
     return derive(pl, M, K, N).stages_per_split <= kFusedMaxStages;
 }
 
@@ -260,6 +260,8 @@ int launch_lookup_r(int R, int mode, const LookupParams& p, int grid, hipStream_
             case 12: return launch_lookup_t<12, false, kFast>(p, grid, stream);
             case 13: return launch_lookup_t<13, false, kFast>(p, grid, stream);
             case 14: return launch_lookup_t<14, false, kFast>(p, grid, stream);
+            case 15: return launch_lookup_t<15, false, kFast>(p, grid, stream);
+            case 16: return launch_lookup_t<16, false, kFast>(p, grid, stream);
             default: break;
             }
         }

@@ -133,7 +133,7 @@ def test_argument_errors_come_before_any_device_call(L):
     assert L.vlut_mpgemm_rows(d, None, d, d, None, 8, 8, 4, d, 8, None, None, 0, None) == -1      # row scales are required
     assert L.vlut_mpgemm_rows(None, d, d, d, None, 8, 8, 4, d, 8, None, None, 0, None) == -1
     assert L.vlut_mpgemm_rows(d, d, d, d, None, 8, 8, 4, d, 7, None, None, 0, None) == -2
-    assert L.vlut_set_plan(3, 0, 0, 0) == -6 and L.vlut_set_plan(0, 15, 0, 0) == -6
+    assert L.vlut_set_plan(3, 0, 0, 0) == -6 and L.vlut_set_plan(0, 17, 0, 0) == -6
     assert L.vlut_set_plan(0, 0, 7, 0) == -6 and L.vlut_set_plan(0, 0, 0, 99) == -6
     assert L.vlut_set_plan(0, 0, 0, 0) == 0
     assert L.vlut_query_plan(8, 8, 8, None) == -1

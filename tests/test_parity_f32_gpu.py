@@ -72,11 +72,12 @@ def test_tiny_and_ragged(B):
     run_f32(B, W, s, x, tag="k4")
 
 
-@pytest.mark.parametrize("R", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14])
+@pytest.mark.parametrize("R", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16])
 def test_every_rows_per_wave(B, R):
     M = 48 * R * 2 - 37
     W, s, x = wl.small_case(420 + R, M, 512, 33)
-    qp = run_f32(B, W, s, x, plan=(16, R, 0, 1), fused=True, tag=f"R{R}")
+    # the quantising variant of the kernel exists up to R = 14; wider forced plans take the two-launch form
+    qp = run_f32(B, W, s, x, plan=(16, R, 0, 1), fused=R <= 14, tag=f"R{R}")
     assert qp[:3] == (16, R, 1)
 
 

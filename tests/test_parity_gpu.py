@@ -147,7 +147,7 @@ def test_every_interleave_factor(B, J):
     run_case(B, W, s, x, plan=(J, 1, 0, 1), tag=f"J{J}-n7")
 
 
-@pytest.mark.parametrize("R", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14])
+@pytest.mark.parametrize("R", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16])
 def test_every_rows_per_wave(B, R):
     M = 48 * R * 2 - 37                                     # two row tiles, the second one ragged
     W, s, x = wl.small_case(20 + R, M, 512, 33)

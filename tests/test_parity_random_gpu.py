@@ -16,7 +16,7 @@ from paper_2512_06443_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 RTOL = 1e-5
-ROWS_PER_WAVE = [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14]
+ROWS_PER_WAVE = [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16]
 
 
 @pytest.fixture(scope="module")
