@@ -1,4 +1,4 @@
-// The kernel for one or two tokens (decoding).
+// The kernel for a few tokens (decoding), two tokens per workgroup.
 // Part of the single translation unit vlut.hip (included there, in this order).
 #pragma once
 
@@ -21,6 +21,9 @@ namespace {
 //           broadcast).  Two tokens: INT16 sums inside a chunk (at most 16 lookups), INT32 across chunks; one token:
 //           INT32 throughout.  The 16*PARTS partial sums per row are added through LDS at the end.
 //   Tiles past the end of K are neither built nor looked up.
+//   More than two tokens: the grid holds one copy of the row tiles per token pair (workgroup = row tile + gx8 * pair,
+//   gx8 = the row tiles rounded up to a multiple of 8, so that the workgroups that stream the same weights sit on the
+//   same XCD and share its L2); every pair is an independent two-token problem.
 // ---------------------------------------------------------------------------------------------
 constexpr int kNarrowChunk = 256;                        // k-groups per chunk = 16 packed tiles, one per wave
 constexpr int narrow_sub_bytes(int ntok) { return ntok == 2 ? 324 : 164; }
@@ -36,6 +39,7 @@ struct NarrowParams {
     int32_t* acc;
     float w_scale;
     int M, K, N, G, KCn, RGtotal, ldy, chunks;
+    int gridx, gx8;           // row tiles, and the stride between the token pairs' copies of them in blockIdx.x
     // fused quantisation (FUSED): fp32 activations [N][ldx] instead of a_q / a_scale
     const float* x;
     float* a_scale_out;       // optional: the token scales, written by workgroup 0
@@ -53,6 +57,7 @@ template <int NTOK, int PARTS, int RR, bool FUSED>
 __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_n[];
     if (lds_base_of(smem_n) != 0u) return;               // table addresses below are absolute LDS addresses
+    static_assert(PARTS == 1 || PARTS == 2, "a row's 16 groups of a tile belong to one lane or to two");
     constexpr int SUB = narrow_sub_bytes(NTOK);           // bytes per sub-table
     constexpr int BUFS = narrow_buffers(NTOK);            // table buffers: one token's tables fit twice
     constexpr int BUF = kNarrowChunk * SUB;               // bytes of one buffer
@@ -64,7 +69,11 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int m0 = blockIdx.x * ROWS;
+    const int pair = (int)blockIdx.x / p.gx8, bx = (int)blockIdx.x - pair * p.gx8;
+    if (bx >= p.gridx) return;                            // padding of the row tiles to a multiple of 8 (uniform)
+    const int t0 = 2 * pair;                              // first token of this workgroup
+    const int Nl = min(2, p.N - t0);                      // its tokens: 1 or 2
+    const int m0 = bx * ROWS;
 
     // ---- build geometry.  Two tokens: thread tid < 768 owns (k-group tid/3, leading digit tid%3) of every chunk;
     //      one token: thread tid < 256 owns k-group tid.
@@ -87,7 +96,7 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
 #pragma unroll
     for (int rr = 0; rr < RR; ++rr) { acc32[rr][0] = 0; acc32[rr][1] = 0; }
 
-    // activations of tokens 0,1 for the four rows of a k-group: bytes 0,1 of a_q[0][4kg + j][*] (chunk 0 of tokens)
+    // activations of the workgroup's two tokens for the four rows of a k-group: two bytes of a_q[t0/8][4kg + j][*]
     auto fetch_act = [&](int c, unsigned (&a)[4]) {
         const int kg = min(c * kNarrowChunk + kg_b, p.G - 1);          // clamped; validity applied at use
         if constexpr (FUSED) {
@@ -96,7 +105,7 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
             for (int j = 0; j < 4; ++j)                                // {code of token 0, code of token 1} of row j
                 a[j] = __builtin_amdgcn_perm((unsigned)d.y, (unsigned)d.x, 0x0c0c0000u | ((4u + j) << 8) | (unsigned)j);
         } else {
-            const unsigned short* src = (const unsigned short*)(p.a_q + (size_t)(4 * kg) * 8);
+            const unsigned short* src = (const unsigned short*)(p.a_q + (size_t)(t0 >> 3) * p.K * 8 + (size_t)(4 * kg) * 8 + (t0 & 7));
 #pragma unroll
             for (int j = 0; j < 4; ++j) a[j] = src[4 * j];             // 8 bytes per activation row
         }
@@ -110,11 +119,9 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
             if constexpr (PARTS == 1) {
                 const i32x4 v = *(const i32x4*)src;
                 w[rr] = wvec{(unsigned)v.x, (unsigned)v.y, (unsigned)v.z, (unsigned)v.w};
-            } else if constexpr (PARTS == 2) {
+            } else {
                 const i32x2 v = *(const i32x2*)src;
                 w[rr] = wvec{(unsigned)v.x, (unsigned)v.y, 0u, 0u};
-            } else {
-                w[rr] = wvec{*(const unsigned*)src, 0u, 0u, 0u};
             }
         }
     };
@@ -136,7 +143,7 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
         lds_i32x2* aq = (lds_i32x2*)(unsigned)TAB;
         const int nquad = p.G;
         auto load4 = [&](int n, int qi) -> f32x4 {
-            const float* src = p.x + (size_t)n * p.ldx + 4 * (size_t)qi;
+            const float* src = p.x + (size_t)(t0 + n) * p.ldx + 4 * (size_t)qi;
             if (p.x_vec) return *(const f32x4*)src;
             return f32x4{src[0], src[1], src[2], src[3]};
         };
@@ -153,10 +160,10 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
 #pragma unroll
             for (int i = 0; i < NVC; ++i) {
                 const int qi = tid + kThreads * i;
-                xv[n][i] = (n < p.N && qi < nquad) ? load4(n, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+                xv[n][i] = (n < Nl && qi < nquad) ? load4(n, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
                 amax[n] = absmax4(amax[n], xv[n][i]);
             }
-            if (n < p.N)
+            if (n < Nl)
                 for (int q0 = kThreads * NVC; q0 < nquad; q0 += kThreads * NVC) {   // NVC loads in flight per pass
                     f32x4 tv[NVC];
 #pragma unroll
@@ -183,7 +190,7 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
             inv[n] = (v > 0.0f) ? 127.0f / v : 0.0f;                   // IEEE divisions, as in quantize_kernel
             sc[n] = v / 127.0f;
         }
-        if (blockIdx.x == 0 && tid < p.N && p.a_scale_out) p.a_scale_out[tid] = tid == 0 ? sc[0] : sc[1];
+        if (bx == 0 && tid < Nl && p.a_scale_out) p.a_scale_out[t0 + tid] = tid == 0 ? sc[0] : sc[1];
 #pragma unroll
         for (int i = 0; i < NVC; ++i) {
             const int qi = tid + kThreads * i;
@@ -196,7 +203,7 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
                 const int qi = q0 + tid + kThreads * i;
 #pragma unroll
                 for (int n = 0; n < NTOK; ++n)
-                    tv[n][i] = (n < p.N && qi < nquad) ? load4(n, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+                    tv[n][i] = (n < Nl && qi < nquad) ? load4(n, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
             }
 #pragma unroll
             for (int i = 0; i < NVC; ++i) {
@@ -349,12 +356,12 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
     for (int i = tid; i < ROWS * 2; i += kThreads) {
         const int ri = i >> 1, n = i & 1;
         const int m = m0 + ri;
-        if (m < p.M && n < p.N) {
+        if (m < p.M && n < Nl) {
             int v = 0;
             for (int pi = 0; pi < 16 * PARTS; ++pi) v += red[(pi * ROWS + ri) * 2 + n];
-            const float s_n = FUSED ? (n ? sc[1] : sc[0]) : p.a_scale[n];
-            if (p.y) p.y[(size_t)n * p.ldy + m] = (float)v * ((p.w_rows ? p.w_rows[m] : p.w_scale) * s_n);
-            if (p.acc) p.acc[(size_t)m * p.N + n] = v;
+            const float s_n = FUSED ? (n ? sc[1] : sc[0]) : p.a_scale[t0 + n];
+            if (p.y) p.y[(size_t)(t0 + n) * p.ldy + m] = (float)v * ((p.w_rows ? p.w_rows[m] : p.w_scale) * s_n);
+            if (p.acc) p.acc[(size_t)m * p.N + t0 + n] = v;
         }
     }
 }

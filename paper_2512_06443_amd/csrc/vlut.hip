@@ -284,26 +284,43 @@ int check_mpgemm_args(const uint8_t* packed, const int8_t* a_q, const float* a_s
     return VLUT_OK;
 }
 
-// ---- N <= 2 kernel: rows per workgroup (16..256) so that the grid is about one workgroup per CU
+// ---- few-token kernel: one copy of the row tiles per token pair.  Measured (K = 2560..6912, 40..250 workgroups):
+//      the time of a launch depends on the rows per workgroup, hardly on the number of workgroups while they all
+//      fit the device at once: 32 rows 7.8 us, 64 rows 8.5-9.8 us, 128 rows 10.3-11.8 us, 256 rows 13.4-15.6 us at
+//      K = 2560 (16 rows, four lanes per row: 8.6-9.0 us, never the best), against 12-16 us for quantiser + general
+//      kernel + split-K sum at 3..16 tokens.  So: the fewest rows (from 32) whose grid is one round of workgroups.
+#ifndef VLUT_NARROW_MAX_N
+#define VLUT_NARROW_MAX_N 32
+#endif
+constexpr int kNarrowMaxN = VLUT_NARROW_MAX_N;
 struct NarrowPlan {
-    int parts, rr, rows, grid, chunks;
+    int parts, rr, rows, gridx, chunks, pairs, gx8, grid;
 };
 
-bool narrow_applies(int64_t N, const void* lut) {
-    return N <= 2 && lut == nullptr && t_forced.Jlog < 0 && t_forced.R == 0 && t_forced.S == 0;
-}
-
-NarrowPlan narrow_plan(int64_t M, int64_t K) {
-    const int64_t want = (M + 255) / 256;
+NarrowPlan narrow_plan(int64_t M, int64_t K, int64_t N) {
     NarrowPlan np;
-    if (want <= 16) np = {4, 1, 16, 0, 0};
-    else if (want <= 32) np = {2, 1, 32, 0, 0};
-    else if (want <= 64) np = {1, 1, 64, 0, 0};
-    else if (want <= 128) np = {1, 2, 128, 0, 0};
-    else np = {1, 4, 256, 0, 0};
-    np.grid = (int)((M + np.rows - 1) / np.rows);
+    np.pairs = (int)((N + 1) / 2);
+    for (int rows = 32; rows <= 256; rows *= 2) {
+        np.rows = rows;
+        np.gridx = (int)((M + rows - 1) / rows);
+        np.gx8 = np.pairs > 1 ? (np.gridx + 7) / 8 * 8 : np.gridx;
+        const int64_t grid = (int64_t)np.gx8 * (np.pairs - 1) + np.gridx;
+        np.grid = (int)(grid < INT32_MAX ? grid : INT32_MAX);
+        if (grid <= 256) break;
+    }
+    np.parts = np.rows == 32 ? 2 : 1;
+    np.rr = np.rows <= 64 ? 1 : np.rows / 64;
     np.chunks = (int)((K / 4 + kNarrowChunk - 1) / kNarrowChunk);
     return np;
+}
+
+// One or two tokens always take this kernel; more tokens while its workgroups fit the device at once with few
+// enough rows each to beat the three launches of the general path (see the figures above).
+bool narrow_applies(int64_t M, int64_t K, int64_t N, const void* lut) {
+    if (N > kNarrowMaxN || lut != nullptr || t_forced.Jlog >= 0 || t_forced.R != 0 || t_forced.S != 0) return false;
+    if (N <= 2) return true;
+    const NarrowPlan np = narrow_plan(M, K, N);
+    return np.grid <= 256 && (np.rows <= 64 || (np.rows == 128 && K <= 4096));
 }
 
 template <int NTOK, int PARTS, int RR, bool FUSED>
@@ -320,7 +337,6 @@ int launch_narrow_t(const NarrowParams& p, int grid, hipStream_t stream) {
 
 template <int NTOK, bool FUSED>
 int launch_narrow_n(const NarrowPlan& np, const NarrowParams& p, hipStream_t stream) {
-    if (np.parts == 4) return launch_narrow_t<NTOK, 4, 1, FUSED>(p, np.grid, stream);
     if (np.parts == 2) return launch_narrow_t<NTOK, 2, 1, FUSED>(p, np.grid, stream);
     if (np.rr == 1) return launch_narrow_t<NTOK, 1, 1, FUSED>(p, np.grid, stream);
     if (np.rr == 2) return launch_narrow_t<NTOK, 1, 2, FUSED>(p, np.grid, stream);
@@ -329,7 +345,11 @@ int launch_narrow_n(const NarrowPlan& np, const NarrowParams& p, hipStream_t str
 
 template <bool FUSED>
 int launch_narrow(const NarrowPlan& np, const NarrowParams& p, hipStream_t stream) {
-    return p.N == 1 ? launch_narrow_n<1, FUSED>(np, p, stream) : launch_narrow_n<2, FUSED>(np, p, stream);
+    NarrowParams q = p;
+    q.gridx = np.gridx;
+    q.gx8 = np.gx8;
+    q.chunks = np.chunks;
+    return q.N == 1 ? launch_narrow_n<1, FUSED>(np, q, stream) : launch_narrow_n<2, FUSED>(np, q, stream);
 }
 
 std::mutex g_pack_mutex;
@@ -348,7 +368,7 @@ F32Layout f32_layout(int64_t M, int64_t K, int64_t N) {
     F32Layout L;
     std::memset(&L, 0, sizeof(L));
     const size_t scale_bytes = round256((size_t)N * sizeof(float));
-    if (narrow_applies(N, nullptr) && narrow_plan(M, K).chunks <= narrow_fused_max_chunks((int)N)) {
+    if (narrow_applies(M, K, N, nullptr) && narrow_plan(M, K, N).chunks <= narrow_fused_max_chunks(N == 1 ? 1 : 2)) {
         L.kind = kF32Narrow;
         return L;
     }
@@ -369,7 +389,7 @@ F32Layout f32_layout(int64_t M, int64_t K, int64_t N) {
     L.kind = kF32TwoLaunches;                    // quantise into the workspace, then the ordinary path
     L.off_aq = scale_bytes;
     L.off_ws = L.off_aq + round256((size_t)((N + 7) / 8) * (size_t)K * 8);
-    const bool narrow = narrow_applies(N, nullptr);
+    const bool narrow = narrow_applies(M, K, N, nullptr);
     const Plan pl = narrow ? Plan{4, 1, 1} : choose_plan(M, K, N);
     L.total = L.off_ws + (pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0);
     return L;
@@ -507,7 +527,7 @@ size_t vlut_lut_bytes(int64_t K, int64_t N) {
 
 size_t vlut_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     if (!shape_ok(M, K, N)) return 0;
-    if (narrow_applies(N, nullptr)) return 0;
+    if (narrow_applies(M, K, N, nullptr)) return 0;
     Plan pl = choose_plan(M, K, N);
     return pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
 }
@@ -533,9 +553,9 @@ int vlut_set_plan(int J, int R, int waves, int split_k) {
 int vlut_query_plan(int64_t M, int64_t K, int64_t N, int* out4) {
     if (!out4) return VLUT_ERR_NULL;
     if (!shape_ok(M, K, N)) return VLUT_ERR_SHAPE;
-    if (narrow_applies(N, nullptr)) {          // the N <= 2 kernel: J reported as 0, R = rows per workgroup
-        const NarrowPlan np = narrow_plan(M, K);
-        out4[0] = 0; out4[1] = np.rows; out4[2] = 1; out4[3] = np.grid;
+    if (narrow_applies(M, K, N, nullptr)) {    // the few-token kernel: J reported as 0, R = rows per workgroup
+        const NarrowPlan np = narrow_plan(M, K, N);
+        out4[0] = 0; out4[1] = np.rows; out4[2] = 1; out4[3] = np.gridx * np.pairs;
         return VLUT_OK;
     }
     Plan pl = choose_plan(M, K, N);
@@ -657,8 +677,8 @@ static int mpgemm_impl(const uint8_t* packed, float w_scale, const float* w_rows
     int rc = check_mpgemm_args(packed, a_q, a_scale, M, K, N, y, ldy, acc_or_null);
     if (rc != VLUT_OK) return rc;
     if (((uintptr_t)a_q) % 16 != 0) return VLUT_ERR_UNSUPPORTED;      // the [N/8][K][8] blocks are read 16 bytes at a time
-    if (narrow_applies(N, lut_or_null)) {      // one or two tokens: the workgroups sweep all of K, no workspace
-        const NarrowPlan np = narrow_plan(M, K);
+    if (narrow_applies(M, K, N, lut_or_null)) {   // a few tokens: the workgroups sweep all of K, no workspace
+        const NarrowPlan np = narrow_plan(M, K, N);
         NarrowParams q;
         std::memset(&q, 0, sizeof(q));
         q.packed = packed; q.a_q = a_q; q.a_scale = a_scale; q.w_rows = w_rows; q.y = y; q.acc = acc_or_null;
@@ -753,7 +773,7 @@ int vlut_mpgemm_f32(const uint8_t* packed, float w_scale, const float* w_scale_r
     char* ws = (char*)workspace;
 
     if (L.kind == kF32Narrow) {
-        const NarrowPlan np = narrow_plan(M, K);
+        const NarrowPlan np = narrow_plan(M, K, N);
         NarrowParams q;
         std::memset(&q, 0, sizeof(q));
         q.packed = packed; q.w_rows = w_rows; q.y = y; q.acc = acc_or_null; q.w_scale = w_one;

@@ -157,14 +157,17 @@ def test_plans_cover_all_benchmark_shapes(L):
     shapes = [(256, 256, 8), (6912, 2560, 128), (8640, 3200, 256), (3200, 8640, 256), (4096, 4096, 512),
               (14336, 4096, 512), (4096, 14336, 512)]
     shapes += [(m, k, n) for (m, k) in [(2560, 2560), (640, 2560), (6912, 2560), (2560, 6912)]
-               for n in (1, 16, 64, 256, 1024)]
+               for n in (1, 2, 3, 4, 7, 8, 16, 24, 32, 33, 64, 256, 1024)]
     for (M, K, N) in shapes:
         assert L.vlut_query_plan(M, K, N, out) == 0
         J, R, S, tiles = list(out)
-        if N <= 2:                                                     # the one-or-two-token kernel: R = rows per workgroup
-            assert J == 0 and R in (16, 32, 64, 128, 256) and S == 1 and tiles * R >= M
+        if J == 0:                                     # the few-token kernel: R = rows per workgroup, a grid per token pair
+            pairs = (N + 1) // 2
+            assert N <= 32 and R in (32, 64, 128, 256) and S == 1 and tiles % pairs == 0 and (tiles // pairs) * R >= M
+            assert N <= 2 or (tiles <= 256 and (R <= 64 or (R == 128 and K <= 4096)))   # one round, few rows each
             assert L.vlut_workspace_bytes(M, K, N) == 0
             continue
+        assert N > 2
         assert J in (1, 2, 4, 8, 16) and 1 <= R <= 16 and 1 <= S <= 16 and tiles >= 1
         n_tile = 128 // J
         tiles_n = -(-N // n_tile)
@@ -215,14 +218,15 @@ def test_g5_host_logic(L):
 def test_f32_entry_host_logic(L):
     """vlut_mpgemm_f32: which kernels it picks, what workspace that needs, and argument errors before any device call."""
     out = (ci * 5)()
-    # one or two tokens: the kernel that sweeps all of K, quantising inside; no workspace
-    for (M, K, N) in [(6912, 2560, 1), (2560, 6912, 2), (640, 2560, 1)]:
+    # a few tokens: the kernel that sweeps all of K, quantising inside, a copy of the row tiles per token pair; no
+    # workspace
+    for (M, K, N) in [(6912, 2560, 1), (2560, 6912, 2), (640, 2560, 1), (6912, 2560, 3), (6912, 2560, 8), (640, 2560, 32)]:
         assert L.vlut_query_plan_f32(M, K, N, out) == 0
         assert out[0] == 0 and out[2] == 1 and out[4] == 1
         assert L.vlut_workspace_bytes_f32(M, K, N) == 0
     # more tokens: quantised once, by a kernel of its own ahead of the lookups; the workspace then holds the scales,
     # the INT8 activations and the split-K partial sums of the ordinary path
-    for (M, K, N) in [(6912, 2560, 128), (14336, 4096, 512), (4096, 14336, 512), (3200, 8640, 256), (6912, 2560, 3)]:
+    for (M, K, N) in [(6912, 2560, 128), (14336, 4096, 512), (4096, 14336, 512), (3200, 8640, 256), (6912, 2560, 12), (640, 2560, 33)]:
         assert L.vlut_query_plan_f32(M, K, N, out) == 0
         assert out[4] == 0
         r256 = lambda v: (v + 255) // 256 * 256

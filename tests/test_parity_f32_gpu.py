@@ -97,7 +97,7 @@ def test_split_k_ranges_past_the_register_cache(B):
 
 
 def test_shapes_the_fused_kernels_do_not_cover_take_two_launches(B):
-    W, s, x = wl.small_case(450, 100, 9216, 12)             # 36 stages in one range do not fit next to the tables
+    W, s, x = wl.small_case(450, 100, 9216, 40)             # 36 stages in one range do not fit next to the tables
     run_f32(B, W, s, x, plan=(16, 2, 0, 1), fused=False, tag="K9216 S1")
     run_f32(B, W, s, x, plan=(4, 2, 0, 1), fused=False, tag="J=4 forced")
     run_f32(B, W, s, x, plan=(16, 2, 0, 2), fused=True, tag="K9216 S2")
@@ -156,6 +156,33 @@ def test_one_or_two_tokens_long_rows(B):
     assert qp[:3] == (16, 1, 5)
 
 
+@pytest.mark.parametrize("N", [3, 4, 5, 6, 7, 8, 11, 16, 23, 32])
+def test_few_tokens_one_launch_per_token_pair(B, N):
+    # 3..32 tokens: the few-token kernel with a copy of its row tiles per token pair, while that grid is one round of
+    # workgroups with few rows each; M picks the rows per workgroup, the odd N leave the last pair with one token
+    for M, K in ((100, 260), (3000, 1028), (9000, 516), (130, 6912)):
+        if N > 8 and M > 1000:
+            continue
+        W, s, x = wl.small_case(600 + 10 * N + M % 7, M, K, N)
+        narrow = not (M == 9000 and N >= 7)                 # 71 tiles of 128 rows x 4 pairs: more than one round
+        qp = run_f32(B, W, s, x, fused=narrow, tag=f"few tokens M{M} K{K} N{N}")
+        assert (qp[0] == 0) == narrow and (not narrow or qp[3] % ((N + 1) // 2) == 0)
+    M = 40000                                               # too many workgroups for one round: the general path
+    W, s, x = wl.small_case(690 + N, M, 64, N)
+    qp = run_f32(B, W, s, x, fused=False, tag=f"few tokens M{M} N{N}")
+    assert qp[0] != 0
+
+
+def test_few_tokens_long_rows_and_unaligned_rows(B):
+    W, s, x = wl.small_case(695, 40, 40000, 5)              # codes do not fit next to the tables: quantiser + kernel
+    qp = run_f32(B, W, s, x, fused=False, tag="K40000 at five tokens")
+    assert qp[0] == 0
+    W, s, x = wl.small_case(696, 300, 1028, 7)
+    odd = np.full((7, 1031), 1e9, np.float32)
+    odd[:, 3:1031] = x
+    run_f32(B, W, s, x, x_dev=dev(odd)[:, 3:1031], fused=True, tag="unaligned rows, seven tokens")
+
+
 def test_stacked_matrices_with_row_scales(B):
     K = 516
     rows, scales = (130, 70, 71), (0.0159, 0.5, 3.25)
@@ -211,7 +238,7 @@ def test_argument_errors(B):
     assert L.vlut_mpgemm_f32(*args(ldx=60)) == B.VLUT_ERR_SHAPE
     assert L.vlut_mpgemm_f32(*args(ldy=63)) == B.VLUT_ERR_SHAPE
     assert L.vlut_mpgemm_f32(*args(K=62)) == B.VLUT_ERR_SHAPE
-    assert L.vlut_mpgemm_f32(*args(N=4)) == B.VLUT_ERR_NULL    # more than two tokens: the INT8 codes need a workspace
+    assert L.vlut_mpgemm_f32(*args(N=33)) == B.VLUT_ERR_NULL   # more than 32 tokens: the INT8 codes need a workspace
     torch.cuda.synchronize()
     # split-K needs the workspace
     B.set_plan(16, 1, 0, 2)
@@ -230,9 +257,9 @@ def test_argument_errors(B):
         B.set_plan(0, 0, 0, 0)
 
 
-@pytest.mark.parametrize("N", [1, 2, 24])
+@pytest.mark.parametrize("N", [1, 2, 5, 40])
 def test_hip_graph_replays_match_eager(B, N):
-    """vlut_mpgemm_f32 captured once (one kernel for one or two tokens, quantiser + split-K lookup + sum otherwise)
+    """vlut_mpgemm_f32 captured once (one kernel for a few tokens, quantiser + split-K lookup + sum otherwise)
     and replayed on changing inputs, with eager launches and synchronisations in between."""
     M, K = 300, 1024
     W = wl.ternary(585, M, K, 0.4)

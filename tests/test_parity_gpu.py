@@ -234,7 +234,7 @@ def test_special_weights(B):
 
 
 def test_gemv_and_other_n(B):
-    for N in (1, 2, 15, 16, 17, 64):
+    for N in (1, 2, 3, 4, 5, 6, 7, 8, 9, 15, 16, 17, 31, 32, 33, 64):
         W, s, x = wl.small_case(50 + N, 640, 2560, N)
         run_case(B, W, s, x, tag=f"N{N}")
 
