@@ -352,7 +352,7 @@ def main():
               "ms": ms_g5, "plan": {"R": case.plan5[0], "split_k": case.plan5[1], "workgroups": case.plan5[2]},
               "packed_weight_bytes": case.pool5[0].numel(), "time_over_2bit": ms_g5 / ms_gemm}
     if case.plan32[0] == 0:
-        kernel_name = "narrow_kernel (one or two tokens: quantisation, table build, lookups and scale in one launch)"
+        kernel_name = "narrow_kernel (few tokens: quantisation, table build, lookups and scale in one launch)"
     elif case.plan32[4] and case.plan32[2] == 1:
         kernel_name = ("lookup_kernel, quantising variant (absmax + INT8 codes, LDS table build, lookup-accumulate, "
                        "epilogue in one launch)")

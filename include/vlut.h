@@ -160,8 +160,9 @@ int vlut_mpgemm_token_outer(const uint8_t* packed, float w_scale, const float* a
  *   acc_or_null   dev or NULL, int32 [M][N] raw accumulators (token-contiguous)
  *   workspace     dev, workspace_bytes >= vlut_workspace_bytes(M, K, N); may be
  *                 NULL when that size is 0
- * For one or two tokens (N <= 2, streamed tables, no plan override) a kernel specialised for that case runs
- * instead; the results are the same numbers.
+ * For a few tokens (streamed tables, no plan override: always for N <= 2, up to N = 32 while one workgroup per
+ * row tile and token pair fits the device at once) a kernel specialised for that case runs instead and needs no
+ * workspace; the results are the same numbers.
  */
 int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale,
                 const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y, int64_t ldy,
@@ -183,9 +184,9 @@ int vlut_mpgemm_rows(const uint8_t* packed, const float* w_scale_rows, const int
 /*
  * Quantisation and mpGeMM in one call, from fp32 activations: the steps of vlut_quantize_act (Sec. 3.4 first
  * paragraph: per-token absmax INT8) and of vlut_mpgemm / vlut_mpgemm_rows (Alg. 1, Eq. 2) with the same readings and
- * the same numbers.  For one or two tokens (decoding) it is one launch: the workgroups quantise the rows themselves
- * (absmax over the whole row, codes kept in LDS), so that neither the INT8 activations nor a second kernel are
- * needed.  For more tokens the quantiser runs as a kernel of its own into the workspace, ahead of the lookup kernel
+ * the same numbers.  For a few tokens (decoding; the cases vlut_query_plan reports with J = 0, with K <= 38912 for one token and 39936 for more) it is one
+ * launch: a workgroup quantises the rows of its one or two tokens itself (absmax over the whole row, codes kept in
+ * LDS), so that neither the INT8 activations nor a second kernel are needed.  For more tokens the quantiser runs as a kernel of its own into the workspace, ahead of the lookup kernel
  * (measured to be the faster arrangement); a lookup kernel that quantises the 8 tokens of its tile itself exists as
  * well and is taken when vlut_set_plan forces a plan with J = 16 whose K range per workgroup is at most 8704.
  *   x             dev, fp32 [N][ldx], ldx >= K (16-byte aligned rows are read as float4)
@@ -281,8 +282,10 @@ int vlut_set_plan(int J, int R, int waves, int split_k);
 /*
  * Reports the launch plan vlut_mpgemm would use for this shape (after any vlut_set_plan override of the
  * calling thread): out4 (host, 4 ints) = { J, R, split_k, number of workgroup tiles }.
- * With N <= 2 and no override, vlut_mpgemm uses a kernel of its own (table entries of one dword, every workgroup
- * sweeps all of K, no workspace); it is reported as { 0, rows per workgroup, 1, number of workgroups }.
+ * With few tokens and no override (N <= 2 always; 3 <= N <= 32 when ceil(N/2) copies of the row tiles of 32, 64 or
+ * - for K <= 4096 - 128 rows are at most 256 workgroups), vlut_mpgemm uses a kernel of its own (two tokens per
+ * workgroup, table entries of one dword, every workgroup sweeps all of K, no workspace); it is reported as
+ * { 0, rows per workgroup, 1, number of workgroups }.
  */
 int vlut_query_plan(int64_t M, int64_t K, int64_t N, int* out4);
 

@@ -5,7 +5,7 @@
 namespace {
 
 // ---------------------------------------------------------------------------------------------
-// N <= 2 (one or two parallel tokens: decoding).  The tables of a 256-group chunk of K then take 83 KB (two tokens: an
+// One or two parallel tokens per workgroup (decoding).  The tables of a 256-group chunk of K then take 83 KB (two tokens: an
 // entry is one dword = two INT16 sums) or 42 KB (one token: an entry is one INT16), and a workgroup can sweep all of K
 // by itself: no split-K partial sums, no second kernel.  Two tokens: the waves build a chunk, barrier, all 16 look it
 // up, barrier.  One token: the tables fit twice, so the build waves fill chunk c + 1 and then join the others in
