@@ -289,10 +289,7 @@ int check_mpgemm_args(const uint8_t* packed, const int8_t* a_q, const float* a_s
 //      fit the device at once: 32 rows 7.8 us, 64 rows 8.5-9.8 us, 128 rows 10.3-11.8 us, 256 rows 13.4-15.6 us at
 //      K = 2560 (16 rows, four lanes per row: 8.6-9.0 us, never the best), against 12-16 us for quantiser + general
 //      kernel + split-K sum at 3..16 tokens.  So: the fewest rows (from 32) whose grid is one round of workgroups.
-#ifndef VLUT_NARROW_MAX_N
-#define VLUT_NARROW_MAX_N 32
-#endif
-constexpr int kNarrowMaxN = VLUT_NARROW_MAX_N;
+constexpr int kNarrowMaxN = 32;
 struct NarrowPlan {
     int parts, rr, rows, gridx, chunks, pairs, gx8, grid;
 };

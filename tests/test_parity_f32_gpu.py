@@ -191,7 +191,8 @@ def test_stacked_matrices_with_row_scales(B):
     M = W.shape[0]
     w_rows = np.concatenate([np.full(m, sc, np.float32) for m, sc in zip(rows, scales)])
     packed = B.pack_weights(dev(W))
-    for plan, N in (((0, 0, 0, 0), 33), ((16, 2, 0, 3), 33), ((0, 0, 0, 0), 2), ((0, 0, 0, 0), 1)):
+    for plan, N in (((0, 0, 0, 0), 33), ((16, 2, 0, 3), 33), ((0, 0, 0, 0), 2), ((0, 0, 0, 0), 1), ((0, 0, 0, 0), 5),
+                    ((0, 0, 0, 0), 16)):
         x = wl.activations(494 + N, N, K)
         print(f"f32 case stacked plan={plan} N={N}", flush=True)
         B.set_plan(*plan)

@@ -200,8 +200,9 @@ def test_stacked_matrices_with_row_scales(B):
     W = np.concatenate(Ws, axis=0)
     M = W.shape[0]
     w_rows = np.concatenate([np.full(m, sc, np.float32) for m, sc in zip(rows, scales)])
-    xs = {33: x, 2: wl.activations(62, 2, K)}
-    for plan, N in (((0, 0, 0, 0), 33), ((16, 2, 0, 3), 33), ((4, 3, 0, 1), 33), ((0, 0, 0, 0), 2)):
+    xs = {33: x, 2: wl.activations(62, 2, K), 7: wl.activations(63, 7, K), 20: wl.activations(64, 20, K)}
+    for plan, N in (((0, 0, 0, 0), 33), ((16, 2, 0, 3), 33), ((4, 3, 0, 1), 33), ((0, 0, 0, 0), 2), ((0, 0, 0, 0), 7),
+                    ((0, 0, 0, 0), 20)):
         x = xs[N]
         print(f"case stacked plan={plan} N={N}", flush=True)
         B.set_plan(*plan)
