@@ -6,14 +6,15 @@ namespace {
 
 // ---------------------------------------------------------------------------------------------
 // One or two parallel tokens per workgroup (decoding).  The tables of a 256-group chunk of K then take 83 KB (two tokens: an
-// entry is one dword = two INT16 sums) or 42 KB (one token: an entry is one INT16), and a workgroup can sweep all of K
+// entry is one dword = two INT16 sums) or 43 KB (one token: an entry is one INT16), and a workgroup can sweep all of K
 // by itself: no split-K partial sums, no second kernel.  Two tokens: the waves build a chunk, barrier, all 16 look it
 // up, barrier.  One token: the tables fit twice, so the build waves fill chunk c + 1 and then join the others in
 // looking chunk c up, one barrier per chunk.
 //   Tables: NTOK = 2: sub-table kg of the chunk = 81 dwords at kg*324 + idx*4; a build lane (kg, leading digit d0)
-//           makes 27 entries and stores them as single dwords.  NTOK = 1: sub-table = 81 INT16 + 1 pad = 41 dwords at
-//           kg*164 + idx*2; a build lane owns a whole sub-table.  Consecutive lanes are 27 or 41 dwords apart: odd, so
-//           every store of a wave is free of bank conflicts.
+//           makes 27 entries and stores them as single dwords; consecutive lanes are 27 dwords apart: odd, so every
+//           store of a wave is free of bank conflicts.  NTOK = 1: sub-table = 81 INT16 + 3 pads = 42 dwords at
+//           kg*168 + idx*2; a build lane owns a whole sub-table and stores it 8 bytes at a time; consecutive lanes
+//           are 21 such units apart (odd): the 32 lanes of a store pass cover the 64 banks once.
 //   Lookups: wave w reads the packed tile w of the chunk (16 groups); a lane owns an output row and 16/PARTS of the
 //           tile's groups (PARTS lanes per row), RR rows one after the other.  Address = lane constant + idx * entry
 //           size, the group's offset is an immediate: 3 VALU instructions per lookup.  With PARTS = 1 all lanes of a
@@ -26,9 +27,9 @@ namespace {
 //   same XCD and share its L2); every pair is an independent two-token problem.
 // ---------------------------------------------------------------------------------------------
 constexpr int kNarrowChunk = 256;                        // k-groups per chunk = 16 packed tiles, one per wave
-constexpr int narrow_sub_bytes(int ntok) { return ntok == 2 ? 324 : 164; }
+constexpr int narrow_sub_bytes(int ntok) { return ntok == 2 ? 324 : 168; }
 constexpr int narrow_buffers(int ntok) { return ntok == 2 ? 1 : 2; }
-constexpr int narrow_tab_bytes(int ntok) { return narrow_buffers(ntok) * kNarrowChunk * narrow_sub_bytes(ntok); }   // 82944 / 83968
+constexpr int narrow_tab_bytes(int ntok) { return narrow_buffers(ntok) * kNarrowChunk * narrow_sub_bytes(ntok); }   // 82944 / 86016
 
 struct NarrowParams {
     const uint8_t* packed;
@@ -49,7 +50,7 @@ struct NarrowParams {
 // FUSED keeps, behind the tables, two dwords per k-group (the four codes of token 0 and of token 1) and the 16 x 2
 // partial absmax values.
 constexpr int narrow_fused_lds_bytes(int ntok, int chunks) { return narrow_tab_bytes(ntok) + chunks * kNarrowChunk * 8 + 128; }
-constexpr int narrow_fused_max_chunks(int ntok) {        // 39 (K <= 39936) for two tokens, 38 for one
+constexpr int narrow_fused_max_chunks(int ntok) {        // 39 (K <= 39936) for two tokens, 37 (K <= 37888) for one
     return (160 * 1024 - narrow_tab_bytes(ntok) - 128) / (kNarrowChunk * 8);
 }
 
@@ -97,17 +98,34 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
     for (int rr = 0; rr < RR; ++rr) { acc32[rr][0] = 0; acc32[rr][1] = 0; }
 
     // activations of the workgroup's two tokens for the four rows of a k-group: two bytes of a_q[t0/8][4kg + j][*]
-    auto fetch_act = [&](int c, unsigned (&a)[4]) {
+    // The activations of a k-group are fetched raw and taken apart when its tables are built (no wait at the fetch):
+    // FUSED: the two dwords of codes the prologue left in LDS; else the 32 bytes a_q[t0/8][4kg .. 4kg+3][0..7] as two
+    // 16-byte loads, consecutive lanes consecutive addresses (2-byte loads of the one token pair, 32 bytes apart,
+    // cost the load unit of the CU more than the build itself).
+    constexpr int AW = FUSED ? 2 : 8;
+    auto fetch_act = [&](int c, unsigned (&raw)[AW]) {
         const int kg = min(c * kNarrowChunk + kg_b, p.G - 1);          // clamped; validity applied at use
         if constexpr (FUSED) {
             const i32x2 d = *(const __attribute__((address_space(3))) i32x2*)(unsigned)(TAB + kg * 8);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)                                // {code of token 0, code of token 1} of row j
-                a[j] = __builtin_amdgcn_perm((unsigned)d.y, (unsigned)d.x, 0x0c0c0000u | ((4u + j) << 8) | (unsigned)j);
+            raw[0] = (unsigned)d.x;
+            raw[1] = (unsigned)d.y;
         } else {
-            const unsigned short* src = (const unsigned short*)(p.a_q + (size_t)(t0 >> 3) * p.K * 8 + (size_t)(4 * kg) * 8 + (t0 & 7));
+            const int8_t* src = p.a_q + (size_t)(t0 >> 3) * p.K * 8 + (size_t)(4 * kg) * 8;
+            const i32x4 v0 = *(const i32x4*)src, v1 = *(const i32x4*)(src + 16);
+            raw[0] = (unsigned)v0.x; raw[1] = (unsigned)v0.y; raw[2] = (unsigned)v0.z; raw[3] = (unsigned)v0.w;
+            raw[4] = (unsigned)v1.x; raw[5] = (unsigned)v1.y; raw[6] = (unsigned)v1.z; raw[7] = (unsigned)v1.w;
+        }
+    };
+    // a[j] = {code of the first token, code of the second token} of row j of the k-group, in the low 16 bits
+    auto decode_act = [&](const unsigned (&raw)[AW], unsigned (&a)[4]) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) a[j] = src[4 * j];             // 8 bytes per activation row
+        for (int j = 0; j < 4; ++j) {
+            if constexpr (FUSED) {
+                a[j] = __builtin_amdgcn_perm(raw[1], raw[0], 0x0c0c0000u | ((4u + j) << 8) | (unsigned)j);
+            } else {                                                   // bytes t0 % 8 and t0 % 8 + 1 of the row's eight
+                const unsigned long long row8 = ((unsigned long long)raw[2 * j + 1] << 32) | raw[2 * j];
+                a[j] = (unsigned)(row8 >> (8 * (t0 & 7))) & 0xffffu;
+            }
         }
     };
     typedef unsigned wvec __attribute__((ext_vector_type(4)));
@@ -128,12 +146,46 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
 
     // The loop streams the packed weights from HBM and a chunk takes less than the latency of a load, so the weights
     // are fetched WD chunks ahead (a ring of WD + 1 register sets; fewer for more rows per lane), the activations two.
+    // Loads complete in the order of their issue, and the first table build needs the activations only: they (or the
+    // fp32 rows they are made from, and the scales of the epilogue) are requested ahead of the weights, so that
+    // quantisation and the first build run while the weights are still on their way from HBM.
     constexpr int WD = RR == 1 ? 4 : (RR == 2 ? 2 : 1);
-    unsigned act_cur[4] = {0, 0, 0, 0}, act_nxt[4] = {0, 0, 0, 0}, act_nx2[4] = {0, 0, 0, 0};
+    unsigned act_cur[AW] = {}, act_nxt[AW] = {}, act_nx2[AW] = {};
     wvec w_ring[WD + 1][RR];                               // w_ring[0] = the chunk being looked up
     wvec (&w_cur)[RR] = w_ring[0];
+    const int nquad = p.G;
+    auto load4 = [&](int n, int qi) -> f32x4 {
+        const float* src = p.x + (size_t)(t0 + n) * p.ldx + 4 * (size_t)qi;
+        if (p.x_vec) return *(const f32x4*)src;
+        return f32x4{src[0], src[1], src[2], src[3]};
+    };
+    constexpr int NVC = 4;                                             // float4 per thread and token kept (K <= 16384)
+    f32x4 xv[NTOK][NVC];
+    if constexpr (FUSED) {
+#pragma unroll
+        for (int n = 0; n < NTOK; ++n)
+#pragma unroll
+            for (int i = 0; i < NVC; ++i) {
+                const int qi = tid + kThreads * i;
+                xv[n][i] = (n < Nl && qi < nquad) ? load4(n, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+    } else if (builds) {
+        fetch_act(0, act_cur);
+        fetch_act(1, act_nxt);
+        if constexpr (BUFS == 2) fetch_act(2, act_nx2);
+    }
+    // the epilogue's scales: thread tid < 2 * ROWS finishes output (row tid / 2, token tid % 2)
+    const int out_m = m0 + (tid >> 1), out_n = tid & 1;
+    const bool out_ok = tid < ROWS * 2 && out_m < p.M && out_n < Nl;
+    float out_w = p.w_scale, out_a = 1.0f;                 // multiplied at the very end: no wait for them here
+    if (out_ok) {
+        if (p.w_rows) out_w = p.w_rows[out_m];
+        if constexpr (!FUSED) out_a = p.a_scale[t0 + out_n];
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int d = 0; d < WD; ++d) fetch_w(d, w_ring[d]);
+    __builtin_amdgcn_sched_barrier(0);
     float sc[2] = {0.0f, 0.0f};                                        // token scales (FUSED)
     if constexpr (FUSED) {
         // Quantise the one or two rows of x over all of K: thread tid takes the float4 (= k-group) tid + 1024 i.
@@ -141,28 +193,16 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
         typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
         lds_f32* red = (lds_f32*)(unsigned)(TAB + p.chunks * kNarrowChunk * 8);   // [wave][token]
         lds_i32x2* aq = (lds_i32x2*)(unsigned)TAB;
-        const int nquad = p.G;
-        auto load4 = [&](int n, int qi) -> f32x4 {
-            const float* src = p.x + (size_t)(t0 + n) * p.ldx + 4 * (size_t)qi;
-            if (p.x_vec) return *(const f32x4*)src;
-            return f32x4{src[0], src[1], src[2], src[3]};
-        };
         auto absmax4 = [](float m, const f32x4 v) {
             return fmaxf(fmaxf(m, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
         };
         auto codes4 = [](const f32x4 v, float inv) { return (int)quant_codes4(v, inv); };
-        constexpr int NVC = 4;                                         // float4 per thread and token kept (K <= 16384)
-        f32x4 xv[NTOK][NVC];
         float amax[NTOK];
 #pragma unroll
         for (int n = 0; n < NTOK; ++n) {
             amax[n] = 0.0f;
 #pragma unroll
-            for (int i = 0; i < NVC; ++i) {
-                const int qi = tid + kThreads * i;
-                xv[n][i] = (n < Nl && qi < nquad) ? load4(n, qi) : f32x4{0.f, 0.f, 0.f, 0.f};
-                amax[n] = absmax4(amax[n], xv[n][i]);
-            }
+            for (int i = 0; i < NVC; ++i) amax[n] = absmax4(amax[n], xv[n][i]);
             if (n < Nl)
                 for (int q0 = kThreads * NVC; q0 < nquad; q0 += kThreads * NVC) {   // NVC loads in flight per pass
                     f32x4 tv[NVC];
@@ -216,10 +256,12 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
     }
     // ---------------- build the tables of chunk cb (topological order of Sec. 4: one add per entry); only the groups
     //                  of real tiles: the padding groups of the last tile get all-zero tables
-    auto do_build = [&](int cb, const unsigned (&act)[4]) {
+    auto do_build = [&](int cb, const unsigned (&raw)[AW]) {
         const int kgg = cb * kNarrowChunk + kg_b;
         if (kgg >= p.KCn * 16) return;
         const bool valid = kgg < p.G;
+        unsigned act[4];
+        decode_act(raw, act);
         const unsigned buf = (unsigned)((cb & (BUFS - 1)) * BUF);
         if constexpr (NTOK == 2) {
             s16x2 a[4];
@@ -243,30 +285,37 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
                 });
             });
         } else {
-            int a[4];
+            // One token: entry idx = 27 d0 + 9 d1 + 3 d2 + d3 is A[idx / 9] + B[idx % 9] with A = (d0-1) x0 + (d1-1) x1
+            // and B = (d2-1) x2 + (d3-1) x3.  Entries are made two at a time (packed INT16, idx even | idx + 1): a
+            // pair inside a block of nine is A (both halves) + {B[r], B[r+1]}, a pair across two blocks is
+            // {A[q], A[q+1]} + {B[8], B[0]}: one packed add per pair, stored four entries at a time.
+            int x[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) a[j] = valid ? (int)(signed char)(act[j] & 0xffu) : 0;
-            int e[82];
-            static_for<0, 3>([&](auto c0) {
-                constexpr int e0 = decltype(c0)::value;
-                const int b0 = e0 == 0 ? -a[0] : (e0 == 1 ? 0 : a[0]);
-                static_for<0, 3>([&](auto c1) {
-                    constexpr int d1 = decltype(c1)::value;
-                    const int b1 = d1 == 0 ? b0 - a[1] : (d1 == 1 ? b0 : b0 + a[1]);
-                    static_for<0, 3>([&](auto c2) {
-                        constexpr int d2 = decltype(c2)::value;
-                        const int b2 = d2 == 0 ? b1 - a[2] : (d2 == 1 ? b1 : b1 + a[2]);
-                        e[27 * e0 + 9 * d1 + 3 * d2 + 0] = b2 - a[3];
-                        e[27 * e0 + 9 * d1 + 3 * d2 + 1] = b2;
-                        e[27 * e0 + 9 * d1 + 3 * d2 + 2] = b2 + a[3];
-                    });
-                });
-            });
-            e[81] = 0;
-            lds_i32* dst = (lds_i32*)(buf + (unsigned)(kg_b * SUB));
+            for (int j = 0; j < 4; ++j) x[j] = valid ? (int)(signed char)(act[j] & 0xffu) : 0;
+            int A[9], Bv[9];
+            A[4] = 0; A[1] = -x[0]; A[7] = x[0]; A[3] = -x[1]; A[5] = x[1];
+            A[0] = A[1] - x[1]; A[2] = A[1] + x[1]; A[6] = x[0] - x[1]; A[8] = x[0] + x[1];
+            Bv[4] = 0; Bv[1] = -x[2]; Bv[7] = x[2]; Bv[3] = -x[3]; Bv[5] = x[3];
+            Bv[0] = Bv[1] - x[3]; Bv[2] = Bv[1] + x[3]; Bv[6] = x[2] - x[3]; Bv[8] = x[2] + x[3];
+            auto pk = [](int lo, int hi) {
+                return as_s16x2((int)__builtin_amdgcn_perm((unsigned)hi, (unsigned)lo, 0x05040100u));
+            };
+            s16x2 Bp[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) Bp[r] = pk(Bv[r], Bv[r + 1]);
+            const s16x2 Bx = pk(Bv[8], Bv[0]);
+            s16x2 P[42];
             static_for<0, 41>([&](auto ci) {
-                constexpr int i = decltype(ci)::value;      // entries 2i (low half) and 2i + 1 (high half)
-                dst[i] = (int)__builtin_amdgcn_perm((unsigned)e[2 * i + 1], (unsigned)e[2 * i], 0x05040100u);
+                constexpr int i = decltype(ci)::value, q = (2 * i) / 9, r = (2 * i) % 9;
+                if constexpr (r < 8) P[i] = pk(A[q], A[q]) + Bp[r];
+                else P[i] = pk(A[q], A[q < 8 ? q + 1 : q]) + Bx;       // i = 40: entry 80 and a pad
+            });
+            P[41] = s16x2{0, 0};
+            typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
+            lds_i32x2* dst = (lds_i32x2*)(buf + (unsigned)(kg_b * SUB));   // lanes 42 dwords apart: conflict-free
+            static_for<0, 21>([&](auto cj) {
+                constexpr int j = decltype(cj)::value;
+                dst[j] = i32x2{as_int(P[2 * j]), as_int(P[2 * j + 1])};
             });
         }
     };
@@ -298,7 +347,7 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
     };
     auto rotate = [&]() {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { act_cur[j] = act_nxt[j]; act_nxt[j] = act_nx2[j]; }
+        for (int j = 0; j < AW; ++j) { act_cur[j] = act_nxt[j]; act_nxt[j] = act_nx2[j]; }
     };
     auto rotate_w = [&]() {
 #pragma unroll
@@ -307,12 +356,17 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
             for (int rr = 0; rr < RR; ++rr) w_ring[d][rr] = w_ring[d + 1][rr];
     };
 
-    if (builds) { fetch_act(0, act_cur); fetch_act(1, act_nxt); }
+    if constexpr (FUSED) {                                 // the codes are in LDS now (else: requested at the start)
+        if (builds) {
+            fetch_act(0, act_cur);
+            fetch_act(1, act_nxt);
+            if constexpr (BUFS == 2) fetch_act(2, act_nx2);
+        }
+    }
     if constexpr (BUFS == 2) {
         // One token: two table buffers, so the build waves fill chunk c + 1 while every wave (they too, afterwards)
         // looks chunk c up: one barrier per chunk.  act_cur always belongs to the next chunk to build.
         if (builds) {
-            fetch_act(2, act_nx2);
             do_build(0, act_cur);
             rotate();
         }
@@ -353,16 +407,16 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
         red[(pi * ROWS + ri) * 2 + 1] = acc32[rr][1];
     }
     wg_barrier_lds();
-    for (int i = tid; i < ROWS * 2; i += kThreads) {
-        const int ri = i >> 1, n = i & 1;
-        const int m = m0 + ri;
-        if (m < p.M && n < Nl) {
-            int v = 0;
-            for (int pi = 0; pi < 16 * PARTS; ++pi) v += red[(pi * ROWS + ri) * 2 + n];
-            const float s_n = FUSED ? (n ? sc[1] : sc[0]) : p.a_scale[t0 + n];
-            if (p.y) p.y[(size_t)(t0 + n) * p.ldy + m] = (float)v * ((p.w_rows ? p.w_rows[m] : p.w_scale) * s_n);
-            if (p.acc) p.acc[(size_t)m * p.N + t0 + n] = v;
-        }
+    if (out_ok) {                                         // all partial sums requested before the first add
+        int part_v[16 * PARTS];
+#pragma unroll
+        for (int pi = 0; pi < 16 * PARTS; ++pi) part_v[pi] = red[pi * ROWS * 2 + tid];
+        int v = 0;
+#pragma unroll
+        for (int pi = 0; pi < 16 * PARTS; ++pi) v += part_v[pi];
+        if constexpr (FUSED) out_a = out_n ? sc[1] : sc[0];
+        if (p.y) p.y[(size_t)(t0 + out_n) * p.ldy + out_m] = (float)v * (out_w * out_a);
+        if (p.acc) p.acc[(size_t)out_m * p.N + t0 + out_n] = v;
     }
 }
 
