@@ -95,6 +95,21 @@ __device__ __forceinline__ int lane_xor16(int x) {
 // Value of lane l ^ 7 (row_half_mirror reverses each group of 8 lanes): a one-instruction partner whose bit 2 differs.
 __device__ __forceinline__ int lane_xor7(int x) { return __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); }
 
+// Maximum over the 64 lanes of a wave, in every lane: four exchanges inside each row of 16 lanes (data parallel
+// primitives, no LDS traffic), then the four row results through scalar registers.
+__device__ __forceinline__ float wave_max_f32(float v) {
+    v = fmaxf(v, __builtin_bit_cast(float, lane_xor16<1>(__builtin_bit_cast(int, v))));
+    v = fmaxf(v, __builtin_bit_cast(float, lane_xor16<2>(__builtin_bit_cast(int, v))));
+    v = fmaxf(v, __builtin_bit_cast(float, lane_xor7(__builtin_bit_cast(int, v))));      // quads are uniform by now
+    v = fmaxf(v, __builtin_bit_cast(float, lane_xor16<8>(__builtin_bit_cast(int, v))));
+    const int iv = __builtin_bit_cast(int, v);
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
 // 16 sub-tables per table row: the 16 lanes of a group hold 16 partial sums of the same 8 tokens (packed INT16 block
 // sums, plus INT32 sums of earlier blocks when WIDE).  Reduce-scatter with partners l^8, l^7, l^2, l^1 (each a
 // single DPP operand): lane l ends with the total of token l >> 1.  The first exchange moves packed INT16 pairs and

@@ -6,15 +6,15 @@ namespace {
 
 // ---------------------------------------------------------------------------------------------
 // One or two parallel tokens per workgroup (decoding).  The tables of a 256-group chunk of K then take 83 KB (two tokens: an
-// entry is one dword = two INT16 sums) or 43 KB (one token: an entry is one INT16), and a workgroup can sweep all of K
+// entry is one dword = two INT16 sums) or 45 KB (one token: an entry is one INT16), and a workgroup can sweep all of K
 // by itself: no split-K partial sums, no second kernel.  Two tokens: the waves build a chunk, barrier, all 16 look it
 // up, barrier.  One token: the tables fit twice, so the build waves fill chunk c + 1 and then join the others in
 // looking chunk c up, one barrier per chunk.
 //   Tables: NTOK = 2: sub-table kg of the chunk = 81 dwords at kg*324 + idx*4; a build lane (kg, leading digit d0)
 //           makes 27 entries and stores them as single dwords; consecutive lanes are 27 dwords apart: odd, so every
-//           store of a wave is free of bank conflicts.  NTOK = 1: sub-table = 81 INT16 + 3 pads = 42 dwords at
-//           kg*168 + idx*2; a build lane owns a whole sub-table and stores it 8 bytes at a time; consecutive lanes
-//           are 21 such units apart (odd): the 32 lanes of a store pass cover the 64 banks once.
+//           store of a wave is free of bank conflicts.  NTOK = 1: sub-table = 81 INT16 + 7 pads = 44 dwords at
+//           kg*176 + idx*2; a build lane owns a whole sub-table and stores it 16 bytes at a time; consecutive lanes
+//           are 11 such units apart (odd): the 16 lanes of a store pass cover the 64 banks once.
 //   Lookups: wave w reads the packed tile w of the chunk (16 groups); a lane owns an output row and 16/PARTS of the
 //           tile's groups (PARTS lanes per row), RR rows one after the other.  Address = lane constant + idx * entry
 //           size, the group's offset is an immediate: 3 VALU instructions per lookup.  With PARTS = 1 all lanes of a
@@ -27,9 +27,9 @@ namespace {
 //   same XCD and share its L2); every pair is an independent two-token problem.
 // ---------------------------------------------------------------------------------------------
 constexpr int kNarrowChunk = 256;                        // k-groups per chunk = 16 packed tiles, one per wave
-constexpr int narrow_sub_bytes(int ntok) { return ntok == 2 ? 324 : 168; }
+constexpr int narrow_sub_bytes(int ntok) { return ntok == 2 ? 324 : 176; }
 constexpr int narrow_buffers(int ntok) { return ntok == 2 ? 1 : 2; }
-constexpr int narrow_tab_bytes(int ntok) { return narrow_buffers(ntok) * kNarrowChunk * narrow_sub_bytes(ntok); }   // 82944 / 86016
+constexpr int narrow_tab_bytes(int ntok) { return narrow_buffers(ntok) * kNarrowChunk * narrow_sub_bytes(ntok); }   // 82944 / 90112
 
 struct NarrowParams {
     const uint8_t* packed;
@@ -50,7 +50,7 @@ struct NarrowParams {
 // FUSED keeps, behind the tables, two dwords per k-group (the four codes of token 0 and of token 1) and the 16 x 2
 // partial absmax values.
 constexpr int narrow_fused_lds_bytes(int ntok, int chunks) { return narrow_tab_bytes(ntok) + chunks * kNarrowChunk * 8 + 128; }
-constexpr int narrow_fused_max_chunks(int ntok) {        // 39 (K <= 39936) for two tokens, 37 (K <= 37888) for one
+constexpr int narrow_fused_max_chunks(int ntok) {        // 39 (K <= 39936) for two tokens, 35 (K <= 35840) for one
     return (160 * 1024 - narrow_tab_bytes(ntok) - 128) / (kNarrowChunk * 8);
 }
 
@@ -186,7 +186,7 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
 #pragma unroll
     for (int d = 0; d < WD; ++d) fetch_w(d, w_ring[d]);
     __builtin_amdgcn_sched_barrier(0);
-    float sc[2] = {0.0f, 0.0f};                                        // token scales (FUSED)
+    float vmax[2] = {0.0f, 0.0f};                                      // absmax of the tokens (FUSED)
     if constexpr (FUSED) {
         // Quantise the one or two rows of x over all of K: thread tid takes the float4 (= k-group) tid + 1024 i.
         typedef __attribute__((address_space(3))) float lds_f32;
@@ -214,7 +214,7 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
 #pragma unroll
                     for (int i = 0; i < NVC; ++i) amax[n] = absmax4(amax[n], tv[i]);
                 }
-            for (int off = 32; off > 0; off >>= 1) amax[n] = fmaxf(amax[n], __shfl_xor(amax[n], off));
+            amax[n] = wave_max_f32(amax[n]);
         }
         if (lane == 0) {
 #pragma unroll
@@ -227,14 +227,21 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
             float v = 0.0f;
 #pragma unroll
             for (int w = 0; w < kWaves; ++w) v = fmaxf(v, red[w * 2 + n]);
-            inv[n] = (v > 0.0f) ? 127.0f / v : 0.0f;                   // IEEE divisions, as in quantize_kernel
-            sc[n] = v / 127.0f;
+            inv[n] = (v > 0.0f) ? 127.0f / v : 0.0f;                   // IEEE division, as in quantize_kernel
+            vmax[n] = v;                                               // the scale v / 127 is divided out where it is used
         }
-        if (bx == 0 && tid < Nl && p.a_scale_out) p.a_scale_out[t0 + tid] = tid == 0 ? sc[0] : sc[1];
+        if (bx == 0 && tid < Nl && p.a_scale_out) p.a_scale_out[t0 + tid] = (tid == 0 ? vmax[0] : vmax[1]) / 127.0f;
 #pragma unroll
         for (int i = 0; i < NVC; ++i) {
             const int qi = tid + kThreads * i;
-            if (qi < nquad) aq[qi] = i32x2{codes4(xv[0][i], inv[0]), NTOK == 2 ? codes4(xv[NTOK - 1][i], inv[NTOK - 1]) : 0};
+            const i32x2 cd = i32x2{codes4(xv[0][i], inv[0]), NTOK == 2 ? codes4(xv[NTOK - 1][i], inv[NTOK - 1]) : 0};
+            if (qi < nquad) aq[qi] = cd;
+            if constexpr (NTOK == 1) {
+                if (i == 0) {                                          // k-group tid: what this lane builds of chunk 0
+                    act_cur[0] = (unsigned)cd.x;
+                    act_cur[1] = 0u;
+                }
+            }
         }
         for (int q0 = kThreads * NVC; q0 < nquad; q0 += kThreads * NVC) {
             f32x4 tv[NTOK][NVC];
@@ -252,7 +259,9 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
                     aq[qi] = i32x2{codes4(tv[0][i], inv[0]), NTOK == 2 ? codes4(tv[NTOK - 1][i], inv[NTOK - 1]) : 0};
             }
         }
-        wg_barrier_lds();
+        // Two tokens: the build lanes read other lanes' codes next.  One token: a build lane starts with the codes
+        // it has just made itself, and the barrier after the first build publishes the rest.
+        if constexpr (NTOK == 2) wg_barrier_lds();
     }
     // ---------------- build the tables of chunk cb (topological order of Sec. 4: one add per entry); only the groups
     //                  of real tiles: the padding groups of the last tile get all-zero tables
@@ -304,18 +313,17 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
 #pragma unroll
             for (int r = 0; r < 8; ++r) Bp[r] = pk(Bv[r], Bv[r + 1]);
             const s16x2 Bx = pk(Bv[8], Bv[0]);
-            s16x2 P[42];
+            s16x2 P[44];
             static_for<0, 41>([&](auto ci) {
                 constexpr int i = decltype(ci)::value, q = (2 * i) / 9, r = (2 * i) % 9;
                 if constexpr (r < 8) P[i] = pk(A[q], A[q]) + Bp[r];
                 else P[i] = pk(A[q], A[q < 8 ? q + 1 : q]) + Bx;       // i = 40: entry 80 and a pad
             });
-            P[41] = s16x2{0, 0};
-            typedef __attribute__((address_space(3))) i32x2 lds_i32x2;
-            lds_i32x2* dst = (lds_i32x2*)(buf + (unsigned)(kg_b * SUB));   // lanes 42 dwords apart: conflict-free
-            static_for<0, 21>([&](auto cj) {
+            P[41] = P[42] = P[43] = s16x2{0, 0};
+            lds_i32x4* dst = (lds_i32x4*)(buf + (unsigned)(kg_b * SUB));   // lanes 44 dwords apart: conflict-free
+            static_for<0, 11>([&](auto cj) {
                 constexpr int j = decltype(cj)::value;
-                dst[j] = i32x2{as_int(P[2 * j]), as_int(P[2 * j + 1])};
+                dst[j] = i32x4{as_int(P[4 * j]), as_int(P[4 * j + 1]), as_int(P[4 * j + 2]), as_int(P[4 * j + 3])};
             });
         }
     };
@@ -356,27 +364,34 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
             for (int rr = 0; rr < RR; ++rr) w_ring[d][rr] = w_ring[d + 1][rr];
     };
 
-    if constexpr (FUSED) {                                 // the codes are in LDS now (else: requested at the start)
-        if (builds) {
-            fetch_act(0, act_cur);
-            fetch_act(1, act_nxt);
-            if constexpr (BUFS == 2) fetch_act(2, act_nx2);
-        }
-    }
+    // Activations: from global memory they are requested two or three chunks ahead (act_cur always belongs to the
+    // next chunk to build); FUSED reads the codes in LDS right before the build.  The build waves issue at raised
+    // priority: the others wait for their tables.
     if constexpr (BUFS == 2) {
         // One token: two table buffers, so the build waves fill chunk c + 1 while every wave (they too, afterwards)
-        // looks chunk c up: one barrier per chunk.  act_cur always belongs to the next chunk to build.
+        // looks chunk c up: one barrier per chunk.
         if (builds) {
+            __builtin_amdgcn_s_setprio(3);
             do_build(0, act_cur);
-            rotate();
+            __builtin_amdgcn_s_setprio(0);
+            if constexpr (!FUSED) rotate();
         }
         wg_barrier_lds();
         for (int c = 0; c < p.chunks; ++c) {
             fetch_w(c + WD, w_ring[WD]);
             if (builds) {
-                fetch_act(c + 3, act_nx2);
-                if (c + 1 < p.chunks) do_build(c + 1, act_cur);
-                rotate();
+                __builtin_amdgcn_s_setprio(3);
+                if constexpr (FUSED) {
+                    if (c + 1 < p.chunks) {
+                        fetch_act(c + 1, act_cur);
+                        do_build(c + 1, act_cur);
+                    }
+                } else {
+                    fetch_act(c + 3, act_nx2);
+                    if (c + 1 < p.chunks) do_build(c + 1, act_cur);
+                    rotate();
+                }
+                __builtin_amdgcn_s_setprio(0);
             }
             do_lookup(c);
             wg_barrier_lds();                  // chunk c + 1 is built, and nobody reads chunk c any more
@@ -386,13 +401,14 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
         for (int c = 0; c < p.chunks; ++c) {
             fetch_w(c + WD, w_ring[WD]);
             if (builds) {
-                fetch_act(c + 2, act_nx2);
+                if constexpr (FUSED) fetch_act(c, act_cur);
+                else fetch_act(c + 2, act_nx2);
                 do_build(c, act_cur);
             }
             wg_barrier_lds();
             do_lookup(c);
             wg_barrier_lds();
-            rotate();
+            if constexpr (!FUSED) rotate();
             rotate_w();
         }
     }
@@ -414,7 +430,7 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
         int v = 0;
 #pragma unroll
         for (int pi = 0; pi < 16 * PARTS; ++pi) v += part_v[pi];
-        if constexpr (FUSED) out_a = out_n ? sc[1] : sc[0];
+        if constexpr (FUSED) out_a = (out_n ? vmax[1] : vmax[0]) / 127.0f;
         if (p.y) p.y[(size_t)(t0 + out_n) * p.ldy + out_m] = (float)v * (out_w * out_a);
         if (p.acc) p.acc[(size_t)out_m * p.N + t0 + out_n] = v;
     }

@@ -210,7 +210,7 @@ __global__ void __launch_bounds__(kTokThreads) quantize_token_kernel(const float
             for (int i = 0; i < NB; ++i) amax = absmax4(amax, xv[i]);
         }
     }
-    for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+    amax = wave_max_f32(amax);
     if ((tid & 63) == 0) red[tid >> 6] = amax;
     __syncthreads();
     float v = 0.0f;
