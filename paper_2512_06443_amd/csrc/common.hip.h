@@ -95,14 +95,17 @@ __device__ __forceinline__ int lane_xor16(int x) {
 // Value of lane l ^ 7 (row_half_mirror reverses each group of 8 lanes): a one-instruction partner whose bit 2 differs.
 __device__ __forceinline__ int lane_xor7(int x) { return __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); }
 
-// Maximum over the 64 lanes of a wave, in every lane: four exchanges inside each row of 16 lanes (data parallel
-// primitives, no LDS traffic), then the four row results through scalar registers.
-__device__ __forceinline__ float wave_max_f32(float v) {
+// Maximum over each row of 16 lanes, in every lane of the row: four exchanges by data parallel primitives (no LDS
+// traffic).
+__device__ __forceinline__ float row_max_f32(float v) {
     v = fmaxf(v, __builtin_bit_cast(float, lane_xor16<1>(__builtin_bit_cast(int, v))));
     v = fmaxf(v, __builtin_bit_cast(float, lane_xor16<2>(__builtin_bit_cast(int, v))));
     v = fmaxf(v, __builtin_bit_cast(float, lane_xor7(__builtin_bit_cast(int, v))));      // quads are uniform by now
-    v = fmaxf(v, __builtin_bit_cast(float, lane_xor16<8>(__builtin_bit_cast(int, v))));
-    const int iv = __builtin_bit_cast(int, v);
+    return fmaxf(v, __builtin_bit_cast(float, lane_xor16<8>(__builtin_bit_cast(int, v))));
+}
+// Maximum over the 64 lanes of a wave, in every lane: the four row results meet through scalar registers.
+__device__ __forceinline__ float wave_max_f32(float v) {
+    const int iv = __builtin_bit_cast(int, row_max_f32(v));
     const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0));
     const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16));
     const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32));

@@ -197,12 +197,20 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
             return fmaxf(fmaxf(m, fmaxf(fabsf(v.x), fabsf(v.y))), fmaxf(fabsf(v.z), fabsf(v.w)));
         };
         auto codes4 = [](const f32x4 v, float inv) { return (int)quant_codes4(v, inv); };
+        // All 16 waves run this prologue at once, four to a SIMD: its length is its instruction count, so whatever a
+        // whole wave has no data for (float4 slots past the end of the row, the second token of a one-token pair)
+        // is skipped by wave-uniform branches.
+        bool slot_live[NVC];
+#pragma unroll
+        for (int i = 0; i < NVC; ++i) slot_live[i] = kThreads * i + wave * 64 < nquad;
         float amax[NTOK];
 #pragma unroll
         for (int n = 0; n < NTOK; ++n) {
             amax[n] = 0.0f;
+            if (n >= Nl) continue;
 #pragma unroll
-            for (int i = 0; i < NVC; ++i) amax[n] = absmax4(amax[n], xv[n][i]);
+            for (int i = 0; i < NVC; ++i)
+                if (slot_live[i]) amax[n] = absmax4(amax[n], xv[n][i]);
             if (n < Nl)
                 for (int q0 = kThreads * NVC; q0 < nquad; q0 += kThreads * NVC) {   // NVC loads in flight per pass
                     f32x4 tv[NVC];
@@ -224,23 +232,22 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
         float inv[NTOK];
 #pragma unroll
         for (int n = 0; n < NTOK; ++n) {
-            float v = 0.0f;
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) v = fmaxf(v, red[w * 2 + n]);
+            const float v = row_max_f32(red[(lane & 15) * 2 + n]);     // the 16 waves' results, one per lane of a row
             inv[n] = (v > 0.0f) ? 127.0f / v : 0.0f;                   // IEEE division, as in quantize_kernel
             vmax[n] = v;                                               // the scale v / 127 is divided out where it is used
         }
         if (bx == 0 && tid < Nl && p.a_scale_out) p.a_scale_out[t0 + tid] = (tid == 0 ? vmax[0] : vmax[1]) / 127.0f;
 #pragma unroll
         for (int i = 0; i < NVC; ++i) {
+            if (!slot_live[i]) continue;
             const int qi = tid + kThreads * i;
-            const i32x2 cd = i32x2{codes4(xv[0][i], inv[0]), NTOK == 2 ? codes4(xv[NTOK - 1][i], inv[NTOK - 1]) : 0};
+            i32x2 cd = i32x2{codes4(xv[0][i], inv[0]), 0};
+            if constexpr (NTOK == 2) {
+                if (Nl == 2) cd.y = codes4(xv[NTOK - 1][i], inv[NTOK - 1]);
+            }
             if (qi < nquad) aq[qi] = cd;
             if constexpr (NTOK == 1) {
-                if (i == 0) {                                          // k-group tid: what this lane builds of chunk 0
-                    act_cur[0] = (unsigned)cd.x;
-                    act_cur[1] = 0u;
-                }
+                if (i == 0) act_cur[0] = (unsigned)cd.x;               // k-group tid: what this lane builds of chunk 0
             }
         }
         for (int q0 = kThreads * NVC; q0 < nquad; q0 += kThreads * NVC) {
