@@ -38,7 +38,7 @@ LDS_MEASURED_PEAK_GBS = CUS * 240 * 2.1                   # 129024 GB/s
 # HBM bytes per launch of the lookup kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), see profiles/
 MEASURED_TRAFFIC_BYTES = {
     "bitnet2b_ffn_up/up/128": 10.95e6,     # profiles/lookup_kernel_bitnet2b_ffn_up_hbm_traffic.md
-    "layer2b4_nsweep/gate/1": 4.62e6,      # profiles/narrow_kernel_layer2b4_gate_n1_stats_and_hbm_traffic.md
+    "layer2b4_nsweep/gate/1": 4.64e6,      # profiles/narrow_kernel_layer2b4_gate_n1_stats_and_hbm_traffic.md
 }
 
 
