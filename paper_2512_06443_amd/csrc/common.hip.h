@@ -57,6 +57,7 @@ struct LookupParams {
     float* a_scale_out;       // optional: the token scales, written by the workgroups of the first row tile
     int64_t ldx;
     int x_vec;                // rows can be read as float4
+    int out_vec;              // y (or the partial-sum slots) can be written four rows at a time
 };
 
 __device__ __forceinline__ unsigned lds_base_of(void* p) {

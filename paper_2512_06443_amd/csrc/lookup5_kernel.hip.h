@@ -105,7 +105,7 @@ __global__ void __launch_bounds__(kThreads) lookup5_kernel(const Lookup5Params p
     typedef __attribute__((address_space(3))) float lds_f32;
     lds_f32* scale_lds = (lds_f32*)(unsigned)kScale5Base;
     float my_scale = 0.0f;
-    if (tid < 8 && n0 + tid < p.N) my_scale = p.w_scale * p.a_scale[n0 + tid];
+    if (tid < 8 && n0 + tid < p.N) my_scale = p.a_scale[n0 + tid];   // times w_scale at the end: no wait here
 
     s16x2 acc16[R][4];
     int acc32[NEED32 ? R : 1][8];
@@ -245,7 +245,7 @@ __global__ void __launch_bounds__(kThreads) lookup5_kernel(const Lookup5Params p
 
     // ---- epilogue: reduce the 16 partial sums per token across the lane group, park as [token][row], store rows.
     lds_i32* park = (lds_i32*)0u;
-    if (tid < 8) scale_lds[tid] = my_scale;
+    if (tid < 8) scale_lds[tid] = p.w_scale * my_scale;
     constexpr int kParkStride = R * kRoundRows + 4;
     const int m0 = rgw0 * 4;
     const int rows_wg = min(p.RGW * 4, p.M - m0);

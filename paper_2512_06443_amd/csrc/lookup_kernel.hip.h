@@ -165,9 +165,10 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     typedef __attribute__((address_space(3))) float lds_f32;
     lds_f32* scale_lds = (lds_f32*)(unsigned)kTableBytes;
     // Loaded now, stored to LDS only when the K loop is over: nothing at the start of the kernel waits for it.
+    // (Nor for a product with it: wave 0, which holds these lanes, is a build wave, and the first barrier of the
+    // kernel waits for its first tables.)
     float my_scale = 0.0f;
-    if (MODE != kFusedQuant && tid < n_tile && n0 + tid < p.N)
-        my_scale = p.w_rows ? p.a_scale[n0 + tid] : p.w_scale * p.a_scale[n0 + tid];
+    if (MODE != kFusedQuant && tid < n_tile && n0 + tid < p.N) my_scale = p.a_scale[n0 + tid];
 
     // Fused quantisation (all 16 waves; called once by either role, after its first loads are on their way): lane =
     // token + 8 * quad, a wave reads 8 consecutive float4 of each of the 8 rows per pass.  Absmax over all of K
@@ -512,7 +513,8 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     // the group with a reduce-scatter (each step halves the tokens a lane keeps), park the sums in LDS as
     // [token][row] and let the whole workgroup write consecutive output rows per token.
     lds_i32* park = (lds_i32*)0u;
-    if (tid < n_tile) scale_lds[tid] = my_scale;     // visible after the first barrier below
+    if (tid < n_tile)                                // visible after the first barrier below
+        scale_lds[tid] = (MODE != kFusedQuant && !p.w_rows) ? p.w_scale * my_scale : my_scale;
     const int m0 = rgw0 * 4;
     const int rows_wg = min(p.RGW * 4, p.M - m0);
     // RC = row-group rounds parked per pass.  All R at once when the tile has few tokens (the R independent
@@ -583,6 +585,52 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         }
         }
         wg_barrier_lds();
+        if (p.out_vec) {
+            // four consecutive rows of one token per thread: one 16-byte read of the parked sums, one 16-byte store
+            for (int i = tid; i < RC * (kRoundRows / 4) * n_tile; i += kThreads) {
+                const int col = 4 * (i % (RC * (kRoundRows / 4)));
+                const int nl = i / (RC * (kRoundRows / 4));
+                const int mrow = c0 * kRoundRows + col;     // row inside the workgroup tile
+                const int n = n0 + nl;
+                if (mrow < rows_wg && mrow < R * kRoundRows && n < p.N) {
+                    const i32x4 v4 = *(const lds_i32x4*)(park + nl * kParkStride + col);
+                    const int val[4] = {v4.x, v4.y, v4.z, v4.w};
+                    const int m = m0 + mrow;
+                    const int cnt = min(4, rows_wg - mrow);
+                    if (p.S == 1 && !p.partial) {
+                        if (p.y) {
+                            const float sn = scale_lds[nl];
+                            float o[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                o[e] = (float)val[e] * ((p.w_rows && e < cnt) ? p.w_rows[m + e] * sn : sn);
+                            float* dsty = p.y + (size_t)n * p.ldy + m;
+                            if (cnt == 4) {
+                                *(f32x4*)dsty = f32x4{o[0], o[1], o[2], o[3]};
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 3; ++e)
+                                    if (e < cnt) dsty[e] = o[e];
+                            }
+                        }
+                        if (p.acc) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (e < cnt) p.acc[(size_t)(m + e) * p.N + n] = val[e];
+                        }
+                    } else {
+                        int32_t* dstw = p.ws + ((size_t)(p.slot0 + ks) * p.N + n) * p.M + m;
+                        if (cnt == 4) {
+                            *(i32x4*)dstw = v4;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 3; ++e)
+                                if (e < cnt) dstw[e] = val[e];
+                        }
+                    }
+                }
+            }
+        } else
         for (int i = tid; i < RC * kRoundRows * n_tile; i += kThreads) {
             const int col = i % (RC * kRoundRows);
             const int nl = i / (RC * kRoundRows);

@@ -207,7 +207,10 @@ int launch_lookup_t(const LookupParams& p, int grid, hipStream_t stream) {
     if (lds > max_lds) return VLUT_ERR_UNSUPPORTED;
     static std::atomic<unsigned> attr_done{0};   // one bit per device: the attribute belongs to the device's copy
     if (!allow_dynamic_lds((const void*)kfn, max_lds, attr_done)) return VLUT_ERR_DEVICE;
-    hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), lds, stream, p);
+    LookupParams q = p;
+    if (q.S > 1 || q.partial) q.out_vec = ((uintptr_t)q.ws % 16 == 0) && (q.M % 4 == 0);
+    else q.out_vec = !q.y || (((uintptr_t)q.y % 16 == 0) && (q.ldy % 4 == 0));
+    hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), lds, stream, q);
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
 
