@@ -292,6 +292,34 @@ def test_acc_only_and_ldy(B):
     assert np.all(yb[:, 100:] == -7.0)                      # nothing written past M
 
 
+@pytest.mark.parametrize("M,plan", [(257, (16, 2, 0, 1)), (257, (16, 2, 0, 3)), (260, (16, 3, 0, 2)), (262, (8, 1, 0, 1)),
+                                    (1030, (16, 9, 0, 1))])
+def test_output_row_stride_and_alignment(B, M, plan):
+    # The general kernel stores four rows at a time where y (or the split-K slots) allows it: row stride and base
+    # aligned to 16 bytes; otherwise, and in the last rows of a ragged M, row by row.  Every combination must give
+    # the oracle's numbers and leave the padding of y alone.
+    K, N = 1028, 40
+    W, s, x = wl.small_case(90 + M, M, K, N)
+    _, _, acc_ref, y_ref = O.mpgemm(W, s, x)
+    packed = B.pack_weights(dev(W))
+    a_q, a_s = B.quantize_act(dev(x))
+    B.set_plan(*plan)
+    try:
+        for ldy, off in ((M, 0), ((M + 3) // 4 * 4, 0), ((M + 3) // 4 * 4 + 4, 0), (M + 5, 0), ((M + 3) // 4 * 4 + 4, 1)):
+            print(f"case out M={M} plan={plan} ldy={ldy} offset={off}", flush=True)
+            buf = torch.full((N * ldy + 8,), -7.0, device="cuda")
+            y = buf[off:off + N * ldy].view(N, ldy)[:, :M]
+            _, acc = B.mpgemm(packed, float(s), a_q, a_s, M, y=y, want_acc=True)
+            torch.cuda.synchronize()
+            assert np.array_equal(acc.cpu().numpy(), acc_ref)
+            full = buf.cpu().numpy()
+            yy = full[off:off + N * ldy].reshape(N, ldy)
+            check_y(yy[:, :M], y_ref)
+            assert np.all(yy[:, M:] == -7.0) and np.all(full[:off] == -7.0) and np.all(full[off + N * ldy:] == -7.0)
+    finally:
+        B.set_plan(0, 0, 0, 0)
+
+
 def test_smallest_shape_many_token_tiles_and_a_side_stream(B):
     W, s, x = wl.small_case(81, 1, 4, 1)                    # M = 1, K = g, N = 1: one lookup in all
     run_case(B, W, s, x, tag="1x4x1")
