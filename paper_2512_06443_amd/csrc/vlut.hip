@@ -289,9 +289,9 @@ int check_mpgemm_args(const uint8_t* packed, const int8_t* a_q, const float* a_s
 
 // ---- few-token kernel: one copy of the row tiles per token pair.  Measured (K = 2560..6912, 40..250 workgroups):
 //      the time of a launch depends on the rows per workgroup, hardly on the number of workgroups while they all
-//      fit the device at once: 32 rows 7.8 us, 64 rows 8.5-9.8 us, 128 rows 10.3-11.8 us, 256 rows 13.4-15.6 us at
-//      K = 2560 (16 rows, four lanes per row: 8.6-9.0 us, never the best), against 12-16 us for quantiser + general
-//      kernel + split-K sum at 3..16 tokens.  So: the fewest rows (from 32) whose grid is one round of workgroups.
+//      fit the device at once (16 rows with four lanes per row were never the best), against 12-16 us for quantiser
+//      + general kernel + split-K sum at 3..32 tokens.  So: the fewest rows (from 32) whose grid is one round of
+//      workgroups, and narrow_applies weighs that against the general path.
 constexpr int kNarrowMaxN = 32;
 struct NarrowPlan {
     int parts, rr, rows, gridx, chunks, pairs, gx8, grid;
@@ -320,7 +320,9 @@ bool narrow_applies(int64_t M, int64_t K, int64_t N, const void* lut) {
     if (N > kNarrowMaxN || lut != nullptr || t_forced.Jlog >= 0 || t_forced.R != 0 || t_forced.S != 0) return false;
     if (N <= 2) return true;
     const NarrowPlan np = narrow_plan(M, K, N);
-    return np.grid <= 256 && (np.rows <= 64 || (np.rows == 128 && K <= 4096));
+    // Measured at N <= 32: this kernel takes about 5 us + (K / 1024) x {0.8, 1.2, 1.9, 3.4} us for 32, 64, 128, 256 rows
+    // per workgroup, the three launches of the general path about 12 us + (K / 1024) x 1.2 us.
+    return np.grid <= 256 && (np.rows <= 64 || (np.rows == 128 && K <= 8192) || (np.rows == 256 && K <= 3072));
 }
 
 template <int NTOK, int PARTS, int RR, bool FUSED>

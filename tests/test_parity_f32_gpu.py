@@ -164,9 +164,9 @@ def test_few_tokens_one_launch_per_token_pair(B, N):
         if N > 8 and M > 1000:
             continue
         W, s, x = wl.small_case(600 + 10 * N + M % 7, M, K, N)
-        narrow = not (M == 9000 and N >= 7)                 # 71 tiles of 128 rows x 4 pairs: more than one round
-        qp = run_f32(B, W, s, x, fused=narrow, tag=f"few tokens M{M} K{K} N{N}")
-        assert (qp[0] == 0) == narrow and (not narrow or qp[3] % ((N + 1) // 2) == 0)
+        qp = run_f32(B, W, s, x, fused=True, tag=f"few tokens M{M} K{K} N{N}")
+        assert qp[0] == 0 and qp[3] % ((N + 1) // 2) == 0
+        assert qp[1] == {100: 32, 3000: 32 if N <= 4 else 64, 9000: 128 if N <= 6 else 256, 130: 32}[M] or N > 8
     M = 40000                                               # too many workgroups for one round: the general path
     W, s, x = wl.small_case(690 + N, M, 64, N)
     qp = run_f32(B, W, s, x, fused=False, tag=f"few tokens M{M} N{N}")
