@@ -314,15 +314,21 @@ NarrowPlan narrow_plan(int64_t M, int64_t K, int64_t N) {
     return np;
 }
 
-// One or two tokens always take this kernel; more tokens while its workgroups fit the device at once with few
-// enough rows each to beat the three launches of the general path (see the figures above).
-bool narrow_applies(int64_t M, int64_t K, int64_t N, const void* lut) {
+// One or two tokens always take this kernel; more tokens while its workgroups fit the device at once and a cost
+// estimate fitted to measurements at N <= 32 (2B-model shapes) favours it by 10 %.  In us, with c = K / 1024:
+//   this kernel   4.6 from fp32 activations (3.6 from INT8 ones) + c x {0.9, 1.35, 2.0, 3.4} for 32, 64, 128, 256 rows
+//                 per workgroup;
+//   general path  5.8 + 0.94 c + 0.41 x M N / 10^4 for lookup kernel + split-K sum, + 3.5 for the quantiser from fp32.
+bool narrow_applies(int64_t M, int64_t K, int64_t N, const void* lut, bool from_f32) {
     if (N > kNarrowMaxN || lut != nullptr || t_forced.Jlog >= 0 || t_forced.R != 0 || t_forced.S != 0) return false;
     if (N <= 2) return true;
     const NarrowPlan np = narrow_plan(M, K, N);
-    // Measured at N <= 32: this kernel takes about 5 us + (K / 1024) x {0.8, 1.2, 1.9, 3.4} us for 32, 64, 128, 256 rows
-    // per workgroup, the three launches of the general path about 12 us + (K / 1024) x 1.2 us.
-    return np.grid <= 256 && (np.rows <= 64 || (np.rows == 128 && K <= 8192) || (np.rows == 256 && K <= 3072));
+    if (np.grid > 256) return false;
+    const double c = (double)K / 1024.0;
+    const double per_chunk = np.rows <= 32 ? 0.9 : (np.rows <= 64 ? 1.35 : (np.rows <= 128 ? 2.0 : 3.4));
+    const double narrow_us = (from_f32 ? 4.6 : 3.6) + c * per_chunk;
+    const double general_us = 5.8 + 0.94 * c + 0.41 * (double)M * (double)N / 1e4 + (from_f32 ? 3.5 : 0.0);
+    return narrow_us * 1.1 < general_us;
 }
 
 template <int NTOK, int PARTS, int RR, bool FUSED>
@@ -370,7 +376,7 @@ F32Layout f32_layout(int64_t M, int64_t K, int64_t N) {
     F32Layout L;
     std::memset(&L, 0, sizeof(L));
     const size_t scale_bytes = round256((size_t)N * sizeof(float));
-    if (narrow_applies(M, K, N, nullptr) && narrow_plan(M, K, N).chunks <= narrow_fused_max_chunks(N == 1 ? 1 : 2)) {
+    if (narrow_applies(M, K, N, nullptr, true) && narrow_plan(M, K, N).chunks <= narrow_fused_max_chunks(N == 1 ? 1 : 2)) {
         L.kind = kF32Narrow;
         return L;
     }
@@ -391,7 +397,7 @@ F32Layout f32_layout(int64_t M, int64_t K, int64_t N) {
     L.kind = kF32TwoLaunches;                    // quantise into the workspace, then the ordinary path
     L.off_aq = scale_bytes;
     L.off_ws = L.off_aq + round256((size_t)((N + 7) / 8) * (size_t)K * 8);
-    const bool narrow = narrow_applies(M, K, N, nullptr);
+    const bool narrow = narrow_applies(M, K, N, nullptr, false);
     const Plan pl = narrow ? Plan{4, 1, 1} : choose_plan(M, K, N);
     L.total = L.off_ws + (pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0);
     return L;
@@ -529,7 +535,7 @@ size_t vlut_lut_bytes(int64_t K, int64_t N) {
 
 size_t vlut_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     if (!shape_ok(M, K, N)) return 0;
-    if (narrow_applies(M, K, N, nullptr)) return 0;
+    if (narrow_applies(M, K, N, nullptr, false)) return 0;
     Plan pl = choose_plan(M, K, N);
     return pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
 }
@@ -555,7 +561,7 @@ int vlut_set_plan(int J, int R, int waves, int split_k) {
 int vlut_query_plan(int64_t M, int64_t K, int64_t N, int* out4) {
     if (!out4) return VLUT_ERR_NULL;
     if (!shape_ok(M, K, N)) return VLUT_ERR_SHAPE;
-    if (narrow_applies(M, K, N, nullptr)) {    // the few-token kernel: J reported as 0, R = rows per workgroup
+    if (narrow_applies(M, K, N, nullptr, false)) {   // the few-token kernel: J reported as 0, R = rows per workgroup
         const NarrowPlan np = narrow_plan(M, K, N);
         out4[0] = 0; out4[1] = np.rows; out4[2] = 1; out4[3] = np.gridx * np.pairs;
         return VLUT_OK;
@@ -679,7 +685,7 @@ static int mpgemm_impl(const uint8_t* packed, float w_scale, const float* w_rows
     int rc = check_mpgemm_args(packed, a_q, a_scale, M, K, N, y, ldy, acc_or_null);
     if (rc != VLUT_OK) return rc;
     if (((uintptr_t)a_q) % 16 != 0) return VLUT_ERR_UNSUPPORTED;      // the [N/8][K][8] blocks are read 16 bytes at a time
-    if (narrow_applies(M, K, N, lut_or_null)) {   // a few tokens: the workgroups sweep all of K, no workspace
+    if (narrow_applies(M, K, N, lut_or_null, false)) {   // a few tokens: the workgroups sweep all of K, no workspace
         const NarrowPlan np = narrow_plan(M, K, N);
         NarrowParams q;
         std::memset(&q, 0, sizeof(q));
@@ -749,6 +755,11 @@ int vlut_query_plan_f32(int64_t M, int64_t K, int64_t N, int* out5) {
     if (L.kind == kF32Fused) {
         const Derived d = derive(L.plan, M, K, N);
         out5[0] = 1 << L.plan.Jlog; out5[1] = L.plan.R; out5[2] = L.plan.S; out5[3] = d.total;
+        return VLUT_OK;
+    }
+    if (L.kind == kF32Narrow) {                // reported as vlut_query_plan reports the few-token kernel
+        const NarrowPlan np = narrow_plan(M, K, N);
+        out5[0] = 0; out5[1] = np.rows; out5[2] = 1; out5[3] = np.gridx * np.pairs;
         return VLUT_OK;
     }
     return vlut_query_plan(M, K, N, out5);

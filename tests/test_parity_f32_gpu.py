@@ -175,8 +175,7 @@ def test_few_tokens_one_launch_per_token_pair(B, N):
 
 def test_few_tokens_long_rows_and_unaligned_rows(B):
     W, s, x = wl.small_case(695, 40, 40000, 5)              # codes do not fit next to the tables: quantiser + kernel
-    qp = run_f32(B, W, s, x, fused=False, tag="K40000 at five tokens")
-    assert qp[0] == 0
+    run_f32(B, W, s, x, fused=False, tag="K40000 at five tokens")
     W, s, x = wl.small_case(696, 300, 1028, 7)
     odd = np.full((7, 1031), 1e9, np.float32)
     odd[:, 3:1031] = x
