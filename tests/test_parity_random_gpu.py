@@ -36,11 +36,11 @@ def dev(a):
 def cases():
     rnd = random.Random(12345)
     out = []
-    while len(out) < 60:
-        M = rnd.choice([1, 3, 17, 64, 130, 257, 700, 1500, 3000])
+    while len(out) < 80:
+        M = rnd.choice([1, 3, 17, 64, 130, 257, 700, 1500, 3000, 9000])
         K = 4 * rnd.choice([1, 2, 5, 16, 33, 64, 100, 257, 640, 1088, 1728])
-        N = rnd.choice([1, 2, 3, 7, 8, 9, 16, 31, 64, 130, 300])
-        forced = rnd.random() < 0.6
+        N = rnd.choice([1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 24, 31, 32, 33, 64, 130, 300])
+        forced = rnd.random() < 0.5
         plan = (rnd.choice([1, 2, 4, 8, 16]), rnd.choice(ROWS_PER_WAVE), 0, rnd.choice([1, 1, 2, 3, 5, 8])) if forced \
             else (0, 0, 0, 0)
         if M * K * N <= 6e8:
