@@ -31,6 +31,7 @@ struct Lookup5Params {
     int S, tiles_m, tiles_n, RGW, dstages_total, dstages_per_split, total_tiles, per_xcd;
     int Ka;        // rows per token chunk of the activation tensor a_q points into
     int partial;   // mixed packing: write INT32 sums to ws slots ks also when K is not split
+    int out_vec;   // y (or the partial-sum slots) can be written four rows at a time
 };
 
 // Table read of lookup I (= row group I) of the half-stage that uses byte B of the weight dwords (slot B & 1).
@@ -255,6 +256,47 @@ __global__ void __launch_bounds__(kThreads) lookup5_kernel(const Lookup5Params p
             park[(l >> 1) * kParkStride + r * kRoundRows + lw * 4 + grp] = reduce16<NEED32>(acc16[r], acc32[NEED32 ? r : 0], l);
     }
     wg_barrier_lds();
+    if (p.out_vec) {
+        // four consecutive rows of one token per thread: one 16-byte read of the parked sums, one 16-byte store
+        for (int i = tid; i < R * (kRoundRows / 4) * 8; i += kThreads) {
+            const int col = 4 * (i % (R * (kRoundRows / 4)));
+            const int nl = i / (R * (kRoundRows / 4));
+            const int n = n0 + nl;
+            if (col < rows_wg && n < p.N) {
+                const i32x4 v4 = *(const lds_i32x4*)(park + nl * kParkStride + col);
+                const int val[4] = {v4.x, v4.y, v4.z, v4.w};
+                const int m = m0 + col;
+                const int cnt = min(4, rows_wg - col);
+                if (p.S == 1 && !p.partial) {
+                    if (p.y) {
+                        const float sn = scale_lds[nl];
+                        float* dsty = p.y + (size_t)n * p.ldy + m;
+                        if (cnt == 4) {
+                            *(f32x4*)dsty = f32x4{(float)val[0] * sn, (float)val[1] * sn, (float)val[2] * sn, (float)val[3] * sn};
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 3; ++e)
+                                if (e < cnt) dsty[e] = (float)val[e] * sn;
+                        }
+                    }
+                    if (p.acc) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (e < cnt) p.acc[(size_t)(m + e) * p.N + n] = val[e];
+                    }
+                } else {
+                    int32_t* dstw = p.ws + ((size_t)ks * p.N + n) * p.M + m;
+                    if (cnt == 4) {
+                        *(i32x4*)dstw = v4;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 3; ++e)
+                            if (e < cnt) dstw[e] = val[e];
+                    }
+                }
+            }
+        }
+    } else
     for (int i = tid; i < R * kRoundRows * 8; i += kThreads) {
         const int col = i % (R * kRoundRows);
         const int nl = i / (R * kRoundRows);

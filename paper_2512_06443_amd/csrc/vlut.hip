@@ -469,7 +469,10 @@ int launch_lookup5_t(const Lookup5Params& p, int grid, hipStream_t stream) {
     auto kfn = lookup5_kernel<R, NEED32>;
     static std::atomic<unsigned> attr_done{0};   // one bit per device: the attribute belongs to the device's copy
     if (!allow_dynamic_lds((const void*)kfn, kLds5Bytes, attr_done)) return VLUT_ERR_DEVICE;
-    hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), kLds5Bytes, stream, p);
+    Lookup5Params q = p;
+    if (q.S > 1 || q.partial) q.out_vec = ((uintptr_t)q.ws % 16 == 0) && (q.M % 4 == 0);
+    else q.out_vec = !q.y || (((uintptr_t)q.y % 16 == 0) && (q.ldy % 4 == 0));
+    hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), kLds5Bytes, stream, q);
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
 

@@ -118,6 +118,32 @@ def test_g5_ldy_and_acc_only(B):
     assert np.all(yb[:, 100:] == -7.0)                      # nothing written past M
 
 
+@pytest.mark.parametrize("M,plan", [(257, (2, 1)), (257, (2, 3)), (260, (4, 2)), (262, (1, 1))])
+def test_g5_output_row_stride_and_alignment(B, M, plan):
+    # Outputs leave four rows at a time where y (or the split-K slots) is aligned for it, row by row otherwise and in
+    # the last rows of a ragged M; the padding of y stays untouched.
+    K, N = 1040, 40
+    W, s, x = wl.small_case(190 + M, M, K, N)
+    _, _, acc_ref, y_ref = O.mpgemm(W, s, x)
+    packed = B.pack_weights_g5(dev(W))
+    a_q, a_s = B.quantize_act(dev(x))
+    B.set_plan_g5(*plan)
+    try:
+        for ldy, off in ((M, 0), ((M + 3) // 4 * 4, 0), ((M + 3) // 4 * 4 + 4, 0), (M + 5, 0), ((M + 3) // 4 * 4 + 4, 1)):
+            print(f"g5 case out M={M} plan={plan} ldy={ldy} offset={off}", flush=True)
+            buf = torch.full((N * ldy + 8,), -7.0, device="cuda")
+            y = buf[off:off + N * ldy].view(N, ldy)[:, :M]
+            _, acc = B.mpgemm_g5(packed, float(s), a_q, a_s, M, y=y, want_acc=True)
+            torch.cuda.synchronize()
+            assert np.array_equal(acc.cpu().numpy(), acc_ref)
+            full = buf.cpu().numpy()
+            yy = full[off:off + N * ldy].reshape(N, ldy)
+            check_y(yy[:, :M], y_ref)
+            assert np.all(yy[:, M:] == -7.0) and np.all(full[:off] == -7.0) and np.all(full[off + N * ldy:] == -7.0)
+    finally:
+        B.set_plan_g5(0, 0)
+
+
 def test_g5_full_size_bitnet2b_ffn_up(B):
     M, K, N = 6912, 2560, 128
     W = wl.ternary(0, M, K, 0.4)
