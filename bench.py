@@ -39,6 +39,7 @@ LDS_MEASURED_PEAK_GBS = CUS * 240 * 2.1                   # 129024 GB/s
 MEASURED_TRAFFIC_BYTES = {
     "bitnet2b_ffn_up/up/128": 10.95e6,     # profiles/lookup_kernel_bitnet2b_ffn_up_hbm_traffic.md
     "layer2b4_nsweep/gate/1": 4.64e6,      # profiles/narrow_kernel_layer2b4_gate_n1_stats_and_hbm_traffic.md
+    "llama8b_linears/gateup/512": 83.6e6,  # profiles/lookup_kernel_bitnet2b_ffn_up_hbm_traffic.md (second part)
 }
 
 
