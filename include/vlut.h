@@ -184,10 +184,11 @@ int vlut_mpgemm_rows(const uint8_t* packed, const float* w_scale_rows, const int
 /*
  * Quantisation and mpGeMM in one call, from fp32 activations: the steps of vlut_quantize_act (Sec. 3.4 first
  * paragraph: per-token absmax INT8) and of vlut_mpgemm / vlut_mpgemm_rows (Alg. 1, Eq. 2) with the same readings and
- * the same numbers.  For a few tokens (decoding; the cases vlut_query_plan reports with J = 0, with K <= 35840 for one token and 39936 for more) it is one
- * launch: a workgroup quantises the rows of its one or two tokens itself (absmax over the whole row, codes kept in
- * LDS), so that neither the INT8 activations nor a second kernel are needed.  For more tokens the quantiser runs as a kernel of its own into the workspace, ahead of the lookup kernel
- * (measured to be the faster arrangement); a lookup kernel that quantises the 8 tokens of its tile itself exists as
+ * the same numbers.  For a few tokens (decoding: always for N <= 2, up to N = 32 where a cost estimate favours it,
+ * reported by vlut_query_plan_f32 with J = 0; K <= 35840 for one token, 39936 for more) it is one launch: a
+ * workgroup quantises the rows of its one or two tokens itself (absmax over the whole row, codes kept in LDS), so
+ * that neither the INT8 activations nor a second kernel are needed.  For more tokens the quantiser runs as a kernel
+ * of its own into the workspace, ahead of the lookup kernel (measured to be the faster arrangement); a lookup kernel that quantises the 8 tokens of its tile itself exists as
  * well and is taken when vlut_set_plan forces a plan with J = 16 whose K range per workgroup is at most 8704.
  *   x             dev, fp32 [N][ldx], ldx >= K (16-byte aligned rows are read as float4)
  *   w_scale / w_scale_rows_or_null   per-tensor scale, or (non-NULL) dev fp32 [M] per-row scales as in
