@@ -144,12 +144,13 @@ __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) 
         }
     };
 
-    // The loop streams the packed weights from HBM and a chunk takes less than the latency of a load, so the weights
-    // are fetched WD chunks ahead (a ring of WD + 1 register sets; fewer for more rows per lane), the activations two.
+    // The loop streams the packed weights from HBM: they are fetched WD chunks ahead (a ring of WD + 1 register sets),
+    // the activations two or three.  One chunk ahead measured best for every tile shape (2 to 4 chunks ahead cost
+    // 3-8 %: a row has only a few chunks, and more loads in flight at the start delay the first ones).
     // Loads complete in the order of their issue, and the first table build needs the activations only: they (or the
     // fp32 rows they are made from, and the scales of the epilogue) are requested ahead of the weights, so that
     // quantisation and the first build run while the weights are still on their way from HBM.
-    constexpr int WD = RR == 1 ? 4 : (RR == 2 ? 2 : 1);
+    constexpr int WD = 1;
     unsigned act_cur[AW] = {}, act_nxt[AW] = {}, act_nx2[AW] = {};
     wvec w_ring[WD + 1][RR];                               // w_ring[0] = the chunk being looked up
     wvec (&w_cur)[RR] = w_ring[0];
