@@ -37,28 +37,62 @@ __global__ void __launch_bounds__(256) token_outer_lookup_kernel(const uint8_t* 
     }
 }
 
-// Sum of the split-K partials (any order is exact: integers) + scale step.
+// Sum of the split-K partials (any order is exact: integers) + scale step.  A thread takes VEC (1 or 4) consecutive
+// output rows of one token; the scales are requested first and up to sixteen partial sums at once, so that the kernel
+// is one memory round trip (a loop that adds the partial sums one by one waits for every load in turn, and scales
+// fetched after the sum wait once more).  VEC = 4 needs M % 4 == 0 and 16-byte aligned ws, y rows and w_rows.
+template <int VEC>
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const int32_t* __restrict__ ws, int S, int M, int N,
                                                             float w_scale, const float* __restrict__ w_rows,
                                                             const float* __restrict__ a_scale,
                                                             float* __restrict__ y, int64_t ldy,
                                                             int32_t* __restrict__ acc) {
+    static_assert(VEC == 1 || VEC == 4, "one row or four rows per thread");
+    const int Mv = M / VEC;
     size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-    if (i >= (size_t)M * N) return;
-    int m = (int)(i % M);
-    int n = (int)(i / M);
-    // Sixteen partial sums are requested at once (a loop that adds them one by one waits for every load in turn,
-    // S memory round trips instead of one).
-    int v = 0;
-    for (int s0 = 0; s0 < S; s0 += 16) {
-        int part[16];
-#pragma unroll
-        for (int k = 0; k < 16; ++k) part[k] = (s0 + k < S) ? ws[((size_t)(s0 + k) * N + n) * M + m] : 0;
-#pragma unroll
-        for (int k = 0; k < 16; ++k) v += part[k];
+    if (i >= (size_t)Mv * N) return;
+    const int m = (int)(i % Mv) * VEC;
+    const int n = (int)(i / Mv);
+    const float as = y ? a_scale[n] : 0.0f;
+    float wr[VEC];
+    if constexpr (VEC == 1) {
+        wr[0] = (y && w_rows) ? w_rows[m] : w_scale;
+    } else {
+        const f32x4 w4 = (y && w_rows) ? *(const f32x4*)(w_rows + m) : f32x4{w_scale, w_scale, w_scale, w_scale};
+        wr[0] = w4.x; wr[1] = w4.y; wr[2] = w4.z; wr[3] = w4.w;
     }
-    if (y) y[(size_t)n * ldy + m] = (float)v * ((w_rows ? w_rows[m] : w_scale) * a_scale[n]);
-    if (acc) acc[(size_t)m * N + n] = v;
+    constexpr int NB = VEC == 1 ? 16 : 8;                   // partial sums in flight
+    int v[VEC] = {};
+    for (int s0 = 0; s0 < S; s0 += NB) {
+        int part[NB][VEC];
+#pragma unroll
+        for (int k = 0; k < NB; ++k) {
+            const int32_t* src = ws + ((size_t)min(s0 + k, S - 1) * N + n) * M + m;   // clamped; masked below
+            if constexpr (VEC == 1) {
+                part[k][0] = *src;
+            } else {
+                const i32x4 q = *(const i32x4*)src;
+                part[k][0] = q.x; part[k][1] = q.y; part[k][2] = q.z; part[k][3] = q.w;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < NB; ++k)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) v[e] += (s0 + k < S) ? part[k][e] : 0;
+    }
+    if (y) {
+        float* dst = y + (size_t)n * ldy + m;
+        if constexpr (VEC == 1) {
+            dst[0] = (float)v[0] * (wr[0] * as);
+        } else {
+            *(f32x4*)dst = f32x4{(float)v[0] * (wr[0] * as), (float)v[1] * (wr[1] * as), (float)v[2] * (wr[2] * as),
+                                 (float)v[3] * (wr[3] * as)};
+        }
+    }
+    if (acc) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[(size_t)(m + e) * N + n] = v[e];
+    }
 }
 
 }  // namespace

@@ -278,6 +278,20 @@ int launch_lookup_r(int R, int mode, const LookupParams& p, int grid, hipStream_
     }
 }
 
+// Second kernel of a split-K (or mixed-packing) launch: four rows per thread when everything is aligned for it.
+int launch_splitk_reduce(const int32_t* ws, int S, int64_t M, int64_t N, float w_scale, const float* w_rows,
+                         const float* a_scale, float* y, int64_t ldy, int32_t* acc, hipStream_t s) {
+    const bool vec = (M % 4 == 0) && ((uintptr_t)ws % 16 == 0) && (!y || ((uintptr_t)y % 16 == 0 && ldy % 4 == 0)) &&
+                     (!w_rows || (uintptr_t)w_rows % 16 == 0);
+    const size_t total = (size_t)(vec ? M / 4 : M) * (size_t)N;
+    const dim3 grid((unsigned)((total + 255) / 256));
+    if (vec) hipLaunchKernelGGL(splitk_reduce_kernel<4>, grid, dim3(256), 0, s, ws, S, (int)M, (int)N, w_scale, w_rows,
+                                a_scale, y, ldy, acc);
+    else hipLaunchKernelGGL(splitk_reduce_kernel<1>, grid, dim3(256), 0, s, ws, S, (int)M, (int)N, w_scale, w_rows,
+                            a_scale, y, ldy, acc);
+    return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
+}
+
 int check_mpgemm_args(const uint8_t* packed, const int8_t* a_q, const float* a_scale, int64_t M, int64_t K,
                       int64_t N, float* y, int64_t ldy, int32_t* acc) {
     if (!shape_ok(M, K, N)) return VLUT_ERR_SHAPE;
@@ -721,12 +735,8 @@ static int mpgemm_impl(const uint8_t* packed, float w_scale, const float* w_rows
     int grid = d.per_xcd * 8;
     rc = d.need32 ? launch_lookup_r<true>(pl.R, mode, p, grid, s) : launch_lookup_r<false>(pl.R, mode, p, grid, s);
     if (rc != VLUT_OK) return rc;
-    if (pl.S > 1) {
-        size_t total = (size_t)M * (size_t)N;
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                           (const int32_t*)workspace, pl.S, (int)M, (int)N, w_scale, w_rows, a_scale, y, ldy, acc_or_null);
-        if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
-    }
+    if (pl.S > 1)
+        return launch_splitk_reduce((const int32_t*)workspace, pl.S, M, N, w_scale, w_rows, a_scale, y, ldy, acc_or_null, s);
     return VLUT_OK;
 }
 
@@ -823,11 +833,9 @@ int vlut_mpgemm_f32(const uint8_t* packed, float w_scale, const float* w_scale_r
                       : launch_lookup_r<false>(pl.R, kFusedQuant, p, grid, s);
     if (rc != VLUT_OK) return rc;
     if (pl.S > 1) {
-        size_t total = (size_t)M * (size_t)N;
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                           (const int32_t*)(ws + L.off_ws), pl.S, (int)M, (int)N, w_one, w_rows, (const float*)scales, y,
-                           ldy, acc_or_null);
-        if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
+        rc = launch_splitk_reduce((const int32_t*)(ws + L.off_ws), pl.S, M, N, w_one, w_rows, (const float*)scales, y, ldy,
+                                  acc_or_null, s);
+        if (rc != VLUT_OK) return rc;
     }
     return VLUT_OK;
 }
@@ -922,13 +930,8 @@ int vlut_mpgemm_g5(const uint8_t* packed, float w_scale, const int8_t* a_q, cons
     int grid = d.per_xcd * 8;
     int rc = d.need32 ? launch_lookup5_r<true>(pl.R, p, grid, s) : launch_lookup5_r<false>(pl.R, p, grid, s);
     if (rc != VLUT_OK) return rc;
-    if (pl.S > 1) {
-        size_t total = (size_t)M * (size_t)N;
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                           (const int32_t*)workspace, pl.S, (int)M, (int)N, w_scale, (const float*)nullptr, a_scale, y, ldy,
-                           acc_or_null);
-        if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
-    }
+    if (pl.S > 1)
+        return launch_splitk_reduce((const int32_t*)workspace, pl.S, M, N, w_scale, nullptr, a_scale, y, ldy, acc_or_null, s);
     return VLUT_OK;
 }
 
@@ -1043,11 +1046,8 @@ int vlut_mpgemm_mixed(const uint8_t* packed, float w_scale, const int8_t* a_q, c
         rc = d.need32 ? launch_lookup_r<true>(pl4.R, kFast, p, grid, s) : launch_lookup_r<false>(pl4.R, kFast, p, grid, s);
         if (rc != VLUT_OK) return rc;
     }
-    const size_t total = (size_t)M * (size_t)N;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
-                       (const int32_t*)workspace, pl5.S + pl4.S, (int)M, (int)N, w_scale, (const float*)nullptr, a_scale, y,
-                       ldy, acc_or_null);
-    return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
+    return launch_splitk_reduce((const int32_t*)workspace, pl5.S + pl4.S, M, N, w_scale, nullptr, a_scale, y, ldy,
+                                acc_or_null, s);
 }
 
 size_t vlut_mfma_workspace_bytes(int64_t M, int64_t K, int64_t N) {
