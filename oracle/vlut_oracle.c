@@ -9,9 +9,9 @@
  * The method is lossless (Sec. 3.4 "INT16-INT32 hierarchical accumulation":
  * no clipping, no scaling, no numerical error), so the result of the lookup
  * path has a plain definition, O = W x A (Table 2), and the oracle is that
- * definition written out as a triple loop.  The only place where the paper's
- * algorithm itself is followed step by step is the table T (Alg. 1, function
- * Precompute, and Eq. 1), because T is a public intermediate of the library.
+ * definition written out as a triple loop.  The table T is a public
+ * intermediate of the library, so it has a definition here too: Eq. 1, every
+ * row the dot product of its decoded pattern with the group's activations.
  *
  * Every function here is pinned by tests/test_oracle_pins.py against facts the
  * paper prints or the mathematics fixes; none is "parity unpinned".
@@ -156,42 +156,42 @@ void oracle_epilogue(const int32_t *acc, int64_t M, int64_t N, float w_scale, co
 
 /*
  * Vector table T of shape [K/g][3^g][N], N contiguous (Sec. 3.3), INT16 entries
- * (Sec. 3.4 step i), built the vanilla way of Alg. 1 function Precompute / Eq. 1:
- * every row i visits its g activation rows and adds, subtracts or skips.
+ * (Sec. 3.4 step i), written as what Eq. 1 defines: row i of sub-table kg is the
+ * plain dot product of the ternary pattern that index i encodes (decoded with
+ * oracle_unpack_indices, the same decoder the packing round trip uses) with the
+ * g activation rows of the group,
+ *   T[kg][i][n] = sum_{j<g} pattern_i[j] * q[g*kg + j][n].
  */
 void oracle_build_lut(const int8_t *q, int64_t K, int64_t N, int g, int16_t *T) {
     int rows = pow3(g);
     int64_t G = K / g;
-    memset(T, 0, (size_t)G * rows * N * sizeof(int16_t));
     for (int64_t kg = 0; kg < G; ++kg)
-        for (int i = 0; i < rows; ++i)
-            for (int j = 0; j < g; ++j) {
-                int v = oracle_get_sign(i, j, g);
-                int16_t *t = T + ((size_t)kg * rows + i) * N;
-                const int8_t *a = q + (size_t)(kg * g + j) * N;
-                if (v == 1)
-                    for (int64_t n = 0; n < N; ++n) t[n] = (int16_t)(t[n] + a[n]);
-                else if (v == -1)
-                    for (int64_t n = 0; n < N; ++n) t[n] = (int16_t)(t[n] - a[n]);
+        for (int i = 0; i < rows; ++i) {
+            uint8_t code = (uint8_t)i;
+            int8_t pattern[8];
+            oracle_unpack_indices(&code, 1, g, g, pattern);
+            for (int64_t n = 0; n < N; ++n) {
+                int dot = 0;
+                for (int j = 0; j < g; ++j) dot += pattern[j] * q[(size_t)(kg * g + j) * N + n];
+                T[((size_t)kg * rows + i) * N + n] = (int16_t)dot;
             }
+        }
 }
 
 /*
- * Alg. 1 main loop, as printed: O[m][n] += T[kg][idx[m][kg]][n], loop order
- * kg, m, n.  Kept only so that tests can check "lookup of the oracle table
- * equals the plain GEMM" (Eq. 2 == Table 2's product); it is not the timed
- * baseline.
+ * Eq. 2 written out per output element: O[m][n] = sum_kg T[kg][idx[m][kg]][n].
+ * Kept only so that tests can check "lookups into the oracle's table give the
+ * plain product of Table 2"; it is not the timed baseline.
  */
 void oracle_lookup_accumulate(const uint8_t *idx, const int16_t *T, int64_t M, int64_t K, int64_t N,
                               int g, int32_t *acc) {
     int rows = pow3(g);
     int64_t G = K / g;
-    memset(acc, 0, (size_t)M * N * sizeof(int32_t));
-    for (int64_t kg = 0; kg < G; ++kg)
-        for (int64_t m = 0; m < M; ++m) {
-            int i = idx[m * G + kg];
-            const int16_t *t = T + ((size_t)kg * rows + i) * N;
-            for (int64_t n = 0; n < N; ++n) acc[m * N + n] += t[n];
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t sum = 0;
+            for (int64_t kg = 0; kg < G; ++kg) sum += T[((size_t)kg * rows + idx[m * G + kg]) * N + n];
+            acc[m * N + n] = (int32_t)sum;
         }
 }
 
