@@ -13,9 +13,15 @@
  *   - Pointers marked "dev" are device (HBM) pointers of the current HIP device;
  *     pointers marked "host" are ordinary host pointers.  Nothing is copied
  *     between host and device by the library.
- *   - The caller owns every buffer.  The library allocates no device memory and
- *     keeps no state between calls, except the optional per-thread tuning
- *     override of vlut_set_plan.
+ *   - The caller owns every buffer.  The library allocates no device memory.
+ *     State it keeps between calls: (i) the per-thread tuning override of
+ *     vlut_set_plan (and a per-thread cache of the launch plans chosen for the
+ *     last few shapes, emptied by vlut_set_plan); (ii) one 4-byte device flag
+ *     per GPU that the pack kernels raise for a non-ternary weight, reset and
+ *     read back inside every vlut_pack_weights* call under a host mutex (the
+ *     pack calls of one process are therefore serialised); (iii) one bit per
+ *     kernel and device that records that the kernel's LDS limit was raised.
+ *     None of it influences results.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Runtime entry points only enqueue work on `stream`; they never
  *     synchronise.  vlut_pack_weights is an offline step and may synchronise.
@@ -84,7 +90,13 @@ size_t vlut_act_bytes(int64_t K, int64_t N);
  * (Sec. 1 quotes 285.5 MiB for K = 14436, N = 512).  0 if the shape is invalid. */
 size_t vlut_lut_bytes(int64_t K, int64_t N);
 
-/* Bytes of scratch vlut_mpgemm needs for this shape (split-K partial sums); may be 0. */
+/*
+ * Bytes of scratch vlut_mpgemm / vlut_mpgemm_rows need for this shape (split-K partial sums); may be 0.  One size
+ * serves both table variants (lut_or_null NULL or not).  The size depends on the launch plan, hence on the
+ * vlut_set_plan override of the CALLING THREAD: query it on the thread that makes the call, after any
+ * vlut_set_plan (a size taken under another override may be too small, which vlut_mpgemm reports as
+ * VLUT_ERR_SMALL_BUFFER, never by writing out of bounds).  0 also when the override fits the shape with no plan.
+ */
 size_t vlut_workspace_bytes(int64_t M, int64_t K, int64_t N);
 
 /*
@@ -148,7 +160,8 @@ int vlut_mpgemm_token_outer(const uint8_t* packed, float w_scale, const float* a
  * one lookup of an 81-row sub-table row and a vector add over the tokens,
  * INT16 inside blocks of at most 64 lookups, INT32 across blocks, then the
  * scale step y[n][m] = (float)acc[m][n] * (w_scale * a_scale[n]).
- *   packed        dev, blob written by vlut_pack_weights for the same M, K
+ *   packed        dev, 16-byte aligned (VLUT_ERR_UNSUPPORTED otherwise), blob written by
+ *                 vlut_pack_weights for the same M, K
  *   w_scale       per-tensor weight scale
  *   a_q, a_scale  dev, as written by vlut_quantize_act for the same K, N
  *   lut_or_null   dev or NULL.  NULL: sub-tables are built in LDS tile by tile
@@ -276,7 +289,11 @@ int vlut_mpgemm_mfma(const uint8_t* packed, float w_scale, const int8_t* a_q, co
  * this thread (interleave factor J in {1,2,4,8,16} = sub-tables per 256-byte
  * table row, row groups per wave R, waves per workgroup, split-K factor).
  * Any argument 0 = choose automatically.  Returns VLUT_ERR_UNSUPPORTED for a
- * combination the kernels are not built for.  Results never depend on the plan.
+ * combination the kernels are not built for.  Whether an accepted override
+ * fits a given shape is only known at the call: when it does not (R > 6 where
+ * a lane makes more than 64 lookups, a split-K factor above the number of K
+ * stages), vlut_mpgemm*, vlut_query_plan* return VLUT_ERR_UNSUPPORTED instead of
+ * running another plan.  Results never depend on the plan.
  */
 int vlut_set_plan(int J, int R, int waves, int split_k);
 

@@ -81,7 +81,9 @@ __device__ __forceinline__ void lookup5_half(const unsigned (&w)[R], unsigned la
 template <int R, bool NEED32>
 __global__ void __launch_bounds__(kThreads) lookup5_kernel(const Lookup5Params p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem5[];
-    if (lds_base_of(smem5) != 0u) return;      // table addresses are formed as idx*256 + slice*16 from LDS address 0
+    // table addresses are formed as idx*256 + slice*16 from LDS address 0; the host checks that the kernel has no
+    // static LDS before the first launch and refuses to launch otherwise, so this branch is never taken
+    if (lds_base_of(smem5) != 0u) return;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);

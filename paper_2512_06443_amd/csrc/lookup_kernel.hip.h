@@ -120,7 +120,8 @@ template <int R, bool NEED32, int MODE>
 __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // The kernel has no static LDS, so the dynamic segment starts at LDS address 0; table addresses are formed
-    // as idx*256 + slice*16 by a byte permute and rely on that.
+    // as idx*256 + slice*16 by a byte permute and rely on that.  The host verifies it (static LDS size of the
+    // kernel == 0) before the first launch and refuses to launch otherwise, so this branch is never taken.
     if (lds_base_of(smem) != 0u) return;
     const int tid = threadIdx.x;
     const int lane = tid & 63;

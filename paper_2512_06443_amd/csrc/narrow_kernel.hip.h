@@ -57,7 +57,9 @@ constexpr int narrow_fused_max_chunks(int ntok) {        // 39 (K <= 39936) for 
 template <int NTOK, int PARTS, int RR, bool FUSED>
 __global__ void __launch_bounds__(kThreads) narrow_kernel(const NarrowParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_n[];
-    if (lds_base_of(smem_n) != 0u) return;               // table addresses below are absolute LDS addresses
+    // table addresses below are absolute LDS addresses; the host checks that the kernel has no static LDS before
+    // the first launch and refuses to launch otherwise, so this branch is never taken
+    if (lds_base_of(smem_n) != 0u) return;
     static_assert(PARTS == 1 || PARTS == 2, "a row's 16 groups of a tile belong to one lane or to two");
     constexpr int SUB = narrow_sub_bytes(NTOK);           // bytes per sub-table
     constexpr int BUFS = narrow_buffers(NTOK);            // table buffers: one token's tables fit twice

@@ -41,11 +41,16 @@ namespace {
 // Host side
 // ---------------------------------------------------------------------------------------------
 // Raises a kernel's dynamic LDS limit once per device (the limit is a property of the kernel on one device).
-bool allow_dynamic_lds(const void* kfn, int bytes, std::atomic<unsigned>& done_mask) {
+// The table kernels form LDS addresses as idx*256 + slice*16 and so need their dynamic LDS segment to start at LDS
+// address 0, i.e. a kernel without static LDS: checked here, once per device, before the first launch (a kernel
+// that fails the check is never launched and the call returns VLUT_ERR_DEVICE).
+bool allow_dynamic_lds(const void* kfn, int bytes, std::atomic<unsigned>& done_mask, bool needs_lds_base0 = true) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return false;
     const unsigned bit = (dev >= 0 && dev < 32) ? (1u << dev) : 0u;
     if (bit && (done_mask.load(std::memory_order_relaxed) & bit)) return true;
+    hipFuncAttributes attr;
+    if (needs_lds_base0 && (hipFuncGetAttributes(&attr, kfn) != hipSuccess || attr.sharedSizeBytes != 0)) return false;
     if (hipFuncSetAttribute(kfn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return false;
     done_mask.fetch_or(bit, std::memory_order_relaxed);
     return true;
@@ -120,13 +125,16 @@ bool plan_valid(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     return true;
 }
 
-Plan search_plan(int64_t M, int64_t K, int64_t N) {
-    Plan best = {0, 4, 1};
+// A plan with R == 0 means: the override of vlut_set_plan fits this shape with no value of the free parameters
+// (callers report VLUT_ERR_UNSUPPORTED).  Without an override there is always a valid plan (R = 1, S = 1).
+Plan search_plan(int64_t M, int64_t K, int64_t N, int max_S = 16) {
+    Plan best = {0, 0, 0};
     double best_cost = 1e300;
     const int Ss[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
     for (int Jlog = 0; Jlog <= 4; ++Jlog)
         for (int R : kSupportedR)
             for (int S : Ss) {
+                if (S > max_S) continue;
                 Plan pl = {t_forced.Jlog >= 0 ? t_forced.Jlog : Jlog, t_forced.R > 0 ? t_forced.R : R,
                            t_forced.S > 0 ? t_forced.S : S};
                 if (!plan_valid(pl, M, K, N)) continue;
@@ -413,6 +421,7 @@ F32Layout f32_layout(int64_t M, int64_t K, int64_t N) {
     L.off_ws = L.off_aq + round256((size_t)((N + 7) / 8) * (size_t)K * 8);
     const bool narrow = narrow_applies(M, K, N, nullptr, false);
     const Plan pl = narrow ? Plan{4, 1, 1} : choose_plan(M, K, N);
+    L.plan = pl;
     L.total = L.off_ws + (pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0);
     return L;
 }
@@ -459,8 +468,10 @@ bool plan5_valid(const Plan5& pl, int64_t M, int64_t K, int64_t N) {
     return pl.S <= d.dstages_total;
 }
 
+// R == 0 in the result: the override of vlut_set_plan_g5 fits this shape with no value of the free parameter
+// (plan5_valid is then false and the callers report VLUT_ERR_UNSUPPORTED).
 Plan5 choose_plan5(int64_t M, int64_t K, int64_t N) {
-    Plan5 best = {1, 1};
+    Plan5 best = {0, 0};
     double best_cost = 1e300;
     const int Ss[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
     for (int R : kSupportedR5)
@@ -552,8 +563,10 @@ size_t vlut_lut_bytes(int64_t K, int64_t N) {
 
 size_t vlut_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     if (!shape_ok(M, K, N)) return 0;
+    // Where the few-token kernel serves the streamed path (no workspace), the materialised-table variant runs a
+    // plan without split-K, so this one size serves both variants.
     if (narrow_applies(M, K, N, nullptr, false)) return 0;
-    Plan pl = choose_plan(M, K, N);
+    const Plan pl = choose_plan(M, K, N);
     return pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
 }
 
@@ -584,6 +597,7 @@ int vlut_query_plan(int64_t M, int64_t K, int64_t N, int* out4) {
         return VLUT_OK;
     }
     Plan pl = choose_plan(M, K, N);
+    if (pl.R == 0) return VLUT_ERR_UNSUPPORTED;          // the override does not fit this shape
     Derived d = derive(pl, M, K, N);
     out4[0] = 1 << pl.Jlog;
     out4[1] = pl.R;
@@ -633,8 +647,8 @@ int vlut_quantize_act(const float* x, int64_t N, int64_t K, int64_t ldx, int8_t*
     const int nquad_per_thread = (int)((K / 4 + 127) / 128);
     auto launch = [&](auto kfn) -> int {
         if (lds > 160 * 1024 - 1024) return VLUT_ERR_UNSUPPORTED;   // the chunk's [K][8] block is staged in LDS
-        if (lds > 48 * 1024 &&
-            hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        static std::atomic<unsigned> attr_done{0};   // per kernel instance (generic lambda), one bit per device
+        if (lds > 48 * 1024 && !allow_dynamic_lds((const void*)kfn, 160 * 1024 - 1024, attr_done, false))
             return VLUT_ERR_DEVICE;
         hipLaunchKernelGGL(kfn, dim3(chunks), dim3(kQuantThreads), lds, s, x, (int)N, (int)K, ldx, a_q, a_scale);
         return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
@@ -702,6 +716,7 @@ static int mpgemm_impl(const uint8_t* packed, float w_scale, const float* w_rows
     int rc = check_mpgemm_args(packed, a_q, a_scale, M, K, N, y, ldy, acc_or_null);
     if (rc != VLUT_OK) return rc;
     if (((uintptr_t)a_q) % 16 != 0) return VLUT_ERR_UNSUPPORTED;      // the [N/8][K][8] blocks are read 16 bytes at a time
+    if (((uintptr_t)packed) % 16 != 0) return VLUT_ERR_UNSUPPORTED;   // packed tiles are read up to 16 bytes at a time
     if (narrow_applies(M, K, N, lut_or_null, false)) {   // a few tokens: the workgroups sweep all of K, no workspace
         const NarrowPlan np = narrow_plan(M, K, N);
         NarrowParams q;
@@ -711,7 +726,10 @@ static int mpgemm_impl(const uint8_t* packed, float w_scale, const float* w_rows
         q.KCn = (int)((K / 4 + 15) / 16); q.RGtotal = (int)((M + 3) / 4); q.ldy = (int)ldy; q.chunks = np.chunks;
         return launch_narrow<false>(np, q, (hipStream_t)stream);
     }
-    Plan pl = choose_plan(M, K, N);
+    // A materialised table where the streamed path would take the few-token kernel (and vlut_workspace_bytes says
+    // 0): a plan without split-K, so that no workspace is needed here either.
+    Plan pl = (lut_or_null && narrow_applies(M, K, N, nullptr, false)) ? search_plan(M, K, N, 1) : choose_plan(M, K, N);
+    if (pl.R == 0) return VLUT_ERR_UNSUPPORTED;          // the override of vlut_set_plan does not fit this shape
     const bool al = lut_or_null && (N % 8 == 0) && (((uintptr_t)lut_or_null) % 16 == 0);
     const int mode = lut_or_null ? kFromGlobal : kFast;
     if (mode != kFast) pl.R = pl.R >= 4 ? 4 : (pl.R >= 2 ? 2 : 1);   // the general-purpose kernels are built for these R only
@@ -786,7 +804,9 @@ int vlut_mpgemm_f32(const uint8_t* packed, float w_scale, const float* w_scale_r
     if (!y && !acc_or_null) return VLUT_ERR_NULL;
     if (y && (ldy < M || ldy > INT32_MAX)) return VLUT_ERR_SHAPE;
     if (ldx < K) return VLUT_ERR_SHAPE;
+    if (((uintptr_t)packed) % 16 != 0) return VLUT_ERR_UNSUPPORTED;
     const F32Layout L = f32_layout(M, K, N);
+    if (L.kind == kF32TwoLaunches && L.plan.R == 0) return VLUT_ERR_UNSUPPORTED;   // override does not fit the shape
     if (L.total > 0) {
         if (!workspace) return VLUT_ERR_NULL;
         if (workspace_bytes < L.total) return VLUT_ERR_SMALL_BUFFER;
@@ -896,6 +916,7 @@ int vlut_query_plan_g5(int64_t M, int64_t K, int64_t N, int* out3) {
     if (!out3) return VLUT_ERR_NULL;
     if (!shape5_ok(M, K, N)) return VLUT_ERR_SHAPE;
     Plan5 pl = choose_plan5(M, K, N);
+    if (!plan5_valid(pl, M, K, N)) return VLUT_ERR_UNSUPPORTED;   // the override does not fit this shape
     Derived5 d = derive5(pl, M, K, N);
     out3[0] = pl.R; out3[1] = pl.S; out3[2] = d.total;
     return VLUT_OK;
@@ -991,6 +1012,7 @@ static bool mixed_plans(int64_t M, int64_t K, int64_t N, Plan5* p5, Plan* p4) {
         *p5 = Plan5{0, 0};
     }
     *p4 = K4 > 0 ? choose_plan(M, K4, N) : Plan{0, 0, 0};
+    if (K4 > 0 && p4->R == 0) return false;              // the override of vlut_set_plan does not fit the 2-bit part
     return true;
 }
 

@@ -32,8 +32,7 @@ def golden():
 
 @pytest.fixture(scope="session")
 def vlut_lib_path():
-    """Path of the built C-ABI library; builds it (hipcc cross-compiles without a GPU) only if nothing is built."""
+    """Path of the built C-ABI library; builds it (hipcc cross-compiles without a GPU) when nothing is built or a
+    source is newer than the library."""
     from paper_2512_06443_amd import build as b
-    if not os.path.exists(b.LIB):
-        b.build()
-    return b.LIB
+    return b.build(force=False)

@@ -152,6 +152,50 @@ def test_split_k_needs_a_workspace(L):
         assert L.vlut_set_plan(0, 0, 0, 0) == 0
 
 
+def test_workspace_size_serves_the_materialised_table_variant_too(L):
+    """The size vlut_workspace_bytes reports is accepted by vlut_mpgemm for lut != NULL as well, also where the
+    streamed path takes the few-token kernel and needs none (the call then reaches the device step: no GPU here)."""
+    d = 0x1000
+    for (M, K, N) in [(70, 4352, 9), (640, 2560, 1), (2560, 2560, 4), (300, 8192, 2), (6912, 2560, 16), (300, 4352, 40)]:
+        need = L.vlut_workspace_bytes(M, K, N)
+        ws = d if need else None
+        for lut in (None, d):
+            rc = L.vlut_mpgemm(d, 1.0, d, d, lut, M, K, N, d, M, None, ws, need, None)
+            assert rc not in (-1, -2, -3, -6), (M, K, N, lut, rc)
+
+
+def test_override_that_does_not_fit_the_shape_is_an_error(L):
+    d = 0x1000
+    out = (ci * 4)()
+    try:
+        # K = 16384: 4096 groups; J = 1 -> 4 groups per stage, 1024 stages x 4 lookups per lane > 64 -> R <= 6 only
+        assert L.vlut_set_plan(1, 9, 0, 1) == 0
+        assert L.vlut_query_plan(300, 16384, 40, out) == -6
+        assert L.vlut_mpgemm(d, 1.0, d, d, None, 300, 16384, 40, d, 300, None, None, 0, None) == -6
+        assert L.vlut_workspace_bytes(300, 16384, 40) == 0
+        # more K splits than stages: K = 256 -> 64 groups = one stage at J = 16
+        assert L.vlut_set_plan(16, 2, 0, 4) == 0
+        assert L.vlut_query_plan(300, 256, 40, out) == -6
+        assert L.vlut_mpgemm(d, 1.0, d, d, None, 300, 256, 40, d, 300, None, d, 1 << 20, None) == -6
+        assert L.vlut_set_plan(16, 2, 0, 1) == 0
+        assert L.vlut_query_plan(300, 256, 40, out) == 0 and tuple(out)[:3] == (16, 2, 1)
+    finally:
+        assert L.vlut_set_plan(0, 0, 0, 0) == 0
+    out3 = (ci * 3)()
+    try:
+        assert L.vlut_set_plan_g5(2, 4) == 0
+        assert L.vlut_query_plan_g5(300, 320, 40, out3) == -6                  # 64 groups = one stage, four splits asked
+    finally:
+        assert L.vlut_set_plan_g5(0, 0) == 0
+
+
+def test_packed_blob_must_be_16_byte_aligned(L):
+    d, odd = 0x1000, 0x1004
+    assert L.vlut_mpgemm(odd, 1.0, d, d, None, 8, 64, 40, d, 8, None, None, 0, None) == -6
+    assert L.vlut_mpgemm_rows(odd, d, d, d, None, 8, 64, 40, d, 8, None, None, 0, None) == -6
+    assert L.vlut_mpgemm_f32(odd, 1.0, None, d, 64, 8, 64, 40, d, 8, None, None, d, 1 << 20, None) == -6
+
+
 def test_plans_cover_all_benchmark_shapes(L):
     out = (ci * 4)()
     shapes = [(256, 256, 8), (6912, 2560, 128), (8640, 3200, 256), (3200, 8640, 256), (4096, 4096, 512),
