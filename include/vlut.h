@@ -182,6 +182,24 @@ int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const f
                 int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * vlut_mpgemm for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same numbers as vlut_mpgemm with
+ * lut_or_null == NULL; the split-K partial sums go to a scratch array that is part of the library's device image
+ * (VLUT_STATIC_SCRATCH_BYTES per GPU the library runs on, held until the process ends).  The call allocates
+ * nothing and frees nothing; the first call on a device looks the array's address up once.
+ *   arguments      as in vlut_mpgemm (no lut, no workspace)
+ *   returns        VLUT_ERR_UNSUPPORTED when vlut_workspace_bytes(M, K, N) exceeds VLUT_STATIC_SCRATCH_BYTES
+ *                  (nothing is launched then); otherwise as vlut_mpgemm
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams or threads)
+ * race on it and must be serialised by the caller; calls on one stream are ordered and safe.  Nothing is carried
+ * from one call to the next (each call overwrites every slot it later reads).
+ */
+#define VLUT_STATIC_SCRATCH_BYTES (32u << 20)
+size_t vlut_static_scratch_bytes(void);
+int vlut_mpgemm_static(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale, int64_t M,
+                       int64_t K, int64_t N, float* y, int64_t ldy, int32_t* acc_or_null, void* stream);
+
+/*
  * vlut_mpgemm for several weight matrices that multiply the same activations in one launch (the q/k/v or the
  * gate/up projections of a decoder layer).  The tables depend on the activations only (Eq. 1, Sec. 3.2), so the
  * matrices are stacked along M before vlut_pack_weights and share every table a workgroup builds; each output

@@ -30,7 +30,7 @@ EXPORTS = [
     "vlut_workspace_bytes_f32", "vlut_query_plan_f32", "vlut_mpgemm_f32",
     "vlut_build_lut_token_outer", "vlut_mpgemm_token_outer",
     "vlut_mixed_k5", "vlut_packed_weight_bytes_mixed", "vlut_workspace_bytes_mixed", "vlut_pack_weights_mixed",
-    "vlut_mpgemm_mixed",
+    "vlut_mpgemm_mixed", "vlut_static_scratch_bytes", "vlut_mpgemm_static",
 ]
 
 _lib = None
@@ -84,6 +84,8 @@ def lib() -> ctypes.CDLL:
         L.vlut_query_plan_f32.argtypes, L.vlut_query_plan_f32.restype = [i64, i64, i64, ctypes.POINTER(ci)], ci
         L.vlut_mpgemm_f32.argtypes = [p, cf, p, p, i64, i64, i64, i64, p, i64, p, p, p, sz, p]
         L.vlut_mpgemm_f32.restype = ci
+        L.vlut_static_scratch_bytes.argtypes, L.vlut_static_scratch_bytes.restype = [], sz
+        L.vlut_mpgemm_static.argtypes, L.vlut_mpgemm_static.restype = [p, cf, p, p, i64, i64, i64, p, i64, p, p], ci
         L.vlut_set_plan.argtypes, L.vlut_set_plan.restype = [ci, ci, ci, ci], ci
         L.vlut_query_plan.argtypes, L.vlut_query_plan.restype = [i64, i64, i64, ctypes.POINTER(ci)], ci
         _lib = L
@@ -195,6 +197,21 @@ def mpgemm(packed: torch.Tensor, w_scale: float, a_q: torch.Tensor, a_scale: tor
             _ptr(acc), _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
             _stream())
     _check(rc, "vlut_mpgemm_mfma" if mfma else "vlut_mpgemm")
+    return y, acc
+
+
+def static_scratch_bytes() -> int:
+    return lib().vlut_static_scratch_bytes()
+
+
+def mpgemm_static(packed: torch.Tensor, w_scale: float, a_q: torch.Tensor, a_scale: torch.Tensor, M: int,
+                  y: torch.Tensor, acc: Optional[torch.Tensor] = None):
+    """Runs vlut_mpgemm_static: the caller passes inputs and outputs only, the split-K scratch is the library's own
+    static device array; neither this wrapper nor the call allocates anything."""
+    K, N = a_q.shape[1], a_scale.shape[0]
+    rc = lib().vlut_mpgemm_static(_ptr(packed), float(w_scale), _ptr(a_q), _ptr(a_scale), M, K, N, _ptr(y), y.stride(0),
+                                  _ptr(acc), _stream())
+    _check(rc, "vlut_mpgemm_static")
     return y, acc
 
 

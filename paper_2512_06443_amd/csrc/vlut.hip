@@ -35,11 +35,34 @@
 #include "narrow_kernel.hip.h"
 #include "small_kernels.hip.h"
 
+// Scratch of vlut_mpgemm_static (split-K partial sums, INT32 [S][N][M]): device memory owned by the library, one
+// copy per GPU, held until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; every use of the memory goes through the per-device pointer kept below.
+static __device__ __align__(256) unsigned char scratch[VLUT_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 // ---------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, looked up once per device (with that device current).
+int static_scratch_ptr(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return VLUT_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return VLUT_ERR_DEVICE;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return VLUT_OK;
+}
+
 // Raises a kernel's dynamic LDS limit once per device (the limit is a property of the kernel on one device).
 // The table kernels form LDS addresses as idx*256 + slice*16 and so need their dynamic LDS segment to start at LDS
 // address 0, i.e. a kernel without static LDS: checked here, once per device, before the first launch (a kernel
@@ -763,6 +786,25 @@ int vlut_mpgemm(const uint8_t* packed, float w_scale, const int8_t* a_q, const f
                 int32_t* acc_or_null, void* workspace, size_t workspace_bytes, void* stream) {
     return mpgemm_impl(packed, w_scale, nullptr, a_q, a_scale, lut_or_null, M, K, N, y, ldy, acc_or_null, workspace,
                        workspace_bytes, stream);
+}
+
+size_t vlut_static_scratch_bytes(void) { return (size_t)VLUT_STATIC_SCRATCH_BYTES; }
+
+int vlut_mpgemm_static(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale, int64_t M, int64_t K,
+                       int64_t N, float* y, int64_t ldy, int32_t* acc_or_null, void* stream) {
+    int rc = check_mpgemm_args(packed, a_q, a_scale, M, K, N, y, ldy, acc_or_null);
+    if (rc != VLUT_OK) return rc;
+    const size_t need = vlut_workspace_bytes(M, K, N);
+    if (need > (size_t)VLUT_STATIC_SCRATCH_BYTES) return VLUT_ERR_UNSUPPORTED;   // partial sums beyond the built-in scratch
+    void* ptr = nullptr;
+    if (need > 0) {
+        rc = static_scratch_ptr(&ptr);
+        if (rc != VLUT_OK) return rc;
+    }
+    // Every partial-sum slot the second kernel reads is written by the first kernel of the same call, so nothing of
+    // an earlier call's contents has to be cleared.
+    return mpgemm_impl(packed, w_scale, nullptr, a_q, a_scale, nullptr, M, K, N, y, ldy, acc_or_null, ptr,
+                       need > 0 ? (size_t)VLUT_STATIC_SCRATCH_BYTES : 0, stream);
 }
 
 int vlut_mpgemm_rows(const uint8_t* packed, const float* w_scale_rows, const int8_t* a_q, const float* a_scale,
