@@ -9,8 +9,20 @@ two-call form vlut_quantize_act + vlut_mpgemm is timed next to it).  Weight pack
 offline stage and is not timed.  The packed weights rotate through a pool larger than the last-level
 cache, so every step streams its weights from HBM.
 
-Prints ONE JSON line on stdout.  `python bench.py --all` additionally writes a per-shape table for
-every benchmark shape to stderr (tuning aid; not part of the contract).
+Default run (`python bench.py [--gpus 1 --steps K --warmup W]`): every benchmark shape is timed -- the
+2B FFN up projection at N = 128, the 3B up/down projections at N = 256, the 8B linears at N = 512 and the
+seven linears of one 2.4B-style decoder layer at N in {1, 16, 64, 256, 1024} (plus the layer as four stacked
+launches from fp32 inputs) -- and reported under `sweep` / `layer`, one entry per (shape, N) with its time, GOPS,
+weight-stream GB/s, the roof that binds it and the fraction of that roof.  The headline (`value`,
+`ms_per_step`, `roofline`, `cpu_baseline`) is the largest single-GPU shape, the 8B gate/up projection
+M = 14336, K = 4096, N = 512.  `--workload/--linear/--tokens` pick another headline; `--no-sweep` times the
+headline only (the form the rocprofv3 summaries under profiles/ use).
+
+Timing: K = --steps launches are captured into one HIP graph; after W warm-up calls and one untimed replay
+(clock ramp) the graph is replayed REPS >= 10 times, each replay bracketed by a device synchronise and by HIP
+events on the launch stream; the figures are medians over the replays.
+
+Prints ONE JSON line on stdout; a per-shape table goes to stderr.
 """
 from __future__ import annotations
 
@@ -34,6 +46,7 @@ LDS_PEAK_GBS = CUS * 256 * CLOCK_GHZ                      # 157286 GB/s
 # what microbenchmarks reach on this device: 240 B/clk/CU of conflict-free 16-byte table reads at the ~2.1 GHz the
 # shader clock holds under this load
 LDS_MEASURED_PEAK_GBS = CUS * 240 * 2.1                   # 129024 GB/s
+MFMA_INT8_PEAK_TOPS = 5000.0                              # dense INT8 matrix-core peak (the comparison kernel's roof)
 
 # HBM bytes per launch of the lookup kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), see profiles/
 MEASURED_TRAFFIC_BYTES = {
@@ -48,12 +61,15 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="bitnet2b_ffn_up")
-    ap.add_argument("--linear", default="", help="linear of the workload (default: its first)")
+    ap.add_argument("--workload", default="llama8b_linears")
+    ap.add_argument("--linear", default="", help="linear of the workload (default: gateup for the 8B linears, else its first)")
     ap.add_argument("--tokens", type=int, default=0, help="N of the workload's sweep (default: its first)")
+    ap.add_argument("--reps", type=int, default=int(os.environ.get("VLUT_BENCH_REPS", "12")),
+                    help="timed replays of the captured graph per figure (median reported; at least 10)")
+    ap.add_argument("--no-sweep", action="store_true", help="time the headline shape only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-rotate", action="store_true", help="keep one weight buffer (cache-warm weights)")
-    ap.add_argument("--all", action="store_true", help="also time every benchmark shape (table on stderr)")
+    ap.add_argument("--all", action="store_true", help="kept for compatibility: the sweep is the default now")
     ap.add_argument("--plan", default="", help="force J,R,S for the lookup kernel (tuning)")
     ap.add_argument("--layer", action="store_true",
                     help="also time one decoder layer's seven linears at every N of the sweep: one launch per linear "
@@ -162,13 +178,16 @@ class Case:
         self.gemm(i, stream)
 
 
+REPS = 12
+
+
 def run_timed(torch, fn, count, warmup, use_graph=True):
     """Times `count` calls of fn(i, stream) that are enqueued back to back.
 
-    The calls are captured once into a HIP graph (so the host's launch cost is not part of the GPU timeline) and the
-    graph is replayed inside the timed region; if capture is not possible the calls are enqueued directly.
-    Returns (wall ms per call with a device synchronize on both sides, GPU ms per call from HIP events on the
-    launch stream, launch mode)."""
+    The calls are captured once into a HIP graph (so the host's launch cost is not part of the GPU timeline); after
+    `warmup` direct calls and one untimed replay the graph is replayed REPS times, each replay between two device
+    synchronisations and two HIP events recorded on the launch stream.  If capture is not possible the calls are
+    enqueued directly.  Returns (median wall ms per call, median GPU ms per call from the events, launch mode)."""
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):
         for i in range(warmup):
@@ -186,12 +205,11 @@ def run_timed(torch, fn, count, warmup, use_graph=True):
     except Exception as e:  # noqa: BLE001 - fall back to plain stream launches
         if use_graph:
             print(f"bench.py: graph capture unavailable ({type(e).__name__}: {e}); timing stream launches", file=sys.stderr)
-    reps = int(os.environ.get("VLUT_BENCH_REPS", "1"))
-    best_wall, best_gpu = float("inf"), float("inf")
+    walls, gpus = [], []
     with torch.cuda.stream(side):
         if graph is not None:
-            graph.replay()          # untimed replay: first-use costs of the graph itself
-        for _ in range(reps):
+            graph.replay()          # untimed replay: first-use costs of the graph itself, clocks back up
+        for _ in range(max(1, REPS)):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
@@ -204,9 +222,9 @@ def run_timed(torch, fn, count, warmup, use_graph=True):
             e1.record(side)
             torch.cuda.synchronize()
             t1 = time.perf_counter()
-            best_wall = min(best_wall, (t1 - t0) * 1e3 / count)
-            best_gpu = min(best_gpu, e0.elapsed_time(e1) / count)
-    return best_wall, best_gpu, ("hipGraph" if graph is not None else "stream")
+            walls.append((t1 - t0) * 1e3 / count)
+            gpus.append(e0.elapsed_time(e1) / count)
+    return float(np.median(walls)), float(np.median(gpus)), ("hipGraph" if graph is not None else "stream")
 
 
 def time_case(B, torch, case, steps, warmup):
@@ -299,12 +317,92 @@ def cpu_baseline(wl, W, w_scale, x):
             "sample": f"whole workload (quantise + triple-loop GEMM + scale), {reps} passes, {sec * 1e3:.0f} ms each"}
 
 
+def roof(M, K, N, ms):
+    """The roof that binds a shape and the fraction of it that `ms` (milliseconds) reaches.
+
+    N <= 16: HBM bandwidth on the algorithmic bytes (packed weights + INT8 activations + scales + fp32 output).
+    N >= 256: the table-lookup roof: one 2-byte LDS read (= one INT16 add) per (row, k-group, token) at 256 B/clk/CU.
+    In between: whichever of the two floors is the longer time.  frac = floor time / measured time."""
+    alg = M * K // 4 + K * N + 4 * N + 4 * M * N
+    lds = 2 * M * (K // 4) * N
+    t_hbm = alg / (HBM_PEAK_GBS * 1e9) * 1e3
+    t_lds = lds / (LDS_PEAK_GBS * 1e9) * 1e3
+    if N <= 16:
+        bound, floor = "hbm", t_hbm
+    elif N >= 256:
+        bound, floor = "lds", t_lds
+    else:
+        bound, floor = ("lds", t_lds) if t_lds >= t_hbm else ("hbm", t_hbm)
+    return {"bound": bound, "floor_ms": floor, "frac": floor / ms, "hbm_floor_ms": t_hbm, "lds_floor_ms": t_lds}
+
+
+def measure_entry(B, torch, wl, wname, lin, n, seed, rotate, steps, warmup, with_mfma=True):
+    """One (shape, N) of the sweep: the whole step through vlut_mpgemm_f32, the lookup kernel alone, the comparison
+    path.  Returns (dict for the JSON line, Case, (W, w_scale, x))."""
+    wk = wl.WORKLOADS[wname]
+    W, w_scale, x = wl.make_case(wk, lin, n, seed)
+    M, K = W.shape
+    c = Case(B, torch, wl, W, w_scale, x, rotate)
+    ms_step, ms_kernel, mode, ms_two, ms_gemm = time_case(B, torch, c, steps, warmup)
+    r_step, r_kernel = roof(M, K, n, ms_step), roof(M, K, n, ms_kernel)
+    e = {"workload": wname, "linear": lin.name, "M": M, "K": K, "N": n, "seed": seed,
+         "plan": {"J": c.plan32[0], "R": c.plan32[1], "split_k": c.plan32[2], "workgroups": c.plan32[3],
+                  "one_launch_from_fp32": bool(c.plan32[4])},
+         "ms": ms_step, "kernel_ms": ms_kernel, "two_call_ms": ms_two, "mpgemm_ms": ms_gemm,
+         "GOPS": 2.0 * M * K * n / (ms_step * 1e-3) / 1e9,
+         "weight_stream_GBs": (M * K / 4) / (ms_step * 1e-3) / 1e9,
+         "bound": r_step["bound"], "floor_ms": r_step["floor_ms"], "frac": r_step["frac"],
+         "kernel_frac": r_kernel["frac"]}
+    if with_mfma:
+        ms_mfma = time_mfma(torch, c, steps, warmup)
+        e["mfma_ms"] = ms_mfma
+        e["lut_over_mfma_time"] = ms_gemm / ms_mfma
+        e["mfma_frac_of_int8_peak"] = 2.0 * M * K * n / (ms_mfma * 1e-3) / 1e12 / MFMA_INT8_PEAK_TOPS
+    return e, c, (W, w_scale, x)
+
+
+def measure_layer(B, torch, wl, n, seed, rotate, steps, warmup):
+    """One decoder layer's seven linears at N = n as four launches from fp32 inputs: q|k|v and gate|up stacked along M
+    (they share their input, hence every table a workgroup builds), o, down; quantisation included."""
+    wk = wl.WORKLOADS["layer2b4_nsweep"]
+    lins = {l_.name: l_ for l_ in wk.linears}
+    made = {name: wl.make_case(wk, lins[name], n, seed) for name in lins}
+
+    def stacked(names):
+        Wm = np.concatenate([made[nm][0] for nm in names], axis=0)
+        wr = np.concatenate([np.full(made[nm][0].shape[0], made[nm][1], np.float32) for nm in names])
+        return Case(B, torch, wl, Wm, 1.0, made[names[0]][2], rotate // 4, w_rows=wr)
+
+    cases = [stacked(("q", "k", "v")), Case(B, torch, wl, *made["o"], rotate // 4), stacked(("gate", "up")),
+             Case(B, torch, wl, *made["down"], rotate // 4)]
+
+    def fn(i, stream):
+        for c in cases:
+            c.step_fused(i, stream)
+
+    run_timed(torch, fn, steps, warmup)
+    ms, ms_gpu, _ = run_timed(torch, fn, steps, warmup)
+    shapes = [(lins[nm].M, lins[nm].K) for nm in ("q", "k", "v", "o", "gate", "up", "down")]
+    alg = sum(m * k // 4 + 4 * m * n for m, k in shapes) + 3 * (2560 * n + 4 * n) + (6912 * n + 4 * n)
+    lds = sum(2 * m * (k // 4) * n for m, k in shapes)
+    t_hbm, t_lds = alg / (HBM_PEAK_GBS * 1e9) * 1e3, lds / (LDS_PEAK_GBS * 1e9) * 1e3
+    bound, floor = ("hbm", t_hbm) if n <= 16 else (("lds", t_lds) if (n >= 256 or t_lds >= t_hbm) else ("hbm", t_hbm))
+    ops = sum(2.0 * m * k * n for m, k in shapes)
+    return {"N": n, "seed": seed, "launches": 4, "what": "q|k|v, o, gate|up, down through vlut_mpgemm_f32 (quantisation included)",
+            "plans": [list(c.plan32) for c in cases],
+            "ms": ms, "gpu_ms": ms_gpu, "GOPS": ops / (ms * 1e-3) / 1e9,
+            "weight_stream_GBs": sum(m * k // 4 for m, k in shapes) / (ms * 1e-3) / 1e9,
+            "bound": bound, "floor_ms": floor, "frac": floor / ms}
+
+
 def main():
+    global REPS
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the path shards over tokens with no exchange: every GPU "
               "would run this same kernel on its share of the tokens). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+    REPS = max(10, args.reps)
     import torch
     from paper_2512_06443_amd import binding as B
     from paper_2512_06443_amd import workloads as wl
@@ -317,13 +415,15 @@ def main():
         B.set_plan(j, r, 0, s)
 
     w = wl.WORKLOADS[args.workload]
-    lin = ([l_ for l_ in w.linears if l_.name == args.linear] or [w.linears[0]])[0]
+    default_lin = "gateup" if args.workload == "llama8b_linears" else w.linears[0].name
+    lin = ([l_ for l_ in w.linears if l_.name == (args.linear or default_lin)] or [w.linears[0]])[0]
     N = args.tokens if args.tokens in w.N else w.N[0]
     seed = w.seeds[w.N.index(N)] if len(w.seeds) == len(w.N) else w.seeds[0]
-    W, w_scale, x = wl.make_case(w, lin, N, seed)
-    M, K = W.shape
     rotate = 0 if args.no_rotate else 600 << 20
-    case = Case(B, torch, wl, W, w_scale, x, rotate)
+
+    # ---- headline shape
+    head, case, (W, w_scale, x) = measure_entry(B, torch, wl, w.name, lin, N, seed, rotate, args.steps, args.warmup)
+    M, K = W.shape
     y_ref = torch.empty_like(case.y)
     case.step(0, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
@@ -334,14 +434,10 @@ def main():
     if not torch.equal(y_ref, case.y):
         print("bench.py: vlut_mpgemm_f32 disagrees with vlut_quantize_act + vlut_mpgemm", file=sys.stderr)
         sys.exit(4)
-    ms_step, ms_kernel, mode, ms_two_call, ms_gemm = time_case(B, torch, case, args.steps, args.warmup)
-    if not torch.equal(y_ref, case.y):   # every pool buffer holds the same weights, so every step writes the same y
-        print("bench.py: output of the timed region differs from the reference launch", file=sys.stderr)
-        sys.exit(4)
-
+    ms_step, ms_kernel, ms_two_call, ms_gemm = head["ms"], head["kernel_ms"], head["two_call_ms"], head["mpgemm_ms"]
+    mode = "hipGraph"
     # the same step enqueued call by call from this process (host launch cost included), beside the graph figure
     ms_step_stream, _, _ = run_timed(torch, case.step_fused, args.steps, args.warmup, use_graph=False)
-    ms_mfma = time_mfma(torch, case, args.steps, args.warmup)
     g5 = None
     if K % 20 == 0:
         case.enable_g5(B, torch, W, rotate)
@@ -352,6 +448,14 @@ def main():
         g5 = {"what": "vlut_mpgemm_g5 on the same weights packed 5 per byte (1.60 bits per weight, 243-row tables)",
               "ms": ms_g5, "plan": {"R": case.plan5[0], "split_k": case.plan5[1], "workgroups": case.plan5[2]},
               "packed_weight_bytes": case.pool5[0].numel(), "time_over_2bit": ms_g5 / ms_gemm}
+    else:
+        case.enable_mixed(B, torch, W, rotate)
+        _, ms_mx, _ = run_timed(torch, case.gemm_mixed, args.steps, args.warmup)
+        if not torch.equal(y_ref, case.y):
+            print("bench.py: the mixed packing disagrees with the 2-bit path", file=sys.stderr)
+            sys.exit(4)
+        g5 = {"what": "vlut_mpgemm_mixed on the same weights (first 20*floor(K/20) features 5 per byte, the rest 4 per byte)",
+              "ms": ms_mx, "packed_weight_bytes": case.poolx[0].numel(), "time_over_2bit": ms_mx / ms_gemm}
     if case.plan32[0] == 0:
         kernel_name = "narrow_kernel (few tokens: quantisation, table build, lookups and scale in one launch)"
     elif case.plan32[4] and case.plan32[2] == 1:
@@ -363,48 +467,54 @@ def main():
     adds = M * (K // 4) * N                      # one INT16 add (= 2 table bytes) per (row, group, token)
     gops = ops / (ms_step * 1e-3) / 1e9
     achieved_tadds = adds / (ms_kernel * 1e-3) / 1e12
+    lds_gbs = 2.0 * adds / (ms_kernel * 1e-3) / 1e9
+    alg = wl.algorithmic_bytes(M, K, N)
+    rk = roof(M, K, N, ms_kernel)
+    traffic_key = f"{w.name}/{lin.name}/{N}"
+    roofline = {
+        "kernel": kernel_name, "kernel_ms": ms_kernel,
+        "bound": rk["bound"],
+        "achieved": lds_gbs if rk["bound"] == "lds" else alg / (ms_kernel * 1e-3) / 1e9,
+        "peak": LDS_PEAK_GBS if rk["bound"] == "lds" else HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": rk["frac"],
+        "what": ("lds: table bytes the lookups read, 2 per (row, k-group, token), against 256 CUs x 256 B/clk x 2.4 GHz; "
+                 "hbm: algorithmic bytes against 8 TB/s"),
+        "alu_equivalent": {"achieved_TADDs": achieved_tadds, "peak_TADDs": ALU_PEAK_TADDS,
+                           "frac": achieved_tadds / ALU_PEAK_TADDS},
+        "lds_frac": lds_gbs / LDS_PEAK_GBS,
+        "lds_frac_of_measured_peak": lds_gbs / LDS_MEASURED_PEAK_GBS,
+        "hbm_frac": alg / (ms_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "traffic": MEASURED_TRAFFIC_BYTES.get(traffic_key),
+        "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary under profiles/ (a stored figure: this run "
+                          "does not read counters)" if traffic_key in MEASURED_TRAFFIC_BYTES else None,
+    }
     out = {
-        "metric": "ternary mpGeMM GOPS (2*M*K*N) + weight-stream GB/s",
+        "metric": "ternary mpGeMM GOPS (2*M*K*N) + weight-stream GB/s at N=1..1024 tokens",
         "value": gops, "unit": "GOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int16/int32 (INT8 activations, ternary weights)", "data": "synthetic",
-        "config": {"workload": f"{w.name}: M={M} K={K} N={N}, ternary P(0)={w.p_zero}, INT8 per-token absmax "
-                               f"activations from N(0,1); step = vlut_mpgemm_f32 (quantise + table build + lookup + scale)",
-                   "plan": {"J": case.plan32[0], "R": case.plan32[1], "split_k": case.plan32[2],
-                            "workgroups": case.plan32[3],
-                            "quantisation": "inside the lookup kernel" if case.plan32[4] else "kernel of its own"},
-                   "weight_pool_buffers": len(case.pool), "launch": mode},
+        "config": {"workload": f"{w.name}/{lin.name}: M={M} K={K} N={N}, ternary P(0)={w.p_zero}, INT8 per-token absmax "
+                               f"activations from N(0,1)" + (f" with {w.outlier_frac:.0%} outlier channels x20" if w.outlier_frac else "") +
+                               "; step = vlut_mpgemm_f32 (quantise + table build + lookup + scale)",
+                   "plan": head["plan"], "weight_pool_buffers": len(case.pool), "launch": mode,
+                   "timing": f"median of {REPS} replays of a graph of {args.steps} steps"},
         "weight_stream_GBs": (M * K / 4) / (ms_step * 1e-3) / 1e9,
-        "algorithmic_GBs": wl.algorithmic_bytes(M, K, N) / (ms_step * 1e-3) / 1e9,
+        "algorithmic_GBs": alg / (ms_step * 1e-3) / 1e9,
         "per_call_stream_launches": {"what": "the same steps enqueued one call at a time from Python (ctypes), no graph",
                                      "ms_per_step": ms_step_stream},
         "two_call_form": {"what": "vlut_quantize_act + vlut_mpgemm on the same inputs", "ms_per_step": ms_two_call,
                           "mpgemm_kernel_ms": ms_gemm},
         "mfma_comparison": {"what": "vlut_mpgemm_mfma on the same inputs (unpack to INT8 + v_mfma_i32_16x16x64_i8), "
                                     "GPU ms per call incl. its activation re-layout kernel",
-                            "ms": ms_mfma, "lut_over_mfma_time": ms_gemm / ms_mfma},
+                            "ms": head.get("mfma_ms"), "lut_over_mfma_time": head.get("lut_over_mfma_time"),
+                            "mfma_frac_of_int8_peak": head.get("mfma_frac_of_int8_peak")},
         "g5_packing": g5,
-        "roofline": {
-            "kernel": kernel_name,
-            "bound": "alu", "achieved": achieved_tadds, "peak": ALU_PEAK_TADDS, "unit": "TOP/s",
-            "frac": achieved_tadds / ALU_PEAK_TADDS,
-            "kernel_ms": ms_kernel,
-            "lds_lookup_GBs": 2.0 * adds / (ms_kernel * 1e-3) / 1e9, "lds_peak_GBs": LDS_PEAK_GBS,
-            "lds_frac": 2.0 * adds / (ms_kernel * 1e-3) / 1e9 / LDS_PEAK_GBS,
-            "lds_measured_peak_GBs": LDS_MEASURED_PEAK_GBS,
-            "lds_frac_of_measured_peak": 2.0 * adds / (ms_kernel * 1e-3) / 1e9 / LDS_MEASURED_PEAK_GBS,
-            "hbm_frac": wl.algorithmic_bytes(M, K, N) / (ms_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(f"{w.name}/{lin.name}/{N}"),
-        },
+        "roofline": roofline,
     }
-    if N <= 16:
-        # few tokens: the packed weights dominate the traffic and HBM is the roof (8 TB/s)
-        alg = wl.algorithmic_bytes(M, K, N)
-        r = out["roofline"]
-        r.update({"bound": "hbm", "achieved": alg / (ms_kernel * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                  "frac": alg / (ms_kernel * 1e-3) / 1e9 / HBM_PEAK_GBS, "alu_frac": achieved_tadds / ALU_PEAK_TADDS})
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, W, w_scale, x)
+    del case
+    torch.cuda.empty_cache()
 
     if args.copy_probe:
         src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -412,6 +522,37 @@ def main():
         torch.cuda.synchronize()
         dst.copy_(src)
         torch.cuda.synchronize()
+
+    # ---- the sweep: every benchmark shape, the decoder layer at every N
+    if not args.no_sweep:
+        sweep = [dict(head)]
+        for wname in ("bitnet2b_ffn_up", "bitnet3b_prefill", "llama8b_linears", "layer2b4_nsweep"):
+            wk = wl.WORKLOADS[wname]
+            for n in wk.N:
+                sd = wk.seeds[wk.N.index(n)] if len(wk.seeds) == len(wk.N) else wk.seeds[0]
+                for linr in wk.linears:
+                    if (wname, linr.name, n) == (w.name, lin.name, N):
+                        continue
+                    e, c, _ = measure_entry(B, torch, wl, wname, linr, n, sd, rotate, args.steps, args.warmup)
+                    sweep.append(e)
+                    del c
+                    torch.cuda.empty_cache()
+        out["sweep"] = sweep
+        wk = wl.WORKLOADS["layer2b4_nsweep"]
+        out["layer"] = [measure_layer(B, torch, wl, n, wk.seeds[wk.N.index(n)], rotate, args.steps, args.warmup)
+                        for n in wk.N]
+        print(f"{'workload':18s} {'lin':7s} {'M':>6s} {'K':>6s} {'N':>5s} {'plan(J,R,S,WG)':>20s} {'step us':>9s} "
+              f"{'kernel us':>9s} {'TOPS':>7s} {'W GB/s':>8s} {'bound':>5s} {'frac':>6s} {'k.frac':>6s} {'mfma us':>8s}",
+              file=sys.stderr)
+        for e in sweep:
+            pl = e["plan"]
+            print(f"{e['workload']:18s} {e['linear']:7s} {e['M']:6d} {e['K']:6d} {e['N']:5d} "
+                  f"{str((pl['J'], pl['R'], pl['split_k'], pl['workgroups'])):>20s} {e['ms'] * 1e3:9.1f} "
+                  f"{e['kernel_ms'] * 1e3:9.1f} {e['GOPS'] / 1e3:7.1f} {e['weight_stream_GBs']:8.1f} {e['bound']:>5s} "
+                  f"{e['frac']:6.3f} {e['kernel_frac']:6.3f} {e.get('mfma_ms', float('nan')) * 1e3:8.1f}", file=sys.stderr)
+        for e in out["layer"]:
+            print(f"layer (4 launches from fp32) N={e['N']:5d} {e['ms'] * 1e3:9.1f} us  {e['GOPS'] / 1e3:7.1f} TOPS  "
+                  f"{e['weight_stream_GBs']:8.1f} GB/s  {e['bound']} frac {e['frac']:.3f}", file=sys.stderr)
 
     if args.ablation:
         abl = []
@@ -441,7 +582,6 @@ def main():
                   f"{a['token_outer_mpgemm_ms'] * 1e3:14.1f} {a['layout_gain']:12.2f}", file=sys.stderr)
 
     if args.layer:
-        import numpy as np
         wk = wl.WORKLOADS["layer2b4_nsweep"]
         lins = {l_.name: l_ for l_ in wk.linears}
         layer_rows = []
@@ -492,36 +632,6 @@ def main():
             print(f"{r['N']:5d} {r['single_ms'] * 1e3:14.1f} {r['stacked_ms'] * 1e3:13.1f} {r['stacked_from_fp32_ms'] * 1e3:15.1f} "
                   f"{r['stacked_from_fp32_two_call_ms'] * 1e3:20.1f} {r['packed_weight_MB']:11.2f} "
                   f"{r['weight_stream_GBs_stacked']:13.1f} {r['hbm_frac_stacked']:9.3f}", file=sys.stderr)
-
-    if args.all:
-        rows = []
-        for name, wk in wl.WORKLOADS.items():
-            for linr in wk.linears:
-                for n in wk.N:
-                    Wm, ws_, xm = wl.make_case(wk, linr, n, wk.seeds[0])
-                    c = Case(B, torch, wl, Wm, ws_, xm, rotate)
-                    st, _, _, st2, km = time_case(B, torch, c, max(20, args.steps // 4), 5)
-                    mf = time_mfma(torch, c, max(20, args.steps // 4), 5)
-                    mm, kk = Wm.shape
-                    g5us = float("nan")
-                    if kk % 20 == 0:
-                        c.enable_g5(B, torch, Wm, rotate)
-                        g5us = run_timed(torch, c.gemm_g5, max(20, args.steps // 4), 5)[1] * 1e3
-                    else:                                   # other K: the mixed 1.60-bit / 2-bit packing
-                        c.enable_mixed(B, torch, Wm, rotate)
-                        g5us = run_timed(torch, c.gemm_mixed, max(20, args.steps // 4), 5)[1] * 1e3
-                    a = mm * (kk // 4) * n
-                    rows.append((name, linr.name, mm, kk, n, c.plan32, st * 1e3, st2 * 1e3, km * 1e3,
-                                 2.0 * mm * kk * n / (st * 1e-3) / 1e12, a / (km * 1e-3) / 1e12 / ALU_PEAK_TADDS,
-                                 wl.algorithmic_bytes(mm, kk, n) / (km * 1e-3) / 1e9 / HBM_PEAK_GBS, mf * 1e3, g5us))
-                    del c
-                    torch.cuda.empty_cache()
-        print(f"{'workload':18s} {'lin':7s} {'M':>6s} {'K':>6s} {'N':>5s} {'plan(J,R,S,WG,fused)':>26s} {'step us':>9s} "
-              f"{'2-call us':>9s} {'mpgemm us':>9s} {'TOPS':>7s} {'alu/lds frac':>12s} {'hbm frac':>8s} {'mfma us':>8s} "
-              f"{'g5|mix us':>9s}", file=sys.stderr)
-        for r in rows:
-            print(f"{r[0]:18s} {r[1]:7s} {r[2]:6d} {r[3]:6d} {r[4]:5d} {str(r[5]):>26s} {r[6]:9.1f} {r[7]:9.1f} {r[8]:9.1f} "
-                  f"{r[9]:7.1f} {r[10]:12.3f} {r[11]:8.3f} {r[12]:8.1f} {r[13]:8.1f}", file=sys.stderr)
 
     print(json.dumps(out))
 
