@@ -155,6 +155,23 @@ __device__ __forceinline__ void wg_barrier_lds() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// ---- two INT16 values in one 32-bit word, "carry-compensated": word = 65536 * hi + lo as a plain integer (the
+// stored high half is hi - 1 when lo is negative).  Sums of such words, formed with ordinary 32-bit additions (also
+// the three-operand ones), are 65536 * sum(hi) + sum(lo) exactly, and both sums are recovered as long as each stays
+// inside INT16 -- which is what the block bound of Sec. 3.4 guarantees for up to 64 lookups of |entry| <= 508.
+// The main lookup kernel keeps its LDS table entries and its block accumulators in this form: one v_add3_u32 then
+// adds the entries of two lookups (four INT16 values) to an accumulator.
+__device__ __forceinline__ int word_lo(int w) { return (int)(short)w; }
+__device__ __forceinline__ int word_hi(int w) { return (w - (int)(short)w) >> 16; }
+// Bytes 2h and 2h+1 of x (two INT8 activations of neighbouring tokens) as one such word.
+__device__ __forceinline__ int unpack_word(unsigned x, int h) {
+    const int lo = (int)(signed char)(x >> (16 * h));
+    const int hi = (int)(signed char)(x >> (16 * h + 8));
+    return (int)((unsigned)hi << 16) + lo;
+}
+// A bit-packed INT16 pair (low half = first value) as such a word.
+__device__ __forceinline__ int packed_to_word(int p) { return p + (int)((unsigned)((int)(short)p >> 15) << 16); }
+
 __device__ __forceinline__ s16x2 as_s16x2(int v) { return __builtin_bit_cast(s16x2, v); }
 __device__ __forceinline__ int as_int(s16x2 v) { return __builtin_bit_cast(int, v); }
 
@@ -163,6 +180,35 @@ __device__ __forceinline__ s16x2 unpack_pair(unsigned x, int h) {
     unsigned sel = h ? 0x070c060cu : 0x050c040cu;   // {0, byte, 0, byte}: value in the high byte of each half
     s16x2 v = as_s16x2((int)__builtin_amdgcn_perm(x, 0u, sel));
     return v >> (short)8;                            // arithmetic shift per half
+}
+
+// reduce16 for accumulators in word form: lane l ends with the total of token l >> 1.
+template <bool WIDE>
+__device__ __forceinline__ int reduce16w(const int (&aw)[4], const int (&a32)[8], int l) {
+    const bool hi3 = (l & 8) != 0, hi2 = (l & 4) != 0, hi1 = (l & 2) != 0;
+    int w[4];
+    if constexpr (!WIDE) {
+        const int kA = hi3 ? aw[2] : aw[0], kB = hi3 ? aw[3] : aw[1];
+        const int rA = lane_xor16<8>(hi3 ? aw[0] : aw[2]);
+        const int rB = lane_xor16<8>(hi3 ? aw[1] : aw[3]);
+        w[0] = word_lo(kA) + word_lo(rA);
+        w[1] = word_hi(kA) + word_hi(rA);
+        w[2] = word_lo(kB) + word_lo(rB);
+        w[3] = word_hi(kB) + word_hi(rB);
+    } else {
+        int v[8];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            v[2 * q] = word_lo(aw[q]) + a32[2 * q];
+            v[2 * q + 1] = word_hi(aw[q]) + a32[2 * q + 1];
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w[e] = (hi3 ? v[e + 4] : v[e]) + lane_xor16<8>(hi3 ? v[e] : v[e + 4]);
+    }
+    const int x0 = (hi2 ? w[2] : w[0]) + lane_xor7(hi2 ? w[0] : w[2]);
+    const int x1 = (hi2 ? w[3] : w[1]) + lane_xor7(hi2 ? w[1] : w[3]);
+    const int y1 = (hi1 ? x1 : x0) + lane_xor16<2>(hi1 ? x0 : x1);
+    return y1 + lane_xor16<1>(y1);
 }
 
 }  // namespace

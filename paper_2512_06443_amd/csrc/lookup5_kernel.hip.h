@@ -42,6 +42,18 @@ __device__ __forceinline__ i32x4 lookup5_read(const unsigned (&w)[R], unsigned l
     return lds_read128<(B & 1) * (kSlot5Bytes / 16)>(addr);
 }
 
+// Adds the 8 entries of one table read to the row group's packed INT16 accumulators (Alg. 1 lines 3-6).
+template <int R, int I>
+__device__ __forceinline__ void lookup_accumulate(s16x2 (&acc16)[R][4], const i32x4 v) {
+    constexpr int r = I % R;
+    // instructions with the accumulator tied to one register ("+v"): the unrolled copies of a stage must not keep
+    // the accumulators in alternating register sets
+    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][0]) : "v"(v.x));
+    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][1]) : "v"(v.y));
+    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][2]) : "v"(v.z));
+    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][3]) : "v"(v.w));
+}
+
 template <int R, int B, int NB, int K0>
 __device__ __forceinline__ void lookup5_batches(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4],
                                                 i32x4 (&cur)[NB]) {

@@ -10,8 +10,9 @@ namespace {
 // Roles inside the 16-wave workgroup: waves 0..3 (one per SIMD) only BUILD tables, waves 4..15 only LOOK UP.
 // The four LDS slots are used as two halves of two slots each: while the lookup waves read one half, the build
 // waves fill the other half with the next two sub-table sets, and one barrier per half-stage hands the halves over.
-// The lookups are bound by VALU issue (one address permute + four packed adds per 16-byte table read), the build
-// by LDS write bandwidth, so the two overlap well.
+// Table entries and block accumulators are words of two INT16 values each (word_lo / word_hi), so that one
+// three-operand 32-bit add accumulates the entries of two lookups: per lookup one address permute, one 16-byte
+// table read and two adds.
 //   R       row groups (of 4 output rows) per lookup wave; workgroup tile = up to 48*R rows
 //   NEED32  more than 64 lookups per lane: widen INT16 block sums into INT32 every 16 stages
 //   MODE    kFast: tables built in LDS from the token-chunked INT8 activations (streamed, the hot path)
@@ -33,87 +34,49 @@ constexpr int kBuildWaves = 4;
 constexpr int kLookupWaves = kWaves - kBuildWaves;     // 12
 constexpr int kRoundRows = kLookupWaves * 4;           // 48 output rows per row-group round of the workgroup
 
-// Issues the table read of lookup number I of half-stage HALF (b-major: I = b*R + r, b = 0,1).  Byte 2*HALF + b of
-// the row group's weight dword is the row of slot 2*HALF + b; the lane reads its 16-byte slice (8 INT16 entries).
-template <int R, int HALF, int I>
-__device__ __forceinline__ i32x4 lookup_read(const unsigned (&w)[R], unsigned lanebase) {
-    constexpr int slot = 2 * HALF + I / R, r = I % R;
-    constexpr unsigned sel = 0x0c0c0000u | ((4u + (unsigned)slot) << 8);
-    const unsigned addr = __builtin_amdgcn_perm(w[r], lanebase, sel);   // idx*256 + slice*16
-    return lds_read128<slot * (kSlotBytes / 16)>(addr);
+// The two table reads of row group RR in half-stage HALF (slots 2*HALF and 2*HALF + 1): bytes 2*HALF and 2*HALF + 1 of
+// the row group's weight dword are the table rows; the lane reads its 16-byte slice (8 entries) of each.
+template <int R, int HALF, int RR>
+__device__ __forceinline__ void lookup_read_pair(const unsigned (&w)[R], unsigned lanebase, i32x4& a, i32x4& b) {
+    constexpr unsigned selA = 0x0c0c0000u | ((4u + (unsigned)(2 * HALF)) << 8);
+    constexpr unsigned selB = 0x0c0c0000u | ((4u + (unsigned)(2 * HALF + 1)) << 8);
+    const unsigned addrA = __builtin_amdgcn_perm(w[RR], lanebase, selA);   // idx*256 + slice*16
+    const unsigned addrB = __builtin_amdgcn_perm(w[RR], lanebase, selB);
+    a = lds_read128<(2 * HALF) * (kSlotBytes / 16)>(addrA);
+    b = lds_read128<(2 * HALF + 1) * (kSlotBytes / 16)>(addrB);
 }
 
-template <int R, int I>
-__device__ __forceinline__ void lookup_accumulate(s16x2 (&acc16)[R][4], const i32x4 v) {
-    constexpr int r = I % R;
+// Adds the entries of two lookups to the row group's accumulators: entries and accumulators are words of two INT16
+// values (see word_lo / word_hi), so one three-operand 32-bit add does four INT16 additions (Alg. 1 lines 3-6: one
+// shared index, one vector add over the tokens).
+template <int R, int RR>
+__device__ __forceinline__ void lookup_accumulate_pair(int (&accw)[R][4], const i32x4 a, const i32x4 b) {
     // Written as instructions with the accumulator tied to one register ("+v"): left to the register allocator, the
     // unrolled copies of the stage keep the accumulators in alternating register sets, which doubles their
     // footprint and caps the row groups a wave can hold.
-    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][0]) : "v"(v.x));
-    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][1]) : "v"(v.y));
-    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][2]) : "v"(v.z));
-    asm volatile("v_pk_add_u16 %0, %0, %1" : "+v"(acc16[r][3]) : "v"(v.w));
+    asm volatile("v_add3_u32 %0, %0, %1, %2" : "+v"(accw[RR][0]) : "v"(a.x), "v"(b.x));
+    asm volatile("v_add3_u32 %0, %0, %1, %2" : "+v"(accw[RR][1]) : "v"(a.y), "v"(b.y));
+    asm volatile("v_add3_u32 %0, %0, %1, %2" : "+v"(accw[RR][2]) : "v"(a.z), "v"(b.z));
+    asm volatile("v_add3_u32 %0, %0, %1, %2" : "+v"(accw[RR][3]) : "v"(a.w), "v"(b.w));
 }
 
-// The 2*R lookups of a half-stage, software pipelined in batches of NB: the reads of batch k+1 are in flight while
-// the packed INT16 adds of batch k issue (Alg. 1 lines 3-6: one shared index, one vector add over the tokens).
-template <int R, int HALF, int NB, int K0>
-__device__ __forceinline__ void lookup_batches(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4],
-                                               i32x4 (&cur)[NB]) {
-    constexpr int total = 2 * R;
-    if constexpr (K0 < total) {
-        i32x4 nxt[NB];
-#pragma unroll
-        for (int i = 0; i < NB; ++i) nxt[i] = i32x4{0, 0, 0, 0};
-        if constexpr (K0 + NB + 0 < total && NB > 0) nxt[0] = lookup_read<R, HALF, (K0 + NB + 0 < total ? K0 + NB + 0 : 0)>(w, lanebase);
-        if constexpr (K0 + NB + 1 < total && NB > 1) nxt[1] = lookup_read<R, HALF, (K0 + NB + 1 < total ? K0 + NB + 1 : 0)>(w, lanebase);
-        if constexpr (K0 + NB + 2 < total && NB > 2) nxt[2] = lookup_read<R, HALF, (K0 + NB + 2 < total ? K0 + NB + 2 : 0)>(w, lanebase);
-        if constexpr (K0 + NB + 3 < total && NB > 3) nxt[3] = lookup_read<R, HALF, (K0 + NB + 3 < total ? K0 + NB + 3 : 0)>(w, lanebase);
-        __builtin_amdgcn_sched_barrier(0);
-        if constexpr (K0 + 0 < total && NB > 0) lookup_accumulate<R, (K0 + 0 < total ? K0 + 0 : 0)>(acc16, cur[0]);
-        if constexpr (K0 + 1 < total && NB > 1) lookup_accumulate<R, (K0 + 1 < total ? K0 + 1 : 0)>(acc16, cur[1]);
-        if constexpr (K0 + 2 < total && NB > 2) lookup_accumulate<R, (K0 + 2 < total ? K0 + 2 : 0)>(acc16, cur[2]);
-        if constexpr (K0 + 3 < total && NB > 3) lookup_accumulate<R, (K0 + 3 < total ? K0 + 3 : 0)>(acc16, cur[3]);
-        __builtin_amdgcn_sched_barrier(0);
-        lookup_batches<R, HALF, NB, K0 + NB>(w, lanebase, acc16, nxt);
-    }
-}
-
+// The 2*R lookups of a half-stage as a rolling pipeline over the row groups: the reads of D row groups are in flight
+// while the adds of the oldest one issue.
 template <int R, int HALF>
-__device__ __forceinline__ void lookup_half(const unsigned (&w)[R], unsigned lanebase, s16x2 (&acc16)[R][4]) {
-    constexpr int NB = R > 14 ? 2 : 4;   // table reads in flight; the widest instances have no registers for four
-    constexpr int total = 2 * R;
-    i32x4 first[NB];
-#pragma unroll
-    for (int i = 0; i < NB; ++i) first[i] = i32x4{0, 0, 0, 0};
-    first[0] = lookup_read<R, HALF, 0>(w, lanebase);
-    if constexpr (total > 1) first[1] = lookup_read<R, HALF, 1>(w, lanebase);
-    if constexpr (total > 2 && NB > 2) first[2] = lookup_read<R, HALF, (total > 2 ? 2 : 0)>(w, lanebase);
-    if constexpr (total > 3 && NB > 3) first[3] = lookup_read<R, HALF, (total > 3 ? 3 : 0)>(w, lanebase);
+__device__ __forceinline__ void lookup_half(const unsigned (&w)[R], unsigned lanebase, int (&accw)[R][4]) {
+    constexpr int D = R > 14 ? 2 : 3;   // row groups (pairs of table reads) in flight; the widest instances have registers for two
+    i32x4 bufA[D], bufB[D];
+    static_for<0, D>([&](auto ic_) {
+        constexpr int i = decltype(ic_)::value;
+        if constexpr (i < R) lookup_read_pair<R, HALF, (i < R ? i : 0)>(w, lanebase, bufA[i], bufB[i]);
+    });
     __builtin_amdgcn_sched_barrier(0);
-    lookup_batches<R, HALF, NB, 0>(w, lanebase, acc16, first);
-}
-
-// Nine table rows that share their two leading digits (b1 = their common part): the third and fourth digits add or
-// subtract a2 and a3.  Row offsets 0..8 from dst.
-__device__ __forceinline__ void build_rows9(unsigned dst, const s16x2 (&b1)[4], const s16x2 (&a2)[4],
-                                            const s16x2 (&a3)[4]) {
-    s16x2 u[4], lo[4], hi[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) { u[q] = b1[q] - a2[q]; lo[q] = u[q] - a3[q]; hi[q] = u[q] + a3[q]; }
-    lds_write128<0 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
-    lds_write128<1 * 16>(dst, i32x4{as_int(u[0]), as_int(u[1]), as_int(u[2]), as_int(u[3])});
-    lds_write128<2 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
-#pragma unroll
-    for (int q = 0; q < 4; ++q) { lo[q] = b1[q] - a3[q]; hi[q] = b1[q] + a3[q]; }
-    lds_write128<3 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
-    lds_write128<4 * 16>(dst, i32x4{as_int(b1[0]), as_int(b1[1]), as_int(b1[2]), as_int(b1[3])});
-    lds_write128<5 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
-#pragma unroll
-    for (int q = 0; q < 4; ++q) { u[q] = b1[q] + a2[q]; lo[q] = u[q] - a3[q]; hi[q] = u[q] + a3[q]; }
-    lds_write128<6 * 16>(dst, i32x4{as_int(lo[0]), as_int(lo[1]), as_int(lo[2]), as_int(lo[3])});
-    lds_write128<7 * 16>(dst, i32x4{as_int(u[0]), as_int(u[1]), as_int(u[2]), as_int(u[3])});
-    lds_write128<8 * 16>(dst, i32x4{as_int(hi[0]), as_int(hi[1]), as_int(hi[2]), as_int(hi[3])});
+    static_for<0, R>([&](auto ic_) {
+        constexpr int i = decltype(ic_)::value;
+        lookup_accumulate_pair<R, i>(accw, bufA[i % D], bufB[i % D]);
+        if constexpr (i + D < R) lookup_read_pair<R, HALF, (i + D < R ? i + D : 0)>(w, lanebase, bufA[i % D], bufB[i % D]);
+        __builtin_amdgcn_sched_barrier(0);
+    });
 }
 
 template <int R, bool NEED32, int MODE>
@@ -249,12 +212,12 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         wg_barrier_lds();
     };
 
-    s16x2 acc16[R][4];
+    int accw[R][4];                       // block sums: two INT16 sums per word (word_lo / word_hi)
     int acc32[NEED32 ? R : 1][8];
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) acc16[r][q] = s16x2{0, 0};
+        for (int q = 0; q < 4; ++q) accw[r][q] = 0;
     if (NEED32) {
 #pragma unroll
         for (int r = 0; r < R; ++r)
@@ -302,73 +265,46 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
             }
         };
 
-        auto build_half = [&](int hs, unsigned (&act)[4][2], bool valid) {
+        // kFromGlobal only: copies the lane's rows of half-stage hs from the materialised table (bit-packed INT16
+        // pairs there, words here)
+        auto build_half = [&](int hs) {
             const unsigned slot = (unsigned)(2 * (hs & 1) + s2);
             const unsigned dst = slot * kSlotBytes + (unsigned)l * 16u;
-            if (MODE == kFromGlobal) {
-                const int kg = (hs >> 1) * 4 * J + 4 * j + 2 * (hs & 1) + s2;
-                auto copy_row = [&](int row) {
-                    i32x4 v = {0, 0, 0, 0};
-                    if (kg < p.G && nb < p.N) {
-                        const int16_t* src = p.lut + ((size_t)kg * kRows + row) * p.N + nb;
-                        if (p.aligned8 && nb + 8 <= p.N) {
-                            v = *(const i32x4*)src;
-                        } else {
-                            int tmp[4] = {0, 0, 0, 0};
+            const int kg = (hs >> 1) * 4 * J + 4 * j + 2 * (hs & 1) + s2;
+            auto copy_row = [&](int row) {
+                i32x4 v = {0, 0, 0, 0};
+                if (kg < p.G && nb < p.N) {
+                    const int16_t* src = p.lut + ((size_t)kg * kRows + row) * p.N + nb;
+                    if (p.aligned8 && nb + 8 <= p.N) {
+                        v = *(const i32x4*)src;
+                    } else {
+                        int tmp[4] = {0, 0, 0, 0};
 #pragma unroll
-                            for (int e = 0; e < 8; ++e) {
-                                unsigned hw = (nb + e < p.N) ? (unsigned)(uint16_t)src[e] : 0u;
-                                tmp[e >> 1] |= (int)(hw << (16 * (e & 1)));
-                            }
-                            v = i32x4{tmp[0], tmp[1], tmp[2], tmp[3]};
+                        for (int e = 0; e < 8; ++e) {
+                            unsigned hw = (nb + e < p.N) ? (unsigned)(uint16_t)src[e] : 0u;
+                            tmp[e >> 1] |= (int)(hw << (16 * (e & 1)));
                         }
+                        v = i32x4{tmp[0], tmp[1], tmp[2], tmp[3]};
                     }
-                    lds_write128<0>(dst + (unsigned)row * kRowBytes, v);
-                };
-#pragma unroll
-                for (int i = 0; i < 9; ++i) copy_row(9 * u + i);
-                copy_row(72 + u);
-                if (u == 0) copy_row(80);
-            } else {
-                // Every row is one packed add/sub away from an earlier one (topological order, Sec. 4).
-                if (!valid) {
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
                 }
-                const short s0 = (short)(u / 3 - 1), s1 = (short)(u % 3 - 1);
-                const s16x2 m0 = {s0, s0}, m1 = {s1, s1};
-                const short e2 = (short)(u / 3 - 1), e3 = (short)(u % 3 - 1);    // digits (d2,d3) of the extra row 72+u
-                const s16x2 x2 = {e2, e2}, x3 = {e3, e3};
-                s16x2 a2[4], a3[4], b1[4], ex[4], top[4];
+                lds_write128<0>(dst + (unsigned)row * kRowBytes,
+                                i32x4{packed_to_word(v.x), packed_to_word(v.y), packed_to_word(v.z), packed_to_word(v.w)});
+            };
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const s16x2 a0 = unpack_pair(act[0][q >> 1], q & 1);
-                    const s16x2 a1 = unpack_pair(act[1][q >> 1], q & 1);
-                    a2[q] = unpack_pair(act[2][q >> 1], q & 1);
-                    a3[q] = unpack_pair(act[3][q >> 1], q & 1);
-                    b1[q] = a0 * m0 + a1 * m1;
-                    top[q] = a0 + a1;                               // leading digits (2,2)
-                    ex[q] = top[q] + a2[q] * x2 + a3[q] * x3;       // row 72 + 3*d2 + d3 with (d2,d3) = (u/3, u%3)
-                }
-                build_rows9(dst + (unsigned)(9 * u) * kRowBytes, b1, a2, a3);
-                lds_write128<0>(dst + (unsigned)(72 + u) * kRowBytes,
-                                i32x4{as_int(ex[0]), as_int(ex[1]), as_int(ex[2]), as_int(ex[3])});
-                if (u == 0) {
-                    lds_write128<80 * 16>(dst, i32x4{as_int(top[0] + a2[0] + a3[0]), as_int(top[1] + a2[1] + a3[1]),
-                                                      as_int(top[2] + a2[2] + a3[2]), as_int(top[3] + a2[3] + a3[3])});
-                }
-            }
+            for (int i = 0; i < 9; ++i) copy_row(9 * u + i);
+            copy_row(72 + u);
+            if (u == 0) copy_row(80);
         };
 
         const int hs0 = 2 * st_begin, hs1 = 2 * st_end;
         if constexpr (MODE == kFusedQuant) quantise_tile();
         if constexpr (MODE == kFromGlobal) {
-            if (hs0 < hs1) build_half(hs0, actA, validA);
+            if (hs0 < hs1) build_half(hs0);
             wg_barrier_lds();
             for (int hs = hs0; hs < hs1; hs += 2) {
-                build_half(hs + 1, actB, validB);     // lookups read half 0 now: fill half 1
+                build_half(hs + 1);                   // lookups read half 0 now: fill half 1
                 wg_barrier_lds();
-                if (hs + 2 < hs1) build_half(hs + 2, actA, validA);   // lookups read half 1 now: fill half 0
+                if (hs + 2 < hs1) build_half(hs + 2);                 // lookups read half 1 now: fill half 0
                 wg_barrier_lds();
             }
         } else {
@@ -377,29 +313,31 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
             // Rows are computed one half-stage ahead: after a barrier a build wave only has to issue its eleven
             // LDS writes, and it computes the next half-stage's rows while those writes drain.  Activations are
             // fetched four half-stages ahead of their use.
-            struct Rows { s16x2 r[9][4], ex[4], last[4]; };
+            struct Rows { int r[9][4], ex[4], last[4]; };
             unsigned act2[4][2], act3[4][2];
             bool valid2 = false, valid3 = false;
+            // Every row is one add or subtract away from an earlier one (topological order, Sec. 4); the arithmetic is
+            // plain 32-bit on words of two entries each (|word| < 2^23 for an activation, so the 24-bit multiplies
+            // by the digits -1, 0, +1 are exact).
             auto compute_rows = [&](unsigned (&act)[4][2], bool valid, Rows& rw) {
                 if (!valid) {
 #pragma unroll
                     for (int c = 0; c < 4; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
                 }
-                const short d0 = (short)(u / 3 - 1), d1 = (short)(u % 3 - 1);   // leading digits of rows 9u..9u+8,
-                const s16x2 m0 = {d0, d0}, m1 = {d1, d1};                         // and digits (d2,d3) of row 72+u
+                const int m0 = u / 3 - 1, m1 = u % 3 - 1;   // leading digits of rows 9u..9u+8, and digits (d2,d3) of row 72+u
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const s16x2 a0 = unpack_pair(act[0][q >> 1], q & 1);
-                    const s16x2 a1 = unpack_pair(act[1][q >> 1], q & 1);
-                    const s16x2 a2 = unpack_pair(act[2][q >> 1], q & 1);
-                    const s16x2 a3 = unpack_pair(act[3][q >> 1], q & 1);
-                    const s16x2 b1 = a0 * m0 + a1 * m1;
-                    const s16x2 top = a0 + a1;                          // leading digits (2,2)
-                    const s16x2 lo = b1 - a2, hi = b1 + a2;
+                    const int a0 = unpack_word(act[0][q >> 1], q & 1);
+                    const int a1 = unpack_word(act[1][q >> 1], q & 1);
+                    const int a2 = unpack_word(act[2][q >> 1], q & 1);
+                    const int a3 = unpack_word(act[3][q >> 1], q & 1);
+                    const int b1 = __mul24(a0, m0) + __mul24(a1, m1);
+                    const int top = a0 + a1;                            // leading digits (2,2)
+                    const int lo = b1 - a2, hi = b1 + a2;
                     rw.r[0][q] = lo - a3; rw.r[1][q] = lo; rw.r[2][q] = lo + a3;
                     rw.r[3][q] = b1 - a3; rw.r[4][q] = b1; rw.r[5][q] = b1 + a3;
                     rw.r[6][q] = hi - a3; rw.r[7][q] = hi; rw.r[8][q] = hi + a3;
-                    rw.ex[q] = top + a2 * m0 + a3 * m1;                 // row 72 + 3*d2 + d3 with (d2,d3) = (u/3, u%3)
+                    rw.ex[q] = top + __mul24(a2, m0) + __mul24(a3, m1);  // row 72 + 3*d2 + d3 with (d2,d3) = (u/3, u%3)
                     rw.last[q] = top + a2 + a3;                         // row 80
                 }
                 // Pin the finished rows in registers here, so that the arithmetic stays where it is written
@@ -417,12 +355,12 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                 const unsigned dst9 = dst + (unsigned)(9 * u) * kRowBytes;
                 static_for<0, 9>([&](auto ic_) {
                     constexpr int i = decltype(ic_)::value;
-                    lds_write128<i * 16>(dst9, i32x4{as_int(rw.r[i][0]), as_int(rw.r[i][1]), as_int(rw.r[i][2]), as_int(rw.r[i][3])});
+                    lds_write128<i * 16>(dst9, i32x4{rw.r[i][0], rw.r[i][1], rw.r[i][2], rw.r[i][3]});
                 });
                 lds_write128<0>(dst + (unsigned)(72 + u) * kRowBytes,
-                                i32x4{as_int(rw.ex[0]), as_int(rw.ex[1]), as_int(rw.ex[2]), as_int(rw.ex[3])});
+                                i32x4{rw.ex[0], rw.ex[1], rw.ex[2], rw.ex[3]});
                 if (u == 0) {
-                    lds_write128<80 * 16>(dst, i32x4{as_int(rw.last[0]), as_int(rw.last[1]), as_int(rw.last[2]), as_int(rw.last[3])});
+                    lds_write128<80 * 16>(dst, i32x4{rw.last[0], rw.last[1], rw.last[2], rw.last[3]});
                 }
             };
             Rows rows;
@@ -480,18 +418,18 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         };
         auto stage = [&](int st, unsigned (&w)[R], unsigned (&wnext)[R]) {
             load_weights(st + 1, wnext);
-            lookup_half<R, 0>(w, lanebase, acc16);
+            lookup_half<R, 0>(w, lanebase, accw);
             wg_barrier_lds();
-            lookup_half<R, 1>(w, lanebase, acc16);
+            lookup_half<R, 1>(w, lanebase, accw);
             wg_barrier_lds();
             if (NEED32 && (((st - st_begin) & 15) == 15)) {   // 16 stages x 4 lookups = block of 64 (Sec. 3.4)
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        acc32[r][2 * q] += (int)acc16[r][q].x;
-                        acc32[r][2 * q + 1] += (int)acc16[r][q].y;
-                        acc16[r][q] = s16x2{0, 0};
+                        acc32[r][2 * q] += word_lo(accw[r][q]);
+                        acc32[r][2 * q + 1] += word_hi(accw[r][q]);
+                        accw[r][q] = 0;
                     }
             }
         };
@@ -532,13 +470,13 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
             if (r < R && Jlog == 4) {
                 // both lanes of a pair hold the same total and store it to the same place
                 park[(l >> 1) * kParkStride + rr * kRoundRows + lw * 4 + grp] =
-                    reduce16<NEED32>(acc16[r], acc32[NEED32 ? r : 0], l);
+                    reduce16w<NEED32>(accw[r], acc32[NEED32 ? r : 0], l);
             } else if (r < R) {
                 int v[8];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    v[2 * q] = (int)acc16[r][q].x + (NEED32 ? acc32[r][2 * q] : 0);
-                    v[2 * q + 1] = (int)acc16[r][q].y + (NEED32 ? acc32[r][2 * q + 1] : 0);
+                    v[2 * q] = word_lo(accw[r][q]) + (NEED32 ? acc32[r][2 * q] : 0);
+                    v[2 * q + 1] = word_hi(accw[r][q]) + (NEED32 ? acc32[r][2 * q + 1] : 0);
                 }
                 // Reduce-scatter over the sub-table selector j (the top Jlog bits of the lane's slice index): each
                 // step exchanges half of the remaining tokens with the lane whose index differs in one bit.

@@ -245,68 +245,37 @@ int launch_lookup_t(const LookupParams& p, int grid, hipStream_t stream) {
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
 
-// The streamed kernels exist for every supported R; the variant that reads a materialised table only for a few
-// small R (the launcher maps R down).
+// Which instances of the lookup kernel are compiled: the streamed kernels for every supported R (the INT32-widening
+// and the quantising variants hold more state per wave and stop earlier), the variant that reads a materialised
+// table for a few small R only (the launcher maps R down).  VLUT_ONLY_R (a build-time macro for experiments)
+// restricts the streamed instances to one R.
+constexpr bool lookup_instance_built(int R, bool need32, int mode) {
+#ifdef VLUT_ONLY_R
+    if (mode != kFromGlobal && R != (VLUT_ONLY_R)) return false;
+#endif
+    if (mode == kFromGlobal) return R == 1 || R == 2 || R == 4;
+    if (need32) return R <= 6;
+    if (mode == kFusedQuant) return R <= kFusedMaxR;
+    return R <= 16;
+}
+
+template <bool NEED32, int MODE, int R = 1>
+int launch_lookup_by_r(int r, const LookupParams& p, int grid, hipStream_t stream) {
+    if constexpr (R > 16) {
+        return VLUT_ERR_UNSUPPORTED;
+    } else {
+        if constexpr (lookup_instance_built(R, NEED32, MODE)) {
+            if (r == R) return launch_lookup_t<R, NEED32, MODE>(p, grid, stream);
+        }
+        return launch_lookup_by_r<NEED32, MODE, R + 1>(r, p, grid, stream);
+    }
+}
+
 template <bool NEED32>
 int launch_lookup_r(int R, int mode, const LookupParams& p, int grid, hipStream_t stream) {
-    if (mode == kFusedQuant) {
-        switch (R) {
-        case 1: return launch_lookup_t<1, NEED32, kFusedQuant>(p, grid, stream);
-        case 2: return launch_lookup_t<2, NEED32, kFusedQuant>(p, grid, stream);
-        case 3: return launch_lookup_t<3, NEED32, kFusedQuant>(p, grid, stream);
-        case 4: return launch_lookup_t<4, NEED32, kFusedQuant>(p, grid, stream);
-        case 5: return launch_lookup_t<5, NEED32, kFusedQuant>(p, grid, stream);
-        case 6: return launch_lookup_t<6, NEED32, kFusedQuant>(p, grid, stream);
-        default: break;
-        }
-        if constexpr (!NEED32) {
-            switch (R) {
-            case 7: return launch_lookup_t<7, false, kFusedQuant>(p, grid, stream);
-            case 8: return launch_lookup_t<8, false, kFusedQuant>(p, grid, stream);
-            case 9: return launch_lookup_t<9, false, kFusedQuant>(p, grid, stream);
-            case 10: return launch_lookup_t<10, false, kFusedQuant>(p, grid, stream);
-            case 11: return launch_lookup_t<11, false, kFusedQuant>(p, grid, stream);
-            case 12: return launch_lookup_t<12, false, kFusedQuant>(p, grid, stream);
-            case 13: return launch_lookup_t<13, false, kFusedQuant>(p, grid, stream);
-            case 14: return launch_lookup_t<14, false, kFusedQuant>(p, grid, stream);
-            default: break;
-            }
-        }
-        return VLUT_ERR_UNSUPPORTED;
-    }
-    if (mode == kFast) {
-        switch (R) {
-        case 1: return launch_lookup_t<1, NEED32, kFast>(p, grid, stream);
-        case 2: return launch_lookup_t<2, NEED32, kFast>(p, grid, stream);
-        case 3: return launch_lookup_t<3, NEED32, kFast>(p, grid, stream);
-        case 4: return launch_lookup_t<4, NEED32, kFast>(p, grid, stream);
-        case 5: return launch_lookup_t<5, NEED32, kFast>(p, grid, stream);
-        case 6: return launch_lookup_t<6, NEED32, kFast>(p, grid, stream);
-        default: break;
-        }
-        if constexpr (!NEED32) {
-            switch (R) {
-            case 7: return launch_lookup_t<7, false, kFast>(p, grid, stream);
-            case 8: return launch_lookup_t<8, false, kFast>(p, grid, stream);
-            case 9: return launch_lookup_t<9, false, kFast>(p, grid, stream);
-            case 10: return launch_lookup_t<10, false, kFast>(p, grid, stream);
-            case 11: return launch_lookup_t<11, false, kFast>(p, grid, stream);
-            case 12: return launch_lookup_t<12, false, kFast>(p, grid, stream);
-            case 13: return launch_lookup_t<13, false, kFast>(p, grid, stream);
-            case 14: return launch_lookup_t<14, false, kFast>(p, grid, stream);
-            case 15: return launch_lookup_t<15, false, kFast>(p, grid, stream);
-            case 16: return launch_lookup_t<16, false, kFast>(p, grid, stream);
-            default: break;
-            }
-        }
-        return VLUT_ERR_UNSUPPORTED;
-    }
-    switch (R) {
-    case 1: return launch_lookup_t<1, NEED32, kFromGlobal>(p, grid, stream);
-    case 2: return launch_lookup_t<2, NEED32, kFromGlobal>(p, grid, stream);
-    case 4: return launch_lookup_t<4, NEED32, kFromGlobal>(p, grid, stream);
-    default: return VLUT_ERR_UNSUPPORTED;
-    }
+    if (mode == kFusedQuant) return launch_lookup_by_r<NEED32, kFusedQuant>(R, p, grid, stream);
+    if (mode == kFast) return launch_lookup_by_r<NEED32, kFast>(R, p, grid, stream);
+    return launch_lookup_by_r<NEED32, kFromGlobal>(R, p, grid, stream);
 }
 
 // Second kernel of a split-K (or mixed-packing) launch: four rows per thread when everything is aligned for it.
@@ -454,7 +423,7 @@ struct Plan5 {
     int R, S;
 };
 thread_local Plan5 t_forced5 = {0, 0};
-const int kSupportedR5[] = {1, 2, 4, 6, 9, 12, 14};
+constexpr int kSupportedR5[] = {1, 2, 4, 6, 9, 12, 14};
 
 bool shape5_ok(int64_t M, int64_t K, int64_t N) {
     return M >= 1 && N >= 1 && K >= 5 && (K % 5) == 0 && M < kMaxDim && K < kMaxDim && N < kMaxDim;
@@ -525,23 +494,29 @@ int launch_lookup5_t(const Lookup5Params& p, int grid, hipStream_t stream) {
 }
 
 template <bool NEED32>
-int launch_lookup5_r(int R, const Lookup5Params& p, int grid, hipStream_t stream) {
-    switch (R) {
-    case 1: return launch_lookup5_t<1, NEED32>(p, grid, stream);
-    case 2: return launch_lookup5_t<2, NEED32>(p, grid, stream);
-    case 4: return launch_lookup5_t<4, NEED32>(p, grid, stream);
-    case 6: return launch_lookup5_t<6, NEED32>(p, grid, stream);
-    default: break;
-    }
-    if constexpr (!NEED32) {
-        switch (R) {
-        case 9: return launch_lookup5_t<9, false>(p, grid, stream);
-        case 12: return launch_lookup5_t<12, false>(p, grid, stream);
-        case 14: return launch_lookup5_t<14, false>(p, grid, stream);
-        default: break;
+int launch_lookup5_r(int R, const Lookup5Params& p, int grid, hipStream_t stream);
+
+constexpr bool lookup5_instance_built(int R, bool need32) {
+    for (int v : kSupportedR5)
+        if (v == R) return !need32 || R <= 6;
+    return false;
+}
+
+template <bool NEED32, int R = 1>
+int launch_lookup5_by_r(int r, const Lookup5Params& p, int grid, hipStream_t stream) {
+    if constexpr (R > 14) {
+        return VLUT_ERR_UNSUPPORTED;
+    } else {
+        if constexpr (lookup5_instance_built(R, NEED32)) {
+            if (r == R) return launch_lookup5_t<R, NEED32>(p, grid, stream);
         }
+        return launch_lookup5_by_r<NEED32, R + 1>(r, p, grid, stream);
     }
-    return VLUT_ERR_UNSUPPORTED;
+}
+
+template <bool NEED32>
+int launch_lookup5_r(int R, const Lookup5Params& p, int grid, hipStream_t stream) {
+    return launch_lookup5_by_r<NEED32>(R, p, grid, stream);
 }
 
 }  // namespace
