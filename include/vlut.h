@@ -305,7 +305,8 @@ int vlut_mpgemm_mfma(const uint8_t* packed, float w_scale, const int8_t* a_q, co
 /*
  * Tuning hook: forces the launch plan of vlut_mpgemm for subsequent calls from
  * this thread (interleave factor J in {1,2,4,8,16} = sub-tables per 256-byte
- * table row, row groups per wave R, waves per workgroup, split-K factor).
+ * table row, row groups per wave R in 1..16, `waves` = lookup waves of the 16-wave
+ * workgroup: 12 (four waves build the tables) or 14 (two do), split-K factor).
  * Any argument 0 = choose automatically.  Returns VLUT_ERR_UNSUPPORTED for a
  * combination the kernels are not built for.  Whether an accepted override
  * fits a given shape is only known at the call: when it does not (R > 6 where
@@ -325,6 +326,13 @@ int vlut_set_plan(int J, int R, int waves, int split_k);
  * { 0, rows per workgroup, 1, number of workgroups }.
  */
 int vlut_query_plan(int64_t M, int64_t K, int64_t N, int* out4);
+
+/*
+ * Lookup waves per workgroup of the plan vlut_query_plan reports (12 or 14: a workgroup tile holds 4 * waves * R output
+ * rows); 0 when the few-token kernel runs; a negative VLUT_ERR_* code for an invalid shape or an override that does
+ * not fit it.
+ */
+int vlut_query_lookup_waves(int64_t M, int64_t K, int64_t N);
 
 #ifdef __cplusplus
 }

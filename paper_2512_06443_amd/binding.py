@@ -30,7 +30,7 @@ EXPORTS = [
     "vlut_workspace_bytes_f32", "vlut_query_plan_f32", "vlut_mpgemm_f32",
     "vlut_build_lut_token_outer", "vlut_mpgemm_token_outer",
     "vlut_mixed_k5", "vlut_packed_weight_bytes_mixed", "vlut_workspace_bytes_mixed", "vlut_pack_weights_mixed",
-    "vlut_mpgemm_mixed", "vlut_static_scratch_bytes", "vlut_mpgemm_static",
+    "vlut_mpgemm_mixed", "vlut_static_scratch_bytes", "vlut_mpgemm_static", "vlut_query_lookup_waves",
 ]
 
 _lib = None
@@ -84,6 +84,7 @@ def lib() -> ctypes.CDLL:
         L.vlut_query_plan_f32.argtypes, L.vlut_query_plan_f32.restype = [i64, i64, i64, ctypes.POINTER(ci)], ci
         L.vlut_mpgemm_f32.argtypes = [p, cf, p, p, i64, i64, i64, i64, p, i64, p, p, p, sz, p]
         L.vlut_mpgemm_f32.restype = ci
+        L.vlut_query_lookup_waves.argtypes, L.vlut_query_lookup_waves.restype = [i64, i64, i64], ci
         L.vlut_static_scratch_bytes.argtypes, L.vlut_static_scratch_bytes.restype = [], sz
         L.vlut_mpgemm_static.argtypes, L.vlut_mpgemm_static.restype = [p, cf, p, p, i64, i64, i64, p, i64, p, p], ci
         L.vlut_set_plan.argtypes, L.vlut_set_plan.restype = [ci, ci, ci, ci], ci
@@ -198,6 +199,14 @@ def mpgemm(packed: torch.Tensor, w_scale: float, a_q: torch.Tensor, a_scale: tor
             _stream())
     _check(rc, "vlut_mpgemm_mfma" if mfma else "vlut_mpgemm")
     return y, acc
+
+
+def query_lookup_waves(M: int, K: int, N: int) -> int:
+    """Lookup waves per workgroup (12 or 14) of the plan vlut_mpgemm would use; 0 for the few-token kernel."""
+    w = lib().vlut_query_lookup_waves(M, K, N)
+    if w < 0:
+        raise VlutError(w, "vlut_query_lookup_waves")
+    return w
 
 
 def static_scratch_bytes() -> int:

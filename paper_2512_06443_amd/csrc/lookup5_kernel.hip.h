@@ -19,6 +19,10 @@ constexpr int kLds5Bytes = kScale5Base + 128 * 4;        // 124928
 constexpr int kBlockLookups5 = 51;
 constexpr int kWidenEvery5 = 12;                         // dword stages between widenings: 48 lookups <= 51
 
+constexpr int kBuildWaves5 = 4;                        // waves 0..3 build, 4..15 look up
+constexpr int kLookupWaves5 = kWaves - kBuildWaves5;   // 12
+constexpr int kRoundRows5 = kLookupWaves5 * 4;         // 48 output rows per row-group round of the workgroup
+
 struct Lookup5Params {
     const uint8_t* packed;
     const int8_t* a_q;
@@ -114,8 +118,8 @@ __global__ void __launch_bounds__(kThreads) lookup5_kernel(const Lookup5Params p
     const unsigned lanebase = (unsigned)l * 16u;
     const int ds_begin = ks * p.dstages_per_split;        // a dword stage = 4 half-stages = 64 groups = 320 weights
     const int ds_end = min(p.dstages_total, ds_begin + p.dstages_per_split);
-    const bool builder = wave < kBuildWaves;
-    const int lw = wave - kBuildWaves;
+    const bool builder = wave < kBuildWaves5;
+    const int lw = wave - kBuildWaves5;
 
     typedef __attribute__((address_space(3))) float lds_f32;
     lds_f32* scale_lds = (lds_f32*)(unsigned)kScale5Base;
@@ -213,7 +217,7 @@ __global__ void __launch_bounds__(kThreads) lookup5_kernel(const Lookup5Params p
         const unsigned char* wbase[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const int rgl = r * kLookupWaves + lw;
+            const int rgl = r * kLookupWaves5 + lw;
             const int rg = rgw0 + rgl;
             const bool valid = (rgl < p.RGW) && (rg < p.RGtotal);
             wbase[r] = p.packed + ((size_t)(valid ? rg : 0) * p.KCn) * 64;
@@ -261,20 +265,20 @@ __global__ void __launch_bounds__(kThreads) lookup5_kernel(const Lookup5Params p
     // ---- epilogue: reduce the 16 partial sums per token across the lane group, park as [token][row], store rows.
     lds_i32* park = (lds_i32*)0u;
     if (tid < 8) scale_lds[tid] = p.w_scale * my_scale;
-    constexpr int kParkStride = R * kRoundRows + 4;
+    constexpr int kParkStride = R * kRoundRows5 + 4;
     const int m0 = rgw0 * 4;
     const int rows_wg = min(p.RGW * 4, p.M - m0);
     if (!builder) {
 #pragma unroll
         for (int r = 0; r < R; ++r)
-            park[(l >> 1) * kParkStride + r * kRoundRows + lw * 4 + grp] = reduce16<NEED32>(acc16[r], acc32[NEED32 ? r : 0], l);
+            park[(l >> 1) * kParkStride + r * kRoundRows5 + lw * 4 + grp] = reduce16<NEED32>(acc16[r], acc32[NEED32 ? r : 0], l);
     }
     wg_barrier_lds();
     if (p.out_vec) {
         // four consecutive rows of one token per thread: one 16-byte read of the parked sums, one 16-byte store
-        for (int i = tid; i < R * (kRoundRows / 4) * 8; i += kThreads) {
-            const int col = 4 * (i % (R * (kRoundRows / 4)));
-            const int nl = i / (R * (kRoundRows / 4));
+        for (int i = tid; i < R * (kRoundRows5 / 4) * 8; i += kThreads) {
+            const int col = 4 * (i % (R * (kRoundRows5 / 4)));
+            const int nl = i / (R * (kRoundRows5 / 4));
             const int n = n0 + nl;
             if (col < rows_wg && n < p.N) {
                 const i32x4 v4 = *(const lds_i32x4*)(park + nl * kParkStride + col);
@@ -311,9 +315,9 @@ __global__ void __launch_bounds__(kThreads) lookup5_kernel(const Lookup5Params p
             }
         }
     } else
-    for (int i = tid; i < R * kRoundRows * 8; i += kThreads) {
-        const int col = i % (R * kRoundRows);
-        const int nl = i / (R * kRoundRows);
+    for (int i = tid; i < R * kRoundRows5 * 8; i += kThreads) {
+        const int col = i % (R * kRoundRows5);
+        const int nl = i / (R * kRoundRows5);
         const int n = n0 + nl;
         if (col < rows_wg && n < p.N) {
             const int val = park[nl * kParkStride + col];

@@ -7,13 +7,16 @@ namespace {
 // ---------------------------------------------------------------------------------------------
 // The lookup kernel (Alg. 1 main loop + streamed Precompute, Sec. 3.4).
 //
-// Roles inside the 16-wave workgroup: waves 0..3 (one per SIMD) only BUILD tables, waves 4..15 only LOOK UP.
+// Roles inside the 16-wave workgroup: waves 0..BW-1 (BW = 4, 2 or 1) only BUILD tables, the other LW = 16 - BW only
+// LOOK UP.  Fewer build waves mean more output rows per table (workgroup tile = 4*LW*R rows) and less repeated work
+// in the build (a build lane then makes the rows of 4/BW leading digit pairs from one unpacking of its activations),
+// but a longer build per half-stage, which only large R hides.
 // The four LDS slots are used as two halves of two slots each: while the lookup waves read one half, the build
 // waves fill the other half with the next two sub-table sets, and one barrier per half-stage hands the halves over.
 // Table entries and block accumulators are words of two INT16 values each (word_lo / word_hi), so that one
 // three-operand 32-bit add accumulates the entries of two lookups: per lookup one address permute, one 16-byte
 // table read and two adds.
-//   R       row groups (of 4 output rows) per lookup wave; workgroup tile = up to 48*R rows
+//   R       row groups (of 4 output rows) per lookup wave; workgroup tile = up to 4*LW*R rows
 //   NEED32  more than 64 lookups per lane: widen INT16 block sums into INT32 every 16 stages
 //   MODE    kFast: tables built in LDS from the token-chunked INT8 activations (streamed, the hot path)
 //           kFusedQuant: as kFast, but the workgroup first quantises its 8 tokens itself (fp32 rows -> absmax ->
@@ -30,9 +33,6 @@ __device__ __forceinline__ void static_for(F&& f) {
 }
 
 enum { kFast = 0, kFusedQuant = 1, kFromGlobal = 2 };
-constexpr int kBuildWaves = 4;
-constexpr int kLookupWaves = kWaves - kBuildWaves;     // 12
-constexpr int kRoundRows = kLookupWaves * 4;           // 48 output rows per row-group round of the workgroup
 
 // The two table reads of row group RR in half-stage HALF (slots 2*HALF and 2*HALF + 1): bytes 2*HALF and 2*HALF + 1 of
 // the row group's weight dword are the table rows; the lane reads its 16-byte slice (8 entries) of each.
@@ -79,8 +79,14 @@ __device__ __forceinline__ void lookup_half(const unsigned (&w)[R], unsigned lan
     });
 }
 
-template <int R, bool NEED32, int MODE>
+template <int R, bool NEED32, int MODE, int BW>
 __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) {
+    constexpr int kBuildWaves = BW;
+    constexpr int kLookupWaves = kWaves - BW;
+    constexpr int kRoundRows = kLookupWaves * 4;     // output rows per row-group round of the workgroup
+    constexpr int kUPerLane = 4 / BW;                // leading digit pairs (table rows 9u..9u+8) per build lane
+    static_assert(BW == 4 || BW == 2 || BW == 1, "build waves");
+    static_assert(MODE != kFromGlobal || BW == 4, "the materialised-table variant keeps four build waves");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     // The kernel has no static LDS, so the dynamic segment starts at LDS address 0; table addresses are formed
     // as idx*256 + slice*16 by a byte permute and rely on that.  The host verifies it (static LDS size of the
@@ -227,10 +233,13 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
 
     if (builder) {
         // ================================ build role ================================
-        // Task of a lane for one half-stage: slot s2 of the half (0/1), slice l, leading digits hh = u (table rows
-        // 9u .. 9u+8); the ninth digit pair (rows 72..80) is shared out one row per lane, lane u = 0 takes two.
-        const int u = (wave * 4 + grp) & 7;
-        const int s2 = (wave * 4 + grp) >> 3;
+        // Task of a lane for one half-stage: slot s2 of the half (0/1), slice l, and kUPerLane leading digit pairs
+        // u = u0 .. u0+kUPerLane-1 (table rows 9u .. 9u+8 each); the ninth digit pair (rows 72..80) is shared out one
+        // row per u, and the lane with u = 0 also takes row 80.
+        constexpr int kGroupsPerSlot = 2 * BW;        // 16-lane groups that share a slot
+        const int s2 = (wave * 4 + grp) / kGroupsPerSlot;
+        const int u0 = ((wave * 4 + grp) % kGroupsPerSlot) * kUPerLane;
+        const int u = u0;                            // (kFromGlobal: one digit pair per lane)
         const int nb = n0 + 8 * t;                   // first token of the slice
         const int chunk_b = nb >> 3;
         unsigned actA[4][2], actB[4][2];
@@ -310,66 +319,81 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         } else {
             // The build waves are few and every barrier waits for them: let them issue first.
             __builtin_amdgcn_s_setprio(3);
-            // Rows are computed one half-stage ahead: after a barrier a build wave only has to issue its eleven
-            // LDS writes, and it computes the next half-stage's rows while those writes drain.  Activations are
-            // fetched four half-stages ahead of their use.
-            struct Rows { int r[9][4], ex[4], last[4]; };
+            // After a barrier a build wave makes the tables of the half the lookup waves have just left: it unpacks
+            // its activations (fetched four half-stages earlier) into words once and then, for each of its digit
+            // pairs, computes a table row and writes it at once, so that arithmetic and LDS writes interleave and only
+            // a few rows are ever live.  Every row is one add or subtract away from an earlier one (topological
+            // order, Sec. 4); the arithmetic is plain 32-bit on words of two entries each (|word| < 2^23 for an
+            // activation, so the 24-bit multiplies by the digits -1, 0, +1 are exact).
             unsigned act2[4][2], act3[4][2];
             bool valid2 = false, valid3 = false;
-            // Every row is one add or subtract away from an earlier one (topological order, Sec. 4); the arithmetic is
-            // plain 32-bit on words of two entries each (|word| < 2^23 for an activation, so the 24-bit multiplies
-            // by the digits -1, 0, +1 are exact).
-            auto compute_rows = [&](unsigned (&act)[4][2], bool valid, Rows& rw) {
+            auto build_rows = [&](int hs, unsigned (&act)[4][2], bool valid) {
                 if (!valid) {
 #pragma unroll
                     for (int c = 0; c < 4; ++c) { act[c][0] = 0u; act[c][1] = 0u; }
                 }
-                const int m0 = u / 3 - 1, m1 = u % 3 - 1;   // leading digits of rows 9u..9u+8, and digits (d2,d3) of row 72+u
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int a0 = unpack_word(act[0][q >> 1], q & 1);
-                    const int a1 = unpack_word(act[1][q >> 1], q & 1);
-                    const int a2 = unpack_word(act[2][q >> 1], q & 1);
-                    const int a3 = unpack_word(act[3][q >> 1], q & 1);
-                    const int b1 = __mul24(a0, m0) + __mul24(a1, m1);
-                    const int top = a0 + a1;                            // leading digits (2,2)
-                    const int lo = b1 - a2, hi = b1 + a2;
-                    rw.r[0][q] = lo - a3; rw.r[1][q] = lo; rw.r[2][q] = lo + a3;
-                    rw.r[3][q] = b1 - a3; rw.r[4][q] = b1; rw.r[5][q] = b1 + a3;
-                    rw.r[6][q] = hi - a3; rw.r[7][q] = hi; rw.r[8][q] = hi + a3;
-                    rw.ex[q] = top + __mul24(a2, m0) + __mul24(a3, m1);  // row 72 + 3*d2 + d3 with (d2,d3) = (u/3, u%3)
-                    rw.last[q] = top + a2 + a3;                         // row 80
-                }
-                // Pin the finished rows in registers here, so that the arithmetic stays where it is written
-                // (between the LDS writes of one half-stage and the barrier) instead of sinking below the barrier.
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-#pragma unroll
-                    for (int i = 0; i < 9; ++i) asm volatile("" : "+v"(rw.r[i][q]));
-                    asm volatile("" : "+v"(rw.ex[q]));
-                    asm volatile("" : "+v"(rw.last[q]));
-                }
-            };
-            auto write_rows = [&](int hs, const Rows& rw) {
                 const unsigned dst = (unsigned)(2 * (hs & 1) + s2) * kSlotBytes + (unsigned)l * 16u;
-                const unsigned dst9 = dst + (unsigned)(9 * u) * kRowBytes;
-                static_for<0, 9>([&](auto ic_) {
-                    constexpr int i = decltype(ic_)::value;
-                    lds_write128<i * 16>(dst9, i32x4{rw.r[i][0], rw.r[i][1], rw.r[i][2], rw.r[i][3]});
+                int a0[4], a1[4], a2[4], a3[4], top[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    a0[q] = unpack_word(act[0][q >> 1], q & 1);
+                    a1[q] = unpack_word(act[1][q >> 1], q & 1);
+                    a2[q] = unpack_word(act[2][q >> 1], q & 1);
+                    a3[q] = unpack_word(act[3][q >> 1], q & 1);
+                    top[q] = a0[q] + a1[q];                             // leading digits (2,2)
+                }
+                auto put = [&](unsigned addr, auto off_tag, const int (&v)[4]) {
+                    lds_write128<decltype(off_tag)::value>(addr, i32x4{v[0], v[1], v[2], v[3]});
+                };
+                static_for<0, kUPerLane>([&](auto ui_) {
+                    constexpr int ui = decltype(ui_)::value;
+                    const int uu = u0 + ui;
+                    const int m0 = uu / 3 - 1, m1 = uu % 3 - 1;   // leading digits of rows 9uu..9uu+8 = digits (d2,d3) of row 72+uu
+                    const unsigned dst9 = dst + (unsigned)(9 * uu) * kRowBytes;
+                    int b1[4], lo[4], hi[4], t[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) b1[q] = __mul24(a0[q], m0) + __mul24(a1[q], m1);
+                    put(dst9, ic<4 * 16>{}, b1);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) lo[q] = b1[q] - a2[q];
+                    put(dst9, ic<1 * 16>{}, lo);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) t[q] = lo[q] - a3[q];
+                    put(dst9, ic<0 * 16>{}, t);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) t[q] = lo[q] + a3[q];
+                    put(dst9, ic<2 * 16>{}, t);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) t[q] = b1[q] - a3[q];
+                    put(dst9, ic<3 * 16>{}, t);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) t[q] = b1[q] + a3[q];
+                    put(dst9, ic<5 * 16>{}, t);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) hi[q] = b1[q] + a2[q];
+                    put(dst9, ic<7 * 16>{}, hi);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) t[q] = hi[q] - a3[q];
+                    put(dst9, ic<6 * 16>{}, t);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) t[q] = hi[q] + a3[q];
+                    put(dst9, ic<8 * 16>{}, t);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) t[q] = top[q] + __mul24(a2[q], m0) + __mul24(a3[q], m1);
+                    put(dst + (unsigned)(72 + uu) * kRowBytes, ic<0>{}, t);   // row 72 + 3*d2 + d3
                 });
-                lds_write128<0>(dst + (unsigned)(72 + u) * kRowBytes,
-                                i32x4{rw.ex[0], rw.ex[1], rw.ex[2], rw.ex[3]});
-                if (u == 0) {
-                    lds_write128<80 * 16>(dst, i32x4{rw.last[0], rw.last[1], rw.last[2], rw.last[3]});
+                if (u0 == 0) {
+                    int t[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) t[q] = top[q] + a2[q] + a3[q];
+                    put(dst, ic<80 * 16>{}, t);                          // row 80
                 }
             };
-            Rows rows;
-            // One half-stage: write the rows computed earlier (half-stage hs, if it exists), compute the rows of
-            // half-stage hs + 1 from `act_next`, refill that activation buffer, and meet the lookup waves.
-            auto step = [&](int hs, unsigned (&act_next)[4][2], bool& valid_next) {
-                if (hs < hs1) write_rows(hs, rows);
-                compute_rows(act_next, valid_next, rows);
-                fetch_act(hs + 5, act_next, valid_next);
+            // One half-stage: build the tables of half-stage hs from `act` (if that half-stage exists), refill the
+            // activation buffer four half-stages ahead, and meet the lookup waves.
+            auto step = [&](int hs, unsigned (&act)[4][2], bool& valid) {
+                if (hs < hs1) build_rows(hs, act, valid);
+                fetch_act(hs + 4, act, valid);
                 wg_barrier_lds();
             };
             if (hs0 < hs1) {
@@ -377,20 +401,15 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                 fetch_act(hs0 + 1, actB, validB);
                 fetch_act(hs0 + 2, act2, valid2);
                 fetch_act(hs0 + 3, act3, valid3);
-                compute_rows(actA, validA, rows);
-                fetch_act(hs0 + 4, actA, validA);
             }
-            // half 0 of the first stage: hand it over as soon as it is written, compute the next rows afterwards
-            if (hs0 < hs1) write_rows(hs0, rows);
-            wg_barrier_lds();
-            compute_rows(actB, validB, rows);
-            fetch_act(hs0 + 5, actB, validB);
+            // half 0 of the first stage, handed over as soon as it is written
+            step(hs0, actA, validA);
             for (int hs = hs0; hs < hs1; hs += 4) {
-                step(hs + 1, act2, valid2);           // lookups read half 0 (hs): fill half 1
-                step(hs + 2, act3, valid3);           // lookups read half 1 (hs+1): fill half 0
-                step(hs + 3, actA, validA);           // (with an odd number of stages the last two steps only meet
+                step(hs + 1, actB, validB);           // lookups read half 0 (hs): fill half 1
+                step(hs + 2, act2, valid2);           // lookups read half 1 (hs+1): fill half 0
+                step(hs + 3, act3, valid3);           // (with an odd number of stages the last two steps only meet
                                                       //  the lookup waves at their two matching barriers)
-                step(hs + 4, actB, validB);
+                step(hs + 4, actA, validA);
             }
             __builtin_amdgcn_s_setprio(0);
         }

@@ -81,9 +81,10 @@ bool allow_dynamic_lds(const void* kfn, int bytes, std::atomic<unsigned>& done_m
 
 struct Plan {
     int Jlog, R, S;
+    int BW;      // build waves of the 16-wave workgroup (4, 2 or 1); the other 16 - BW waves look up
 };
 
-thread_local Plan t_forced = {-1, 0, 0};
+thread_local Plan t_forced = {-1, 0, 0, 0};
 
 const int kSupportedR[] = {1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16};
 
@@ -110,7 +111,7 @@ Derived derive(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     int J = 1 << pl.Jlog;
     d.n_tile = 128 >> pl.Jlog;
     d.tiles_n = (int)((N + d.n_tile - 1) / d.n_tile);
-    int cap = kLookupWaves * pl.R;                    // row groups a workgroup can hold
+    int cap = (kWaves - pl.BW) * pl.R;                // row groups a workgroup can hold
     d.tiles_m = (d.RGtotal + cap - 1) / cap;
     d.RGW = (d.RGtotal + d.tiles_m - 1) / d.tiles_m;  // balanced rows per workgroup
     d.stages_total = (d.G + 4 * J - 1) / (4 * J);
@@ -121,27 +122,37 @@ Derived derive(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     return d;
 }
 
-// Cost model in CU clocks, fitted to microbenchmarks of this chip.  Per stage (4 slots) the lookup waves issue, per
-// SIMD, 3 waves x 4 lookups x 5 VALU instructions per row group, next to ~230 VALU instructions of the SIMD's build
-// wave; the LDS pipe serves the table reads (~4.3 clk per wave read) and ~83 KB of table writes (~1400 clk).
+// Cost model in nanoseconds, fitted to K-scans of this chip at 256 workgroups (one round).  A stage (4 slots = 64
+// k-groups at 16 sub-tables per table row) costs a fixed part (the table build and its LDS writes, which share the LDS
+// pipe with the table reads) plus a part per row group of the slowest lookup wave (two table reads, two address
+// permutes and four three-operand adds per slot pair); with two build waves the fixed part is smaller and every
+// workgroup holds 7/6 of the rows, but the build itself takes ~1.37 us per stage, which only R >= 7 hides.  Outside
+// the K loop: first loads and first build, then the cross-lane reduction and the stores of every row group.
 double plan_cost(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     Derived d = derive(pl, M, K, N);
-    double rw = (double)((d.RGW + kLookupWaves - 1) / kLookupWaves);   // row groups of the slowest lookup wave
-    // Measured (K-scans at 256 workgroups, cycles of the shader clock): a stage of 64 k-groups costs about
-    // 2280 + 283 per row-group round: the table writes and the table reads share one LDS pipe and add up.
-    // Outside the K loop: first loads and first build, then the reduction and the stores of every round.
-    double stage = 2280.0 + 283.0 * rw;
-    double wg = d.stages_per_split * stage + 5900.0 + 840.0 * rw + (d.need32 ? 0.05 * d.stages_per_split * stage : 0.0);
+    const int lookup_waves = kWaves - pl.BW;
+    const double rw = (double)((d.RGW + lookup_waves - 1) / lookup_waves);   // row groups of the slowest lookup wave
+    double stage, outside;
+    if (pl.BW == 4) {
+        stage = 867.0 + 90.0 * rw;
+        outside = 1300.0 + 450.0 * rw;
+    } else {
+        stage = 745.0 + 106.0 * rw;
+        if (stage < 1370.0) stage = 1370.0;
+        outside = 1000.0 + 530.0 * rw;
+    }
+    double wg = d.stages_per_split * stage * (d.need32 ? 1.05 : 1.0) + outside;
     double rounds = (double)((d.total + 255) / 256);
-    double t = rounds * wg;
-    if (pl.S > 1) t += 5000.0 + 600.0 * pl.S + (double)pl.S * (double)M * (double)N * 8.0 / (256.0 * 16.0);   // second kernel
+    double t = 2000.0 + rounds * wg;
+    if (pl.S > 1) t += 2400.0 + 290.0 * pl.S + (double)pl.S * (double)M * (double)N * 8.0 / (256.0 * 16.0 * 2.1);   // second kernel
     // weight bytes pulled from L2 by all token tiles (256 CUs x ~24 B/clk)
-    double traffic = (double)d.tiles_n * (double)d.RGtotal * d.KCn * 64.0 / (256.0 * 24.0);
+    double traffic = (double)d.tiles_n * (double)d.RGtotal * d.KCn * 64.0 / (256.0 * 24.0 * 2.1);
     return t > traffic ? t : traffic;
 }
 
 bool plan_valid(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     if (pl.Jlog < 0 || pl.Jlog > 4 || !r_supported(pl.R) || pl.S < 1 || pl.S > 16) return false;
+    if (pl.BW != 4 && pl.BW != 2 && pl.BW != 1) return false;
     Derived d = derive(pl, M, K, N);
     if (d.need32 && pl.R > 6) return false;      // register budget of the INT32 variant
     if (pl.S > d.stages_total) return false;
@@ -150,19 +161,23 @@ bool plan_valid(const Plan& pl, int64_t M, int64_t K, int64_t N) {
 
 // A plan with R == 0 means: the override of vlut_set_plan fits this shape with no value of the free parameters
 // (callers report VLUT_ERR_UNSUPPORTED).  Without an override there is always a valid plan (R = 1, S = 1).
-Plan search_plan(int64_t M, int64_t K, int64_t N, int max_S = 16) {
-    Plan best = {0, 0, 0};
+const int kBuildWaveChoices[] = {4, 2};
+Plan search_plan(int64_t M, int64_t K, int64_t N, int max_S = 16, bool four_build_waves_only = false) {
+    Plan best = {0, 0, 0, 0};
     double best_cost = 1e300;
     const int Ss[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
     for (int Jlog = 0; Jlog <= 4; ++Jlog)
         for (int R : kSupportedR)
             for (int S : Ss) {
                 if (S > max_S) continue;
-                Plan pl = {t_forced.Jlog >= 0 ? t_forced.Jlog : Jlog, t_forced.R > 0 ? t_forced.R : R,
-                           t_forced.S > 0 ? t_forced.S : S};
-                if (!plan_valid(pl, M, K, N)) continue;
-                double c = plan_cost(pl, M, K, N);
-                if (c < best_cost) { best_cost = c; best = pl; }
+                for (int BW : kBuildWaveChoices) {
+                    if (four_build_waves_only && BW != 4) continue;
+                    Plan pl = {t_forced.Jlog >= 0 ? t_forced.Jlog : Jlog, t_forced.R > 0 ? t_forced.R : R,
+                               t_forced.S > 0 ? t_forced.S : S, t_forced.BW > 0 ? t_forced.BW : BW};
+                    if (!plan_valid(pl, M, K, N)) continue;
+                    double c = plan_cost(pl, M, K, N);
+                    if (c < best_cost) { best_cost = c; best = pl; }
+                }
             }
     return best;
 }
@@ -174,13 +189,13 @@ bool fused_plan_valid(const Plan& pl, int64_t M, int64_t K, int64_t N) {
 }
 
 bool search_fused_plan(int64_t M, int64_t K, int64_t N, Plan* out) {
-    if (t_forced.Jlog >= 0 && t_forced.Jlog != 4) return false;
+    if ((t_forced.Jlog >= 0 && t_forced.Jlog != 4) || (t_forced.BW != 0 && t_forced.BW != 4)) return false;
     bool found = false;
     double best_cost = 1e300;
     const int Ss[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
     for (int R : kSupportedR)
         for (int S : Ss) {
-            Plan pl = {4, t_forced.R > 0 ? t_forced.R : R, t_forced.S > 0 ? t_forced.S : S};
+            Plan pl = {4, t_forced.R > 0 ? t_forced.R : R, t_forced.S > 0 ? t_forced.S : S, 4};
             if (!fused_plan_valid(pl, M, K, N)) continue;
             double c = plan_cost(pl, M, K, N);
             if (c < best_cost) { best_cost = c; *out = pl; found = true; }
@@ -221,7 +236,7 @@ bool choose_fused_plan(int64_t M, int64_t K, int64_t N, Plan* out) {
             *out = t_fcache[i].plan;
             return t_fcache[i].found;
         }
-    Plan pl = {4, 1, 1};
+    Plan pl = {4, 1, 1, 4};
     const bool found = search_fused_plan(M, K, N, &pl);
     t_fcache[t_fcache_next] = {M, K, N, pl, found};
     t_fcache_next = (t_fcache_next + 1) % 8;
@@ -230,9 +245,9 @@ bool choose_fused_plan(int64_t M, int64_t K, int64_t N, Plan* out) {
     return found;
 }
 
-template <int R, bool NEED32, int MODE>
+template <int R, bool NEED32, int MODE, int BW>
 int launch_lookup_t(const LookupParams& p, int grid, hipStream_t stream) {
-    auto kfn = lookup_kernel<R, NEED32, MODE>;
+    auto kfn = lookup_kernel<R, NEED32, MODE, BW>;
     constexpr int max_lds = MODE == kFusedQuant ? kFusedMaxLds : kLdsBytes;
     const int lds = MODE == kFusedQuant ? kFusedAqBase + p.stages_per_split * kFusedStageBytes : kLdsBytes;
     if (lds > max_lds) return VLUT_ERR_UNSUPPORTED;
@@ -259,23 +274,27 @@ constexpr bool lookup_instance_built(int R, bool need32, int mode) {
     return R <= 16;
 }
 
-template <bool NEED32, int MODE, int R = 1>
+constexpr bool lookup_bw_built(int BW, int mode) { return BW == 4 || (BW == 2 && mode == kFast); }
+
+template <bool NEED32, int MODE, int BW, int R = 1>
 int launch_lookup_by_r(int r, const LookupParams& p, int grid, hipStream_t stream) {
     if constexpr (R > 16) {
         return VLUT_ERR_UNSUPPORTED;
     } else {
         if constexpr (lookup_instance_built(R, NEED32, MODE)) {
-            if (r == R) return launch_lookup_t<R, NEED32, MODE>(p, grid, stream);
+            if (r == R) return launch_lookup_t<R, NEED32, MODE, BW>(p, grid, stream);
         }
-        return launch_lookup_by_r<NEED32, MODE, R + 1>(r, p, grid, stream);
+        return launch_lookup_by_r<NEED32, MODE, BW, R + 1>(r, p, grid, stream);
     }
 }
 
 template <bool NEED32>
-int launch_lookup_r(int R, int mode, const LookupParams& p, int grid, hipStream_t stream) {
-    if (mode == kFusedQuant) return launch_lookup_by_r<NEED32, kFusedQuant>(R, p, grid, stream);
-    if (mode == kFast) return launch_lookup_by_r<NEED32, kFast>(R, p, grid, stream);
-    return launch_lookup_by_r<NEED32, kFromGlobal>(R, p, grid, stream);
+int launch_lookup_r(int R, int BW, int mode, const LookupParams& p, int grid, hipStream_t stream) {
+    if (mode == kFusedQuant && BW == 4) return launch_lookup_by_r<NEED32, kFusedQuant, 4>(R, p, grid, stream);
+    if (mode == kFast && BW == 4) return launch_lookup_by_r<NEED32, kFast, 4>(R, p, grid, stream);
+    if (mode == kFast && BW == 2) return launch_lookup_by_r<NEED32, kFast, 2>(R, p, grid, stream);
+    if (mode == kFromGlobal && BW == 4) return launch_lookup_by_r<NEED32, kFromGlobal, 4>(R, p, grid, stream);
+    return VLUT_ERR_UNSUPPORTED;
 }
 
 // Second kernel of a split-K (or mixed-packing) launch: four rows per thread when everything is aligned for it.
@@ -334,7 +353,7 @@ NarrowPlan narrow_plan(int64_t M, int64_t K, int64_t N) {
 //                 per workgroup;
 //   general path  5.8 + 0.94 c + 0.41 x M N / 10^4 for lookup kernel + split-K sum, + 3.5 for the quantiser from fp32.
 bool narrow_applies(int64_t M, int64_t K, int64_t N, const void* lut, bool from_f32) {
-    if (N > kNarrowMaxN || lut != nullptr || t_forced.Jlog >= 0 || t_forced.R != 0 || t_forced.S != 0) return false;
+    if (N > kNarrowMaxN || lut != nullptr || t_forced.Jlog >= 0 || t_forced.R != 0 || t_forced.S != 0 || t_forced.BW != 0) return false;
     if (N <= 2) return true;
     const NarrowPlan np = narrow_plan(M, K, N);
     if (np.grid > 256) return false;
@@ -398,7 +417,7 @@ F32Layout f32_layout(int64_t M, int64_t K, int64_t N) {
     // it (every workgroup reads the whole rows of its 8 tokens and 16 row tiles repeat the work: +5.6 us on the
     // lookup kernel at M = 6912, K = 2560, N = 128, against 3.2 us + the gap between two kernels).  The fused form
     // is therefore only taken when a launch plan is forced (an override selects the kernel too).
-    const bool forced = t_forced.Jlog >= 0 || t_forced.R > 0 || t_forced.S > 0;
+    const bool forced = t_forced.Jlog >= 0 || t_forced.R > 0 || t_forced.S > 0 || t_forced.BW > 0;
     const bool fused = forced && choose_fused_plan(M, K, N, &L.plan);
     if (fused) {
         L.kind = kF32Fused;
@@ -412,7 +431,7 @@ F32Layout f32_layout(int64_t M, int64_t K, int64_t N) {
     L.off_aq = scale_bytes;
     L.off_ws = L.off_aq + round256((size_t)((N + 7) / 8) * (size_t)K * 8);
     const bool narrow = narrow_applies(M, K, N, nullptr, false);
-    const Plan pl = narrow ? Plan{4, 1, 1} : choose_plan(M, K, N);
+    const Plan pl = narrow ? Plan{4, 1, 1, 4} : choose_plan(M, K, N);
     L.plan = pl;
     L.total = L.off_ws + (pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0);
     return L;
@@ -440,7 +459,7 @@ Derived5 derive5(const Plan5& pl, int64_t M, int64_t K, int64_t N) {
     d.KCn = (d.G + 15) / 16;
     d.RGtotal = (int)((M + 3) / 4);
     d.tiles_n = (int)((N + 7) / 8);
-    int cap = kLookupWaves * pl.R;
+    int cap = kLookupWaves5 * pl.R;
     d.tiles_m = (d.RGtotal + cap - 1) / cap;
     d.RGW = (d.RGtotal + d.tiles_m - 1) / d.tiles_m;
     d.dstages_total = (d.G + 63) / 64;
@@ -471,7 +490,7 @@ Plan5 choose_plan5(int64_t M, int64_t K, int64_t N) {
             Plan5 pl = {t_forced5.R > 0 ? t_forced5.R : R, t_forced5.S > 0 ? t_forced5.S : S};
             if (!plan5_valid(pl, M, K, N)) continue;
             Derived5 d = derive5(pl, M, K, N);
-            double rw = (double)((d.RGW + kLookupWaves - 1) / kLookupWaves);
+            double rw = (double)((d.RGW + kLookupWaves5 - 1) / kLookupWaves5);
             // a dword stage = four half-stages; each writes a 62 KB slot and reads it rw times per lookup wave
             double wg = d.dstages_per_split * 4.0 * (1900.0 + 75.0 * rw) + 5900.0 + 840.0 * rw;
             double t = (double)((d.total + 255) / 256) * wg;
@@ -576,9 +595,9 @@ int vlut_set_plan(int J, int R, int waves, int split_k) {
         if (Jlog < 0) return VLUT_ERR_UNSUPPORTED;
     }
     if (R != 0 && !r_supported(R)) return VLUT_ERR_UNSUPPORTED;
-    if (waves != 0 && waves != kWaves) return VLUT_ERR_UNSUPPORTED;
+    if (waves != 0 && waves != kWaves && waves != 12 && waves != 14) return VLUT_ERR_UNSUPPORTED;
     if (split_k < 0 || split_k > 16) return VLUT_ERR_UNSUPPORTED;
-    t_forced = {Jlog, R, split_k};
+    t_forced = {Jlog, R, split_k, (waves == 12 || waves == 14) ? kWaves - waves : 0};
     t_cache_used = 0;
     t_cache_next = 0;
     t_fcache_used = 0;
@@ -602,6 +621,14 @@ int vlut_query_plan(int64_t M, int64_t K, int64_t N, int* out4) {
     out4[2] = pl.S;
     out4[3] = d.total;
     return VLUT_OK;
+}
+
+int vlut_query_lookup_waves(int64_t M, int64_t K, int64_t N) {
+    if (!shape_ok(M, K, N)) return VLUT_ERR_SHAPE;
+    if (narrow_applies(M, K, N, nullptr, false)) return 0;
+    const Plan pl = choose_plan(M, K, N);
+    if (pl.R == 0) return VLUT_ERR_UNSUPPORTED;
+    return kWaves - pl.BW;
 }
 
 int vlut_pack_weights(const int8_t* w_ternary, int64_t M, int64_t K, uint8_t* packed, size_t packed_bytes,
@@ -727,10 +754,14 @@ static int mpgemm_impl(const uint8_t* packed, float w_scale, const float* w_rows
     // A materialised table where the streamed path would take the few-token kernel (and vlut_workspace_bytes says
     // 0): a plan without split-K, so that no workspace is needed here either.
     Plan pl = (lut_or_null && narrow_applies(M, K, N, nullptr, false)) ? search_plan(M, K, N, 1) : choose_plan(M, K, N);
+    if (lut_or_null && pl.R != 0 && pl.BW != 4) pl = search_plan(M, K, N, narrow_applies(M, K, N, nullptr, false) ? 1 : 16, true);
     if (pl.R == 0) return VLUT_ERR_UNSUPPORTED;          // the override of vlut_set_plan does not fit this shape
     const bool al = lut_or_null && (N % 8 == 0) && (((uintptr_t)lut_or_null) % 16 == 0);
     const int mode = lut_or_null ? kFromGlobal : kFast;
-    if (mode != kFast) pl.R = pl.R >= 4 ? 4 : (pl.R >= 2 ? 2 : 1);   // the general-purpose kernels are built for these R only
+    if (mode != kFast) {   // the materialised-table variant is built for these R and four build waves only
+        pl.R = pl.R >= 4 ? 4 : (pl.R >= 2 ? 2 : 1);
+        pl.BW = 4;
+    }
     Derived d = derive(pl, M, K, N);
     size_t ws_need = pl.S > 1 ? (size_t)pl.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
     if (ws_need > 0) {
@@ -749,7 +780,7 @@ static int mpgemm_impl(const uint8_t* packed, float w_scale, const float* w_rows
     p.Ka = (int)K;
     hipStream_t s = (hipStream_t)stream;
     int grid = d.per_xcd * 8;
-    rc = d.need32 ? launch_lookup_r<true>(pl.R, mode, p, grid, s) : launch_lookup_r<false>(pl.R, mode, p, grid, s);
+    rc = d.need32 ? launch_lookup_r<true>(pl.R, pl.BW, mode, p, grid, s) : launch_lookup_r<false>(pl.R, pl.BW, mode, p, grid, s);
     if (rc != VLUT_OK) return rc;
     if (pl.S > 1)
         return launch_splitk_reduce((const int32_t*)workspace, pl.S, M, N, w_scale, w_rows, a_scale, y, ldy, acc_or_null, s);
@@ -866,8 +897,8 @@ int vlut_mpgemm_f32(const uint8_t* packed, float w_scale, const float* w_scale_r
     p.stages_total = d.stages_total; p.stages_per_split = d.stages_per_split;
     p.total_tiles = d.total; p.per_xcd = d.per_xcd;
     const int grid = d.per_xcd * 8;
-    int rc = d.need32 ? launch_lookup_r<true>(pl.R, kFusedQuant, p, grid, s)
-                      : launch_lookup_r<false>(pl.R, kFusedQuant, p, grid, s);
+    int rc = d.need32 ? launch_lookup_r<true>(pl.R, pl.BW, kFusedQuant, p, grid, s)
+                      : launch_lookup_r<false>(pl.R, pl.BW, kFusedQuant, p, grid, s);
     if (rc != VLUT_OK) return rc;
     if (pl.S > 1) {
         rc = launch_splitk_reduce((const int32_t*)(ws + L.off_ws), pl.S, M, N, w_one, w_rows, (const float*)scales, y, ldy,
@@ -1028,7 +1059,7 @@ static bool mixed_plans(int64_t M, int64_t K, int64_t N, Plan5* p5, Plan* p4) {
     } else {
         *p5 = Plan5{0, 0};
     }
-    *p4 = K4 > 0 ? choose_plan(M, K4, N) : Plan{0, 0, 0};
+    *p4 = K4 > 0 ? choose_plan(M, K4, N) : Plan{0, 0, 0, 0};
     if (K4 > 0 && p4->R == 0) return false;              // the override of vlut_set_plan does not fit the 2-bit part
     return true;
 }
@@ -1082,7 +1113,7 @@ int vlut_mpgemm_mixed(const uint8_t* packed, float w_scale, const int8_t* a_q, c
         p.total_tiles = d.total; p.per_xcd = d.per_xcd;
         p.Ka = (int)K; p.partial = 1; p.slot0 = pl5.S;
         const int grid = d.per_xcd * 8;
-        rc = d.need32 ? launch_lookup_r<true>(pl4.R, kFast, p, grid, s) : launch_lookup_r<false>(pl4.R, kFast, p, grid, s);
+        rc = d.need32 ? launch_lookup_r<true>(pl4.R, pl4.BW, kFast, p, grid, s) : launch_lookup_r<false>(pl4.R, pl4.BW, kFast, p, grid, s);
         if (rc != VLUT_OK) return rc;
     }
     return launch_splitk_reduce((const int32_t*)workspace, pl5.S + pl4.S, M, N, w_scale, nullptr, a_scale, y, ldy,

@@ -29,6 +29,7 @@ def L(vlut_lib_path):
     lib.vlut_mpgemm_mfma.argtypes = g
     lib.vlut_mpgemm_rows.argtypes = [vp, vp] + g[2:]
     lib.vlut_set_plan.argtypes = [ci, ci, ci, ci]
+    lib.vlut_query_lookup_waves.argtypes = [i64, i64, i64]
     lib.vlut_packed_weight_bytes_g5.argtypes, lib.vlut_packed_weight_bytes_g5.restype = [i64, i64], sz
     lib.vlut_packed_offset_g5.argtypes, lib.vlut_packed_offset_g5.restype = [i64, i64, i64, i64], sz
     lib.vlut_workspace_bytes_g5.argtypes, lib.vlut_workspace_bytes_g5.restype = [i64, i64, i64], sz
@@ -135,6 +136,7 @@ def test_argument_errors_come_before_any_device_call(L):
     assert L.vlut_mpgemm_rows(d, d, d, d, None, 8, 8, 4, d, 7, None, None, 0, None) == -2
     assert L.vlut_set_plan(3, 0, 0, 0) == -6 and L.vlut_set_plan(0, 17, 0, 0) == -6
     assert L.vlut_set_plan(0, 0, 7, 0) == -6 and L.vlut_set_plan(0, 0, 0, 99) == -6
+    assert L.vlut_set_plan(0, 0, 12, 0) == 0 and L.vlut_set_plan(0, 0, 14, 0) == 0 and L.vlut_set_plan(0, 0, 16, 0) == 0
     assert L.vlut_set_plan(0, 0, 0, 0) == 0
     assert L.vlut_query_plan(8, 8, 8, None) == -1
 
@@ -212,7 +214,7 @@ def test_plans_cover_all_benchmark_shapes(L):
             per_chunk = {32: 0.9, 64: 1.35, 128: 2.0, 256: 3.4}[R]
             c = K / 1024
             assert N <= 2 or (tiles <= 256 and (3.6 + c * per_chunk) * 1.1 < 5.8 + 0.94 * c + 0.41 * M * N / 1e4)
-            assert L.vlut_workspace_bytes(M, K, N) == 0
+            assert L.vlut_workspace_bytes(M, K, N) == 0 and L.vlut_query_lookup_waves(M, K, N) == 0
             continue
         assert N > 2
         assert J in (1, 2, 4, 8, 16) and 1 <= R <= 16 and 1 <= S <= 16 and tiles >= 1
@@ -220,7 +222,9 @@ def test_plans_cover_all_benchmark_shapes(L):
         tiles_n = -(-N // n_tile)
         assert tiles % (tiles_n * S) == 0
         tiles_m = tiles // (tiles_n * S)
-        assert tiles_m * 48 * R >= M                                   # every row is covered (12 lookup waves x 4 rows x R)
+        waves = L.vlut_query_lookup_waves(M, K, N)
+        assert waves in (12, 14)
+        assert tiles_m * 4 * waves * R >= M                            # every row is covered (lookup waves x 4 rows x R)
 
 
 def test_g5_host_logic(L):

@@ -147,12 +147,15 @@ def test_every_interleave_factor(B, J):
     run_case(B, W, s, x, plan=(J, 1, 0, 1), tag=f"J{J}-n7")
 
 
+@pytest.mark.parametrize("waves", [12, 14])
 @pytest.mark.parametrize("R", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15, 16])
-def test_every_rows_per_wave(B, R):
-    M = 48 * R * 2 - 37                                     # two row tiles, the second one ragged
+def test_every_rows_per_wave(B, R, waves):
+    # waves = lookup waves of the workgroup (the other 4 or 2 build the tables): a tile holds 4 * waves * R rows
+    M = 4 * waves * R * 2 - 37                              # two row tiles, the second one ragged
     W, s, x = wl.small_case(20 + R, M, 512, 33)
-    run_case(B, W, s, x, plan=(8, R, 0, 1), tag=f"R{R}")
-    run_case(B, W, s, x, plan=(16, R, 0, 1), tag=f"R{R}-J16")   # the 16-sub-table plans have their own epilogue
+    run_case(B, W, s, x, plan=(8, R, waves, 1), tag=f"R{R}")
+    assert B.query_lookup_waves(M, 512, 33) in (12, 14)
+    run_case(B, W, s, x, plan=(16, R, waves, 1), tag=f"R{R}-J16")   # the 16-sub-table plans have their own epilogue
 
 
 @pytest.mark.parametrize("J,R,S", [(1, 2, 1), (1, 6, 1), (2, 3, 1), (4, 5, 2), (16, 4, 3), (8, 2, 6), (16, 3, 1),
@@ -160,7 +163,8 @@ def test_every_rows_per_wave(B, R):
 def test_int32_widening_and_split_k(B, J, R, S):
     # K = 4352 -> 1088 groups: more than 64 lookups per lane for small J, so the INT16 blocks get widened
     W, s, x = wl.small_case(30 + J + S, 300, 4352, 40)
-    run_case(B, W, s, x, plan=(J, R, 0, S), tag=f"widen J{J} R{R} S{S}")
+    for waves in (12, 14):
+        run_case(B, W, s, x, plan=(J, R, waves, S), tag=f"widen J{J} R{R} S{S} waves{waves}")
 
 
 def test_int16_block_is_overflow_free_at_the_extremes(B):
@@ -170,7 +174,7 @@ def test_int16_block_is_overflow_free_at_the_extremes(B):
     x[1::2] = -5.0
     for sign in (1, -1):
         W = np.full((M, K), sign, np.int8)
-        for plan in [(1, 1, 0, 1), (16, 1, 0, 1), (4, 2, 0, 2)]:
+        for plan in [(1, 1, 0, 1), (16, 1, 0, 1), (4, 2, 0, 2), (16, 1, 14, 1), (2, 3, 14, 1)]:
             run_case(B, W, np.float32(0.5), x, plan=plan, tag=f"extreme {sign}")
     q, _ = O.quantize(x)
     assert np.all(np.abs(q) == 127)

@@ -41,7 +41,8 @@ def cases():
         K = 4 * rnd.choice([1, 2, 5, 16, 33, 64, 100, 257, 640, 1088, 1728])
         N = rnd.choice([1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 24, 31, 32, 33, 64, 130, 300])
         forced = rnd.random() < 0.5
-        plan = (rnd.choice([1, 2, 4, 8, 16]), rnd.choice(ROWS_PER_WAVE), 0, rnd.choice([1, 1, 2, 3, 5, 8])) if forced \
+        plan = (rnd.choice([1, 2, 4, 8, 16]), rnd.choice(ROWS_PER_WAVE), rnd.choice([0, 12, 14]),
+                rnd.choice([1, 1, 2, 3, 5, 8])) if forced \
             else (0, 0, 0, 0)
         if M * K * N <= 6e8:
             out.append((len(out), M, K, N, plan))

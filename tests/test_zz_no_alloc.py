@@ -26,7 +26,11 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
+PLANS = {(2560, 6912, 64): (16, 6, 0, 4), (300, 1024, 40): (16, 1, 0, 4)}    # split-K plans: both calls need the scratch
+
+
 def _prepare(B, seed, M, K, N):
+    B.set_plan(*PLANS.get((M, K, N), (0, 0, 0, 0)))
     W, s, x = wl.small_case(seed, M, K, N)
     packed = B.pack_weights(dev(W))
     a_q, a_s = B.quantize_act(dev(x))
@@ -34,21 +38,27 @@ def _prepare(B, seed, M, K, N):
     y = torch.full((N, M), -7.0, dtype=torch.float32, device="cuda")
     acc = torch.full((M, N), -7, dtype=torch.int32, device="cuda")
     torch.cuda.synchronize()
+    B.set_plan(0, 0, 0, 0)
     return W, s, x, packed, a_q, a_s, y_ref, acc_ref, y, acc
 
 
 def test_static_scratch_entry_matches_mpgemm_on_two_calls_in_a_row(B):
     assert B.static_scratch_bytes() == 32 << 20
-    # (2560, 6912, 64): split-K 4; then a smaller input with another split count; both automatic plans
+    # (2560, 6912, 64) with four K splits, then a smaller input (300, 1024, 40), also split four ways
     big = _prepare(B, 700, 2560, 6912, 64)
     small = _prepare(B, 701, 300, 1024, 40)
-    for (M, K, N) in ((2560, 6912, 64), (300, 1024, 40)):
-        plan = B.query_plan(M, K, N)
-        print(f"static-scratch case M={M} K={K} N={N} plan={plan} ws={B.workspace_bytes(M, K, N)}", flush=True)
-        assert plan[2] > 1 and 0 < B.workspace_bytes(M, K, N) <= B.static_scratch_bytes()
-    for (W, s, x, packed, a_q, a_s, y_ref, acc_ref, y, acc), M in ((big, 2560), (small, 300)):
-        B.mpgemm_static(packed, float(s), a_q, a_s, M, y, acc)                   # back to back on one stream
-    torch.cuda.synchronize()
+    try:
+        for (M, K, N) in ((2560, 6912, 64), (300, 1024, 40)):
+            B.set_plan(*PLANS[(M, K, N)])
+            plan = B.query_plan(M, K, N)
+            print(f"static-scratch case M={M} K={K} N={N} plan={plan} ws={B.workspace_bytes(M, K, N)}", flush=True)
+            assert plan[2] > 1 and 0 < B.workspace_bytes(M, K, N) <= B.static_scratch_bytes()
+        for (W, s, x, packed, a_q, a_s, y_ref, acc_ref, y, acc), shape in ((big, (2560, 6912, 64)), (small, (300, 1024, 40))):
+            B.set_plan(*PLANS[shape])                                            # the override only selects the launch plan
+            B.mpgemm_static(packed, float(s), a_q, a_s, shape[0], y, acc)        # back to back on one stream
+        torch.cuda.synchronize()
+    finally:
+        B.set_plan(0, 0, 0, 0)
     for (W, s, x, packed, a_q, a_s, y_ref, acc_ref, y, acc) in (big, small):
         assert torch.equal(acc, acc_ref) and torch.equal(y.view(torch.int32), y_ref.view(torch.int32))
         _, _, acc_o, y_o = O.mpgemm(W, s, x)
@@ -64,10 +74,12 @@ def test_static_scratch_entry_matches_mpgemm_on_two_calls_in_a_row(B):
 
 
 def test_static_scratch_entry_rejects_what_does_not_fit(B):
-    M, K, N = 4096, 14336, 1024                                                  # automatic plan splits K: > 32 MiB
-    need = B.workspace_bytes(M, K, N)
-    if need <= B.static_scratch_bytes():
-        pytest.skip("the automatic plan of this shape fits the scratch")
-    d = torch.empty(16, dtype=torch.uint8, device="cuda")
-    rc = B.lib().vlut_mpgemm_static(d.data_ptr(), 1.0, d.data_ptr(), d.data_ptr(), M, K, N, d.data_ptr(), M, None, None)
-    assert rc == B.VLUT_ERR_UNSUPPORTED
+    M, K, N = 4096, 14336, 1024
+    B.set_plan(16, 6, 0, 4)                                                      # four K splits: 64 MiB of partial sums
+    try:
+        assert B.workspace_bytes(M, K, N) == 4 * M * N * 4 > B.static_scratch_bytes()
+        d = torch.empty(16, dtype=torch.uint8, device="cuda")
+        rc = B.lib().vlut_mpgemm_static(d.data_ptr(), 1.0, d.data_ptr(), d.data_ptr(), M, K, N, d.data_ptr(), M, None, None)
+        assert rc == B.VLUT_ERR_UNSUPPORTED
+    finally:
+        B.set_plan(0, 0, 0, 0)
