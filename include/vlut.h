@@ -287,15 +287,17 @@ int vlut_mpgemm_mixed(const uint8_t* packed, float w_scale, const int8_t* a_q, c
                       int64_t K, int64_t N, float* y, int64_t ldy, int32_t* acc_or_null, void* workspace,
                       size_t workspace_bytes, void* stream);
 
-/* Bytes of scratch vlut_mpgemm_mfma needs: a [tokens padded to 16][K padded to 64] INT8 copy of the activations. */
+/* Bytes of scratch vlut_mpgemm_mfma needs (INT32 partial sums when it splits K over workgroups); may be 0. */
 size_t vlut_mfma_workspace_bytes(int64_t M, int64_t K, int64_t N);
 
 /*
  * Same contract and same results as vlut_mpgemm (lut_or_null must be NULL), but
  * computed the multiply-add way the paper contrasts with (Sec. 2.2.1): packed
- * bytes are unpacked to INT8 and multiplied on the INT8 matrix cores.  In-run
- * comparison only.  workspace is required: 16-byte aligned,
- * workspace_bytes >= vlut_mfma_workspace_bytes(M, K, N).
+ * bytes are unpacked to INT8 and multiplied on the INT8 matrix cores, as a tiled
+ * GEMM (128 rows x up to 128 tokens per workgroup, operands staged in LDS, K split
+ * over workgroups for few tokens).  In-run comparison only.  workspace: 16-byte
+ * aligned, workspace_bytes >= vlut_mfma_workspace_bytes(M, K, N); may be NULL when
+ * that size is 0.  packed and a_q must be 16-byte aligned.
  */
 int vlut_mpgemm_mfma(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale,
                      const int16_t* lut_or_null, int64_t M, int64_t K, int64_t N, float* y,

@@ -538,6 +538,33 @@ int launch_lookup5_r(int R, const Lookup5Params& p, int grid, hipStream_t stream
     return launch_lookup5_by_r<NEED32>(R, p, grid, stream);
 }
 
+// ---- comparison path: tokens per workgroup from N, K split so that few tiles still give every CU a few workgroups
+struct MfmaPlan {
+    int BN, tiles_m, tiles_n, S, steps_per_split, grid;
+};
+
+MfmaPlan mfma_plan(int64_t M, int64_t K, int64_t N) {
+    MfmaPlan mp;
+    mp.BN = N > 64 ? 128 : (N > 32 ? 64 : (N > 16 ? 32 : 16));
+    mp.tiles_m = (int)((M + kMfRows - 1) / kMfRows);
+    // the kernel hides latency with resident waves only: narrower token tiles while the wide ones give a CU fewer
+    // than about three workgroups
+    if (mp.BN == 128 && (int64_t)mp.tiles_m * ((N + 127) / 128) < 768) mp.BN = 64;
+    mp.tiles_n = (int)((N + mp.BN - 1) / mp.BN);
+    const int steps = (int)((K / 4 + 15) / 16);
+    const int64_t tiles = (int64_t)mp.tiles_m * mp.tiles_n;
+    int S = 1;
+    if (tiles < 512) {
+        S = (int)((768 + tiles - 1) / tiles);                // about three workgroups per CU
+        if (S > 16) S = 16;
+        if (S > steps / 4) S = steps / 4 > 0 ? steps / 4 : 1;  // at least four K steps per split
+    }
+    mp.steps_per_split = (steps + S - 1) / S;
+    mp.S = (steps + mp.steps_per_split - 1) / mp.steps_per_split;
+    mp.grid = (int)(tiles * mp.S);
+    return mp;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1122,7 +1149,8 @@ int vlut_mpgemm_mixed(const uint8_t* packed, float w_scale, const int8_t* a_q, c
 
 size_t vlut_mfma_workspace_bytes(int64_t M, int64_t K, int64_t N) {
     if (!shape_ok(M, K, N)) return 0;
-    return (size_t)((N + 15) / 16 * 16) * (size_t)((K + 63) / 64 * 64);
+    const MfmaPlan mp = mfma_plan(M, K, N);
+    return mp.S > 1 ? (size_t)mp.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
 }
 
 int vlut_mpgemm_mfma(const uint8_t* packed, float w_scale, const int8_t* a_q, const float* a_scale,
@@ -1131,27 +1159,34 @@ int vlut_mpgemm_mfma(const uint8_t* packed, float w_scale, const int8_t* a_q, co
     int rc = check_mpgemm_args(packed, a_q, a_scale, M, K, N, y, ldy, acc_or_null);
     if (rc != VLUT_OK) return rc;
     if (lut_or_null) return VLUT_ERR_UNSUPPORTED;
-    if (!workspace) return VLUT_ERR_NULL;
-    if (workspace_bytes < vlut_mfma_workspace_bytes(M, K, N)) return VLUT_ERR_SMALL_BUFFER;
-    if (((uintptr_t)workspace) % 16 != 0) return VLUT_ERR_UNSUPPORTED;
+    if (((uintptr_t)a_q) % 16 != 0 || ((uintptr_t)packed) % 16 != 0) return VLUT_ERR_UNSUPPORTED;
+    const MfmaPlan mp = mfma_plan(M, K, N);
+    const size_t need = mp.S > 1 ? (size_t)mp.S * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
+    if (need > 0) {
+        if (!workspace) return VLUT_ERR_NULL;
+        if (workspace_bytes < need) return VLUT_ERR_SMALL_BUFFER;
+        if (((uintptr_t)workspace) % 16 != 0) return VLUT_ERR_UNSUPPORTED;
+    }
     hipStream_t s = (hipStream_t)stream;
     MfmaParams p;
     std::memset(&p, 0, sizeof(p));
-    p.packed = packed; p.aT = (const int8_t*)workspace; p.a_scale = a_scale; p.y = y; p.acc = acc_or_null;
-    p.w_scale = w_scale; p.M = (int)M; p.N = (int)N; p.Npad = (int)((N + 15) / 16 * 16); p.Kp = (int)((K + 63) / 64 * 64);
-    p.KCn = (int)((K / 4 + 15) / 16); p.RGtotal = (int)((M + 3) / 4); p.ldy = (int)ldy;
-    const size_t dwords = (size_t)p.Npad * (p.Kp / 4);
-    hipLaunchKernelGGL(act_transpose_kernel, dim3((unsigned)((dwords + 255) / 256)), dim3(256), 0, s, a_q, (int)N, (int)K, p.Npad,
-                       p.Kp, (int8_t*)workspace);
+    p.packed = packed; p.a_q = a_q; p.a_scale = a_scale; p.y = y; p.acc = acc_or_null; p.ws = (int32_t*)workspace;
+    p.w_scale = w_scale; p.M = (int)M; p.K = (int)K; p.N = (int)N;
+    p.KCn = (int)((K / 4 + 15) / 16); p.RGtotal = (int)((M + 3) / 4); p.ldy = (int)ldy; p.chunks = (int)((N + 7) / 8);
+    p.S = mp.S; p.steps_per_split = mp.steps_per_split; p.tiles_m = mp.tiles_m; p.tiles_n = mp.tiles_n;
+    if (mp.S > 1) p.out_vec = (M % 4 == 0) ? 1 : 0;
+    else p.out_vec = (!y || (((uintptr_t)y % 16 == 0) && (ldy % 4 == 0))) ? 1 : 0;
+    const dim3 grid((unsigned)mp.grid);
+    switch (mp.BN) {
+    case 128: hipLaunchKernelGGL(mfma_kernel<128>, grid, dim3(256), 0, s, p); break;
+    case 64: hipLaunchKernelGGL(mfma_kernel<64>, grid, dim3(256), 0, s, p); break;
+    case 32: hipLaunchKernelGGL(mfma_kernel<32>, grid, dim3(256), 0, s, p); break;
+    default: hipLaunchKernelGGL(mfma_kernel<16>, grid, dim3(256), 0, s, p); break;
+    }
     if (hipGetLastError() != hipSuccess) return VLUT_ERR_DEVICE;
-    const unsigned gx = (unsigned)((M + 63) / 64);
-    // Tokens per workgroup (16, 32 or 64): the widest tile that still gives about four workgroups per CU, since the
-    // kernel hides memory latency with resident waves only.
-    const unsigned g64 = (unsigned)((p.Npad + 63) / 64), g32 = (unsigned)((p.Npad + 31) / 32), g16 = (unsigned)(p.Npad / 16);
-    if (N > 32 && (size_t)gx * g64 >= 1024) hipLaunchKernelGGL(mfma_kernel<4>, dim3(gx, g64), dim3(256), 0, s, p);
-    else if (N > 16 && (size_t)gx * g32 >= 1024) hipLaunchKernelGGL(mfma_kernel<2>, dim3(gx, g32), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL(mfma_kernel<1>, dim3(gx, g16), dim3(256), 0, s, p);
-    return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
+    if (mp.S > 1)
+        return launch_splitk_reduce((const int32_t*)workspace, mp.S, M, N, w_scale, nullptr, a_scale, y, ldy, acc_or_null, s);
+    return VLUT_OK;
 }
 
 }  // extern "C"

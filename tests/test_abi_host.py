@@ -119,9 +119,13 @@ def test_argument_errors_come_before_any_device_call(L):
     assert L.vlut_build_lut(d, 8, 4, d, 2 * 81 * 4 * 2 - 1, None) == -3
     assert L.vlut_build_lut(d, 9, 4, d, 1 << 20, None) == -2
     L.vlut_mfma_workspace_bytes.argtypes, L.vlut_mfma_workspace_bytes.restype = [i64, i64, i64], sz
-    assert L.vlut_mfma_workspace_bytes(8, 8, 4) == 16 * 64 and L.vlut_mfma_workspace_bytes(8, 6, 4) == 0
-    assert L.vlut_mpgemm_mfma(d, 1.0, d, d, None, 8, 8, 4, d, 8, None, None, 0, None) == -1        # needs its workspace
-    assert L.vlut_mpgemm_mfma(d, 1.0, d, d, None, 8, 8, 4, d, 8, None, d, 16 * 64 - 1, None) == -3
+    assert L.vlut_mfma_workspace_bytes(8, 6, 4) == 0                      # invalid shape
+    assert L.vlut_mfma_workspace_bytes(8, 8, 4) == 0                      # one K step: nothing to split
+    need = L.vlut_mfma_workspace_bytes(640, 2560, 16)                     # few tiles, 40 K steps: K is split
+    assert need > 0 and need % (640 * 16 * 4) == 0 and need // (640 * 16 * 4) <= 16
+    assert L.vlut_mfma_workspace_bytes(14336, 4096, 512) == 0             # enough tiles without a split
+    assert L.vlut_mpgemm_mfma(d, 1.0, d, d, None, 640, 2560, 16, d, 640, None, None, 0, None) == -1   # needs its workspace
+    assert L.vlut_mpgemm_mfma(d, 1.0, d, d, None, 640, 2560, 16, d, 640, None, d, need - 1, None) == -3
     assert L.vlut_mpgemm_mfma(d, 1.0, d, d, d, 8, 8, 4, d, 8, None, d, 1 << 20, None) == -6        # no materialised table here
     for fn in (L.vlut_mpgemm, L.vlut_mpgemm_mfma):
         assert fn(None, 1.0, d, d, None, 8, 8, 4, d, 8, None, None, 0, None) == -1
