@@ -243,6 +243,99 @@ __global__ void __launch_bounds__(kTokThreads) quantize_token_kernel(const float
 }
 
 // ---------------------------------------------------------------------------------------------
+// The same quantiser as two kernels, for inputs of a few million values: reading x twice costs less than either the
+// single-byte stores of quantize_token_kernel or the few workgroups of quantize_kernel.
+//   absmax_token_kernel    one workgroup per token: amax[n] = max_k |x[n][k]|
+//   quantize_chunk_kernel  one workgroup per (chunk of 8 tokens, range of K): a thread reads the same four k of the 8
+//                          rows, quantises, transposes the bytes in registers and stores the 32 bytes [4 k][8 tokens]
+//                          of the token-chunked layout with two 16-byte stores (full lines per wave)
+// Same decisions in fp32 as the other two kernels (amax, IEEE divisions, rint, clamp), hence the same bits.
+// ---------------------------------------------------------------------------------------------
+template <bool VEC>
+__global__ void __launch_bounds__(kTokThreads) absmax_token_kernel(const float* __restrict__ x, int N, int K, int64_t ldx,
+                                                                   float* __restrict__ amax_out) {
+    __shared__ float red[kTokThreads / 64];
+    const int tid = threadIdx.x;
+    const int n = blockIdx.x;
+    if (n >= N) return;
+    const float* row = x + (size_t)n * ldx;
+    const int nquad = K >> 2;
+    float amax = 0.0f;
+    for (int q0 = 0; q0 < nquad; q0 += kTokThreads * 8) {       // eight loads in flight per thread and pass
+        f32x4 xv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int qi = q0 + tid + kTokThreads * i;
+            const float* src = row + 4 * (size_t)(qi < nquad ? qi : 0);
+            xv[i] = qi < nquad ? (VEC ? *(const f32x4*)src : f32x4{src[0], src[1], src[2], src[3]}) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            amax = fmaxf(fmaxf(amax, fmaxf(fabsf(xv[i].x), fabsf(xv[i].y))), fmaxf(fabsf(xv[i].z), fabsf(xv[i].w)));
+    }
+    amax = wave_max_f32(amax);
+    if ((tid & 63) == 0) red[tid >> 6] = amax;
+    __syncthreads();
+    if (tid == 0) {
+        float v = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kTokThreads / 64; ++w) v = fmaxf(v, red[w]);
+        amax_out[n] = v;
+    }
+}
+
+// 4 x 4 byte transpose: in[r] holds bytes (r,0..3); out[c] holds bytes (0..3, c).
+__device__ __forceinline__ void transpose_bytes4(const unsigned (&in)[4], unsigned (&out)[4]) {
+    const unsigned t01l = __builtin_amdgcn_perm(in[1], in[0], 0x05010400u), t01h = __builtin_amdgcn_perm(in[1], in[0], 0x07030602u);
+    const unsigned t23l = __builtin_amdgcn_perm(in[3], in[2], 0x05010400u), t23h = __builtin_amdgcn_perm(in[3], in[2], 0x07030602u);
+    out[0] = __builtin_amdgcn_perm(t23l, t01l, 0x05040100u);
+    out[1] = __builtin_amdgcn_perm(t23l, t01l, 0x07060302u);
+    out[2] = __builtin_amdgcn_perm(t23h, t01h, 0x05040100u);
+    out[3] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
+}
+
+template <bool VEC>
+__global__ void __launch_bounds__(kTokThreads) quantize_chunk_kernel(const float* __restrict__ x, int N, int K, int64_t ldx,
+                                                                     const float* __restrict__ amax,
+                                                                     int8_t* __restrict__ a_q, float* __restrict__ a_scale,
+                                                                     int quads_per_block) {
+    __shared__ float s_inv[8];
+    const int tid = threadIdx.x;
+    const int chunk = blockIdx.x;
+    if (tid < 8) {
+        const int n = chunk * 8 + tid;
+        const float v = n < N ? amax[n] : 0.0f;
+        s_inv[tid] = (v > 0.0f) ? 127.0f / v : 0.0f;           // IEEE divisions, as in the other quantisers
+        if (n < N && blockIdx.y == 0) a_scale[n] = v / 127.0f;
+    }
+    __syncthreads();
+    float inv[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) inv[t] = s_inv[t];
+    const int nquad = K >> 2;
+    const int q_begin = blockIdx.y * quads_per_block;
+    const int q_end = min(nquad, q_begin + quads_per_block);
+    int8_t* dst = a_q + (size_t)chunk * K * 8;
+    for (int qi = q_begin + tid; qi < q_end; qi += kTokThreads) {
+        unsigned c[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int n = chunk * 8 + t;
+            const float* src = x + (size_t)(n < N ? n : 0) * ldx + 4 * (size_t)qi;
+            const f32x4 v = n < N ? (VEC ? *(const f32x4*)src : f32x4{src[0], src[1], src[2], src[3]}) : f32x4{0.f, 0.f, 0.f, 0.f};
+            c[t] = n < N ? quant_codes4(v, inv[t]) : 0u;         // tokens past N: zeros
+        }
+        unsigned lo[4], hi[4];                                   // lo[k] = tokens 0-3 of k, hi[k] = tokens 4-7
+        const unsigned c_lo[4] = {c[0], c[1], c[2], c[3]}, c_hi[4] = {c[4], c[5], c[6], c[7]};
+        transpose_bytes4(c_lo, lo);
+        transpose_bytes4(c_hi, hi);
+        i32x4* o = (i32x4*)(dst + (size_t)qi * 32);
+        o[0] = i32x4{(int)lo[0], (int)hi[0], (int)lo[1], (int)hi[1]};
+        o[1] = i32x4{(int)lo[2], (int)hi[2], (int)lo[3], (int)hi[3]};
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Whole table in global memory (Alg. 1 Precompute / Eq. 1), topological order of Sec. 4:
 // every row is one add/sub away from an earlier one.  One thread per (group, token).
 // ---------------------------------------------------------------------------------------------

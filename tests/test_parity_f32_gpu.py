@@ -134,6 +134,21 @@ def test_row_stride_and_unaligned_rows(B):
     run_f32(B, W1, s1, x1, x_dev=dev(odd)[:, 3:1031], tag="unaligned rows, two tokens")
 
 
+def test_two_kernel_quantiser_for_large_inputs(B):
+    """More than about four million activation values: the quantiser inside vlut_mpgemm_f32 runs as two kernels
+    (absmax per token, then chunks of 8 tokens per K range); same codes and scales, bit for bit.  Ragged last chunk,
+    K ranges that do not divide K, rows that cannot be read as float4."""
+    for (M, K, N, pad) in [(64, 8192, 520, 0), (40, 14336, 300, 0), (33, 8200, 515, 3)]:
+        W, s, x = wl.small_case(480 + N, M, K, N)
+        assert N * K >= 1 << 22
+        if pad:                                              # rows start at addresses that are no multiple of 16
+            big = np.full((N, K + pad + 1), 1e9, np.float32)
+            big[:, 1:K + 1] = x
+            run_f32(B, W, s, x, tag="two-kernel quantiser, unaligned", x_dev=dev(big)[:, 1:K + 1])
+        else:
+            run_f32(B, W, s, x, tag="two-kernel quantiser")
+
+
 @pytest.mark.parametrize("M", [100, 5000, 10000, 20000, 40000])
 def test_one_or_two_tokens_every_tile_shape(B, M):
     for N, K in ((1, 260), (2, 1028)):
