@@ -50,9 +50,11 @@ MFMA_INT8_PEAK_TOPS = 5000.0                              # dense INT8 matrix-co
 
 # HBM bytes per launch of the lookup kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), see profiles/
 MEASURED_TRAFFIC_BYTES = {
-    "bitnet2b_ffn_up/up/128": 10.95e6,     # profiles/lookup_kernel_bitnet2b_ffn_up_hbm_traffic.md
-    "layer2b4_nsweep/gate/1": 4.64e6,      # profiles/narrow_kernel_layer2b4_gate_n1_stats_and_hbm_traffic.md
-    "llama8b_linears/gateup/512": 83.6e6,  # profiles/lookup_kernel_bitnet2b_ffn_up_hbm_traffic.md (second part)
+    "llama8b_linears/gateup/512": 77.5e6,  # profiles/lookup_kernel_llama8b_gateup_n512_stats_sq_counters_hbm_traffic.md
+    "bitnet3b_prefill/up/256": 22.8e6,     # profiles/lookup_kernel_bitnet3b_up_n256_stats_sq_counters_hbm_traffic.md
+    "bitnet2b_ffn_up/up/128": 10.96e6,     # profiles/lookup_kernel_bitnet2b_ffn_up_n128_stats_sq_counters_hbm_traffic.md
+    "layer2b4_nsweep/gate/16": 6.34e6,     # profiles/layer2b4_gate_n16_kernel_stats_hbm_traffic.md
+    "layer2b4_nsweep/gate/1": 4.66e6,      # profiles/narrow_kernel_layer2b4_gate_n1_stats_and_hbm_traffic.md
 }
 
 
