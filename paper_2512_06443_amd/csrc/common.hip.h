@@ -58,6 +58,7 @@ struct LookupParams {
     int64_t ldx;
     int x_vec;                // rows can be read as float4
     int out_vec;              // y (or the partial-sum slots) can be written four rows at a time
+    unsigned magic_S, magic_tiles_n;   // floor(2^32 / S), floor(2^32 / tiles_n) (0xffffffff for a divisor of 1): set by the launcher
 };
 
 __device__ __forceinline__ unsigned lds_base_of(void* p) {
@@ -93,6 +94,9 @@ __device__ __forceinline__ int lane_xor16(int x) {
     if (MASK == 2) return __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xF, 0xF, false);
     return __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, false);
 }
+// Value of lane l ^ 8 where the result is not the operand of an addition the exchange could be folded into: every
+// lane has a source lane, so the value itself serves as the fill value and no register has to be zeroed first.
+__device__ __forceinline__ int lane_xor8_plain(int x) { return __builtin_amdgcn_update_dpp(x, x, 0x128, 0xF, 0xF, false); }
 // Value of lane l ^ 7 (row_half_mirror reverses each group of 8 lanes): a one-instruction partner whose bit 2 differs.
 __device__ __forceinline__ int lane_xor7(int x) { return __builtin_amdgcn_update_dpp(0, x, 0x141, 0xF, 0xF, false); }
 
@@ -182,19 +186,27 @@ __device__ __forceinline__ s16x2 unpack_pair(unsigned x, int h) {
     return v >> (short)8;                            // arithmetic shift per half
 }
 
-// reduce16 for accumulators in word form: lane l ends with the total of token l >> 1.
+// Start value of a word accumulator whose halves are kept biased by +32768 each (see reduce16w): with at most 64
+// lookups of |entry| <= 508 per block both halves stay inside [256, 65280].
+constexpr int kBiasedZero = (int)0x80008000u;
+
+// reduce16 for accumulators in word form: lane l ends with the total of token l >> 1.  Without INT32 partial sums
+// (WIDE == false) the words must have started at kBiasedZero.
 template <bool WIDE>
 __device__ __forceinline__ int reduce16w(const int (&aw)[4], const int (&a32)[8], int l) {
     const bool hi3 = (l & 8) != 0, hi2 = (l & 4) != 0, hi1 = (l & 2) != 0;
     int w[4];
     if constexpr (!WIDE) {
-        const int kA = hi3 ? aw[2] : aw[0], kB = hi3 ? aw[3] : aw[1];
-        const int rA = lane_xor16<8>(hi3 ? aw[0] : aw[2]);
-        const int rB = lane_xor16<8>(hi3 ? aw[1] : aw[3]);
-        w[0] = word_lo(kA) + word_lo(rA);
-        w[1] = word_hi(kA) + word_hi(rA);
-        w[2] = word_lo(kB) + word_lo(rB);
-        w[3] = word_hi(kB) + word_hi(rB);
+        // Here the accumulators started at kBiasedZero instead of 0: both halves carry +32768, so they are plain
+        // unsigned 16-bit fields (no borrow between them) and come apart with a mask and a shift; the 16 biases of a
+        // total are taken off at the end.
+        const unsigned kA = (unsigned)(hi3 ? aw[2] : aw[0]), kB = (unsigned)(hi3 ? aw[3] : aw[1]);
+        const unsigned rA = (unsigned)lane_xor8_plain(hi3 ? aw[0] : aw[2]);
+        const unsigned rB = (unsigned)lane_xor8_plain(hi3 ? aw[1] : aw[3]);
+        w[0] = (int)((kA & 0xffffu) + (rA & 0xffffu));
+        w[1] = (int)((kA >> 16) + (rA >> 16));
+        w[2] = (int)((kB & 0xffffu) + (rB & 0xffffu));
+        w[3] = (int)((kB >> 16) + (rB >> 16));
     } else {
         int v[8];
 #pragma unroll
@@ -208,7 +220,7 @@ __device__ __forceinline__ int reduce16w(const int (&aw)[4], const int (&a32)[8]
     const int x0 = (hi2 ? w[2] : w[0]) + lane_xor7(hi2 ? w[0] : w[2]);
     const int x1 = (hi2 ? w[3] : w[1]) + lane_xor7(hi2 ? w[1] : w[3]);
     const int y1 = (hi1 ? x1 : x0) + lane_xor16<2>(hi1 ? x0 : x1);
-    return y1 + lane_xor16<1>(y1);
+    return (y1 - (WIDE ? 0 : 16 * 32768)) + lane_xor16<1>(y1);
 }
 
 }  // namespace

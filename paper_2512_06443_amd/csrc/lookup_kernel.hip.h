@@ -79,8 +79,51 @@ __device__ __forceinline__ void lookup_half(const unsigned (&w)[R], unsigned lan
     });
 }
 
+// The kernel's argument struct, read field by field from the kernel-argument segment (scalar loads).
+typedef const __attribute__((address_space(4))) LookupParams* LookupKernelArgs;
+__device__ __forceinline__ LookupParams read_lookup_params(LookupKernelArgs a) {
+    LookupParams r;
+    r.packed = a->packed;
+    r.a_q = a->a_q;
+    r.a_scale = a->a_scale;
+    r.w_rows = a->w_rows;
+    r.lut = a->lut;
+    r.y = a->y;
+    r.acc = a->acc;
+    r.ws = a->ws;
+    r.w_scale = a->w_scale;
+    r.M = a->M;
+    r.K = a->K;
+    r.N = a->N;
+    r.G = a->G;
+    r.KCn = a->KCn;
+    r.RGtotal = a->RGtotal;
+    r.ldy = a->ldy;
+    r.Jlog = a->Jlog;
+    r.S = a->S;
+    r.tiles_m = a->tiles_m;
+    r.tiles_n = a->tiles_n;
+    r.RGW = a->RGW;
+    r.stages_total = a->stages_total;
+    r.stages_per_split = a->stages_per_split;
+    r.total_tiles = a->total_tiles;
+    r.per_xcd = a->per_xcd;
+    r.aligned8 = a->aligned8;
+    r.Ka = a->Ka;
+    r.partial = a->partial;
+    r.slot0 = a->slot0;
+    r.x = a->x;
+    r.a_scale_out = a->a_scale_out;
+    r.ldx = a->ldx;
+    r.x_vec = a->x_vec;
+    r.out_vec = a->out_vec;
+    r.magic_S = a->magic_S;
+    r.magic_tiles_n = a->magic_tiles_n;
+    return r;
+}
+
 template <int R, bool NEED32, int MODE, int BW>
-__global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) {
+__global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams launch_params) {
     constexpr int kBuildWaves = BW;
     constexpr int kLookupWaves = kWaves - BW;
     constexpr int kRoundRows = kLookupWaves * 4;     // output rows per row-group round of the workgroup
@@ -92,53 +135,81 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
     // as idx*256 + slice*16 by a byte permute and rely on that.  The host verifies it (static LDS size of the
     // kernel == 0) before the first launch and refuses to launch otherwise, so this branch is never taken.
     if (lds_base_of(smem) != 0u) return;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);   // wave-uniform by construction
 
-    // Fetch every launch parameter now, in one batch of scalar loads.  Left alone, the compiler loads only what the
-    // early exit below needs and the rest after it, so each workgroup would wait for the argument buffer twice.
+    // The launch parameters live in a local copy that is filled from the kernel-argument segment (the struct is the
+    // kernel's only argument, at offset 0): once here, in one batch of scalar loads (the argument buffer is cold,
+    // and left alone the compiler would fetch its cache lines one after the other, where each is first needed), and
+    // again after the K loop of every tile through a pointer the optimiser cannot see through.  So the parameters
+    // need no registers during the K loop, and the loads that bring them back are hidden behind the epilogue.
+    (void)launch_params;
+    const LookupKernelArgs kernel_args = (LookupKernelArgs)__builtin_amdgcn_kernarg_segment_ptr();
+    LookupParams p = read_lookup_params(kernel_args);
     asm volatile("" ::"s"(p.per_xcd), "s"(p.total_tiles), "s"(p.S), "s"(p.tiles_n), "s"(p.Jlog), "s"(p.RGW),
-                 "s"(p.stages_per_split), "s"(p.stages_total), "s"(p.K), "s"(p.N), "s"(p.G), "s"(p.KCn), "s"(p.RGtotal),
-                 "s"(p.M), "s"(p.ldy), "s"(p.w_scale), "s"(p.packed), "s"(p.a_q), "s"(p.a_scale), "s"(p.y), "s"(p.acc),
-                 "s"(p.ws), "s"(p.lut), "s"(p.aligned8), "s"(p.w_rows), "s"(p.x), "s"(p.a_scale_out), "s"(p.ldx),
-                 "s"(p.x_vec));
+                 "s"(p.stages_per_split), "s"(p.stages_total), "s"(p.K), "s"(p.N), "s"(p.G), "s"(p.KCn),
+                 "s"(p.RGtotal), "s"(p.M), "s"(p.ldy), "s"(p.w_scale), "s"(p.packed), "s"(p.a_q), "s"(p.a_scale),
+                 "s"(p.y), "s"(p.acc), "s"(p.ws), "s"(p.lut), "s"(p.aligned8), "s"(p.w_rows), "s"(p.x),
+                 "s"(p.a_scale_out), "s"(p.ldx), "s"(p.x_vec), "s"(p.out_vec), "s"(p.Ka), "s"(p.slot0),
+                 "s"(p.magic_S), "s"(p.magic_tiles_n));
 
-    // ---- which tile (XCD-aware: the 8 XCDs take contiguous ranges of the tile list, so the
-    //      workgroups that share a weight tile also share an L2)
-    int L = (int)(blockIdx.x & 7) * p.per_xcd + (int)(blockIdx.x >> 3);
-    if ((int)(blockIdx.x >> 3) >= p.per_xcd || L >= p.total_tiles) return;
-    const int ks = L % p.S;
-    L /= p.S;
-    const int nt = L % p.tiles_n;
-    const int mt = L / p.tiles_n;
+    const bool builder = wave < kBuildWaves;          // scalar condition
+    const int lw = wave - kBuildWaves;                // index among the lookup waves
 
+    typedef __attribute__((address_space(3))) float lds_f32;
+    lds_f32* scale_lds = (lds_f32*)(unsigned)kTableBytes;   // output scale of every token of the tile, behind the tables
+
+    // ---- the tiles of this workgroup.  The grid is one workgroup per compute unit (or fewer); the 8 XCDs take
+    //      contiguous ranges of the tile list (workgroups that share a weight tile also share an L2), and inside
+    //      a range the workgroups of the XCD take tiles round robin.  The trip count is the same for every wave of the
+    //      workgroup, and so is the number of barriers either role passes per tile.
+    const int xcd = (int)(blockIdx.x & 7), wg_in_xcd = (int)(blockIdx.x >> 3), wgs_per_xcd = (int)(gridDim.x >> 3);
+    const int tiles_here = min(p.per_xcd, p.total_tiles - xcd * p.per_xcd);
+    for (int ti = wg_in_xcd; ti < tiles_here; ti += wgs_per_xcd) {
+    // The lane's coordinates, from a copy of the thread index the optimiser cannot see through: everything derived
+    // from them is then computed per tile, where it is used, instead of once before the tile loop and held in
+    // registers (or spilled) across the K loop.
+    int tid = (int)threadIdx.x;
+    asm volatile("" : "+v"(tid));
     const int Jlog = p.Jlog;
     const int J = 1 << Jlog;
     const int TClog = 4 - Jlog;          // log2(token chunks per sub-table)
     const int n_tile = 128 >> Jlog;
-    const int n0 = nt * n_tile;
-    const int rgw0 = mt * p.RGW;          // first row group of this workgroup
-
+    const int lane = tid & 63;
     const int l = lane & 15;             // 16-byte slice of the table rows this lane reads or writes
     const int grp = lane >> 4;
     const int j = l >> TClog;            // sub-table selector of the slice
     const int t = l & ((1 << TClog) - 1);   // 8-token chunk of the slice
     const unsigned lanebase = (unsigned)l * 16u;
-
+    // With 8-token tiles (16 sub-tables per table row) every lookup wave owns consecutive row groups and writes its
+    // own results (no workgroup barrier after the K loop), so the build waves go straight on to the next tile of the
+    // workgroup and its first tables are ready when the lookup waves arrive.  Otherwise row groups are dealt round
+    // robin and the whole workgroup transposes and writes the tile.
+    const bool own_rows = Jlog == 4;
+    const int rg_per_wave = (p.RGW + kLookupWaves - 1) / kLookupWaves;
+    // Tile index -> (K split, token tile, row tile).  The two divisions are multiplications by floor(2^32 / d)
+    // (from the host) with one correction step: the product's high word is the quotient or one less.
+    auto divide = [](unsigned x, unsigned d, unsigned magic, unsigned& q, unsigned& r) {
+        q = __umulhi(x, magic);
+        r = x - q * d;
+        if (r >= d) { ++q; r -= d; }
+    };
+    unsigned L1, uks, umt, unt;
+    divide((unsigned)(xcd * p.per_xcd + ti), (unsigned)p.S, p.magic_S, L1, uks);
+    divide(L1, (unsigned)p.tiles_n, p.magic_tiles_n, umt, unt);
+    const int ks = (int)uks, nt = (int)unt, mt = (int)umt;
+    const int n0 = nt * n_tile;
+    const int rgw0 = mt * p.RGW;          // first row group of this workgroup
     const int st_begin = ks * p.stages_per_split;
     const int st_end = min(p.stages_total, st_begin + p.stages_per_split);
-    const bool builder = wave < kBuildWaves;          // scalar condition
-    const int lw = wave - kBuildWaves;                // index among the lookup waves
 
-    // Output scale of every token of the tile, parked behind the tables (read in the epilogue).
-    typedef __attribute__((address_space(3))) float lds_f32;
-    lds_f32* scale_lds = (lds_f32*)(unsigned)kTableBytes;
-    // Loaded now, stored to LDS only when the K loop is over: nothing at the start of the kernel waits for it.
-    // (Nor for a product with it: wave 0, which holds these lanes, is a build wave, and the first barrier of the
-    // kernel waits for its first tables.)
+    // The token scales are loaded at the start of a tile and stored to LDS after the tile's first barrier (by then
+    // every wave has finished the stores of the previous tile, which read them); the epilogue reads them many
+    // barriers later.  tid < n_tile <= 128 are lanes of build waves.
     float my_scale = 0.0f;
     if (MODE != kFusedQuant && tid < n_tile && n0 + tid < p.N) my_scale = p.a_scale[n0 + tid];
+    auto publish_scales = [&]() {
+        if (tid < n_tile) scale_lds[tid] = (MODE != kFusedQuant && !p.w_rows) ? p.w_scale * my_scale : my_scale;
+    };
 
     // Fused quantisation (all 16 waves; called once by either role, after its first loads are on their way): lane =
     // token + 8 * quad, a wave reads 8 consecutive float4 of each of the 8 rows per pass.  Absmax over all of K
@@ -220,10 +291,12 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
 
     int accw[R][4];                       // block sums: two INT16 sums per word (word_lo / word_hi)
     int acc32[NEED32 ? R : 1][8];
+    // (the 16-lane reduction of the own-rows epilogue takes biased halves when there are no INT32 partial sums)
+    const int acc_zero = (own_rows && !NEED32) ? kBiasedZero : 0;
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) accw[r][q] = 0;
+        for (int q = 0; q < 4; ++q) accw[r][q] = acc_zero;
     if (NEED32) {
 #pragma unroll
         for (int r = 0; r < R; ++r)
@@ -242,7 +315,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         const int u = u0;                            // (kFromGlobal: one digit pair per lane)
         const int nb = n0 + 8 * t;                   // first token of the slice
         const int chunk_b = nb >> 3;
-        unsigned actA[4][2], actB[4][2];
+        unsigned actA[4][2] = {}, actB[4][2] = {};       // (initialised: otherwise they count as carried from tile to tile)
         bool validA = false, validB = false;
 
         // Half-stage hs = 2*stage + half holds slots 2*half, 2*half+1 = sub-tables kg = stage*4J + 4j + slot.
@@ -310,6 +383,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         if constexpr (MODE == kFromGlobal) {
             if (hs0 < hs1) build_half(hs0);
             wg_barrier_lds();
+            publish_scales();
             for (int hs = hs0; hs < hs1; hs += 2) {
                 build_half(hs + 1);                   // lookups read half 0 now: fill half 1
                 wg_barrier_lds();
@@ -325,7 +399,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
             // a few rows are ever live.  Every row is one add or subtract away from an earlier one (topological
             // order, Sec. 4); the arithmetic is plain 32-bit on words of two entries each (|word| < 2^23 for an
             // activation, so the 24-bit multiplies by the digits -1, 0, +1 are exact).
-            unsigned act2[4][2], act3[4][2];
+            unsigned act2[4][2] = {}, act3[4][2] = {};
             bool valid2 = false, valid3 = false;
             auto build_rows = [&](int hs, unsigned (&act)[4][2], bool valid) {
                 if (!valid) {
@@ -404,6 +478,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
             }
             // half 0 of the first stage, handed over as soon as it is written
             step(hs0, actA, validA);
+            publish_scales();
             for (int hs = hs0; hs < hs1; hs += 4) {
                 step(hs + 1, actB, validB);           // lookups read half 0 (hs): fill half 1
                 step(hs + 2, act2, valid2);           // lookups read half 1 (hs+1): fill half 0
@@ -417,13 +492,22 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
         // ================================ lookup role ================================
         // Row group r of this wave: its packed tiles start at a wave-uniform address (scalar registers); the lane
         // adds its row (grp) and, per stage, the tile and dword it needs.
+        // The wave's row groups are first, first + step, ... : consecutive ones when the wave writes its own rows,
+        // else dealt round robin over the lookup waves (round r of the epilogue then covers consecutive rows).
+        // nvalid of them lie inside the tile and the matrix; the others repeat the last valid one and are never
+        // stored.  Few scalar instructions per row group: this runs before the tile's first barrier.
         const unsigned char* wbase[R];
+        {
+            const int first = own_rows ? lw * rg_per_wave : lw;
+            const int lim = min(p.RGW, p.RGtotal - rgw0) - first;           // existing row groups from `first` on
+            int nvalid = own_rows ? min(lim, rg_per_wave) : (lim + kLookupWaves - 1) / kLookupWaves;
+            nvalid = max(0, min(nvalid, R));
+            const unsigned last = (unsigned)max(nvalid - 1, 0);
+            const unsigned tile_bytes = (unsigned)p.KCn * 64u;               // packed bytes of a row group
+            const unsigned step_bytes = own_rows ? tile_bytes : tile_bytes * (unsigned)kLookupWaves;   // < 2^28
+            const unsigned char* base0 = p.packed + (size_t)(rgw0 + (nvalid > 0 ? first : 0)) * tile_bytes;
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int rgl = r * kLookupWaves + lw;   // r-major: round r of the epilogue covers 48 consecutive rows
-            const int rg = rgw0 + rgl;
-            const bool valid = (rgl < p.RGW) && (rg < p.RGtotal);
-            wbase[r] = p.packed + ((size_t)(valid ? rg : 0) * p.KCn) * 64;
+            for (int r = 0; r < R; ++r) wbase[r] = base0 + min((unsigned)r, last) * step_bytes;      // < 2^32
         }
         // Weight dwords (4 lookups each) are fetched one whole stage ahead.  Dword q = st*J + j of each row.
         // Out-of-range cases need no masking: a tile index past the end of K is clamped to the last tile and meets
@@ -469,12 +553,101 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
 
     // ---- epilogue.  Per row group: widen to INT32, add the J partial sums of each token across the 16 lanes of
     // the group with a reduce-scatter (each step halves the tokens a lane keeps), park the sums in LDS as
-    // [token][row] and let the whole workgroup write consecutive output rows per token.
-    lds_i32* park = (lds_i32*)0u;
-    if (tid < n_tile)                                // visible after the first barrier below
-        scale_lds[tid] = (MODE != kFusedQuant && !p.w_rows) ? p.w_scale * my_scale : my_scale;
+    // [token][row] and write consecutive output rows per token.
+    {   // the parameters again, for this epilogue and the next tile
+        LookupKernelArgs again = kernel_args;
+        asm volatile("" : "+s"(again));
+        p = read_lookup_params(again);
+    }
     const int m0 = rgw0 * 4;
     const int rows_wg = min(p.RGW * 4, p.M - m0);
+    // What the stores need:
+    float* const out_y = p.y;
+    int32_t* const out_acc = p.acc;
+    int32_t* const out_ws = p.ws + (size_t)(p.slot0 + ks) * p.N * p.M;
+    const float* const w_rows = p.w_rows;
+    const int out_ldy = p.ldy, out_N = p.N, out_M = p.M;
+    const bool final_out = p.S == 1 && !p.partial, out_vec = p.out_vec != 0;
+    // The lane's coordinates again, from a copy of the thread index the optimiser cannot see through: otherwise every
+    // address below is computed before the tile loop and held in registers (or spilled) across the K loop.
+    int tid_e = tid;
+    asm volatile("" : "+v"(tid_e));
+    const int lane_e = tid_e & 63, l_e = lane_e & 15, grp_e = lane_e >> 4, t_e = l_e & ((1 << TClog) - 1);
+    // Four consecutive rows of one token (INT32 sums `v4`, rows m .. m + cnt - 1, token n with tile-local index nl).
+    auto store_quad = [&](const i32x4 v4, int m, int cnt, int n, int nl) {
+        const int val[4] = {v4.x, v4.y, v4.z, v4.w};
+        if (final_out) {
+            if (out_y) {
+                const float sn = scale_lds[nl];
+                float o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    o[e] = (float)val[e] * ((w_rows && e < cnt) ? w_rows[m + e] * sn : sn);
+                float* dsty = out_y + (size_t)n * out_ldy + m;
+                if (cnt == 4) {
+                    *(f32x4*)dsty = f32x4{o[0], o[1], o[2], o[3]};
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 3; ++e)
+                        if (e < cnt) dsty[e] = o[e];
+                }
+            }
+            if (out_acc) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (e < cnt) out_acc[(size_t)(m + e) * out_N + n] = val[e];
+            }
+        } else {
+            int32_t* dstw = out_ws + (size_t)n * out_M + m;
+            if (cnt == 4) {
+                *(i32x4*)dstw = v4;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 3; ++e)
+                    if (e < cnt) dstw[e] = val[e];
+            }
+        }
+    };
+    auto store_one = [&](int val, int m, int n, int nl) {
+        if (final_out) {
+            if (out_y) out_y[(size_t)n * out_ldy + m] = (float)val * (w_rows ? w_rows[m] * scale_lds[nl] : scale_lds[nl]);
+            if (out_acc) out_acc[(size_t)m * out_N + n] = val;
+        } else {
+            out_ws[(size_t)n * out_M + m] = val;
+        }
+    };
+    if (own_rows) {
+        // Every lookup wave on its own: its R row groups are 4R consecutive rows; the totals go through a private
+        // patch of LDS (in the second half of the table slots: the build waves, already at work on the next tile,
+        // write only the first half before the next barrier) and come back as runs of consecutive rows per token.
+        // LDS operations of one wave complete in order, so the wave only waits for its own writes.
+        if (!builder) {
+            constexpr int kOwnStride = 4 * R + 4;               // ints per parked token; +4 spreads the tokens over banks
+            lds_i32* own = (lds_i32*)(unsigned)(2 * kSlotBytes + lw * (8 * kOwnStride * 4));
+#pragma unroll
+            for (int r = 0; r < R; ++r)   // both lanes of a pair hold the same total and store it to the same place
+                own[(l_e >> 1) * kOwnStride + 4 * r + grp_e] = reduce16w<NEED32>(accw[r], acc32[NEED32 ? r : 0], l_e);
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            const int mrow0 = lw * rg_per_wave * 4;                       // first row of this wave inside the tile
+            const int rows_w = min(rg_per_wave * 4, rows_wg - mrow0);     // <= 0: nothing to write
+            if (out_vec) {
+                for (int it = lane_e; it < 8 * R; it += 64) {
+                    const int q = it % R, nl = it / R;
+                    const int n = n0 + nl;
+                    if (4 * q < rows_w && n < out_N)
+                        store_quad(*(const lds_i32x4*)(own + nl * kOwnStride + 4 * q), m0 + mrow0 + 4 * q,
+                                   min(4, rows_w - 4 * q), n, nl);
+                }
+            } else {
+                for (int it = lane_e; it < 8 * 4 * R; it += 64) {
+                    const int col = it % (4 * R), nl = it / (4 * R);
+                    const int n = n0 + nl;
+                    if (col < rows_w && n < out_N) store_one(own[nl * kOwnStride + col], m0 + mrow0 + col, n, nl);
+                }
+            }
+        }
+    } else {
+    lds_i32* park = (lds_i32*)0u;
     // RC = row-group rounds parked per pass.  All R at once when the tile has few tokens (the R independent
     // reduction chains then overlap); two at a time when [tokens][rows] would not fit in LDS.
     auto epilogue = [&](auto rc_tag) {
@@ -486,23 +659,18 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
 #pragma unroll
         for (int rr = 0; rr < RC; ++rr) {
             const int r = c0 + rr;
-            if (r < R && Jlog == 4) {
-                // both lanes of a pair hold the same total and store it to the same place
-                park[(l >> 1) * kParkStride + rr * kRoundRows + lw * 4 + grp] =
-                    reduce16w<NEED32>(accw[r], acc32[NEED32 ? r : 0], l);
-            } else if (r < R) {
+            if (r < R) {
                 int v[8];
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     v[2 * q] = word_lo(accw[r][q]) + (NEED32 ? acc32[r][2 * q] : 0);
                     v[2 * q + 1] = word_hi(accw[r][q]) + (NEED32 ? acc32[r][2 * q + 1] : 0);
                 }
-                // Reduce-scatter over the sub-table selector j (the top Jlog bits of the lane's slice index): each
-                // step exchanges half of the remaining tokens with the lane whose index differs in one bit.
+                // Reduce-scatter over the sub-table selector j (the top Jlog bits of the lane_e's slice index): each
+                // step exchanges half of the remaining tokens with the lane_e whose index differs in one bit.
                 int tokoff = 0;
-                bool owner = true;
                 if (Jlog > 0) {
-                    const bool hi = (l & 8) != 0;
+                    const bool hi = (l_e & 8) != 0;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         const int send = hi ? v[e] : v[e + 4];
@@ -512,7 +680,7 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                     tokoff += hi ? 4 : 0;
                 }
                 if (Jlog > 1) {
-                    const bool hi = (l & 4) != 0;
+                    const bool hi = (l_e & 4) != 0;
 #pragma unroll
                     for (int e = 0; e < 2; ++e) {
                         const int send = hi ? v[e] : v[e + 2];
@@ -522,94 +690,46 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams p) 
                     tokoff += hi ? 2 : 0;
                 }
                 if (Jlog > 2) {
-                    const bool hi = (l & 2) != 0;
+                    const bool hi = (l_e & 2) != 0;
                     const int send = hi ? v[0] : v[1];
                     const int keep = hi ? v[1] : v[0];
                     v[0] = keep + lane_xor16<2>(send);
                     tokoff += hi ? 1 : 0;
                 }
-                if (Jlog > 3) {
-                    v[0] += lane_xor16<1>(v[0]);
-                    owner = (l & 1) == 0;
-                }
-                const int cnt = 8 >> min(Jlog, 3);
-                if (owner) {
-                    const int col = rr * kRoundRows + lw * 4 + grp;
+                const int cnt = 8 >> Jlog;      // Jlog <= 3 here
+                const int col = rr * kRoundRows + lw * 4 + grp_e;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        if (e < cnt) park[(8 * t + tokoff + e) * kParkStride + col] = v[e];
-                }
+                for (int e = 0; e < 8; ++e)
+                    if (e < cnt) park[(8 * t_e + tokoff + e) * kParkStride + col] = v[e];
             }
         }
         }
         wg_barrier_lds();
-        if (p.out_vec) {
+        if (out_vec) {
             // four consecutive rows of one token per thread: one 16-byte read of the parked sums, one 16-byte store
-            for (int i = tid; i < RC * (kRoundRows / 4) * n_tile; i += kThreads) {
+            for (int i = tid_e; i < RC * (kRoundRows / 4) * n_tile; i += kThreads) {
                 const int col = 4 * (i % (RC * (kRoundRows / 4)));
                 const int nl = i / (RC * (kRoundRows / 4));
                 const int mrow = c0 * kRoundRows + col;     // row inside the workgroup tile
                 const int n = n0 + nl;
-                if (mrow < rows_wg && mrow < R * kRoundRows && n < p.N) {
-                    const i32x4 v4 = *(const lds_i32x4*)(park + nl * kParkStride + col);
-                    const int val[4] = {v4.x, v4.y, v4.z, v4.w};
-                    const int m = m0 + mrow;
-                    const int cnt = min(4, rows_wg - mrow);
-                    if (p.S == 1 && !p.partial) {
-                        if (p.y) {
-                            const float sn = scale_lds[nl];
-                            float o[4];
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                o[e] = (float)val[e] * ((p.w_rows && e < cnt) ? p.w_rows[m + e] * sn : sn);
-                            float* dsty = p.y + (size_t)n * p.ldy + m;
-                            if (cnt == 4) {
-                                *(f32x4*)dsty = f32x4{o[0], o[1], o[2], o[3]};
-                            } else {
-#pragma unroll
-                                for (int e = 0; e < 3; ++e)
-                                    if (e < cnt) dsty[e] = o[e];
-                            }
-                        }
-                        if (p.acc) {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (e < cnt) p.acc[(size_t)(m + e) * p.N + n] = val[e];
-                        }
-                    } else {
-                        int32_t* dstw = p.ws + ((size_t)(p.slot0 + ks) * p.N + n) * p.M + m;
-                        if (cnt == 4) {
-                            *(i32x4*)dstw = v4;
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 3; ++e)
-                                if (e < cnt) dstw[e] = val[e];
-                        }
-                    }
-                }
+                if (mrow < rows_wg && mrow < R * kRoundRows && n < out_N)
+                    store_quad(*(const lds_i32x4*)(park + nl * kParkStride + col), m0 + mrow, min(4, rows_wg - mrow), n, nl);
             }
         } else
-        for (int i = tid; i < RC * kRoundRows * n_tile; i += kThreads) {
+        for (int i = tid_e; i < RC * kRoundRows * n_tile; i += kThreads) {
             const int col = i % (RC * kRoundRows);
             const int nl = i / (RC * kRoundRows);
             const int mrow = c0 * kRoundRows + col;         // row inside the workgroup tile
             const int n = n0 + nl;
-            if (mrow < rows_wg && mrow < R * kRoundRows && n < p.N) {
-                const int val = park[nl * kParkStride + col];
-                const int m = m0 + mrow;
-                if (p.S == 1 && !p.partial) {
-                    if (p.y) p.y[(size_t)n * p.ldy + m] = (float)val * (p.w_rows ? p.w_rows[m] * scale_lds[nl] : scale_lds[nl]);
-                    if (p.acc) p.acc[(size_t)m * p.N + n] = val;
-                } else {
-                    p.ws[((size_t)(p.slot0 + ks) * p.N + n) * p.M + m] = val;
-                }
-            }
+            if (mrow < rows_wg && mrow < R * kRoundRows && n < out_N) store_one(park[nl * kParkStride + col], m0 + mrow, n, nl);
         }
         wg_barrier_lds();
     }
     };
     if (n_tile * (R * kRoundRows + 4) * 4 <= kTableBytes) epilogue(std::integral_constant<int, R>{});
     else epilogue(std::integral_constant<int, (R > 1 ? 2 : 1)>{});
+    }
+    }   // tiles of this workgroup
 }
 
 }  // namespace

@@ -19,6 +19,7 @@
 
 #include <cstdint>
 #include <cstring>
+#include <algorithm>
 #include <atomic>
 #include <mutex>
 #include <type_traits>
@@ -245,8 +246,25 @@ bool choose_fused_plan(int64_t M, int64_t K, int64_t N, Plan* out) {
     return found;
 }
 
+// Compute units of the current device (cached per device; 0 if the query fails).
+int compute_units() {
+    static std::atomic<int> cached[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    int v = cached[dev].load(std::memory_order_relaxed);
+    if (v > 0) return v;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) return 0;
+    cached[dev].store(v, std::memory_order_relaxed);
+    return v;
+}
+
+// The lookup kernel's workgroups are persistent: at most one per compute unit (a workgroup needs more than half of a
+// unit's LDS), spread evenly over the 8 XCDs; each walks through its share of the tile list.
 template <int R, bool NEED32, int MODE, int BW>
-int launch_lookup_t(const LookupParams& p, int grid, hipStream_t stream) {
+int launch_lookup_t(const LookupParams& p, int /*tiles_grid*/, hipStream_t stream) {
+    const int cus = compute_units();
+    if (cus < 8) return VLUT_ERR_DEVICE;
+    const int grid = 8 * std::min(p.per_xcd, cus / 8);
     auto kfn = lookup_kernel<R, NEED32, MODE, BW>;
     constexpr int max_lds = MODE == kFusedQuant ? kFusedMaxLds : kLdsBytes;
     const int lds = MODE == kFusedQuant ? kFusedAqBase + p.stages_per_split * kFusedStageBytes : kLdsBytes;
@@ -256,6 +274,8 @@ int launch_lookup_t(const LookupParams& p, int grid, hipStream_t stream) {
     LookupParams q = p;
     if (q.S > 1 || q.partial) q.out_vec = ((uintptr_t)q.ws % 16 == 0) && (q.M % 4 == 0);
     else q.out_vec = !q.y || (((uintptr_t)q.y % 16 == 0) && (q.ldy % 4 == 0));
+    q.magic_S = q.S > 1 ? (unsigned)((1ull << 32) / (unsigned)q.S) : 0xffffffffu;
+    q.magic_tiles_n = q.tiles_n > 1 ? (unsigned)((1ull << 32) / (unsigned)q.tiles_n) : 0xffffffffu;
     hipLaunchKernelGGL(kfn, dim3(grid), dim3(kThreads), lds, stream, q);
     return hipGetLastError() == hipSuccess ? VLUT_OK : VLUT_ERR_DEVICE;
 }
