@@ -123,12 +123,14 @@ Derived derive(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     return d;
 }
 
-// Cost model in nanoseconds, fitted to K-scans of this chip at 256 workgroups (one round).  A stage (4 slots = 64
+// Cost model in nanoseconds, fitted to K-scans and in-kernel timestamps on this chip.  A stage (4 slots = 64
 // k-groups at 16 sub-tables per table row) costs a fixed part (the table build and its LDS writes, which share the LDS
 // pipe with the table reads) plus a part per row group of the slowest lookup wave (two table reads, two address
 // permutes and four three-operand adds per slot pair); with two build waves the fixed part is smaller and every
-// workgroup holds 7/6 of the rows, but the build itself takes ~1.37 us per stage, which only R >= 7 hides.  Outside
-// the K loop: first loads and first build, then the cross-lane reduction and the stores of every row group.
+// workgroup holds 7/6 of the rows, but the build itself takes ~1.37 us per stage, which only R >= 7 hides.  Per tile,
+// outside the K loop: the cross-lane reduction and the stores of every row group (bound by the SIMD that holds the
+// most lookup waves: four of 14, three of 12) and the hand-over to the next tile; once per workgroup: the argument
+// fetch, the first activations and the first table.
 double plan_cost(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     Derived d = derive(pl, M, K, N);
     const int lookup_waves = kWaves - pl.BW;
@@ -136,15 +138,15 @@ double plan_cost(const Plan& pl, int64_t M, int64_t K, int64_t N) {
     double stage, outside;
     if (pl.BW == 4) {
         stage = 867.0 + 90.0 * rw;
-        outside = 1300.0 + 450.0 * rw;
+        outside = 600.0 + 190.0 * rw;
     } else {
         stage = 745.0 + 106.0 * rw;
         if (stage < 1370.0) stage = 1370.0;
-        outside = 1000.0 + 530.0 * rw;
+        outside = 600.0 + 250.0 * rw;
     }
     double wg = d.stages_per_split * stage * (d.need32 ? 1.05 : 1.0) + outside;
-    double rounds = (double)((d.total + 255) / 256);
-    double t = 2000.0 + rounds * wg;
+    double rounds = (double)((d.total + 255) / 256);          // tiles of the busiest workgroup
+    double t = 2000.0 + 2100.0 + rounds * wg;
     if (pl.S > 1) t += 2400.0 + 290.0 * pl.S + (double)pl.S * (double)M * (double)N * 8.0 / (256.0 * 16.0 * 2.1);   // second kernel
     // weight bytes pulled from L2 by all token tiles (256 CUs x ~24 B/clk)
     double traffic = (double)d.tiles_n * (double)d.RGtotal * d.KCn * 64.0 / (256.0 * 24.0 * 2.1);
