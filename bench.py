@@ -50,10 +50,10 @@ MFMA_INT8_PEAK_TOPS = 5000.0                              # dense INT8 matrix-co
 
 # HBM bytes per launch of the lookup kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), see profiles/
 MEASURED_TRAFFIC_BYTES = {
-    "llama8b_linears/gateup/512": 77.5e6,  # profiles/lookup_kernel_llama8b_gateup_n512_stats_sq_counters_hbm_traffic.md
-    "bitnet3b_prefill/up/256": 22.8e6,     # profiles/lookup_kernel_bitnet3b_up_n256_stats_sq_counters_hbm_traffic.md
-    "bitnet2b_ffn_up/up/128": 10.96e6,     # profiles/lookup_kernel_bitnet2b_ffn_up_n128_stats_sq_counters_hbm_traffic.md
-    "layer2b4_nsweep/gate/16": 6.34e6,     # profiles/layer2b4_gate_n16_kernel_stats_hbm_traffic.md
+    "llama8b_linears/gateup/512": 75.8e6,  # profiles/lookup_kernel_llama8b_gateup_n512_stats_sq_counters_hbm_traffic.md
+    "bitnet3b_prefill/up/256": 22.6e6,     # profiles/lookup_kernel_bitnet3b_up_n256_stats_sq_counters_hbm_traffic.md
+    "bitnet2b_ffn_up/up/128": 10.85e6,     # profiles/lookup_kernel_bitnet2b_ffn_up_n128_stats_sq_counters_hbm_traffic.md
+    "layer2b4_nsweep/gate/16": 6.33e6,     # profiles/layer2b4_gate_n16_kernel_stats_hbm_traffic.md
     "layer2b4_nsweep/gate/1": 4.66e6,      # profiles/narrow_kernel_layer2b4_gate_n1_stats_and_hbm_traffic.md
 }
 
