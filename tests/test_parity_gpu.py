@@ -394,6 +394,25 @@ def test_split_k_repeated_and_many_tiles(B):
     run_case(B, W, s, x, plan=(16, 1, 0, 2), tag="split-K, 4200 output tiles")
 
 
+@pytest.mark.parametrize("shape,plan", [((3000, 1028, 777), (8, 1, 0, 3)), ((2999, 400, 300), (16, 5, 0, 2)),
+                                        ((700, 400, 520), (16, 1, 14, 2)), ((2999, 400, 777), (4, 1, 12, 2)),
+                                        ((3000, 2560, 130), (16, 5, 14, 3)), ((1501, 1028, 520), (16, 3, 12, 1))])
+def test_workgroups_walk_through_many_tiles(B, shape, plan):
+    """The lookup kernel's workgroups are persistent (at most one per compute unit): with more tiles than that every
+    workgroup takes several in a row — up to 36 here — and nothing may carry over from one tile to the next: ragged
+    row and token tiles, K splits, 8-token tiles (each lookup wave writes its own rows while the build waves are
+    already on the next tile) and wider ones (the whole workgroup writes the tile), 12 and 14 lookup waves."""
+    M, K, N = shape
+    W, s, x = wl.small_case(700 + M + N, M, K, N)
+    B.set_plan(*plan)
+    try:
+        tiles = B.query_plan(M, K, N)[3]
+    finally:
+        B.set_plan(0, 0, 0, 0)
+    assert tiles > 512, tiles                              # more than two tiles per workgroup on 256 compute units
+    run_case(B, W, s, x, plan=plan, tag=f"{tiles} tiles")
+
+
 def test_run_to_run_determinism(B):
     w = wl.WORKLOADS["bitnet2b_ffn_up"]
     W, s, x = wl.small_case(90, 1000, 2560, 128)
