@@ -263,7 +263,7 @@ int compute_units() {
 // The lookup kernel's workgroups are persistent: at most one per compute unit (a workgroup needs more than half of a
 // unit's LDS), spread evenly over the 8 XCDs; each walks through its share of the tile list.
 template <int R, bool NEED32, int MODE, int BW>
-int launch_lookup_t(const LookupParams& p, int /*tiles_grid*/, hipStream_t stream) {
+int launch_lookup_t(const LookupParams& p, hipStream_t stream) {
     const int cus = compute_units();
     if (cus < 8) return VLUT_ERR_DEVICE;
     const int grid = 8 * std::min(p.per_xcd, cus / 8);
@@ -299,23 +299,23 @@ constexpr bool lookup_instance_built(int R, bool need32, int mode) {
 constexpr bool lookup_bw_built(int BW, int mode) { return BW == 4 || (BW == 2 && mode == kFast); }
 
 template <bool NEED32, int MODE, int BW, int R = 1>
-int launch_lookup_by_r(int r, const LookupParams& p, int grid, hipStream_t stream) {
+int launch_lookup_by_r(int r, const LookupParams& p, hipStream_t stream) {
     if constexpr (R > 16) {
         return VLUT_ERR_UNSUPPORTED;
     } else {
         if constexpr (lookup_instance_built(R, NEED32, MODE)) {
-            if (r == R) return launch_lookup_t<R, NEED32, MODE, BW>(p, grid, stream);
+            if (r == R) return launch_lookup_t<R, NEED32, MODE, BW>(p, stream);
         }
-        return launch_lookup_by_r<NEED32, MODE, BW, R + 1>(r, p, grid, stream);
+        return launch_lookup_by_r<NEED32, MODE, BW, R + 1>(r, p, stream);
     }
 }
 
 template <bool NEED32>
-int launch_lookup_r(int R, int BW, int mode, const LookupParams& p, int grid, hipStream_t stream) {
-    if (mode == kFusedQuant && BW == 4) return launch_lookup_by_r<NEED32, kFusedQuant, 4>(R, p, grid, stream);
-    if (mode == kFast && BW == 4) return launch_lookup_by_r<NEED32, kFast, 4>(R, p, grid, stream);
-    if (mode == kFast && BW == 2) return launch_lookup_by_r<NEED32, kFast, 2>(R, p, grid, stream);
-    if (mode == kFromGlobal && BW == 4) return launch_lookup_by_r<NEED32, kFromGlobal, 4>(R, p, grid, stream);
+int launch_lookup_r(int R, int BW, int mode, const LookupParams& p, hipStream_t stream) {
+    if (mode == kFusedQuant && BW == 4) return launch_lookup_by_r<NEED32, kFusedQuant, 4>(R, p, stream);
+    if (mode == kFast && BW == 4) return launch_lookup_by_r<NEED32, kFast, 4>(R, p, stream);
+    if (mode == kFast && BW == 2) return launch_lookup_by_r<NEED32, kFast, 2>(R, p, stream);
+    if (mode == kFromGlobal && BW == 4) return launch_lookup_by_r<NEED32, kFromGlobal, 4>(R, p, stream);
     return VLUT_ERR_UNSUPPORTED;
 }
 
@@ -861,8 +861,7 @@ static int mpgemm_impl(const uint8_t* packed, float w_scale, const float* w_rows
     p.aligned8 = al ? 1 : 0;
     p.Ka = (int)K;
     hipStream_t s = (hipStream_t)stream;
-    int grid = d.per_xcd * 8;
-    rc = d.need32 ? launch_lookup_r<true>(pl.R, pl.BW, mode, p, grid, s) : launch_lookup_r<false>(pl.R, pl.BW, mode, p, grid, s);
+    rc = d.need32 ? launch_lookup_r<true>(pl.R, pl.BW, mode, p, s) : launch_lookup_r<false>(pl.R, pl.BW, mode, p, s);
     if (rc != VLUT_OK) return rc;
     if (pl.S > 1)
         return launch_splitk_reduce((const int32_t*)workspace, pl.S, M, N, w_scale, w_rows, a_scale, y, ldy, acc_or_null, s);
@@ -979,9 +978,8 @@ int vlut_mpgemm_f32(const uint8_t* packed, float w_scale, const float* w_scale_r
     p.Jlog = pl.Jlog; p.S = pl.S; p.tiles_m = d.tiles_m; p.tiles_n = d.tiles_n; p.RGW = d.RGW;
     p.stages_total = d.stages_total; p.stages_per_split = d.stages_per_split;
     p.total_tiles = d.total; p.per_xcd = d.per_xcd;
-    const int grid = d.per_xcd * 8;
-    int rc = d.need32 ? launch_lookup_r<true>(pl.R, pl.BW, kFusedQuant, p, grid, s)
-                      : launch_lookup_r<false>(pl.R, pl.BW, kFusedQuant, p, grid, s);
+    int rc = d.need32 ? launch_lookup_r<true>(pl.R, pl.BW, kFusedQuant, p, s)
+                      : launch_lookup_r<false>(pl.R, pl.BW, kFusedQuant, p, s);
     if (rc != VLUT_OK) return rc;
     if (pl.S > 1) {
         rc = launch_splitk_reduce((const int32_t*)(ws + L.off_ws), pl.S, M, N, w_one, w_rows, (const float*)scales, y, ldy,
@@ -1195,8 +1193,7 @@ int vlut_mpgemm_mixed(const uint8_t* packed, float w_scale, const int8_t* a_q, c
         p.stages_total = d.stages_total; p.stages_per_split = d.stages_per_split;
         p.total_tiles = d.total; p.per_xcd = d.per_xcd;
         p.Ka = (int)K; p.partial = 1; p.slot0 = pl5.S;
-        const int grid = d.per_xcd * 8;
-        rc = d.need32 ? launch_lookup_r<true>(pl4.R, pl4.BW, kFast, p, grid, s) : launch_lookup_r<false>(pl4.R, pl4.BW, kFast, p, grid, s);
+        rc = d.need32 ? launch_lookup_r<true>(pl4.R, pl4.BW, kFast, p, s) : launch_lookup_r<false>(pl4.R, pl4.BW, kFast, p, s);
         if (rc != VLUT_OK) return rc;
     }
     return launch_splitk_reduce((const int32_t*)workspace, pl5.S + pl4.S, M, N, w_scale, nullptr, a_scale, y, ldy,
