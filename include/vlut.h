@@ -320,7 +320,8 @@ int vlut_set_plan(int J, int R, int waves, int split_k);
 
 /*
  * Reports the launch plan vlut_mpgemm would use for this shape (after any vlut_set_plan override of the
- * calling thread): out4 (host, 4 ints) = { J, R, split_k, number of workgroup tiles }.
+ * calling thread): out4 (host, 4 ints) = { J, R, split_k, number of workgroup tiles }.  (The launch itself has at
+ * most one workgroup per compute unit; each walks through its share of the tiles.)
  * With few tokens and no override (N <= 2 always; 3 <= N <= 32 when ceil(N/2) copies of the row tiles are at most
  * 256 workgroups and a cost estimate favours it: few rows per workgroup, or a short K), vlut_mpgemm uses a kernel
  * of its own (two tokens per
