@@ -16,6 +16,10 @@ namespace {
 // Table entries and block accumulators are words of two INT16 values each (word_lo / word_hi), so that one
 // three-operand 32-bit add accumulates the entries of two lookups: per lookup one address permute, one 16-byte
 // table read and two adds.
+// Workgroups are persistent: the launch has at most one per compute unit, and each walks through its share of the
+// output tiles (row tile x token tile x K split).  With 8-token tiles the lookup waves finish a tile on their own
+// (cross-lane sums, transposition through a private patch of LDS, stores) while the build waves already fetch the
+// activations and build the first tables of the next tile.
 //   R       row groups (of 4 output rows) per lookup wave; workgroup tile = up to 4*LW*R rows
 //   NEED32  more than 64 lookups per lane: widen INT16 block sums into INT32 every 16 stages
 //   MODE    kFast: tables built in LDS from the token-chunked INT8 activations (streamed, the hot path)
