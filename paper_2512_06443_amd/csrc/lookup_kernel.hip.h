@@ -626,7 +626,9 @@ __global__ void __launch_bounds__(kThreads) lookup_kernel(const LookupParams lau
         // write only the first half before the next barrier) and come back as runs of consecutive rows per token.
         // LDS operations of one wave complete in order, so the wave only waits for its own writes.
         if (!builder) {
-            constexpr int kOwnStride = 4 * R + 4;               // ints per parked token; +4 spreads the tokens over banks
+            // ints per parked token: four times an odd number >= R, so that the 8 tokens x 4 rows a wave writes at
+            // once fall into 32 distinct banks (4R + 4 = 64 at R = 15 put all tokens into the same four)
+            constexpr int kOwnStride = 4 * (R | 1);
             lds_i32* own = (lds_i32*)(unsigned)(2 * kSlotBytes + lw * (8 * kOwnStride * 4));
 #pragma unroll
             for (int r = 0; r < R; ++r)   // both lanes of a pair hold the same total and store it to the same place
